@@ -1,0 +1,174 @@
+/*
+ * libspecdec -- MI355X (gfx950) implementation of the draft-then-verify hot path of
+ * Speculative Decoding (SpecDec, arXiv 2203.16487).
+ *
+ * C ABI.  Every pointer marked (device) is device memory owned by the caller; every
+ * pointer marked (host) is ordinary host memory.  The library allocates no device memory:
+ * weights, workspaces, inputs and outputs are the caller's.  `stream` is a hipStream_t
+ * passed as void* (NULL = the null stream).  Calls validate their arguments on the host,
+ * enqueue work on `stream` and return without synchronising (except where stated).
+ * Return value: SPECDEC_OK or a negative specdec_status; specdec_last_error() gives text.
+ * A context is not thread-safe.  All work of one context must be issued on one device.
+ *
+ * Notation (paper Sec. 2): x source, y^_{<=j} tokens decoded so far, y~_{j+1..j+k} the k
+ * drafted tokens, c the bifurcation position.  The decoder input stream of a sequence is
+ * u_0 = BOS, u_t = y^_t.  Keys/values of u_0..u_{j-1} are cached; u_j is "pending": it is
+ * the first row of the next verification pass.
+ *
+ * Model storage.  All tensors bf16, matrices [out_features, in_features] row-major
+ * (y = x W^T + b).  Tensor order (n = specdec_num_weights):
+ *   embed [V,d]                                   (tied: input embedding and output projection)
+ *   per encoder layer: attn.wqkv [3d,d], attn.bqkv [3d], attn.wo [d,d], attn.bo [d],
+ *                      ln1.g [d], ln1.b [d], ffn.w1 [F,d], ffn.b1 [F], ffn.w2 [d,F],
+ *                      ffn.b2 [d], ln2.g [d], ln2.b [d]
+ *   per decoder layer: self.wqkv [3d,d], self.bqkv [3d], self.wo [d,d], self.bo [d],
+ *                      ln1.g, ln1.b, cross.wq [d,d], cross.bq [d], cross.wkv [2d,d],
+ *                      cross.bkv [2d], cross.wo [d,d], cross.bo [d], ln2.g, ln2.b,
+ *                      ffn.w1, ffn.b1, ffn.w2, ffn.b2, ln3.g, ln3.b
+ * Architecture (the paper only names a 6+6 Transformer of 512/2048, Sec. 4.1): post-LN
+ * sublayers, LayerNorm eps 1e-5, interleaved sinusoidal positions from 0, embeddings scaled
+ * by sqrt(d), scores scaled by 1/sqrt(64), ReLU.  d_model = 64 * n_heads.
+ */
+#ifndef SPECDEC_H
+#define SPECDEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct specdec_ctx specdec_ctx; /* opaque, host side */
+
+typedef enum {
+  SPECDEC_OK = 0,
+  SPECDEC_ERR_INVALID_ARG = -1, /* NULL pointer, value out of range */
+  SPECDEC_ERR_BAD_STATE = -2,   /* call order: model/state not bound, begin not called ... */
+  SPECDEC_ERR_TOO_LARGE = -3,   /* exceeds the limits given at create / buffer too small */
+  SPECDEC_ERR_HIP = -4,         /* a HIP call failed */
+  SPECDEC_ERR_NO_DEVICE = -5    /* no usable GPU */
+} specdec_status;
+
+typedef enum { SPECDEC_VERIFIER = 0, SPECDEC_DRAFTER = 1 } specdec_role;
+
+typedef struct {
+  int32_t enc_layers, dec_layers, d_model, n_heads, d_ffn, vocab;
+  int32_t bos_id, eos_id, pad_id, mask_id;
+} specdec_model_desc;
+
+typedef struct {
+  int32_t max_batch; /* sequences decoded together                                  */
+  int32_t k_max;     /* largest block size k (paper uses 10..30, Table 3); <= 31     */
+  int32_t max_src;   /* longest source (encoder memory rows per sequence)            */
+  int32_t max_tgt;   /* longest decoder stream: j <= max_tgt                         */
+} specdec_limits;
+
+enum { SPECDEC_BETA_MAX = 8 }; /* top-beta lists are kept to this depth (paper uses <= 5, Table 4) */
+
+/* ---- life cycle -------------------------------------------------------------------- */
+int specdec_create(specdec_ctx** out, const specdec_limits* limits); /* host only */
+void specdec_destroy(specdec_ctx* ctx);
+const char* specdec_last_error(const specdec_ctx* ctx); /* (host) valid until the next call */
+
+/* Number of weight tensors of a model and the shape of tensor idx (cols = 1 for vectors). */
+int specdec_num_weights(const specdec_model_desc* desc, int32_t* out);
+int specdec_weight_shape(const specdec_model_desc* desc, int32_t idx, int64_t* rows, int64_t* cols);
+
+/* Sequence state (token streams, lengths, flags, per-step scratch shared by both models):
+ * size query, then bind a (device) buffer of at least that size, 256-byte aligned. */
+int specdec_state_bytes(const specdec_ctx* ctx, size_t* out);
+int specdec_bind_state(specdec_ctx* ctx, void* state /*device*/, size_t bytes);
+
+/* Per-model workspace (KV arenas, cross-attention K/V, activations, position table). */
+int specdec_workspace_bytes(const specdec_ctx* ctx, const specdec_model_desc* desc, size_t* out);
+/* weights: (host) array of n_weights (device) pointers in the order above.  The workspace
+ * is (device), 256-byte aligned.  Builds the position table on `stream`. */
+int specdec_bind_model(specdec_ctx* ctx, specdec_role role, const specdec_model_desc* desc,
+                       const void* const* weights, int32_t n_weights, void* workspace,
+                       size_t workspace_bytes, void* stream);
+
+/* ---- per batch ---------------------------------------------------------------------- */
+/* Start decoding B sequences: every stream = [BOS], j = 0, nothing cached, not finished.
+ * max_new = cap on tokens committed per sequence (the paper's "termination condition",
+ * Sec. 2, is EOS; a length cap is the usual second one). */
+int specdec_begin(specdec_ctx* ctx, int32_t B, int32_t max_new, void* stream);
+
+/* Encoder pass of every bound model over src (device int32 [B, S_max], right-padded;
+ * src_len device int32 [B], 1 <= src_len <= S_max <= max_src), then the cross-attention
+ * keys/values of every decoder layer, computed once per input (Sec. 3.1.2: the encoder is
+ * forwarded only once). */
+int specdec_encode(specdec_ctx* ctx, const int32_t* src, const int32_t* src_len, int32_t S_max,
+                   void* stream);
+
+/* Instead of specdec_encode: take a given encoder memory (device bf16 [B, S_max, d]) for one
+ * model and compute that model's cross-attention keys/values from it. */
+int specdec_set_memory(specdec_ctx* ctx, specdec_role role, const void* memory,
+                       const int32_t* src_len, int32_t S_max, void* stream);
+
+/* Replace the streams by given ones: tokens device int32 [B, L_max+1] holds u_0..u_j per
+ * sequence, len device int32 [B] holds j (0 <= j <= L_max <= max_tgt).  After this call no
+ * model has anything cached for these streams (cached lengths 0) unless a cache is loaded
+ * with specdec_load_cache.  The max_new cap counts tokens committed after this call. */
+int specdec_set_stream(specdec_ctx* ctx, const int32_t* tokens, const int32_t* len, int32_t L_max,
+                       void* stream);
+/* Load self-attention keys/values of u_0..u_{n-1} for one model: k_cache, v_cache device
+ * bf16 [dec_layers, B, L_max, d]; n device int32 [B] (n <= j for the verifier, n <= j+1 for
+ * the drafter).  Rows at and beyond n are ignored. */
+int specdec_load_cache(specdec_ctx* ctx, specdec_role role, const void* k_cache,
+                       const void* v_cache, const int32_t* n, int32_t L_max, void* stream);
+
+/* Cache the keys/values of every stream token a model has not cached yet (u_0..u_{j-1} for
+ * the verifier, u_0..u_j for the drafter) with causal decoder passes of up to k_max+1 rows
+ * per sequence.  Needed after specdec_set_stream unless a cache is loaded. */
+int specdec_prefill(specdec_ctx* ctx, specdec_role role, void* stream);
+
+/* ---- the hot path -------------------------------------------------------------------- */
+/* Spec-Drafter inference (Sec. 3.1.3, Eq. 7): append k [MASK] slots to the stream, one
+ * non-autoregressive decoder pass, argmax per slot -> draft device int32 [B, k].  Stream
+ * tokens the drafter has not cached yet are processed (causally) in the same pass and
+ * cached; mask slots attend to the whole stream and to all k slots. */
+int specdec_draft(specdec_ctx* ctx, int32_t k, int32_t* draft, void* stream);
+
+/* Verification (Sec. 2 Eq. 1-3; Sec. 3.2 Eq. 8-10): one KV-cached pass of the verifier's
+ * decoder over rows [u_j, y~_{j+1}, .., y~_{j+k}] (causal; keys/values of the rows are
+ * appended after the cached ones), vocabulary projection and log-softmax statistics fused
+ * with the acceptance test.  Draft i is accepted iff drafts 1..i-1 were and, on row i-1,
+ *   log P(y~) >= log P(beta-th ranked token)   and   log P(top-1) - log P(y~) <= tau.
+ * beta = 1, tau = 0 is the strict top-1 rule.  Outputs (device int32 [B]):
+ *   accept_len = number of accepted drafts a (= c - 1),
+ *   next_token = the verifier's arg-max token on row a (lowest index among maxima); when all
+ *   k drafts are accepted this is the token after the last draft.
+ * Finished sequences report accept_len 0 and next_token pad_id.
+ * logits_or_null: optional device fp32 [B, k+1, V] receiving every row's logits (parity
+ * mode; slow).  Does not change any length: calling it twice gives the same result. */
+int specdec_verify(specdec_ctx* ctx, const int32_t* draft, int32_t k, int32_t beta, float tau,
+                   int32_t* accept_len, int32_t* next_token, float* logits_or_null, void* stream);
+
+/* Commit (Eq. 3): append y~_{j+1..j+a} and next_token to each stream, stop a sequence after
+ * its first EOS or at its cap; j advances by the number of tokens appended, which also is
+ * the number of this pass's cache rows that become valid -- rejected rows are simply left
+ * beyond j (rollback moves no data).  Uses the drafts of the latest specdec_verify.
+ * n_active_or_null: optional device int32 [1] receiving the number of unfinished sequences. */
+int specdec_commit(specdec_ctx* ctx, const int32_t* accept_len, const int32_t* next_token,
+                   int32_t* n_active_or_null, void* stream);
+
+/* ---- read back ----------------------------------------------------------------------- */
+/* tokens device int32 [B, out_cap]: tokens committed since begin / set_stream (right-padded
+ * with pad_id); out_len device int32 [B]; finished_or_null device int32 [B]. */
+int specdec_get_output(specdec_ctx* ctx, int32_t* tokens, int32_t out_cap, int32_t* out_len,
+                       int32_t* finished_or_null, void* stream);
+/* Cached self-attention keys/values of one model, rows [0, L) of every sequence, in the
+ * layout of specdec_load_cache ([dec_layers, B, L, d] bf16).  Rows beyond a sequence's
+ * cached length hold whatever the last pass wrote there. */
+int specdec_get_cache(specdec_ctx* ctx, specdec_role role, void* k_cache, void* v_cache, int32_t L,
+                      void* stream);
+/* Per-row statistics of the latest specdec_verify, device fp32 [B, k+1, 4 + SPECDEC_BETA_MAX]:
+ * {max logit, arg-max (as float), log-sum-exp, logit of the draft scored on this row (or
+ * -inf on the last row), the SPECDEC_BETA_MAX largest logits in descending order}. */
+int specdec_get_row_stats(specdec_ctx* ctx, float* stats, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECDEC_H */

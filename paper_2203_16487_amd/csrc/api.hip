@@ -1,0 +1,513 @@
+// C ABI of libspecdec: context, argument checks, workspace layout and the launch sequence
+// of every entry point declared in include/specdec.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/specdec.h"
+#include "kernels.h"
+
+using sd::bf16;
+
+namespace {
+
+struct EncLayer {
+  const bf16 *wqkv, *bqkv, *wo, *bo, *ln1g, *ln1b, *w1, *b1, *w2, *b2, *ln2g, *ln2b;
+};
+struct DecLayer {
+  const bf16 *wqkv, *bqkv, *wo, *bo, *ln1g, *ln1b;
+  const bf16 *cwq, *cbq, *cwkv, *cbkv, *cwo, *cbo, *ln2g, *ln2b;
+  const bf16 *w1, *b1, *w2, *b2, *ln3g, *ln3b;
+};
+
+struct Model {
+  bool bound = false;
+  bool has_memory = false;
+  specdec_model_desc d{};
+  const bf16* embed = nullptr;
+  std::vector<EncLayer> enc;
+  std::vector<DecLayer> dec;
+  // workspace
+  float* pe = nullptr;       // [n_pos][d]
+  bf16 *kc = nullptr, *vc = nullptr;   // [Ld][Bmax][H][Lcap][64]
+  bf16 *xk = nullptr, *xv = nullptr;   // [Ld][Bmax][H][Scap][64]
+  float* x = nullptr;        // [Rmax][d] residual stream
+  bf16* xb = nullptr;        // [Rmax][d]
+  bf16* q = nullptr;         // [Rmax][d]
+  bf16* att = nullptr;       // [Rmax][d]
+  bf16* hid = nullptr;       // [Rmax][F]
+  float* part = nullptr;     // [Rmax][n_tiles][kPartF]
+  float* row_stats = nullptr;  // [Rmax][4+kTopN]
+  // encoder activations, rows = Bmax * Scap
+  float* ex = nullptr;
+  bf16 *exb = nullptr, *eqkv = nullptr, *eatt = nullptr, *ehid = nullptr;
+  int *etok = nullptr, *epos = nullptr;
+  sd::RowMap rm{};
+  size_t kv_layer = 0, xkv_layer = 0;  // elements per layer of the arenas
+};
+
+}  // namespace
+
+struct specdec_ctx {
+  specdec_limits lim{};
+  int Lcap = 0, Tmax = 0, n_pos = 0;
+  bool state_bound = false;
+  sd::SeqState st{};
+  Model m[2];
+  int B = 0;          // batch of the current begin()
+  int max_new = 0;
+  int last_k = 0;     // k of the latest verify (0: none)
+  int S_cur = 0;      // S_max of the current memory
+  int uncached_ub[2] = {0, 0};
+  bool trusted[2] = {false, false};
+  char err[512] = {0};
+};
+
+namespace {
+
+int fail(const specdec_ctx* c, int code, const char* fmt, ...) {
+  if (c) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(const_cast<specdec_ctx*>(c)->err, sizeof(c->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+#define HIPCHK(c, expr)                                                                   \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess)                                                                 \
+      return fail(c, SPECDEC_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));     \
+  } while (0)
+
+bool desc_ok(const specdec_model_desc* d) {
+  return d && d->enc_layers >= 0 && d->dec_layers >= 1 && d->n_heads >= 1 && d->n_heads <= 32 &&
+         d->d_model == 64 * d->n_heads && d->d_ffn >= 64 && d->d_ffn % 64 == 0 && d->d_ffn <= 16384 &&
+         d->vocab >= SPECDEC_BETA_MAX && d->vocab <= (1 << 24) && d->bos_id >= 0 && d->bos_id < d->vocab &&
+         d->eos_id >= 0 && d->eos_id < d->vocab && d->pad_id >= 0 && d->pad_id < d->vocab &&
+         d->mask_id >= 0 && d->mask_id < d->vocab;
+}
+constexpr int kEncT = 12, kDecT = 20;
+int n_weights(const specdec_model_desc* d) { return 1 + kEncT * d->enc_layers + kDecT * d->dec_layers; }
+
+void weight_shape(const specdec_model_desc* d, int idx, int64_t* r, int64_t* c) {
+  const int64_t D = d->d_model, F = d->d_ffn;
+  if (idx == 0) { *r = d->vocab; *c = D; return; }
+  idx -= 1;
+  static const int enc_kind[kEncT] = {0, 1, 2, 3, 3, 3, 4, 5, 6, 3, 3, 3};
+  // kinds: 0 [3d,d] 1 [3d] 2 [d,d] 3 [d] 4 [F,d] 5 [F] 6 [d,F] 7 [2d,d] 8 [2d]
+  static const int dec_kind[kDecT] = {0, 1, 2, 3, 3, 3, 2, 3, 7, 8, 2, 3, 3, 3, 4, 5, 6, 3, 3, 3};
+  int kind;
+  if (idx < kEncT * d->enc_layers) kind = enc_kind[idx % kEncT];
+  else kind = dec_kind[(idx - kEncT * d->enc_layers) % kDecT];
+  switch (kind) {
+    case 0: *r = 3 * D; *c = D; break;
+    case 1: *r = 3 * D; *c = 1; break;
+    case 2: *r = D; *c = D; break;
+    case 3: *r = D; *c = 1; break;
+    case 4: *r = F; *c = D; break;
+    case 5: *r = F; *c = 1; break;
+    case 6: *r = D; *c = F; break;
+    case 7: *r = 2 * D; *c = D; break;
+    default: *r = 2 * D; *c = 1; break;
+  }
+}
+
+// bump allocator over a (possibly null) base: the same walk sizes and carves a buffer
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+  template <class T>
+  T* take(size_t n) {
+    off = (off + 255) & ~size_t(255);
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+size_t carve_state(const specdec_ctx* c, void* base, sd::SeqState* out) {
+  Carver cv(base);
+  const size_t Bm = c->lim.max_batch;
+  sd::SeqState s{};
+  s.tok_pitch = c->lim.max_tgt + 1;
+  s.k_max = c->lim.k_max;
+  s.tokens = cv.take<int>(Bm * s.tok_pitch);
+  s.len = cv.take<int>(Bm);
+  s.start = cv.take<int>(Bm);
+  s.cap = cv.take<int>(Bm);
+  s.finished = cv.take<int>(Bm);
+  s.cached[0] = cv.take<int>(Bm);
+  s.cached[1] = cv.take<int>(Bm);
+  s.src_len = cv.take<int>(Bm);
+  s.last_draft = cv.take<int>(Bm * s.k_max);
+  s.scratch = cv.take<int>(8);
+  if (out) *out = s;
+  return (cv.off + 255) & ~size_t(255);
+}
+
+size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base, Model* m) {
+  Carver cv(base);
+  const size_t Bm = c->lim.max_batch, D = d->d_model, F = d->d_ffn, H = d->n_heads;
+  const size_t Rmax = Bm * c->Tmax;
+  const size_t n_tiles = (d->vocab + 127) / 128;
+  Model t;
+  t.kv_layer = Bm * H * c->Lcap * 64;
+  t.xkv_layer = Bm * H * (size_t)c->lim.max_src * 64;
+  t.pe = cv.take<float>((size_t)c->n_pos * D);
+  t.kc = cv.take<bf16>(t.kv_layer * d->dec_layers);
+  t.vc = cv.take<bf16>(t.kv_layer * d->dec_layers);
+  t.xk = cv.take<bf16>(t.xkv_layer * d->dec_layers);
+  t.xv = cv.take<bf16>(t.xkv_layer * d->dec_layers);
+  t.x = cv.take<float>(Rmax * D);
+  t.xb = cv.take<bf16>(Rmax * D);
+  t.q = cv.take<bf16>(Rmax * D);
+  t.att = cv.take<bf16>(Rmax * D);
+  t.hid = cv.take<bf16>(Rmax * F);
+  t.part = cv.take<float>(Rmax * n_tiles * sd::kPartF);
+  t.row_stats = cv.take<float>(Rmax * (4 + SPECDEC_BETA_MAX));
+  t.rm.row_b = cv.take<int>(Rmax);
+  t.rm.row_pos = cv.take<int>(Rmax);
+  t.rm.row_tok = cv.take<int>(Rmax);
+  t.rm.row_lim = cv.take<int>(Rmax);
+  t.rm.row_draft = cv.take<int>(Rmax);
+  t.rm.seq_rows = cv.take<int>(Bm);
+  if (d->enc_layers > 0) {
+    const size_t Re = Bm * (size_t)c->lim.max_src;
+    t.ex = cv.take<float>(Re * D);
+    t.exb = cv.take<bf16>(Re * D);
+    t.eqkv = cv.take<bf16>(Re * 3 * D);
+    t.eatt = cv.take<bf16>(Re * D);
+    t.ehid = cv.take<bf16>(Re * F);
+    t.etok = cv.take<int>(Re);
+    t.epos = cv.take<int>(Re);
+  }
+  if (m) {
+    m->kv_layer = t.kv_layer; m->xkv_layer = t.xkv_layer;
+    m->pe = t.pe; m->kc = t.kc; m->vc = t.vc; m->xk = t.xk; m->xv = t.xv;
+    m->x = t.x; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
+    m->part = t.part; m->row_stats = t.row_stats; m->rm = t.rm;
+    m->ex = t.ex; m->exb = t.exb; m->eqkv = t.eqkv; m->eatt = t.eatt; m->ehid = t.ehid;
+    m->etok = t.etok; m->epos = t.epos;
+  }
+  return (cv.off + 255) & ~size_t(255);
+}
+
+inline hipStream_t S(void* s) { return static_cast<hipStream_t>(s); }
+
+// Embedding + every decoder layer over the R = B*T rows described by m.rm.
+// Leaves the final hidden states in m.x (fp32) and m.xb (bf16).
+int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
+  const int R = B * T, D = m.d.d_model, F = m.d.d_ffn, H = m.d.n_heads;
+  const int Lcap = c->Lcap, Scap = c->lim.max_src;
+  HIPCHK(c, sd::embed_rows(st, m.rm.row_tok, m.rm.row_pos, m.embed, m.pe, m.x, m.xb, R, D));
+  for (int l = 0; l < m.d.dec_layers; ++l) {
+    const DecLayer& L = m.dec[l];
+    bf16* kc = m.kc + m.kv_layer * l;
+    bf16* vc = m.vc + m.kv_layer * l;
+    HIPCHK(c, sd::gemm_qkv_append(st, m.xb, L.wqkv, R, D, D, L.bqkv, m.q, kc, vc, m.rm.row_b,
+                                  m.rm.row_pos, H, Lcap));
+    sd::AttnArgs a{};
+    a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
+    a.k = kc; a.v = vc; a.kv_b = (long)H * Lcap * 64; a.kv_h = (long)Lcap * 64; a.kv_row = 64;
+    a.o = m.att; a.o_b = (long)T * D; a.o_row = D;
+    a.q_count = m.rm.seq_rows; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
+    a.T = T; a.H = H; a.B = B;
+    HIPCHK(c, sd::attention(st, a));
+    HIPCHK(c, sd::gemm_f32(st, m.att, D, L.wo, R, D, D, L.bo, m.x, m.x, D));
+    HIPCHK(c, sd::layer_norm(st, m.x, L.ln1g, L.ln1b, m.xb, R, D));
+    HIPCHK(c, sd::gemm_bf16(st, m.xb, D, L.cwq, R, D, D, L.cbq, m.q, D, false));
+    a.k = m.xk + m.xkv_layer * l; a.v = m.xv + m.xkv_layer * l;
+    a.kv_b = (long)H * Scap * 64; a.kv_h = (long)Scap * 64;
+    a.lim_row = nullptr; a.lim_seq = c->st.src_len;
+    HIPCHK(c, sd::attention(st, a));
+    HIPCHK(c, sd::gemm_f32(st, m.att, D, L.cwo, R, D, D, L.cbo, m.x, m.x, D));
+    HIPCHK(c, sd::layer_norm(st, m.x, L.ln2g, L.ln2b, m.xb, R, D));
+    HIPCHK(c, sd::gemm_bf16(st, m.xb, D, L.w1, R, F, D, L.b1, m.hid, F, true));
+    HIPCHK(c, sd::gemm_f32(st, m.hid, F, L.w2, R, D, F, L.b2, m.x, m.x, D));
+    HIPCHK(c, sd::layer_norm(st, m.x, L.ln3g, L.ln3b, m.xb, R, D));
+  }
+  return SPECDEC_OK;
+}
+
+int cross_kv_from(specdec_ctx* c, Model& m, const bf16* memory, int B, int S_max, hipStream_t st) {
+  const int D = m.d.d_model;
+  for (int l = 0; l < m.d.dec_layers; ++l)
+    HIPCHK(c, sd::gemm_cross_kv(st, memory, m.dec[l].cwkv, B * S_max, D, D, m.dec[l].cbkv,
+                                m.xk + m.xkv_layer * l, m.xv + m.xkv_layer * l, S_max, m.d.n_heads,
+                                c->lim.max_src));
+  m.has_memory = true;
+  return SPECDEC_OK;
+}
+
+int check_ready(specdec_ctx* c, int role, bool need_memory) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (role != SPECDEC_VERIFIER && role != SPECDEC_DRAFTER) return fail(c, SPECDEC_ERR_INVALID_ARG, "bad role %d", role);
+  if (!c->state_bound) return fail(c, SPECDEC_ERR_BAD_STATE, "state buffer not bound");
+  if (!c->m[role].bound) return fail(c, SPECDEC_ERR_BAD_STATE, "model of role %d not bound", role);
+  if (c->B <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_begin not called");
+  if (need_memory && !c->m[role].has_memory)
+    return fail(c, SPECDEC_ERR_BAD_STATE, "no encoder memory: call specdec_encode or specdec_set_memory");
+  return SPECDEC_OK;
+}
+
+}  // namespace
+
+// ============================================================================= ABI
+extern "C" {
+
+int specdec_create(specdec_ctx** out, const specdec_limits* lim) {
+  if (!out || !lim) return SPECDEC_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (lim->max_batch < 1 || lim->max_batch > 4096 || lim->k_max < 1 || lim->k_max > 31 ||
+      lim->max_src < 1 || lim->max_src > 65536 || lim->max_tgt < 1 || lim->max_tgt > 65536)
+    return SPECDEC_ERR_INVALID_ARG;
+  specdec_ctx* c = new (std::nothrow) specdec_ctx();
+  if (!c) return SPECDEC_ERR_TOO_LARGE;
+  c->lim = *lim;
+  c->Tmax = 2 * lim->k_max + 1;
+  c->Lcap = lim->max_tgt + lim->k_max + 1;
+  c->n_pos = c->Lcap;
+  *out = c;
+  return SPECDEC_OK;
+}
+
+void specdec_destroy(specdec_ctx* c) { delete c; }
+
+const char* specdec_last_error(const specdec_ctx* c) { return c ? c->err : "null context"; }
+
+int specdec_num_weights(const specdec_model_desc* d, int32_t* out) {
+  if (!out || !desc_ok(d)) return SPECDEC_ERR_INVALID_ARG;
+  *out = n_weights(d);
+  return SPECDEC_OK;
+}
+
+int specdec_weight_shape(const specdec_model_desc* d, int32_t idx, int64_t* rows, int64_t* cols) {
+  if (!rows || !cols || !desc_ok(d) || idx < 0 || idx >= n_weights(d)) return SPECDEC_ERR_INVALID_ARG;
+  weight_shape(d, idx, rows, cols);
+  return SPECDEC_OK;
+}
+
+int specdec_state_bytes(const specdec_ctx* c, size_t* out) {
+  if (!c || !out) return SPECDEC_ERR_INVALID_ARG;
+  *out = carve_state(c, nullptr, nullptr);
+  return SPECDEC_OK;
+}
+
+int specdec_bind_state(specdec_ctx* c, void* state, size_t bytes) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (!state || (reinterpret_cast<uintptr_t>(state) & 255)) return fail(c, SPECDEC_ERR_INVALID_ARG, "state buffer null or not 256-byte aligned");
+  if (bytes < carve_state(c, nullptr, nullptr)) return fail(c, SPECDEC_ERR_TOO_LARGE, "state buffer too small");
+  carve_state(c, state, &c->st);
+  c->state_bound = true;
+  c->B = 0;
+  return SPECDEC_OK;
+}
+
+int specdec_workspace_bytes(const specdec_ctx* c, const specdec_model_desc* d, size_t* out) {
+  if (!c || !out) return SPECDEC_ERR_INVALID_ARG;
+  if (!desc_ok(d)) return fail(c, SPECDEC_ERR_INVALID_ARG, "bad model description");
+  *out = carve_model(c, d, nullptr, nullptr);
+  return SPECDEC_OK;
+}
+
+int specdec_bind_model(specdec_ctx* c, specdec_role role, const specdec_model_desc* d, const void* const* weights,
+                       int32_t nw, void* workspace, size_t bytes, void* stream) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (role != SPECDEC_VERIFIER && role != SPECDEC_DRAFTER) return fail(c, SPECDEC_ERR_INVALID_ARG, "bad role");
+  if (!desc_ok(d)) return fail(c, SPECDEC_ERR_INVALID_ARG, "bad model description (need d_model = 64*n_heads, d_ffn %% 64 == 0)");
+  if (!weights || nw != n_weights(d)) return fail(c, SPECDEC_ERR_INVALID_ARG, "expected %d weight tensors, got %d", n_weights(d), nw);
+  for (int i = 0; i < nw; ++i)
+    if (!weights[i] || (reinterpret_cast<uintptr_t>(weights[i]) & 15))
+      return fail(c, SPECDEC_ERR_INVALID_ARG, "weight %d null or not 16-byte aligned", i);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return fail(c, SPECDEC_ERR_INVALID_ARG, "workspace null or not 256-byte aligned");
+  if (bytes < carve_model(c, d, nullptr, nullptr)) return fail(c, SPECDEC_ERR_TOO_LARGE, "workspace too small");
+  const Model& other = c->m[1 - role];
+  if (other.bound && (other.d.vocab != d->vocab || other.d.bos_id != d->bos_id || other.d.eos_id != d->eos_id))
+    return fail(c, SPECDEC_ERR_INVALID_ARG, "drafter and verifier must share the vocabulary and special ids");
+  int dev_count = 0;
+  if (hipGetDeviceCount(&dev_count) != hipSuccess || dev_count < 1) return fail(c, SPECDEC_ERR_NO_DEVICE, "no GPU");
+
+  Model& m = c->m[role];
+  m = Model();
+  m.d = *d;
+  auto W = [&](int i) { return static_cast<const bf16*>(weights[i]); };
+  int i = 0;
+  m.embed = W(i++);
+  m.enc.resize(d->enc_layers);
+  for (auto& L : m.enc) {
+    L.wqkv = W(i++); L.bqkv = W(i++); L.wo = W(i++); L.bo = W(i++); L.ln1g = W(i++); L.ln1b = W(i++);
+    L.w1 = W(i++); L.b1 = W(i++); L.w2 = W(i++); L.b2 = W(i++); L.ln2g = W(i++); L.ln2b = W(i++);
+  }
+  m.dec.resize(d->dec_layers);
+  for (auto& L : m.dec) {
+    L.wqkv = W(i++); L.bqkv = W(i++); L.wo = W(i++); L.bo = W(i++); L.ln1g = W(i++); L.ln1b = W(i++);
+    L.cwq = W(i++); L.cbq = W(i++); L.cwkv = W(i++); L.cbkv = W(i++); L.cwo = W(i++); L.cbo = W(i++);
+    L.ln2g = W(i++); L.ln2b = W(i++);
+    L.w1 = W(i++); L.b1 = W(i++); L.w2 = W(i++); L.b2 = W(i++); L.ln3g = W(i++); L.ln3b = W(i++);
+  }
+  carve_model(c, d, workspace, &m);
+  HIPCHK(c, sd::build_pos_table(S(stream), m.pe, c->n_pos, d->d_model));
+  m.bound = true;
+  return SPECDEC_OK;
+}
+
+int specdec_begin(specdec_ctx* c, int32_t B, int32_t max_new, void* stream) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (!c->state_bound) return fail(c, SPECDEC_ERR_BAD_STATE, "state buffer not bound");
+  if (!c->m[0].bound && !c->m[1].bound) return fail(c, SPECDEC_ERR_BAD_STATE, "no model bound");
+  if (B < 1 || max_new < 0) return fail(c, SPECDEC_ERR_INVALID_ARG, "B = %d, max_new = %d", B, max_new);
+  if (B > c->lim.max_batch) return fail(c, SPECDEC_ERR_TOO_LARGE, "B = %d exceeds max_batch = %d", B, c->lim.max_batch);
+  const Model& any = c->m[0].bound ? c->m[0] : c->m[1];
+  HIPCHK(c, sd::begin_state(S(stream), c->st, B, max_new, c->lim.max_tgt, any.d.bos_id));
+  c->B = B;
+  c->max_new = max_new;
+  c->last_k = 0;
+  c->uncached_ub[0] = 0;
+  c->uncached_ub[1] = 1;
+  c->trusted[0] = c->trusted[1] = false;
+  c->m[0].has_memory = c->m[1].has_memory = false;
+  return SPECDEC_OK;
+}
+
+int specdec_set_memory(specdec_ctx* c, specdec_role role, const void* memory, const int32_t* src_len,
+                       int32_t S_max, void* stream) {
+  int rc = check_ready(c, role, false);
+  if (rc) return rc;
+  if (!memory || !src_len || (reinterpret_cast<uintptr_t>(memory) & 15)) return fail(c, SPECDEC_ERR_INVALID_ARG, "memory/src_len null or misaligned");
+  if (S_max < 1) return fail(c, SPECDEC_ERR_INVALID_ARG, "S_max = %d", S_max);
+  if (S_max > c->lim.max_src) return fail(c, SPECDEC_ERR_TOO_LARGE, "S_max = %d exceeds max_src = %d", S_max, c->lim.max_src);
+  HIPCHK(c, sd::set_src_len(S(stream), c->st, src_len, c->B, S_max));
+  c->S_cur = S_max;
+  return cross_kv_from(c, c->m[role], static_cast<const bf16*>(memory), c->B, S_max, S(stream));
+}
+
+int specdec_encode(specdec_ctx* c, const int32_t* src, const int32_t* src_len, int32_t S_max, void* stream) {
+  (void)src; (void)src_len; (void)S_max; (void)stream;
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_encode: encoder pass not available in this build");
+}
+
+int specdec_set_stream(specdec_ctx* c, const int32_t* tokens, const int32_t* len, int32_t L_max, void* stream) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (!c->state_bound || c->B <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "bind state and call specdec_begin first");
+  if (!tokens || !len) return fail(c, SPECDEC_ERR_INVALID_ARG, "null tokens/len");
+  if (L_max < 0) return fail(c, SPECDEC_ERR_INVALID_ARG, "L_max = %d", L_max);
+  if (L_max > c->lim.max_tgt) return fail(c, SPECDEC_ERR_TOO_LARGE, "L_max = %d exceeds max_tgt = %d", L_max, c->lim.max_tgt);
+  HIPCHK(c, sd::set_stream(S(stream), c->st, tokens, len, c->B, L_max, c->max_new, c->lim.max_tgt));
+  c->uncached_ub[0] = L_max;
+  c->uncached_ub[1] = L_max + 1;
+  c->trusted[0] = c->trusted[1] = false;
+  c->last_k = 0;
+  return SPECDEC_OK;
+}
+
+int specdec_load_cache(specdec_ctx* c, specdec_role role, const void* k_cache, const void* v_cache,
+                       const int32_t* n, int32_t L_max, void* stream) {
+  int rc = check_ready(c, role, false);
+  if (rc) return rc;
+  if (!k_cache || !v_cache || !n) return fail(c, SPECDEC_ERR_INVALID_ARG, "null cache/n");
+  if ((reinterpret_cast<uintptr_t>(k_cache) | reinterpret_cast<uintptr_t>(v_cache)) & 15) return fail(c, SPECDEC_ERR_INVALID_ARG, "cache not 16-byte aligned");
+  if (L_max < 0) return fail(c, SPECDEC_ERR_INVALID_ARG, "L_max = %d", L_max);
+  if (L_max > c->lim.max_tgt + 1) return fail(c, SPECDEC_ERR_TOO_LARGE, "L_max = %d exceeds max_tgt + 1", L_max);
+  Model& m = c->m[role];
+  const int H = m.d.n_heads;
+  const size_t flat_layer = (size_t)c->B * L_max * m.d.d_model;
+  for (int l = 0; l < m.d.dec_layers; ++l) {
+    HIPCHK(c, sd::cache_from_flat(S(stream), m.kc + m.kv_layer * l, static_cast<const bf16*>(k_cache) + flat_layer * l, c->B, H, c->Lcap, L_max));
+    HIPCHK(c, sd::cache_from_flat(S(stream), m.vc + m.kv_layer * l, static_cast<const bf16*>(v_cache) + flat_layer * l, c->B, H, c->Lcap, L_max));
+  }
+  HIPCHK(c, sd::set_cached(S(stream), c->st, role, n, c->B, L_max));
+  c->trusted[role] = true;
+  return SPECDEC_OK;
+}
+
+int specdec_prefill(specdec_ctx* c, specdec_role role, void* stream) {
+  (void)stream;
+  int rc = check_ready(c, role, true);
+  if (rc) return rc;
+  return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_prefill: not available in this build");
+}
+
+int specdec_draft(specdec_ctx* c, int32_t k, int32_t* draft, void* stream) {
+  (void)k; (void)draft; (void)stream;
+  int rc = check_ready(c, SPECDEC_DRAFTER, true);
+  if (rc) return rc;
+  return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_draft: not available in this build");
+}
+
+int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, float tau, int32_t* accept_len,
+                   int32_t* next_token, float* logits, void* stream) {
+  int rc = check_ready(c, SPECDEC_VERIFIER, true);
+  if (rc) return rc;
+  if (!draft || !accept_len || !next_token) return fail(c, SPECDEC_ERR_INVALID_ARG, "null draft/accept_len/next_token");
+  if (k < 1) return fail(c, SPECDEC_ERR_INVALID_ARG, "k = %d", k);
+  if (k > c->lim.k_max) return fail(c, SPECDEC_ERR_TOO_LARGE, "k = %d exceeds k_max = %d", k, c->lim.k_max);
+  Model& m = c->m[SPECDEC_VERIFIER];
+  if (beta < 1 || beta > SPECDEC_BETA_MAX || beta > m.d.vocab) return fail(c, SPECDEC_ERR_INVALID_ARG, "beta = %d outside [1, %d]", beta, SPECDEC_BETA_MAX);
+  if (!(tau >= 0.f) || !std::isfinite(tau)) return fail(c, SPECDEC_ERR_INVALID_ARG, "tau must be finite and >= 0");
+  if (c->uncached_ub[0] > 0 && !c->trusted[0]) return fail(c, SPECDEC_ERR_BAD_STATE, "verifier cache does not cover the stream: call specdec_prefill or specdec_load_cache");
+  hipStream_t st = S(stream);
+  const int B = c->B, T = k + 1, R = B * T;
+  HIPCHK(c, sd::assemble_verify(st, c->st, m.rm, draft, B, k, m.d.vocab));
+  rc = decoder_layers(c, m, B, T, st);
+  if (rc) return rc;
+  const int n_tiles = (m.d.vocab + 127) / 128;
+  HIPCHK(c, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.part, logits));
+  HIPCHK(c, sd::accept_rows(st, m.part, n_tiles, m.rm, c->st, B, k, beta, tau, m.d.pad_id, m.row_stats, accept_len, next_token));
+  c->last_k = k;
+  return SPECDEC_OK;
+}
+
+int specdec_commit(specdec_ctx* c, const int32_t* accept_len, const int32_t* next_token, int32_t* n_active, void* stream) {
+  int rc = check_ready(c, SPECDEC_VERIFIER, false);
+  if (rc) return rc;
+  if (!accept_len || !next_token) return fail(c, SPECDEC_ERR_INVALID_ARG, "null accept_len/next_token");
+  if (c->last_k <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_commit without a preceding specdec_verify");
+  HIPCHK(c, sd::commit_rows(S(stream), c->st, accept_len, next_token, c->B, c->m[0].d.eos_id, n_active));
+  c->last_k = 0;
+  c->uncached_ub[1] += c->lim.k_max + 1;
+  return SPECDEC_OK;
+}
+
+int specdec_get_output(specdec_ctx* c, int32_t* tokens, int32_t out_cap, int32_t* out_len, int32_t* finished, void* stream) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (!c->state_bound || c->B <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "nothing to read: begin not called");
+  if (!tokens || !out_len || out_cap < 1) return fail(c, SPECDEC_ERR_INVALID_ARG, "null output or out_cap < 1");
+  const Model& any = c->m[0].bound ? c->m[0] : c->m[1];
+  HIPCHK(c, sd::get_output(S(stream), c->st, tokens, out_cap, out_len, finished, c->B, any.d.pad_id));
+  return SPECDEC_OK;
+}
+
+int specdec_get_cache(specdec_ctx* c, specdec_role role, void* k_cache, void* v_cache, int32_t L, void* stream) {
+  int rc = check_ready(c, role, false);
+  if (rc) return rc;
+  if (!k_cache || !v_cache) return fail(c, SPECDEC_ERR_INVALID_ARG, "null cache");
+  if (L < 1 || L > c->Lcap) return fail(c, SPECDEC_ERR_INVALID_ARG, "L = %d outside [1, %d]", L, c->Lcap);
+  Model& m = c->m[role];
+  const size_t flat_layer = (size_t)c->B * L * m.d.d_model;
+  for (int l = 0; l < m.d.dec_layers; ++l) {
+    HIPCHK(c, sd::cache_to_flat(S(stream), m.kc + m.kv_layer * l, static_cast<bf16*>(k_cache) + flat_layer * l, c->B, m.d.n_heads, c->Lcap, L));
+    HIPCHK(c, sd::cache_to_flat(S(stream), m.vc + m.kv_layer * l, static_cast<bf16*>(v_cache) + flat_layer * l, c->B, m.d.n_heads, c->Lcap, L));
+  }
+  return SPECDEC_OK;
+}
+
+int specdec_get_row_stats(specdec_ctx* c, float* stats, void* stream) {
+  int rc = check_ready(c, SPECDEC_VERIFIER, false);
+  if (rc) return rc;
+  if (!stats) return fail(c, SPECDEC_ERR_INVALID_ARG, "null stats");
+  if (c->last_k <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "no verification pass to report");
+  const size_t n = (size_t)c->B * (c->last_k + 1) * (4 + SPECDEC_BETA_MAX);
+  HIPCHK(c, hipMemcpyAsync(stats, c->m[0].row_stats, n * sizeof(float), hipMemcpyDeviceToDevice, S(stream)));
+  return SPECDEC_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,109 @@
+// Host-side launchers of the gfx950 kernels.  Plain pointers and sizes; every function
+// enqueues on `st` and returns the launch status.  Shapes are validated by the callers in
+// api.hip before anything is launched.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace sd {
+
+typedef __bf16 bf16;
+
+// Row bookkeeping of one decoder pass.  Row r belongs to sequence row_b[r] (-1 = padding
+// row: computed but never stored into a cache), sits at stream position row_pos[r], feeds
+// token row_tok[r], may attend to self-attention keys [0, row_lim[r]) and scores draft token
+// row_draft[r] (-1 = none).  Rows of sequence b are b*T .. b*T + seq_rows[b] - 1.
+struct RowMap {
+  int* row_b;
+  int* row_pos;
+  int* row_tok;
+  int* row_lim;
+  int* row_draft;
+  int* seq_rows;
+};
+
+// ---- gemm.hip: C = A W^T (+bias) with different epilogues; A [M,K] bf16, W [N,K] bf16 ----
+// out fp32 [M,ldo] = A W^T + bias + resid (resid may alias out, may be null)
+hipError_t gemm_f32(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
+                    const bf16* bias, const float* resid, float* out, int ldo);
+// out bf16 [M,ldo] = act(A W^T + bias)
+hipError_t gemm_bf16(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
+                     const bf16* bias, bf16* out, int ldo, bool relu);
+// Self-attention projection of decoder rows, N = 3d: q -> q_out [M,d]; k, v of row r ->
+// caches [B][H][Lcap][64] at sequence row_b[r], position row_pos[r] (the KV append).
+hipError_t gemm_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
+                           const bf16* bias, bf16* q_out, bf16* kc, bf16* vc, const int* row_b,
+                           const int* row_pos, int H, int Lcap);
+// Cross-attention keys/values of the encoder memory, N = 2d: memory rows m = b*S + s ->
+// xk, xv [B][H][Scap][64].
+hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
+                         const bf16* bias, bf16* xk, bf16* xv, int S, int H, int Scap);
+
+// Vocabulary projection fused with per-row statistics.  For every row and every 128-column
+// vocabulary tile one partial record of kPartF floats is written to part[M][n_tiles][kPartF]:
+// {tile max, tile arg-max (int bits), sum exp(z - tile max), logit of column row_draft[m] if
+// it lies in the tile else -inf, the kTopN largest logits of the tile, descending}.
+// logits (optional, fp32 [M, V]) receives the full rows.
+constexpr int kPartF = 12;
+hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int V, int K,
+                       const int* row_draft, float* part, float* logits);
+
+// ---- attn.hip ------------------------------------------------------------------------
+struct AttnArgs {
+  const bf16* q;  long q_b, q_row;            // q + b*q_b + i*q_row + h*64
+  const bf16* k;  const bf16* v;
+  long kv_b, kv_h, kv_row;                     // k + b*kv_b + h*kv_h + key*kv_row
+  bf16* o;        long o_b, o_row;             // o + b*o_b + i*o_row + h*64
+  const int* q_count;                          // [B] queries of sequence b (null: T)
+  const int* lim_row;                          // [B*T] visible keys per query (null: lim_seq)
+  const int* lim_seq;                          // [B]  visible keys of every query of b
+  int T;                                       // max queries per sequence
+  int H, B;
+};
+hipError_t attention(hipStream_t st, const AttnArgs& a);
+
+// ---- misc.hip ------------------------------------------------------------------------
+hipError_t build_pos_table(hipStream_t st, float* pe, int n_pos, int d);
+hipError_t embed_rows(hipStream_t st, const int* tok, const int* pos, const bf16* E,
+                      const float* pe, float* x, bf16* xb, int R, int d);
+// x <- LayerNorm(x) * g + b in place (fp32), xb <- bf16(x)
+hipError_t layer_norm(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R,
+                      int d);
+hipError_t fill_i32(hipStream_t st, int* p, int v, long n);
+
+struct SeqState {       // device arrays of the bound state buffer, all [max_batch] unless noted
+  int* tokens;          // [max_batch][tok_pitch] stream u_0..u_j
+  int* len;             // j
+  int* start;           // j when decoding started (tokens after it are output)
+  int* cap;             // j may not exceed this (start + max_new, <= max_tgt)
+  int* finished;
+  int* cached[2];       // per role: stream positions whose K/V are cached
+  int* src_len;
+  int* last_draft;      // [max_batch][k_max]
+  int* scratch;         // [8] counters
+  int tok_pitch, k_max;
+};
+// rows of a verification pass: [u_j, drafts]; also stores the drafts for commit
+hipError_t assemble_verify(hipStream_t st, const SeqState& s, const RowMap& rm, const int* draft,
+                           int B, int k, int V);
+// merge vocabulary partials, apply the top-beta/tau rule, leading-accept scan
+hipError_t accept_rows(hipStream_t st, const float* part, int n_tiles, const RowMap& rm,
+                       const SeqState& s, int B, int k, int beta, float tau, int pad_id,
+                       float* row_stats, int* accept_len, int* next_token);
+hipError_t commit_rows(hipStream_t st, const SeqState& s, const int* accept_len,
+                       const int* next_token, int B, int eos_id, int* n_active);
+hipError_t begin_state(hipStream_t st, const SeqState& s, int B, int max_new, int max_tgt,
+                       int bos_id);
+hipError_t set_stream(hipStream_t st, const SeqState& s, const int* tokens, const int* len, int B,
+                      int L_max, int max_new, int max_tgt);
+hipError_t set_src_len(hipStream_t st, const SeqState& s, const int* src_len, int B, int S_max);
+hipError_t set_cached(hipStream_t st, const SeqState& s, int role, const int* n, int B, int hi);
+hipError_t get_output(hipStream_t st, const SeqState& s, int* tokens, int out_cap, int* out_len,
+                      int* finished, int B, int pad_id);
+// cache [B][H][Lcap][64]  <->  flat [B][L][d]
+hipError_t cache_from_flat(hipStream_t st, bf16* cache, const bf16* flat, int B, int H, int Lcap,
+                           int L);
+hipError_t cache_to_flat(hipStream_t st, const bf16* cache, bf16* flat, int B, int H, int Lcap,
+                         int L);
+
+}  // namespace sd

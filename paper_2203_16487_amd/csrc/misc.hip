@@ -1,0 +1,352 @@
+// Small kernels around the GEMMs: embedding, LayerNorm, row assembly, the acceptance test
+// (paper Sec. 3.2, Eq. 8-10), commit (Sec. 2, Eq. 3) and state / cache marshalling.
+#include "common.h"
+#include "kernels.h"
+
+namespace sd {
+
+static inline dim3 blocks_for(long n, int t) { return dim3((unsigned)((n + t - 1) / t)); }
+
+// ----------------------------------------------------------------------------- positions
+// PE(p, 2i) = sin(p / 10000^(2i/d)), PE(p, 2i+1) = cos(same), evaluated in fp64.
+__global__ void pos_table_kernel(float* pe, int n_pos, int d) {
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long)n_pos * d) return;
+  int p = (int)(idx / d), c = (int)(idx % d);
+  int i = c >> 1;
+  double ang = (double)p / pow(10000.0, 2.0 * (double)i / (double)d);
+  pe[idx] = (float)((c & 1) ? cos(ang) : sin(ang));
+}
+hipError_t build_pos_table(hipStream_t st, float* pe, int n_pos, int d) {
+  long n = (long)n_pos * d;
+  hipLaunchKernelGGL(pos_table_kernel, blocks_for(n, 256), dim3(256), 0, st, pe, n_pos, d);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------- embedding
+// x[r] = E[tok[r]] * sqrt(d) + PE[pos[r]]  (fp32) and its bf16 copy
+__global__ void embed_kernel(const int* __restrict__ tok, const int* __restrict__ pos,
+                             const bf16* __restrict__ E, const float* __restrict__ pe,
+                             float* __restrict__ x, bf16* __restrict__ xb, int R, int d, float scale) {
+  int r = blockIdx.x;
+  if (r >= R) return;
+  const bf16* e = E + (size_t)tok[r] * d;
+  const float* p = pe + (size_t)pos[r] * d;
+  for (int c = threadIdx.x; c < d; c += blockDim.x) {
+    float v = (float)e[c] * scale + p[c];
+    x[(size_t)r * d + c] = v;
+    xb[(size_t)r * d + c] = (bf16)v;
+  }
+}
+hipError_t embed_rows(hipStream_t st, const int* tok, const int* pos, const bf16* E,
+                      const float* pe, float* x, bf16* xb, int R, int d) {
+  if (R <= 0) return hipSuccess;
+  hipLaunchKernelGGL(embed_kernel, dim3(R), dim3(128), 0, st, tok, pos, E, pe, x, xb, R, d,
+                     sqrtf((float)d));
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------- LayerNorm
+// One wave per row; mean and biased variance as two reductions over registers; eps 1e-5.
+constexpr int kLnMaxPerLane = 32;  // d <= 2048
+__global__ __launch_bounds__(256) void ln_kernel(float* __restrict__ x, const bf16* __restrict__ g,
+                                                 const bf16* __restrict__ bta, bf16* __restrict__ xb,
+                                                 int R, int d) {
+  const int lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= R) return;
+  float* xr = x + (size_t)r * d;
+  float v[kLnMaxPerLane];
+  const int per = d >> 6;  // d is a multiple of 64
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < kLnMaxPerLane; ++i)
+    if (i < per) { v[i] = xr[i * 64 + lane]; s += v[i]; }
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < kLnMaxPerLane; ++i)
+    if (i < per) { float t = v[i] - mean; q += t * t; }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+#pragma unroll
+  for (int i = 0; i < kLnMaxPerLane; ++i)
+    if (i < per) {
+      int c = i * 64 + lane;
+      float y = (v[i] - mean) * rstd * (float)g[c] + (float)bta[c];
+      xr[c] = y;
+      xb[(size_t)r * d + c] = (bf16)y;
+    }
+}
+hipError_t layer_norm(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R, int d) {
+  if (R <= 0) return hipSuccess;
+  hipLaunchKernelGGL(ln_kernel, dim3((R + 3) / 4), dim3(256), 0, st, x, g, b, xb, R, d);
+  return hipGetLastError();
+}
+
+__global__ void fill_i32_kernel(int* p, int v, long n) {
+  long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+hipError_t fill_i32(hipStream_t st, int* p, int v, long n) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_i32_kernel, blocks_for(n, 256), dim3(256), 0, st, p, v, n);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------- verify rows
+// Row i of sequence b: token u_j (i = 0) or draft i (i >= 1) at position j + i; it may look
+// at keys [0, j + i + 1) and it scores draft i + 1 (none on the last row).
+__global__ void assemble_verify_kernel(SeqState s, RowMap rm, const int* __restrict__ draft, int B, int k, int V) {
+  int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  int T = k + 1;
+  if (idx >= B * T) return;
+  int b = idx / T, i = idx - b * T;
+  int j = s.len[b];
+  int tok = (i == 0) ? s.tokens[(size_t)b * s.tok_pitch + j] : draft[b * k + i - 1];
+  rm.row_b[idx] = b;
+  rm.row_pos[idx] = j + i;
+  rm.row_tok[idx] = min(max(tok, 0), V - 1);   // ids index the embedding table
+  rm.row_lim[idx] = j + i + 1;
+  rm.row_draft[idx] = (i < k) ? draft[b * k + i] : -1;
+  if (i < k) s.last_draft[b * s.k_max + i] = draft[b * k + i];
+  if (i == 0) rm.seq_rows[b] = T;
+}
+hipError_t assemble_verify(hipStream_t st, const SeqState& s, const RowMap& rm, const int* draft, int B, int k, int V) {
+  hipLaunchKernelGGL(assemble_verify_kernel, blocks_for((long)B * (k + 1), 128), dim3(128), 0, st, s, rm, draft, B, k, V);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------- acceptance
+// One wave per sequence.  For each row the per-tile partials are merged:
+//   m = max logit, arg-max = lowest column among maxima, LSE, z_d = logit of the scored
+//   draft, s_1 >= s_2 >= ... the kTopN largest logits (with multiplicity).
+// Eq. 8:  log P(draft) >= log P(beta-th ranked)   <=>  z_d >= s_beta
+// Eq. 9:  log P(top-1) - log P(draft) <= tau      <=>  m - z_d <= tau
+// (log-softmax subtracts the same LSE from every logit of the row).  a = number of leading
+// rows that pass; next = arg-max of row a.
+__global__ __launch_bounds__(64) void accept_kernel(const float* __restrict__ part, int n_tiles, RowMap rm,
+                                                    SeqState s, int B, int k, int beta, float tau, int pad_id,
+                                                    float* __restrict__ row_stats, int* __restrict__ accept_len,
+                                                    int* __restrict__ next_token) {
+  const int b = blockIdx.x, lane = threadIdx.x;
+  const int T = k + 1;
+  int a = 0;
+  bool open = true;          // still in the leading run of accepted drafts
+  int next = pad_id;
+  for (int i = 0; i < T; ++i) {
+    const int r = b * T + i;
+    const float* pr = part + (size_t)r * n_tiles * kPartF;
+    float m = kNegInf, zd = kNegInf;
+    int am = 0x7fffffff;
+    float top[kTopN];
+#pragma unroll
+    for (int t = 0; t < kTopN; ++t) top[t] = kNegInf;
+    for (int t = lane; t < n_tiles; t += 64) {
+      const float* p = pr + (size_t)t * kPartF;
+      float tm = p[0];
+      int ti = __float_as_int(p[1]);
+      if (tm > m || (tm == m && ti < am)) { m = tm; am = ti; }
+      zd = fmaxf(zd, p[3]);
+#pragma unroll
+      for (int q = 0; q < kTopN; ++q) top_insert<kTopN>(top, p[4 + q]);
+    }
+    // wave merge of max / arg-max / draft logit
+    float gm = wave_max(m);
+    int cand = (m == gm) ? am : 0x7fffffff;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cand = min(cand, __shfl_xor(cand, o, 64));
+    zd = wave_max(zd);
+    // log-sum-exp relative to the global max
+    float se = 0.f;
+    for (int t = lane; t < n_tiles; t += 64) {
+      const float* p = pr + (size_t)t * kPartF;
+      se += p[2] * __expf(p[0] - gm);
+    }
+    se = wave_sum(se);
+    const float lse = gm + __logf(se);
+    // global top list: kTopN rounds of "largest head over the lanes, pop it there"
+    float gtop[kTopN];
+    int head = 0;
+#pragma unroll
+    for (int q = 0; q < kTopN; ++q) {
+      float mine = kNegInf;
+#pragma unroll
+      for (int t = 0; t < kTopN; ++t) if (t == head) mine = top[t];
+      float best = wave_max(mine);
+      gtop[q] = best;
+      // the lowest lane holding the best pops
+      unsigned long long mask = __ballot(mine == best && best > kNegInf);
+      if (mask != 0ull && lane == (int)__builtin_ctzll(mask)) ++head;
+    }
+    if (lane == 0) {
+      float* rs = row_stats + (size_t)r * (4 + kTopN);
+      rs[0] = gm; rs[1] = (float)cand; rs[2] = lse; rs[3] = zd;
+#pragma unroll
+      for (int q = 0; q < kTopN; ++q) rs[4 + q] = gtop[q];
+    }
+    float sbeta = kNegInf;
+#pragma unroll
+    for (int q = 0; q < kTopN; ++q) if (q == beta - 1) sbeta = gtop[q];
+    if (open) {
+      next = cand;           // arg-max of the first row not (yet) passed
+      bool ok = (i < k) && (zd >= sbeta) && (gm - zd <= tau);
+      if (ok) ++a; else open = false;
+    }
+  }
+  if (lane == 0) {
+    bool fin = s.finished[b] != 0;
+    accept_len[b] = fin ? 0 : a;
+    next_token[b] = fin ? pad_id : next;
+  }
+}
+hipError_t accept_rows(hipStream_t st, const float* part, int n_tiles, const RowMap& rm, const SeqState& s,
+                       int B, int k, int beta, float tau, int pad_id, float* row_stats, int* accept_len,
+                       int* next_token) {
+  hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(64), 0, st, part, n_tiles, rm, s, B, k, beta, tau, pad_id,
+                     row_stats, accept_len, next_token);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------- commit
+// Eq. 3: the iteration's output is the accepted drafts followed by the verifier's token; a
+// sequence stops after its first EOS or when it reaches its cap.  j advances by the number
+// of tokens appended: exactly that many of this pass's cache rows become valid.
+__global__ void commit_kernel(SeqState s, const int* __restrict__ accept_len, const int* __restrict__ next_token,
+                              int B, int eos_id, int* n_active) {
+  __shared__ int active;
+  if (threadIdx.x == 0) active = 0;
+  __syncthreads();
+  int mine = 0;
+  for (int b = threadIdx.x; b < B; b += blockDim.x) {
+    if (!s.finished[b]) {
+      int a = accept_len[b];
+      a = max(0, min(a, s.k_max));
+      int j = s.len[b];
+      const int cap = s.cap[b];
+      int* u = s.tokens + (size_t)b * s.tok_pitch;
+      int fin = 0;
+      for (int i = 0; i <= a && !fin; ++i) {
+        if (j >= cap) { fin = 1; break; }
+        int t = (i < a) ? s.last_draft[b * s.k_max + i] : next_token[b];
+        u[++j] = t;
+        if (t == eos_id || j >= cap) fin = 1;
+      }
+      s.len[b] = j;
+      s.cached[0][b] = j;   // the verifier's rows of the kept tokens are now valid cache
+      s.finished[b] = fin;
+      if (!fin) ++mine;
+    }
+  }
+  if (mine) atomicAdd(&active, mine);
+  __syncthreads();
+  if (threadIdx.x == 0 && n_active) *n_active = active;
+}
+hipError_t commit_rows(hipStream_t st, const SeqState& s, const int* accept_len, const int* next_token, int B,
+                       int eos_id, int* n_active) {
+  hipLaunchKernelGGL(commit_kernel, dim3(1), dim3(256), 0, st, s, accept_len, next_token, B, eos_id, n_active);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------- state
+__global__ void begin_kernel(SeqState s, int B, int max_new, int max_tgt, int bos_id) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  s.tokens[(size_t)b * s.tok_pitch] = bos_id;
+  s.len[b] = 0;
+  s.start[b] = 0;
+  s.cap[b] = min(max_new, max_tgt);
+  s.finished[b] = (max_new <= 0);
+  s.cached[0][b] = 0;
+  s.cached[1][b] = 0;
+}
+hipError_t begin_state(hipStream_t st, const SeqState& s, int B, int max_new, int max_tgt, int bos_id) {
+  hipLaunchKernelGGL(begin_kernel, blocks_for(B, 128), dim3(128), 0, st, s, B, max_new, max_tgt, bos_id);
+  return hipGetLastError();
+}
+
+__global__ void set_stream_kernel(SeqState s, const int* __restrict__ tokens, const int* __restrict__ len, int B,
+                                  int L_max, int max_new, int max_tgt) {
+  int b = blockIdx.x;
+  if (b >= B) return;
+  int j = min(max(len[b], 0), L_max);
+  for (int i = threadIdx.x; i <= j; i += blockDim.x)
+    s.tokens[(size_t)b * s.tok_pitch + i] = tokens[(size_t)b * (L_max + 1) + i];
+  if (threadIdx.x == 0) {
+    s.len[b] = j;
+    s.start[b] = j;
+    s.cap[b] = min(j + max_new, max_tgt);
+    s.finished[b] = (j >= min(j + max_new, max_tgt));
+    s.cached[0][b] = 0;
+    s.cached[1][b] = 0;
+  }
+}
+hipError_t set_stream(hipStream_t st, const SeqState& s, const int* tokens, const int* len, int B, int L_max,
+                      int max_new, int max_tgt) {
+  hipLaunchKernelGGL(set_stream_kernel, dim3(B), dim3(64), 0, st, s, tokens, len, B, L_max, max_new, max_tgt);
+  return hipGetLastError();
+}
+
+__global__ void copy_i32_kernel(int* dst, const int* src, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = src[i];
+}
+__global__ void clamp_copy_i32_kernel(int* dst, const int* src, int n, int lo, int hi) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) dst[i] = min(max(src[i], lo), hi);
+}
+hipError_t set_src_len(hipStream_t st, const SeqState& s, const int* src_len, int B, int S_max) {
+  hipLaunchKernelGGL(clamp_copy_i32_kernel, blocks_for(B, 128), dim3(128), 0, st, s.src_len, src_len, B, 1, S_max);
+  return hipGetLastError();
+}
+hipError_t set_cached(hipStream_t st, const SeqState& s, int role, const int* n, int B, int hi) {
+  hipLaunchKernelGGL(clamp_copy_i32_kernel, blocks_for(B, 128), dim3(128), 0, st, s.cached[role], n, B, 0, hi);
+  return hipGetLastError();
+}
+
+__global__ void get_output_kernel(SeqState s, int* __restrict__ tokens, int out_cap, int* __restrict__ out_len,
+                                  int* __restrict__ finished, int B, int pad_id) {
+  int b = blockIdx.x;
+  if (b >= B) return;
+  int st0 = s.start[b], n = s.len[b] - st0;
+  for (int i = threadIdx.x; i < out_cap; i += blockDim.x)
+    tokens[(size_t)b * out_cap + i] = (i < n) ? s.tokens[(size_t)b * s.tok_pitch + st0 + 1 + i] : pad_id;
+  if (threadIdx.x == 0) {
+    out_len[b] = n;
+    if (finished) finished[b] = s.finished[b];
+  }
+}
+hipError_t get_output(hipStream_t st, const SeqState& s, int* tokens, int out_cap, int* out_len, int* finished,
+                      int B, int pad_id) {
+  hipLaunchKernelGGL(get_output_kernel, dim3(B), dim3(64), 0, st, s, tokens, out_cap, out_len, finished, B, pad_id);
+  return hipGetLastError();
+}
+
+// ----------------------------------------------------------------------------- cache layout
+// flat [B][L][H*64]  <->  cache [B][H][Lcap][64]; one 16-byte chunk per thread
+__global__ void cache_flat_kernel(bf16* cache, bf16* flat, int B, int H, int Lcap, int L, int to_flat) {
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  long n = (long)B * L * H * 8;
+  if (idx >= n) return;
+  int ch = (int)(idx & 7);
+  long t = idx >> 3;
+  int h = (int)(t % H); t /= H;
+  int l = (int)(t % L);
+  int b = (int)(t / L);
+  uint4* c = reinterpret_cast<uint4*>(cache + (((size_t)b * H + h) * Lcap + l) * kHeadDim + ch * 8);
+  uint4* f = reinterpret_cast<uint4*>(flat + (((size_t)b * L + l) * H + h) * kHeadDim + ch * 8);
+  if (to_flat) *f = *c; else *c = *f;
+}
+hipError_t cache_from_flat(hipStream_t st, bf16* cache, const bf16* flat, int B, int H, int Lcap, int L) {
+  long n = (long)B * L * H * 8;
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(cache_flat_kernel, blocks_for(n, 256), dim3(256), 0, st, cache, const_cast<bf16*>(flat), B, H, Lcap, L, 0);
+  return hipGetLastError();
+}
+hipError_t cache_to_flat(hipStream_t st, const bf16* cache, bf16* flat, int B, int H, int Lcap, int L) {
+  long n = (long)B * L * H * 8;
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(cache_flat_kernel, blocks_for(n, 256), dim3(256), 0, st, const_cast<bf16*>(cache), flat, B, H, Lcap, L, 1);
+  return hipGetLastError();
+}
+
+}  // namespace sd
