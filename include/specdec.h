@@ -153,6 +153,11 @@ int specdec_verify(specdec_ctx* ctx, const int32_t* draft, int32_t k, int32_t be
 int specdec_commit(specdec_ctx* ctx, const int32_t* accept_len, const int32_t* next_token,
                    int32_t* n_active_or_null, void* stream);
 
+/* Roll sequences back: j_b <- min(j_b, len[b]) (len device int32 [B]); cached lengths are cut
+ * to match and a sequence whose j drops below its cap is unfinished again.  Like the
+ * rollback inside commit this moves no data: rows beyond j are simply dead. */
+int specdec_rewind(specdec_ctx* ctx, const int32_t* len, void* stream);
+
 /* ---- read back ----------------------------------------------------------------------- */
 /* tokens device int32 [B, out_cap]: tokens committed since begin / set_stream (right-padded
  * with pad_id); out_len device int32 [B]; finished_or_null device int32 [B]. */
@@ -167,6 +172,26 @@ int specdec_get_cache(specdec_ctx* ctx, specdec_role role, void* k_cache, void* 
  * {max logit, arg-max (as float), log-sum-exp, logit of the draft scored on this row (or
  * -inf on the last row), the SPECDEC_BETA_MAX largest logits in descending order}. */
 int specdec_get_row_stats(specdec_ctx* ctx, float* stats, void* stream);
+
+/* ---- timing of one kernel kind ----------------------------------------------------------- */
+/* While a kind is selected every launch of that kernel is bracketed by a pair of HIP events
+ * on the launch stream (up to 4096 launches between two reads; later ones are not recorded).
+ * specdec_profile_read waits for the recorded events (it synchronises on them), returns their
+ * summed duration in milliseconds and their number, and clears the record. */
+typedef enum {
+  SPECDEC_KIND_NONE = -1,
+  SPECDEC_KIND_GEMM_F32 = 0,   /* projections with fp32 output + residual (O, cross-O, FFN2) */
+  SPECDEC_KIND_GEMM_BF16 = 1,  /* projections with bf16 output (cross-Q, FFN1)               */
+  SPECDEC_KIND_GEMM_QKV = 2,   /* self-attention projection with KV append                  */
+  SPECDEC_KIND_ATTN = 3,       /* self- and cross-attention                                 */
+  SPECDEC_KIND_VOCAB = 4,      /* fused vocabulary projection + row statistics              */
+  SPECDEC_KIND_LN = 5,
+  SPECDEC_KIND_ACCEPT = 6,
+  SPECDEC_KIND_OTHER = 7,
+  SPECDEC_KIND_COUNT = 8
+} specdec_kernel_kind;
+int specdec_profile_select(specdec_ctx* ctx, int32_t kind);
+int specdec_profile_read(specdec_ctx* ctx, double* total_ms /*host*/, int32_t* launches /*host*/);
 
 #ifdef __cplusplus
 }

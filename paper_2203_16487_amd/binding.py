@@ -58,6 +58,9 @@ EXPORTS = {
     "specdec_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p]),
     "specdec_commit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "specdec_rewind": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "specdec_profile_select": (C.c_int, [C.c_void_p, C.c_int32]),
+    "specdec_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int32)]),
     "specdec_get_output": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "specdec_get_cache": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "specdec_get_row_stats": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -73,6 +76,10 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2203_16487_amd.build` "
                                "(there is no fallback path)")
+        # PyTorch owns the device memory this binding hands over, so both must talk to ONE HIP
+        # runtime: importing torch first makes its libamdhip64 the one libspecdec binds to
+        # (two runtimes in one process do not see the GPU).
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         for name, (res, args) in EXPORTS.items():
             f = getattr(L, name)
@@ -194,6 +201,23 @@ def specdec_verify(ctx, draft, k: int, beta: int, tau: float, accept_len, next_t
 
 def specdec_commit(ctx, accept_len, next_token, n_active=None):
     _check(ctx, lib().specdec_commit(ctx, _ptr(accept_len), _ptr(next_token), _ptr(n_active), _stream()))
+
+
+def specdec_rewind(ctx, length):
+    _check(ctx, lib().specdec_rewind(ctx, _ptr(length), _stream()))
+
+
+KIND = dict(none=-1, gemm_f32=0, gemm_bf16=1, gemm_qkv=2, attn=3, vocab=4, ln=5, accept=6, other=7)
+
+
+def specdec_profile_select(ctx, kind: int):
+    _check(ctx, lib().specdec_profile_select(ctx, kind))
+
+
+def specdec_profile_read(ctx):
+    ms, n = C.c_double(), C.c_int32()
+    _check(ctx, lib().specdec_profile_read(ctx, C.byref(ms), C.byref(n)))
+    return ms.value, n.value
 
 
 def specdec_get_output(ctx, tokens, out_len, finished=None):

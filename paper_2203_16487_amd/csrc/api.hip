@@ -65,6 +65,10 @@ struct specdec_ctx {
   int S_cur = 0;      // S_max of the current memory
   int uncached_ub[2] = {0, 0};
   bool trusted[2] = {false, false};
+  // event timing of one kernel kind
+  int prof_kind = SPECDEC_KIND_NONE;
+  std::vector<hipEvent_t> prof_ev;
+  int prof_used = 0;
   char err[512] = {0};
 };
 
@@ -84,6 +88,23 @@ int fail(const specdec_ctx* c, int code, const char* fmt, ...) {
     hipError_t e_ = (expr);                                                               \
     if (e_ != hipSuccess)                                                                 \
       return fail(c, SPECDEC_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));     \
+  } while (0)
+
+constexpr int kProfPairs = 4096;
+inline bool prof_begin(specdec_ctx* c, int kind, hipStream_t st) {
+  if (c->prof_kind != kind || c->prof_used + 2 > (int)c->prof_ev.size()) return false;
+  return hipEventRecord(c->prof_ev[c->prof_used], st) == hipSuccess;
+}
+inline void prof_end(specdec_ctx* c, hipStream_t st) {
+  (void)hipEventRecord(c->prof_ev[c->prof_used + 1], st);
+  c->prof_used += 2;
+}
+// launch `expr` (a kernels.h launcher on stream st) as kernel kind `kind`
+#define LAUNCH(c, kind, st, expr)            \
+  do {                                       \
+    bool p_ = prof_begin(c, kind, st);       \
+    HIPCHK(c, expr);                         \
+    if (p_) prof_end(c, st);                 \
   } while (0)
 
 bool desc_ok(const specdec_model_desc* d) {
@@ -207,12 +228,12 @@ inline hipStream_t S(void* s) { return static_cast<hipStream_t>(s); }
 int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
   const int R = B * T, D = m.d.d_model, F = m.d.d_ffn, H = m.d.n_heads;
   const int Lcap = c->Lcap, Scap = c->lim.max_src;
-  HIPCHK(c, sd::embed_rows(st, m.rm.row_tok, m.rm.row_pos, m.embed, m.pe, m.x, m.xb, R, D));
+  LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::embed_rows(st, m.rm.row_tok, m.rm.row_pos, m.embed, m.pe, m.x, m.xb, R, D));
   for (int l = 0; l < m.d.dec_layers; ++l) {
     const DecLayer& L = m.dec[l];
     bf16* kc = m.kc + m.kv_layer * l;
     bf16* vc = m.vc + m.kv_layer * l;
-    HIPCHK(c, sd::gemm_qkv_append(st, m.xb, L.wqkv, R, D, D, L.bqkv, m.q, kc, vc, m.rm.row_b,
+    LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::gemm_qkv_append(st, m.xb, L.wqkv, R, D, D, L.bqkv, m.q, kc, vc, m.rm.row_b,
                                   m.rm.row_pos, H, Lcap));
     sd::AttnArgs a{};
     a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
@@ -220,19 +241,19 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
     a.o = m.att; a.o_b = (long)T * D; a.o_row = D;
     a.q_count = m.rm.seq_rows; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
     a.T = T; a.H = H; a.B = B;
-    HIPCHK(c, sd::attention(st, a));
-    HIPCHK(c, sd::gemm_f32(st, m.att, D, L.wo, R, D, D, L.bo, m.x, m.x, D));
-    HIPCHK(c, sd::layer_norm(st, m.x, L.ln1g, L.ln1b, m.xb, R, D));
-    HIPCHK(c, sd::gemm_bf16(st, m.xb, D, L.cwq, R, D, D, L.cbq, m.q, D, false));
+    LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.wo, R, D, D, L.bo, m.x, m.x, D));
+    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln1g, L.ln1b, m.xb, R, D));
+    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.xb, D, L.cwq, R, D, D, L.cbq, m.q, D, false));
     a.k = m.xk + m.xkv_layer * l; a.v = m.xv + m.xkv_layer * l;
     a.kv_b = (long)H * Scap * 64; a.kv_h = (long)Scap * 64;
     a.lim_row = nullptr; a.lim_seq = c->st.src_len;
-    HIPCHK(c, sd::attention(st, a));
-    HIPCHK(c, sd::gemm_f32(st, m.att, D, L.cwo, R, D, D, L.cbo, m.x, m.x, D));
-    HIPCHK(c, sd::layer_norm(st, m.x, L.ln2g, L.ln2b, m.xb, R, D));
-    HIPCHK(c, sd::gemm_bf16(st, m.xb, D, L.w1, R, F, D, L.b1, m.hid, F, true));
-    HIPCHK(c, sd::gemm_f32(st, m.hid, F, L.w2, R, D, F, L.b2, m.x, m.x, D));
-    HIPCHK(c, sd::layer_norm(st, m.x, L.ln3g, L.ln3b, m.xb, R, D));
+    LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.cwo, R, D, D, L.cbo, m.x, m.x, D));
+    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln2g, L.ln2b, m.xb, R, D));
+    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.xb, D, L.w1, R, F, D, L.b1, m.hid, F, true));
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.hid, F, L.w2, R, D, F, L.b2, m.x, m.x, D));
+    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln3g, L.ln3b, m.xb, R, D));
   }
   return SPECDEC_OK;
 }
@@ -279,7 +300,11 @@ int specdec_create(specdec_ctx** out, const specdec_limits* lim) {
   return SPECDEC_OK;
 }
 
-void specdec_destroy(specdec_ctx* c) { delete c; }
+void specdec_destroy(specdec_ctx* c) {
+  if (!c) return;
+  for (hipEvent_t e : c->prof_ev) (void)hipEventDestroy(e);
+  delete c;
+}
 
 const char* specdec_last_error(const specdec_ctx* c) { return c ? c->err : "null context"; }
 
@@ -456,12 +481,12 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
   if (c->uncached_ub[0] > 0 && !c->trusted[0]) return fail(c, SPECDEC_ERR_BAD_STATE, "verifier cache does not cover the stream: call specdec_prefill or specdec_load_cache");
   hipStream_t st = S(stream);
   const int B = c->B, T = k + 1, R = B * T;
-  HIPCHK(c, sd::assemble_verify(st, c->st, m.rm, draft, B, k, m.d.vocab));
+  LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::assemble_verify(st, c->st, m.rm, draft, B, k, m.d.vocab));
   rc = decoder_layers(c, m, B, T, st);
   if (rc) return rc;
   const int n_tiles = (m.d.vocab + 127) / 128;
-  HIPCHK(c, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.part, logits));
-  HIPCHK(c, sd::accept_rows(st, m.part, n_tiles, m.rm, c->st, B, k, beta, tau, m.d.pad_id, m.row_stats, accept_len, next_token));
+  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.part, logits));
+  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::accept_rows(st, m.part, n_tiles, m.rm, c->st, B, k, beta, tau, m.d.pad_id, m.row_stats, accept_len, next_token));
   c->last_k = k;
   return SPECDEC_OK;
 }
@@ -474,6 +499,46 @@ int specdec_commit(specdec_ctx* c, const int32_t* accept_len, const int32_t* nex
   HIPCHK(c, sd::commit_rows(S(stream), c->st, accept_len, next_token, c->B, c->m[0].d.eos_id, n_active));
   c->last_k = 0;
   c->uncached_ub[1] += c->lim.k_max + 1;
+  return SPECDEC_OK;
+}
+
+int specdec_rewind(specdec_ctx* c, const int32_t* len, void* stream) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (!c->state_bound || c->B <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "begin not called");
+  if (!len) return fail(c, SPECDEC_ERR_INVALID_ARG, "null len");
+  HIPCHK(c, sd::rewind_state(S(stream), c->st, len, c->B));
+  c->last_k = 0;
+  return SPECDEC_OK;
+}
+
+int specdec_profile_select(specdec_ctx* c, int32_t kind) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (kind < SPECDEC_KIND_NONE || kind >= SPECDEC_KIND_COUNT) return fail(c, SPECDEC_ERR_INVALID_ARG, "bad kernel kind %d", kind);
+  if (kind != SPECDEC_KIND_NONE && c->prof_ev.empty()) {
+    c->prof_ev.reserve(2 * kProfPairs);
+    for (int i = 0; i < 2 * kProfPairs; ++i) {
+      hipEvent_t e;
+      HIPCHK(c, hipEventCreate(&e));
+      c->prof_ev.push_back(e);
+    }
+  }
+  c->prof_kind = kind;
+  c->prof_used = 0;
+  return SPECDEC_OK;
+}
+
+int specdec_profile_read(specdec_ctx* c, double* total_ms, int32_t* launches) {
+  if (!c || !total_ms || !launches) return SPECDEC_ERR_INVALID_ARG;
+  double tot = 0.0;
+  for (int i = 0; i + 1 < c->prof_used; i += 2) {
+    HIPCHK(c, hipEventSynchronize(c->prof_ev[i + 1]));
+    float ms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&ms, c->prof_ev[i], c->prof_ev[i + 1]));
+    tot += ms;
+  }
+  *total_ms = tot;
+  *launches = c->prof_used / 2;
+  c->prof_used = 0;
   return SPECDEC_OK;
 }
 

@@ -96,6 +96,7 @@ hipError_t begin_state(hipStream_t st, const SeqState& s, int B, int max_new, in
                        int bos_id);
 hipError_t set_stream(hipStream_t st, const SeqState& s, const int* tokens, const int* len, int B,
                       int L_max, int max_new, int max_tgt);
+hipError_t rewind_state(hipStream_t st, const SeqState& s, const int* len, int B);
 hipError_t set_src_len(hipStream_t st, const SeqState& s, const int* src_len, int B, int S_max);
 hipError_t set_cached(hipStream_t st, const SeqState& s, int role, const int* n, int B, int hi);
 hipError_t get_output(hipStream_t st, const SeqState& s, int* tokens, int out_cap, int* out_len,

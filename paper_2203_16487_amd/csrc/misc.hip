@@ -286,6 +286,25 @@ hipError_t set_stream(hipStream_t st, const SeqState& s, const int* tokens, cons
   return hipGetLastError();
 }
 
+// Rollback to given lengths: nothing moves, rows beyond the new j are dead.
+__global__ void rewind_kernel(SeqState s, const int* __restrict__ len, int B) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int j = s.len[b];
+  int jn = min(j, max(len[b], 0));
+  if (jn < j) {
+    s.len[b] = jn;
+    s.start[b] = min(s.start[b], jn);
+    s.cached[0][b] = min(s.cached[0][b], jn);
+    s.cached[1][b] = min(s.cached[1][b], jn + 1);
+    s.finished[b] = (jn >= s.cap[b]);
+  }
+}
+hipError_t rewind_state(hipStream_t st, const SeqState& s, const int* len, int B) {
+  hipLaunchKernelGGL(rewind_kernel, blocks_for(B, 128), dim3(128), 0, st, s, len, B);
+  return hipGetLastError();
+}
+
 __global__ void copy_i32_kernel(int* dst, const int* src, int n) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) dst[i] = src[i];
