@@ -55,7 +55,7 @@ struct Model {
 
 struct specdec_ctx {
   specdec_limits lim{};
-  int Lcap = 0, Tmax = 0, n_pos = 0;
+  int Lcap = 0, Scap = 0, Tmax = 0, n_pos = 0;
   bool state_bound = false;
   sd::SeqState st{};
   Model m[2];
@@ -181,7 +181,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   const size_t n_tiles = (d->vocab + 127) / 128;
   Model t;
   t.kv_layer = Bm * H * c->Lcap * 64;
-  t.xkv_layer = Bm * H * (size_t)c->lim.max_src * 64;
+  t.xkv_layer = Bm * H * (size_t)c->Scap * 64;
   t.pe = cv.take<float>((size_t)c->n_pos * D);
   t.kc = cv.take<bf16>(t.kv_layer * d->dec_layers);
   t.vc = cv.take<bf16>(t.kv_layer * d->dec_layers);
@@ -227,7 +227,7 @@ inline hipStream_t S(void* s) { return static_cast<hipStream_t>(s); }
 // Leaves the final hidden states in m.x (fp32) and m.xb (bf16).
 int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
   const int R = B * T, D = m.d.d_model, F = m.d.d_ffn, H = m.d.n_heads;
-  const int Lcap = c->Lcap, Scap = c->lim.max_src;
+  const int Lcap = c->Lcap, Scap = c->Scap;
   LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::embed_rows(st, m.rm.row_tok, m.rm.row_pos, m.embed, m.pe, m.x, m.xb, R, D));
   for (int l = 0; l < m.d.dec_layers; ++l) {
     const DecLayer& L = m.dec[l];
@@ -237,17 +237,20 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
                                   m.rm.row_pos, H, Lcap));
     sd::AttnArgs a{};
     a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
-    a.k = kc; a.v = vc; a.kv_b = (long)H * Lcap * 64; a.kv_h = (long)Lcap * 64; a.kv_row = 64;
+    a.k = kc; a.k_b = (long)H * Lcap * 64; a.k_h = (long)Lcap * 64; a.k_row = 64;
+    a.v = vc; a.v_b = (long)H * Lcap * 64; a.v_h = (long)Lcap * 64; a.v_row = Lcap;
     a.o = m.att; a.o_b = (long)T * D; a.o_row = D;
     a.q_count = m.rm.seq_rows; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
     a.T = T; a.H = H; a.B = B;
+    a.key_split = Lcap > 256;
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.wo, R, D, D, L.bo, m.x, m.x, D));
     LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln1g, L.ln1b, m.xb, R, D));
     LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.xb, D, L.cwq, R, D, D, L.cbq, m.q, D, false));
-    a.k = m.xk + m.xkv_layer * l; a.v = m.xv + m.xkv_layer * l;
-    a.kv_b = (long)H * Scap * 64; a.kv_h = (long)Scap * 64;
+    a.k = m.xk + m.xkv_layer * l; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64;
+    a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_row = Scap;
     a.lim_row = nullptr; a.lim_seq = c->st.src_len;
+    a.key_split = c->S_cur > 256;
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.cwo, R, D, D, L.cbo, m.x, m.x, D));
     LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln2g, L.ln2b, m.xb, R, D));
@@ -263,7 +266,7 @@ int cross_kv_from(specdec_ctx* c, Model& m, const bf16* memory, int B, int S_max
   for (int l = 0; l < m.d.dec_layers; ++l)
     HIPCHK(c, sd::gemm_cross_kv(st, memory, m.dec[l].cwkv, B * S_max, D, D, m.dec[l].cbkv,
                                 m.xk + m.xkv_layer * l, m.xv + m.xkv_layer * l, S_max, m.d.n_heads,
-                                c->lim.max_src));
+                                c->Scap));
   m.has_memory = true;
   return SPECDEC_OK;
 }
@@ -294,7 +297,8 @@ int specdec_create(specdec_ctx** out, const specdec_limits* lim) {
   if (!c) return SPECDEC_ERR_TOO_LARGE;
   c->lim = *lim;
   c->Tmax = 2 * lim->k_max + 1;
-  c->Lcap = lim->max_tgt + lim->k_max + 1;
+  c->Lcap = (lim->max_tgt + lim->k_max + 1 + 31) & ~31;   // rows of the KV arenas (32-key chunks)
+  c->Scap = (lim->max_src + 31) & ~31;
   c->n_pos = c->Lcap;
   *out = c;
   return SPECDEC_OK;
@@ -446,8 +450,8 @@ int specdec_load_cache(specdec_ctx* c, specdec_role role, const void* k_cache, c
   const int H = m.d.n_heads;
   const size_t flat_layer = (size_t)c->B * L_max * m.d.d_model;
   for (int l = 0; l < m.d.dec_layers; ++l) {
-    HIPCHK(c, sd::cache_from_flat(S(stream), m.kc + m.kv_layer * l, static_cast<const bf16*>(k_cache) + flat_layer * l, c->B, H, c->Lcap, L_max));
-    HIPCHK(c, sd::cache_from_flat(S(stream), m.vc + m.kv_layer * l, static_cast<const bf16*>(v_cache) + flat_layer * l, c->B, H, c->Lcap, L_max));
+    HIPCHK(c, sd::cache_from_flat(S(stream), m.kc + m.kv_layer * l, static_cast<const bf16*>(k_cache) + flat_layer * l, c->B, H, c->Lcap, L_max, false));
+    HIPCHK(c, sd::cache_from_flat(S(stream), m.vc + m.kv_layer * l, static_cast<const bf16*>(v_cache) + flat_layer * l, c->B, H, c->Lcap, L_max, true));
   }
   HIPCHK(c, sd::set_cached(S(stream), c->st, role, n, c->B, L_max));
   c->trusted[role] = true;
@@ -486,7 +490,8 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
   if (rc) return rc;
   const int n_tiles = (m.d.vocab + 127) / 128;
   LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.part, logits));
-  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::accept_rows(st, m.part, n_tiles, m.rm, c->st, B, k, beta, tau, m.d.pad_id, m.row_stats, accept_len, next_token));
+  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, n_tiles, R, m.row_stats));
+  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::accept_rows(st, m.row_stats, c->st, B, k, beta, tau, m.d.pad_id, accept_len, next_token));
   c->last_k = k;
   return SPECDEC_OK;
 }
@@ -559,8 +564,8 @@ int specdec_get_cache(specdec_ctx* c, specdec_role role, void* k_cache, void* v_
   Model& m = c->m[role];
   const size_t flat_layer = (size_t)c->B * L * m.d.d_model;
   for (int l = 0; l < m.d.dec_layers; ++l) {
-    HIPCHK(c, sd::cache_to_flat(S(stream), m.kc + m.kv_layer * l, static_cast<bf16*>(k_cache) + flat_layer * l, c->B, m.d.n_heads, c->Lcap, L));
-    HIPCHK(c, sd::cache_to_flat(S(stream), m.vc + m.kv_layer * l, static_cast<bf16*>(v_cache) + flat_layer * l, c->B, m.d.n_heads, c->Lcap, L));
+    HIPCHK(c, sd::cache_to_flat(S(stream), m.kc + m.kv_layer * l, static_cast<bf16*>(k_cache) + flat_layer * l, c->B, m.d.n_heads, c->Lcap, L, false));
+    HIPCHK(c, sd::cache_to_flat(S(stream), m.vc + m.kv_layer * l, static_cast<bf16*>(v_cache) + flat_layer * l, c->B, m.d.n_heads, c->Lcap, L, true));
   }
   return SPECDEC_OK;
 }

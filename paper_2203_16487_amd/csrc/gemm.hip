@@ -4,35 +4,79 @@
 
 namespace sd {
 
+// Workgroup ids are dealt round-robin to the 8 XCDs (id % 8), each with its own L2.  Tiles are
+// numbered n-major (m fastest) and XCD x takes the contiguous run [x*per, (x+1)*per): the
+// tiles that run together on one XCD then share a few weight column-panels and the
+// activation rows, which stay in that XCD's L2.  Returns false for the padding blocks.
+__device__ __forceinline__ bool xcd_tile(int MT, int NT, int& mt, int& nt) {
+  const int nb = MT * NT, id = blockIdx.x;
+  const int per = (nb + 7) >> 3;
+  const int t = (id & 7) * per + (id >> 3);
+  if ((id >> 3) >= per || t >= nb) return false;
+  nt = t / MT;
+  mt = t - nt * MT;
+  return true;
+}
+static inline int xcd_grid(int MT, int NT) { return 8 * ((MT * NT + 7) / 8); }
+
+// fp32 staging tile in LDS, [BM][BN]; rows r and r+4 come from the two lane halves of one
+// MFMA register, so bit 5 of the column is flipped for every other group of 4 rows.
+template <int BN>
+__device__ __forceinline__ int cs_off(int row, int col) {
+  return row * BN + (col ^ (((row >> 2) & 1) << 5));
+}
+
 // ----------------------------------------------------------------------------- epilogues
+// Each gets 8 consecutive columns [n, n+8) of row m (n % 8 == 0, inside the matrix).
 struct EpiF32 {
   const bf16* bias;
   const float* resid;
   float* out;
   int ldo;
-  __device__ __forceinline__ void operator()(int m, int n, float v) const {
-    if (bias) v += (float)bias[n];
-    size_t o = (size_t)m * ldo + n;
-    if (resid) v += resid[o];
-    out[o] = v;
+  __device__ __forceinline__ void operator()(int m, int n, float (&v)[8]) const {
+    const size_t o = (size_t)m * ldo + n;
+    if (bias) {
+      bf16x8 b = *reinterpret_cast<const bf16x8*>(bias + n);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] += (float)b[i];
+    }
+    if (resid) {
+      f32x4 r0 = *reinterpret_cast<const f32x4*>(resid + o), r1 = *reinterpret_cast<const f32x4*>(resid + o + 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { v[i] += r0[i]; v[4 + i] += r1[i]; }
+    }
+    f32x4 w0 = {v[0], v[1], v[2], v[3]}, w1 = {v[4], v[5], v[6], v[7]};
+    *reinterpret_cast<f32x4*>(out + o) = w0;
+    *reinterpret_cast<f32x4*>(out + o + 4) = w1;
   }
 };
+
+__device__ __forceinline__ bf16x8 pack_bias(float (&v)[8], const bf16* bias, int n, bool relu) {
+  bf16x8 b = *reinterpret_cast<const bf16x8*>(bias + n);
+  bf16x8 o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float t = v[i] + (float)b[i];
+    if (relu) t = fmaxf(t, 0.f);
+    o[i] = (bf16)t;
+  }
+  return o;
+}
 
 struct EpiBf16 {
   const bf16* bias;
   bf16* out;
   int ldo;
   int relu;
-  __device__ __forceinline__ void operator()(int m, int n, float v) const {
-    if (bias) v += (float)bias[n];
-    if (relu) v = fmaxf(v, 0.f);
-    out[(size_t)m * ldo + n] = (bf16)v;
+  __device__ __forceinline__ void operator()(int m, int n, float (&v)[8]) const {
+    *reinterpret_cast<bf16x8*>(out + (size_t)m * ldo + n) = pack_bias(v, bias, n, relu != 0);
   }
 };
 
 // Decoder self-attention projection: columns [0,d) are queries, [d,2d) keys, [2d,3d) values.
-// Keys/values go straight into the cache row of the token they belong to: this is the
-// "append" of the KV cache, fused into the projection.
+// Keys go straight into the cache row of the token they belong to and values into the
+// transposed value cache: this is the "append" of the KV cache, fused into the projection.
+//   key cache   [B][H][Lcap][64]      value cache [B][H][64][Lcap]
 struct EpiQkvAppend {
   const bf16* bias;
   bf16* q;
@@ -41,56 +85,103 @@ struct EpiQkvAppend {
   const int* row_b;
   const int* row_pos;
   int d, H, Lcap;
-  __device__ __forceinline__ void operator()(int m, int n, float v) const {
-    v += (float)bias[n];
-    int part = n / d, c = n - part * d;
+  __device__ __forceinline__ void operator()(int m, int n, float (&v)[8]) const {
+    bf16x8 o = pack_bias(v, bias, n, false);
+    const int part = n / d, c = n - part * d;
     if (part == 0) {
-      q[(size_t)m * d + c] = (bf16)v;
+      *reinterpret_cast<bf16x8*>(q + (size_t)m * d + c) = o;
       return;
     }
-    int b = row_b[m];
+    const int b = row_b[m];
     if (b < 0) return;
-    int h = c >> 6, e = c & 63;
-    size_t o = (((size_t)b * H + h) * Lcap + row_pos[m]) * kHeadDim + e;
-    (part == 1 ? kc : vc)[o] = (bf16)v;
+    const int h = c >> 6, e = c & 63, pos = row_pos[m];
+    if (part == 1) {
+      *reinterpret_cast<bf16x8*>(kc + (((size_t)b * H + h) * Lcap + pos) * kHeadDim + e) = o;
+    } else {
+      bf16* dst = vc + (((size_t)b * H + h) * kHeadDim + e) * Lcap + pos;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) dst[(size_t)i * Lcap] = o[i];
+    }
   }
 };
 
+// Cross-attention keys/values of the encoder memory: row m = b*S + s.
+//   xk [B][H][Scap][64]     xv [B][H][64][Scap] (transposed like the value cache)
 struct EpiCrossKv {
   const bf16* bias;
   bf16* xk;
   bf16* xv;
   int d, H, S, Scap;
-  __device__ __forceinline__ void operator()(int m, int n, float v) const {
-    v += (float)bias[n];
-    int part = n / d, c = n - part * d;
-    int b = m / S, s = m - b * S;
-    int h = c >> 6, e = c & 63;
-    size_t o = (((size_t)b * H + h) * Scap + s) * kHeadDim + e;
-    (part == 0 ? xk : xv)[o] = (bf16)v;
+  __device__ __forceinline__ void operator()(int m, int n, float (&v)[8]) const {
+    bf16x8 o = pack_bias(v, bias, n, false);
+    const int part = n / d, c = n - part * d;
+    const int b = m / S, s = m - b * S;
+    const int h = c >> 6, e = c & 63;
+    if (part == 0) {
+      *reinterpret_cast<bf16x8*>(xk + (((size_t)b * H + h) * Scap + s) * kHeadDim + e) = o;
+    } else {
+      bf16* dst = xv + (((size_t)b * H + h) * kHeadDim + e) * Scap + s;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) dst[(size_t)i * Scap] = o[i];
+    }
   }
 };
 
-template <class Epi>
-__global__ __launch_bounds__(kGemmThreads) void gemm_kernel(const bf16* __restrict__ A, int lda,
-                                                            const bf16* __restrict__ W, int ldw,
-                                                            int M, int N, int K, Epi epi) {
-  __shared__ __attribute__((aligned(16))) bf16 smem[kGemmSmemBytes / 2];
-  const int m0 = blockIdx.y * GM, n0 = blockIdx.x * GN;
-  GemmAcc acc;
-  gemm_mainloop(A, lda, W, ldw, M, N, K, m0, n0, smem, acc);
-  gemm_foreach(acc, m0, n0, [&](int m, int n, float v) {
-    if (m < M && n < N) epi(m, n, v);
-  });
+template <class Cfg, class Epi>
+__global__ __launch_bounds__(Cfg::kThreads) void gemm_kernel(const bf16* __restrict__ A, int lda,
+                                                             const bf16* __restrict__ W, int ldw,
+                                                             int M, int N, int K, int MT, int NT,
+                                                             Epi epi) {
+  extern __shared__ __attribute__((aligned(1024))) bf16 smem[];
+  static_assert(Cfg::kSmemBytes >= Cfg::kBM * Cfg::kBN * 4, "staging tile must fit in the ring");
+  int mt, nt;
+  if (!xcd_tile(MT, NT, mt, nt)) return;
+  const int m0 = mt * Cfg::kBM, n0 = nt * Cfg::kBN;
+  GemmAcc<Cfg> acc;
+  gemm_mainloop<Cfg>(A, lda, W, ldw, M, N, 0, K / GK, m0, n0, smem, acc);
+  float* cs = reinterpret_cast<float*>(smem);
+  gemm_foreach<Cfg>(acc, 0, 0, [&](int r, int c, float v) { cs[cs_off<Cfg::kBN>(r, c)] = v; });
+  __syncthreads();
+  constexpr int CPR = Cfg::kBN / 8;   // 8-column chunks per row
+  for (int idx = threadIdx.x; idx < Cfg::kBM * CPR; idx += Cfg::kThreads) {
+    const int r = idx / CPR, c = (idx - r * CPR) * 8;
+    const int m = m0 + r, n = n0 + c;
+    if (m < M && n < N) {
+      const float* src = cs + cs_off<Cfg::kBN>(r, c);
+      f32x4 a = *reinterpret_cast<const f32x4*>(src), b = *reinterpret_cast<const f32x4*>(src + 4);
+      float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+      epi(m, n, v);
+    }
+  }
+}
+
+typedef GemmCfg<128, 128, 2> CfgWide;      // 64 KB LDS: two blocks per CU
+typedef GemmCfg<64, 64, 4> CfgSmall;       // 64 KB LDS; many tiles for narrow outputs
+
+template <class Cfg, class Epi>
+static hipError_t launch_cfg(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
+                             const Epi& epi) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<Cfg, Epi>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kSmemBytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int MT = (M + Cfg::kBM - 1) / Cfg::kBM, NT = (N + Cfg::kBN - 1) / Cfg::kBN;
+  hipLaunchKernelGGL((gemm_kernel<Cfg, Epi>), dim3(xcd_grid(MT, NT)), dim3(Cfg::kThreads), Cfg::kSmemBytes, st,
+                     A, lda, W, K, M, N, K, MT, NT, epi);
+  return hipGetLastError();
 }
 
 template <class Epi>
 static hipError_t launch(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
                          const Epi& epi) {
   if (M <= 0 || N <= 0) return hipSuccess;
-  dim3 grid((N + GN - 1) / GN, (M + GM - 1) / GM);
-  hipLaunchKernelGGL(gemm_kernel<Epi>, grid, dim3(kGemmThreads), 0, st, A, lda, W, K, M, N, K, epi);
-  return hipGetLastError();
+  // enough 128x128 tiles to give every CU one?  else take 64x64 tiles
+  const long wide_tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+  if (wide_tiles >= 200) return launch_cfg<CfgWide>(st, A, lda, W, M, N, K, epi);
+  return launch_cfg<CfgSmall>(st, A, lda, W, M, N, K, epi);
 }
 
 hipError_t gemm_f32(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
@@ -117,25 +208,22 @@ hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, in
 // max / arg-max / top list / draft logit and once for the sum of exponentials, the two halves
 // are merged with lane shuffles, and one partial record per (row, tile) is written.  Logits
 // never reach memory unless the caller asks for them.
-__device__ __forceinline__ int cs_off(int row, int col) {
-  // rows r and r+4 are written by the two lane halves of one MFMA register: flip bank half
-  return row * GN + (col ^ (((row >> 2) & 1) << 5));
-}
+typedef GemmCfg<128, 128, 2> CfgVocab;
 
-__global__ __launch_bounds__(kGemmThreads) void vocab_kernel(const bf16* __restrict__ A,
-                                                             const bf16* __restrict__ E, int M,
-                                                             int V, int K,
-                                                             const int* __restrict__ row_draft,
-                                                             float* __restrict__ part,
-                                                             float* __restrict__ logits) {
-  __shared__ __attribute__((aligned(16))) bf16 smem[kGemmSmemBytes / 2];
-  const int m0 = blockIdx.y * GM, n0 = blockIdx.x * GN;
-  const int n_tiles = gridDim.x;
-  GemmAcc acc;
-  gemm_mainloop(A, K, E, K, M, V, K, m0, n0, smem, acc);
-  // the main loop ends with a barrier: the staging buffers are free
+__global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* __restrict__ A,
+                                                                   const bf16* __restrict__ E, int M,
+                                                                   int V, int K, int MT, int NT,
+                                                                   const int* __restrict__ row_draft,
+                                                                   float* __restrict__ part,
+                                                                   float* __restrict__ logits) {
+  extern __shared__ __attribute__((aligned(1024))) bf16 smem[];
+  int mt, nt;
+  if (!xcd_tile(MT, NT, mt, nt)) return;
+  const int m0 = mt * 128, n0 = nt * 128;
+  GemmAcc<CfgVocab> acc;
+  gemm_mainloop<CfgVocab>(A, K, E, K, M, V, 0, K / GK, m0, n0, smem, acc);
   float* cs = reinterpret_cast<float*>(smem);  // [128][128] fp32 = 64 KB
-  gemm_foreach(acc, 0, 0, [&](int r, int c, float v) { cs[cs_off(r, c)] = v; });
+  gemm_foreach<CfgVocab>(acc, 0, 0, [&](int r, int c, float v) { cs[cs_off<128>(r, c)] = v; });
   __syncthreads();
 
   const int tid = threadIdx.x;
@@ -153,7 +241,7 @@ __global__ __launch_bounds__(kGemmThreads) void vocab_kernel(const bf16* __restr
   for (int j = 0; j < 64; ++j) {
     int c = half * 64 + ((j + rot) & 63);
     int n = n0 + c;
-    float v = cs[cs_off(row, c)];
+    float v = cs[cs_off<128>(row, c)];
     if (n < V) {
       if (v > best || (v == best && n < besti)) { best = v; besti = n; }
       top_insert<kTopN>(top, v);
@@ -163,7 +251,7 @@ __global__ __launch_bounds__(kGemmThreads) void vocab_kernel(const bf16* __restr
   float se = 0.f;
   for (int j = 0; j < 64; ++j) {
     int c = half * 64 + ((j + rot) & 63);
-    if (n0 + c < V) se += __expf(cs[cs_off(row, c)] - best);
+    if (n0 + c < V) se += __expf(cs[cs_off<128>(row, c)] - best);
   }
   // merge the two halves of the row (lanes tid and tid^1)
   float obest = __shfl_xor(best, 1, 64);
@@ -181,7 +269,7 @@ __global__ __launch_bounds__(kGemmThreads) void vocab_kernel(const bf16* __restr
 #pragma unroll
   for (int i = 0; i < kTopN; ++i) top_insert<kTopN>(top, otop[i]);
   if (half == 0 && m < M) {
-    float* p = part + ((size_t)m * n_tiles + blockIdx.x) * kPartF;
+    float* p = part + ((size_t)m * NT + nt) * kPartF;
     p[0] = nb;
     p[1] = __int_as_float(nbi);
     p[2] = tot;
@@ -190,9 +278,9 @@ __global__ __launch_bounds__(kGemmThreads) void vocab_kernel(const bf16* __restr
     for (int i = 0; i < kTopN; ++i) p[4 + i] = top[i];
   }
   if (logits) {
-    for (int idx = tid; idx < GM * GN; idx += kGemmThreads) {
+    for (int idx = tid; idx < 128 * 128; idx += CfgVocab::kThreads) {
       int r = idx >> 7, c = idx & 127;
-      if (m0 + r < M && n0 + c < V) logits[(size_t)(m0 + r) * V + n0 + c] = cs[cs_off(r, c)];
+      if (m0 + r < M && n0 + c < V) logits[(size_t)(m0 + r) * V + n0 + c] = cs[cs_off<128>(r, c)];
     }
   }
 }
@@ -200,9 +288,16 @@ __global__ __launch_bounds__(kGemmThreads) void vocab_kernel(const bf16* __restr
 hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int V, int K,
                        const int* row_draft, float* part, float* logits) {
   if (M <= 0) return hipSuccess;
-  dim3 grid((V + GN - 1) / GN, (M + GM - 1) / GM);
-  hipLaunchKernelGGL(vocab_kernel, grid, dim3(kGemmThreads), 0, st, A, E, M, V, K, row_draft, part,
-                     logits);
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, CfgVocab::kSmemBytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int MT = (M + 127) / 128, NT = (V + 127) / 128;
+  hipLaunchKernelGGL(vocab_kernel, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
+                     A, E, M, V, K, MT, NT, row_draft, part, logits);
   return hipGetLastError();
 }
 

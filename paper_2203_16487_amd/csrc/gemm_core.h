@@ -1,124 +1,156 @@
-// 128x128x64 bf16 "NT" GEMM main loop on MFMA 32x32x16 (gfx950), fp32 accumulation.
+// bf16 "NT" GEMM main loop on MFMA 32x32x16 (gfx950), fp32 accumulation.
 //   C[m][n] = sum_k A[m][k] * W[n][k]      A [M,K] row-major (lda), W [N,K] row-major (ldw)
-// Both operands are K-contiguous, which is how activations and nn-style weights lie in
-// memory, so every global load is a 16-byte row segment and every MFMA operand is one
-// 16-byte LDS read.  256 threads = 4 waves in a 2x2 arrangement, 64x64 outputs per wave.
+// Both operands are K-contiguous (activations and nn-style weights), so every global access
+// is a 16-byte row segment and every MFMA operand is one 16-byte LDS read.
+//
+// Tiles of BM x BN x 64 move from global memory straight into LDS (global_load_lds, 16 bytes
+// per lane, no register staging) through a ring of STAGES buffers, so that STAGES-1 tiles of
+// loads are in flight while one is being multiplied: HBM/L2 latency (~1-2 us) is covered by
+// depth, not by occupancy.  Waves form a WAVES_M x WAVES_N arrangement (4 or 8 waves).
 #pragma once
 #include "common.h"
 
 namespace sd {
 
-constexpr int GM = 128, GN = 128, GK = 64;
+constexpr int GK = 64;               // k extent of one pipeline stage
 constexpr int kGemmThreads = 256;
-constexpr int kTileElems = 128 * GK;                 // bf16 elements of one operand tile
-constexpr int kGemmSmemBytes = 2 * 2 * kTileElems * 2;  // double-buffered A and W tiles (64 KB)
 
-// LDS tile: 128 rows of 64 bf16 (8 chunks of 16 B).  Chunk c of row r lives at chunk
-// c ^ ((r >> 1) & 7): 16 consecutive rows reading the same logical chunk then touch all
-// 64 banks exactly once, and so does a 16-lane group writing two full rows.
+#define SD_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
+#define SD_GLB_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+// Workgroup barrier without the release/acquire fences of __syncthreads(): those would wait
+// for every outstanding global_load_lds (vmcnt(0)) and flatten the pipeline.  The memory
+// clobber keeps the compiler from moving LDS accesses across it.
+__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// LDS tile rows are 64 bf16 = 8 chunks of 16 B.  Chunk c of row r lives at chunk
+// c ^ ((r >> 1) & 7): 16 consecutive rows reading the same logical chunk touch all 64 banks.
 __device__ __forceinline__ int lds_off(int row, int chunk) {
   return row * GK + ((chunk ^ ((row >> 1) & 7)) << 3);
 }
 
-struct GemmAcc {
-  f32x16 c[2][2];  // [m-tile][n-tile] of the wave's 64x64 block
+template <int BM, int BN, int STAGES, int WAVES_M = 2, int WAVES_N = 2>
+struct GemmCfg {
+  static constexpr int kBM = BM, kBN = BN, kStages = STAGES;
+  static constexpr int kWavesM = WAVES_M, kWavesN = WAVES_N, kWaves = WAVES_M * WAVES_N;
+  static constexpr int kThreads = 64 * kWaves;
+  static constexpr int kRows = BM + BN;                 // LDS rows per stage (A rows then W rows)
+  static constexpr int kIPW = kRows / 8 / kWaves;       // global_load_lds per wave per stage
+  static constexpr int kStageElems = kRows * GK;
+  static constexpr int kSmemBytes = STAGES * kStageElems * 2;
+  static constexpr int kWM = BM / WAVES_M, kWN = BN / WAVES_N;   // wave tile
+  static constexpr int kTM = kWM / 32, kTN = kWN / 32;           // MFMA tiles per wave
+  static_assert(kRows % (8 * kWaves) == 0 && kWM % 32 == 0 && kWN % 32 == 0, "tile shape");
 };
 
-// Runs the whole K loop for the block tile at (m0, n0).  Rows >= M / >= N read as zero.
-// K must be a multiple of 64; lda, ldw multiples of 8; A, W 16-byte aligned.
+template <class Cfg>
+struct GemmAcc {
+  f32x16 c[Cfg::kTM][Cfg::kTN];
+};
+
+template <class Cfg>
+struct GemmFrag {
+  bf16x8 a[Cfg::kTM], b[Cfg::kTN];
+};
+
+template <class Cfg>
+__device__ __forceinline__ void load_frags(GemmFrag<Cfg>& f, const bf16* sA, const bf16* sW, int wm,
+                                           int wn, int lrow, int lhalf, int kk) {
+#pragma unroll
+  for (int i = 0; i < Cfg::kTM; ++i)
+    f.a[i] = *reinterpret_cast<const bf16x8*>(sA + lds_off(wm + i * 32 + lrow, kk * 2 + lhalf));
+#pragma unroll
+  for (int j = 0; j < Cfg::kTN; ++j)
+    f.b[j] = *reinterpret_cast<const bf16x8*>(sW + lds_off(wn + j * 32 + lrow, kk * 2 + lhalf));
+}
+
+template <class Cfg>
+__device__ __forceinline__ void mma_frags(GemmAcc<Cfg>& acc, const GemmFrag<Cfg>& f) {
+#pragma unroll
+  for (int i = 0; i < Cfg::kTM; ++i)
+#pragma unroll
+    for (int j = 0; j < Cfg::kTN; ++j)
+      acc.c[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc.c[i][j], 0, 0, 0);
+}
+
+// Whole K range [k_begin, k_begin + 64*KT) of the block tile at (m0, n0).  Rows beyond M / N
+// are clamped to the last valid row (their products land in outputs that are never stored).
+// Requirements: K % 64 == 0, lda/ldw % 8 == 0, A and W 16-byte aligned, smem 1024-aligned.
+template <class Cfg>
 __device__ __forceinline__ void gemm_mainloop(const bf16* __restrict__ A, int lda,
                                               const bf16* __restrict__ W, int ldw, int M, int N,
-                                              int K, int m0, int n0, bf16* smem, GemmAcc& acc) {
+                                              int k_begin, int KT, int m0, int n0, bf16* smem,
+                                              GemmAcc<Cfg>& acc) {
+  constexpr int IPW = Cfg::kIPW, STAGES = Cfg::kStages;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int wm = (wave / Cfg::kWavesN) * Cfg::kWM, wn = (wave % Cfg::kWavesN) * Cfg::kWN;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < Cfg::kTM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < Cfg::kTN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc.c[i][j][r] = 0.f;
 
-  // this thread's four 16-byte segments of each operand tile
-  const uint4* ga[4];
-  const uint4* gw[4];
-  int so[4];
-  bool oka[4], okw[4];
+  // One global_load_lds moves 64 lanes x 16 B = 8 tile rows; lane l lands at row l/8, physical
+  // chunk l%8, so it fetches the logical chunk that the swizzle maps there.
+  const bf16* gptr[IPW];
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    int idx = p * 256 + tid, row = idx >> 3, ch = idx & 7;
-    so[p] = lds_off(row, ch);
-    oka[p] = (m0 + row) < M;
-    okw[p] = (n0 + row) < N;
-    ga[p] = reinterpret_cast<const uint4*>(A + (size_t)(oka[p] ? m0 + row : 0) * lda + ch * 8);
-    gw[p] = reinterpret_cast<const uint4*>(W + (size_t)(okw[p] ? n0 + row : 0) * ldw + ch * 8);
+  for (int i = 0; i < IPW; ++i) {
+    const int row = (wave * IPW + i) * 8 + (lane >> 3);
+    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+    if (row < Cfg::kBM) {
+      gptr[i] = A + (size_t)min(m0 + row, M - 1) * lda + k_begin + chunk * 8;
+    } else {
+      gptr[i] = W + (size_t)min(n0 + row - Cfg::kBM, N - 1) * ldw + k_begin + chunk * 8;
+    }
   }
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
-  uint4 ra[4], rw[4];
+  auto issue = [&](int kt, int slot) {
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    ra[p] = oka[p] ? ga[p][0] : zero4;
-    rw[p] = okw[p] ? gw[p][0] : zero4;
-  }
-  bf16* sA = smem;                    // [2][kTileElems]
-  bf16* sW = smem + 2 * kTileElems;   // [2][kTileElems]
+    for (int i = 0; i < IPW; ++i) {
+      bf16* dst = smem + slot * Cfg::kStageElems + (wave * IPW + i) * 8 * GK;
+      __builtin_amdgcn_global_load_lds(SD_GLB_PTR(gptr[i] + kt * GK), SD_LDS_PTR(dst), 16, 0, 0);
+    }
+  };
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    *reinterpret_cast<uint4*>(sA + so[p]) = ra[p];
-    *reinterpret_cast<uint4*>(sW + so[p]) = rw[p];
-  }
-  __syncthreads();
+  for (int s = 0; s < STAGES - 1; ++s)
+    if (s < KT) issue(s, s);
 
-  const int KT = K / GK;
   const int lrow = lane & 31, lhalf = lane >> 5;
   for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < KT) {
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {   // 8 bf16 per uint4 -> advance by 8 uint4 per 64-k step
-        ra[p] = oka[p] ? ga[p][(kt + 1) * 8] : zero4;
-        rw[p] = okw[p] ? gw[p][(kt + 1) * 8] : zero4;
-      }
-    }
-    const bf16* cA = sA + cur * kTileElems;
-    const bf16* cW = sW + cur * kTileElems;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 a[2], b[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-        a[i] = *reinterpret_cast<const bf16x8*>(cA + lds_off(wm + i * 32 + lrow, kk * 2 + lhalf));
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-        b[j] = *reinterpret_cast<const bf16x8*>(cW + lds_off(wn + j * 32 + lrow, kk * 2 + lhalf));
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc.c[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc.c[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < KT) {
-      bf16* nA = sA + (cur ^ 1) * kTileElems;
-      bf16* nW = sW + (cur ^ 1) * kTileElems;
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        *reinterpret_cast<uint4*>(nA + so[p]) = ra[p];
-        *reinterpret_cast<uint4*>(nW + so[p]) = rw[p];
-      }
-    }
-    __syncthreads();
+    // tile kt has landed once at most STAGES-2 younger tiles are still in flight
+    if (kt + STAGES - 2 < KT) wait_vmcnt<IPW * (STAGES - 2)>(); else wait_vmcnt<0>();
+    block_barrier();   // everyone's part of tile kt is in LDS; everyone is done with tile kt-1
+    if (kt + STAGES - 1 < KT) issue(kt + STAGES - 1, (kt + STAGES - 1) % STAGES);
+    const bf16* sA = smem + (kt % STAGES) * Cfg::kStageElems;
+    const bf16* sW = sA + Cfg::kBM * GK;
+    // fragments of step kk+1 are fetched from LDS while the MFMAs of step kk run
+    GemmFrag<Cfg> f0, f1;
+    load_frags<Cfg>(f0, sA, sW, wm, wn, lrow, lhalf, 0);
+    load_frags<Cfg>(f1, sA, sW, wm, wn, lrow, lhalf, 1);
+    mma_frags<Cfg>(acc, f0);
+    load_frags<Cfg>(f0, sA, sW, wm, wn, lrow, lhalf, 2);
+    mma_frags<Cfg>(acc, f1);
+    load_frags<Cfg>(f1, sA, sW, wm, wn, lrow, lhalf, 3);
+    mma_frags<Cfg>(acc, f0);
+    mma_frags<Cfg>(acc, f1);
   }
+  block_barrier();   // LDS may be reused by the caller's epilogue
 }
 
 // Visits every output element the calling lane holds: f(m, n, value).
 // MFMA 32x32 result layout: register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, col l%32.
-template <class F>
-__device__ __forceinline__ void gemm_foreach(const GemmAcc& acc, int m0, int n0, F&& f) {
+template <class Cfg, class F>
+__device__ __forceinline__ void gemm_foreach(const GemmAcc<Cfg>& acc, int m0, int n0, F&& f) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+  const int wm = (wave / Cfg::kWavesN) * Cfg::kWM, wn = (wave % Cfg::kWavesN) * Cfg::kWN;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < Cfg::kTM; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < Cfg::kTN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         int m = m0 + wm + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);

@@ -51,14 +51,16 @@ hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int 
 // ---- attn.hip ------------------------------------------------------------------------
 struct AttnArgs {
   const bf16* q;  long q_b, q_row;            // q + b*q_b + i*q_row + h*64
-  const bf16* k;  const bf16* v;
-  long kv_b, kv_h, kv_row;                     // k + b*kv_b + h*kv_h + key*kv_row
-  bf16* o;        long o_b, o_row;             // o + b*o_b + i*o_row + h*64
-  const int* q_count;                          // [B] queries of sequence b (null: T)
-  const int* lim_row;                          // [B*T] visible keys per query (null: lim_seq)
-  const int* lim_seq;                          // [B]  visible keys of every query of b
-  int T;                                       // max queries per sequence
+  const bf16* k;  long k_b, k_h, k_row;       // keys   [key][64]:  k + b*k_b + h*k_h + key*k_row
+  const bf16* v;  long v_b, v_h, v_row;       // values [64][key]:  v + b*v_b + h*v_h + e*v_row + key
+                                              //   (v_row % 32 == 0: whole 32-key chunks are read)
+  bf16* o;        long o_b, o_row;            // o + b*o_b + i*o_row + h*64
+  const int* q_count;                         // [B] queries of sequence b (null: T)
+  const int* lim_row;                         // [B*T] visible keys per query (null: lim_seq)
+  const int* lim_seq;                         // [B]  visible keys of every query of b
+  int T;                                      // max queries per sequence (q_b = T rows apart)
   int H, B;
+  int key_split;                              // 1: the 4 waves of a block split one pair's keys
 };
 hipError_t attention(hipStream_t st, const AttnArgs& a);
 
@@ -86,10 +88,11 @@ struct SeqState {       // device arrays of the bound state buffer, all [max_bat
 // rows of a verification pass: [u_j, drafts]; also stores the drafts for commit
 hipError_t assemble_verify(hipStream_t st, const SeqState& s, const RowMap& rm, const int* draft,
                            int B, int k, int V);
-// merge vocabulary partials, apply the top-beta/tau rule, leading-accept scan
-hipError_t accept_rows(hipStream_t st, const float* part, int n_tiles, const RowMap& rm,
-                       const SeqState& s, int B, int k, int beta, float tau, int pad_id,
-                       float* row_stats, int* accept_len, int* next_token);
+// merge the vocabulary partials of every row into row_stats [R][4 + kTopN]
+hipError_t merge_rows(hipStream_t st, const float* part, int n_tiles, int R, float* row_stats);
+// top-beta / tau rule on the merged rows and the leading-accept scan per sequence
+hipError_t accept_rows(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k,
+                       int beta, float tau, int pad_id, int* accept_len, int* next_token);
 hipError_t commit_rows(hipStream_t st, const SeqState& s, const int* accept_len,
                        const int* next_token, int B, int eos_id, int* n_active);
 hipError_t begin_state(hipStream_t st, const SeqState& s, int B, int max_new, int max_tgt,
@@ -101,10 +104,10 @@ hipError_t set_src_len(hipStream_t st, const SeqState& s, const int* src_len, in
 hipError_t set_cached(hipStream_t st, const SeqState& s, int role, const int* n, int B, int hi);
 hipError_t get_output(hipStream_t st, const SeqState& s, int* tokens, int out_cap, int* out_len,
                       int* finished, int B, int pad_id);
-// cache [B][H][Lcap][64]  <->  flat [B][L][d]
+// key cache [B][H][Lcap][64] / value cache [B][H][64][Lcap]  <->  flat [B][L][d]
 hipError_t cache_from_flat(hipStream_t st, bf16* cache, const bf16* flat, int B, int H, int Lcap,
-                           int L);
+                           int L, bool transposed);
 hipError_t cache_to_flat(hipStream_t st, const bf16* cache, bf16* flat, int B, int H, int Lcap,
-                         int L);
+                         int L, bool transposed);
 
 }  // namespace sd

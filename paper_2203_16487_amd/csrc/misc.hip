@@ -48,39 +48,55 @@ hipError_t embed_rows(hipStream_t st, const int* tok, const int* pos, const bf16
 
 // ----------------------------------------------------------------------------- LayerNorm
 // One wave per row; mean and biased variance as two reductions over registers; eps 1e-5.
-constexpr int kLnMaxPerLane = 32;  // d <= 2048
+// All loads of a row are issued before the first use (PER is a compile-time count), so a
+// row costs one memory round trip, not one per element.
+template <int PER>   // d = 64 * PER
 __global__ __launch_bounds__(256) void ln_kernel(float* __restrict__ x, const bf16* __restrict__ g,
                                                  const bf16* __restrict__ bta, bf16* __restrict__ xb,
-                                                 int R, int d) {
+                                                 int R) {
+  constexpr int d = 64 * PER;
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= R) return;
   float* xr = x + (size_t)r * d;
-  float v[kLnMaxPerLane];
-  const int per = d >> 6;  // d is a multiple of 64
+  float v[PER], gg[PER], bb[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) v[i] = xr[i * 64 + lane];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) { gg[i] = (float)g[i * 64 + lane]; bb[i] = (float)bta[i * 64 + lane]; }
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < kLnMaxPerLane; ++i)
-    if (i < per) { v[i] = xr[i * 64 + lane]; s += v[i]; }
+  for (int i = 0; i < PER; ++i) s += v[i];
   const float mean = wave_sum(s) / (float)d;
   float q = 0.f;
 #pragma unroll
-  for (int i = 0; i < kLnMaxPerLane; ++i)
-    if (i < per) { float t = v[i] - mean; q += t * t; }
+  for (int i = 0; i < PER; ++i) { float t = v[i] - mean; q += t * t; }
   const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
 #pragma unroll
-  for (int i = 0; i < kLnMaxPerLane; ++i)
-    if (i < per) {
-      int c = i * 64 + lane;
-      float y = (v[i] - mean) * rstd * (float)g[c] + (float)bta[c];
-      xr[c] = y;
-      xb[(size_t)r * d + c] = (bf16)y;
-    }
+  for (int i = 0; i < PER; ++i) {
+    const int c = i * 64 + lane;
+    const float y = (v[i] - mean) * rstd * gg[i] + bb[i];
+    xr[c] = y;
+    xb[(size_t)r * d + c] = (bf16)y;
+  }
+}
+template <int PER>
+static hipError_t ln_launch(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R) {
+  hipLaunchKernelGGL(ln_kernel<PER>, dim3((R + 3) / 4), dim3(256), 0, st, x, g, b, xb, R);
+  return hipGetLastError();
 }
 hipError_t layer_norm(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R, int d) {
   if (R <= 0) return hipSuccess;
-  hipLaunchKernelGGL(ln_kernel, dim3((R + 3) / 4), dim3(256), 0, st, x, g, b, xb, R, d);
-  return hipGetLastError();
+  switch (d / 64) {   // d = 64 * heads, heads <= 32
+#define SD_LN_CASE(P) case P: return ln_launch<P>(st, x, g, b, xb, R);
+    SD_LN_CASE(1) SD_LN_CASE(2) SD_LN_CASE(3) SD_LN_CASE(4) SD_LN_CASE(5) SD_LN_CASE(6) SD_LN_CASE(7) SD_LN_CASE(8)
+    SD_LN_CASE(9) SD_LN_CASE(10) SD_LN_CASE(11) SD_LN_CASE(12) SD_LN_CASE(13) SD_LN_CASE(14) SD_LN_CASE(15)
+    SD_LN_CASE(16) SD_LN_CASE(17) SD_LN_CASE(18) SD_LN_CASE(19) SD_LN_CASE(20) SD_LN_CASE(21) SD_LN_CASE(22)
+    SD_LN_CASE(23) SD_LN_CASE(24) SD_LN_CASE(25) SD_LN_CASE(26) SD_LN_CASE(27) SD_LN_CASE(28) SD_LN_CASE(29)
+    SD_LN_CASE(30) SD_LN_CASE(31) SD_LN_CASE(32)
+#undef SD_LN_CASE
+    default: return hipErrorInvalidValue;
+  }
 }
 
 __global__ void fill_i32_kernel(int* p, int v, long n) {
@@ -117,93 +133,92 @@ hipError_t assemble_verify(hipStream_t st, const SeqState& s, const RowMap& rm, 
 }
 
 // ----------------------------------------------------------------------------- acceptance
-// One wave per sequence.  For each row the per-tile partials are merged:
+// Stage 1, one wave per row: merge the per-tile partials of the vocabulary kernel into
 //   m = max logit, arg-max = lowest column among maxima, LSE, z_d = logit of the scored
 //   draft, s_1 >= s_2 >= ... the kTopN largest logits (with multiplicity).
+__global__ __launch_bounds__(64) void merge_rows_kernel(const float* __restrict__ part, int n_tiles, int R,
+                                                        float* __restrict__ row_stats) {
+  const int r = blockIdx.x, lane = threadIdx.x;
+  if (r >= R) return;
+  const float* pr = part + (size_t)r * n_tiles * kPartF;
+  float m = kNegInf, zd = kNegInf;
+  int am = 0x7fffffff;
+  float top[kTopN];
+#pragma unroll
+  for (int t = 0; t < kTopN; ++t) top[t] = kNegInf;
+  for (int t = lane; t < n_tiles; t += 64) {
+    const float* p = pr + (size_t)t * kPartF;
+    f32x4 p0 = *reinterpret_cast<const f32x4*>(p), p1 = *reinterpret_cast<const f32x4*>(p + 4),
+          p2 = *reinterpret_cast<const f32x4*>(p + 8);
+    float tm = p0[0];
+    int ti = __float_as_int(p0[1]);
+    if (tm > m || (tm == m && ti < am)) { m = tm; am = ti; }
+    zd = fmaxf(zd, p0[3]);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) { top_insert<kTopN>(top, p1[q]); top_insert<kTopN>(top, p2[q]); }
+  }
+  const float gm = wave_max(m);
+  int cand = (m == gm) ? am : 0x7fffffff;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cand = min(cand, __shfl_xor(cand, o, 64));
+  zd = wave_max(zd);
+  float se = 0.f;
+  for (int t = lane; t < n_tiles; t += 64) {
+    const float* p = pr + (size_t)t * kPartF;
+    se += p[2] * __expf(p[0] - gm);
+  }
+  se = wave_sum(se);
+  const float lse = gm + __logf(se);
+  // global top list: kTopN rounds of "largest head over the lanes, pop it there"
+  float gtop[kTopN];
+  int head = 0;
+#pragma unroll
+  for (int q = 0; q < kTopN; ++q) {
+    float mine = kNegInf;
+#pragma unroll
+    for (int t = 0; t < kTopN; ++t) if (t == head) mine = top[t];
+    const float best = wave_max(mine);
+    gtop[q] = best;
+    const unsigned long long mask = __ballot(mine == best && best > kNegInf);
+    if (mask != 0ull && lane == (int)__builtin_ctzll(mask)) ++head;   // lowest holder pops
+  }
+  if (lane == 0) {
+    float* rs = row_stats + (size_t)r * (4 + kTopN);
+    rs[0] = gm; rs[1] = (float)cand; rs[2] = lse; rs[3] = zd;
+#pragma unroll
+    for (int q = 0; q < kTopN; ++q) rs[4 + q] = gtop[q];
+  }
+}
+hipError_t merge_rows(hipStream_t st, const float* part, int n_tiles, int R, float* row_stats) {
+  if (R <= 0) return hipSuccess;
+  hipLaunchKernelGGL(merge_rows_kernel, dim3(R), dim3(64), 0, st, part, n_tiles, R, row_stats);
+  return hipGetLastError();
+}
+
+// Stage 2, one thread per sequence (paper Sec. 3.2):
 // Eq. 8:  log P(draft) >= log P(beta-th ranked)   <=>  z_d >= s_beta
 // Eq. 9:  log P(top-1) - log P(draft) <= tau      <=>  m - z_d <= tau
 // (log-softmax subtracts the same LSE from every logit of the row).  a = number of leading
 // rows that pass; next = arg-max of row a.
-__global__ __launch_bounds__(64) void accept_kernel(const float* __restrict__ part, int n_tiles, RowMap rm,
-                                                    SeqState s, int B, int k, int beta, float tau, int pad_id,
-                                                    float* __restrict__ row_stats, int* __restrict__ accept_len,
-                                                    int* __restrict__ next_token) {
-  const int b = blockIdx.x, lane = threadIdx.x;
+__global__ void accept_kernel(const float* __restrict__ row_stats, SeqState s, int B, int k, int beta, float tau,
+                              int pad_id, int* __restrict__ accept_len, int* __restrict__ next_token) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
   const int T = k + 1;
   int a = 0;
-  bool open = true;          // still in the leading run of accepted drafts
-  int next = pad_id;
-  for (int i = 0; i < T; ++i) {
-    const int r = b * T + i;
-    const float* pr = part + (size_t)r * n_tiles * kPartF;
-    float m = kNegInf, zd = kNegInf;
-    int am = 0x7fffffff;
-    float top[kTopN];
-#pragma unroll
-    for (int t = 0; t < kTopN; ++t) top[t] = kNegInf;
-    for (int t = lane; t < n_tiles; t += 64) {
-      const float* p = pr + (size_t)t * kPartF;
-      float tm = p[0];
-      int ti = __float_as_int(p[1]);
-      if (tm > m || (tm == m && ti < am)) { m = tm; am = ti; }
-      zd = fmaxf(zd, p[3]);
-#pragma unroll
-      for (int q = 0; q < kTopN; ++q) top_insert<kTopN>(top, p[4 + q]);
-    }
-    // wave merge of max / arg-max / draft logit
-    float gm = wave_max(m);
-    int cand = (m == gm) ? am : 0x7fffffff;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) cand = min(cand, __shfl_xor(cand, o, 64));
-    zd = wave_max(zd);
-    // log-sum-exp relative to the global max
-    float se = 0.f;
-    for (int t = lane; t < n_tiles; t += 64) {
-      const float* p = pr + (size_t)t * kPartF;
-      se += p[2] * __expf(p[0] - gm);
-    }
-    se = wave_sum(se);
-    const float lse = gm + __logf(se);
-    // global top list: kTopN rounds of "largest head over the lanes, pop it there"
-    float gtop[kTopN];
-    int head = 0;
-#pragma unroll
-    for (int q = 0; q < kTopN; ++q) {
-      float mine = kNegInf;
-#pragma unroll
-      for (int t = 0; t < kTopN; ++t) if (t == head) mine = top[t];
-      float best = wave_max(mine);
-      gtop[q] = best;
-      // the lowest lane holding the best pops
-      unsigned long long mask = __ballot(mine == best && best > kNegInf);
-      if (mask != 0ull && lane == (int)__builtin_ctzll(mask)) ++head;
-    }
-    if (lane == 0) {
-      float* rs = row_stats + (size_t)r * (4 + kTopN);
-      rs[0] = gm; rs[1] = (float)cand; rs[2] = lse; rs[3] = zd;
-#pragma unroll
-      for (int q = 0; q < kTopN; ++q) rs[4 + q] = gtop[q];
-    }
-    float sbeta = kNegInf;
-#pragma unroll
-    for (int q = 0; q < kTopN; ++q) if (q == beta - 1) sbeta = gtop[q];
-    if (open) {
-      next = cand;           // arg-max of the first row not (yet) passed
-      bool ok = (i < k) && (zd >= sbeta) && (gm - zd <= tau);
-      if (ok) ++a; else open = false;
-    }
+  for (; a < k; ++a) {
+    const float* rs = row_stats + (size_t)(b * T + a) * (4 + kTopN);
+    const float zd = rs[3];
+    if (!(zd >= rs[4 + beta - 1] && rs[0] - zd <= tau)) break;
   }
-  if (lane == 0) {
-    bool fin = s.finished[b] != 0;
-    accept_len[b] = fin ? 0 : a;
-    next_token[b] = fin ? pad_id : next;
-  }
+  const bool fin = s.finished[b] != 0;
+  accept_len[b] = fin ? 0 : a;
+  next_token[b] = fin ? pad_id : (int)row_stats[(size_t)(b * T + a) * (4 + kTopN) + 1];
 }
-hipError_t accept_rows(hipStream_t st, const float* part, int n_tiles, const RowMap& rm, const SeqState& s,
-                       int B, int k, int beta, float tau, int pad_id, float* row_stats, int* accept_len,
-                       int* next_token) {
-  hipLaunchKernelGGL(accept_kernel, dim3(B), dim3(64), 0, st, part, n_tiles, rm, s, B, k, beta, tau, pad_id,
-                     row_stats, accept_len, next_token);
+hipError_t accept_rows(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k, int beta,
+                       float tau, int pad_id, int* accept_len, int* next_token) {
+  hipLaunchKernelGGL(accept_kernel, blocks_for(B, 64), dim3(64), 0, st, row_stats, s, B, k, beta, tau, pad_id,
+                     accept_len, next_token);
   return hipGetLastError();
 }
 
@@ -341,7 +356,8 @@ hipError_t get_output(hipStream_t st, const SeqState& s, int* tokens, int out_ca
 }
 
 // ----------------------------------------------------------------------------- cache layout
-// flat [B][L][H*64]  <->  cache [B][H][Lcap][64]; one 16-byte chunk per thread
+// flat [B][L][H*64]  <->  key cache [B][H][Lcap][64] (16-byte chunks) or transposed value
+// cache [B][H][64][Lcap] (element-wise; only used to load / inspect caches)
 __global__ void cache_flat_kernel(bf16* cache, bf16* flat, int B, int H, int Lcap, int L, int to_flat) {
   long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
   long n = (long)B * L * H * 8;
@@ -355,17 +371,35 @@ __global__ void cache_flat_kernel(bf16* cache, bf16* flat, int B, int H, int Lca
   uint4* f = reinterpret_cast<uint4*>(flat + (((size_t)b * L + l) * H + h) * kHeadDim + ch * 8);
   if (to_flat) *f = *c; else *c = *f;
 }
-hipError_t cache_from_flat(hipStream_t st, bf16* cache, const bf16* flat, int B, int H, int Lcap, int L) {
-  long n = (long)B * L * H * 8;
-  if (n <= 0) return hipSuccess;
-  hipLaunchKernelGGL(cache_flat_kernel, blocks_for(n, 256), dim3(256), 0, st, cache, const_cast<bf16*>(flat), B, H, Lcap, L, 0);
+__global__ void cache_flat_t_kernel(bf16* cache, bf16* flat, int B, int H, int Lcap, int L, int to_flat) {
+  long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  long n = (long)B * L * H * kHeadDim;
+  if (idx >= n) return;
+  int e = (int)(idx & 63);
+  long t = idx >> 6;
+  int h = (int)(t % H); t /= H;
+  int l = (int)(t % L);
+  int b = (int)(t / L);
+  bf16* c = cache + (((size_t)b * H + h) * kHeadDim + e) * Lcap + l;
+  bf16* f = flat + (((size_t)b * L + l) * H + h) * kHeadDim + e;
+  if (to_flat) *f = *c; else *c = *f;
+}
+static hipError_t cache_flat(hipStream_t st, bf16* cache, bf16* flat, int B, int H, int Lcap, int L, bool tr, int to_flat) {
+  if ((long)B * L <= 0) return hipSuccess;
+  if (tr) {
+    long n = (long)B * L * H * kHeadDim;
+    hipLaunchKernelGGL(cache_flat_t_kernel, blocks_for(n, 256), dim3(256), 0, st, cache, flat, B, H, Lcap, L, to_flat);
+  } else {
+    long n = (long)B * L * H * 8;
+    hipLaunchKernelGGL(cache_flat_kernel, blocks_for(n, 256), dim3(256), 0, st, cache, flat, B, H, Lcap, L, to_flat);
+  }
   return hipGetLastError();
 }
-hipError_t cache_to_flat(hipStream_t st, const bf16* cache, bf16* flat, int B, int H, int Lcap, int L) {
-  long n = (long)B * L * H * 8;
-  if (n <= 0) return hipSuccess;
-  hipLaunchKernelGGL(cache_flat_kernel, blocks_for(n, 256), dim3(256), 0, st, const_cast<bf16*>(cache), flat, B, H, Lcap, L, 1);
-  return hipGetLastError();
+hipError_t cache_from_flat(hipStream_t st, bf16* cache, const bf16* flat, int B, int H, int Lcap, int L, bool tr) {
+  return cache_flat(st, cache, const_cast<bf16*>(flat), B, H, Lcap, L, tr, 0);
+}
+hipError_t cache_to_flat(hipStream_t st, const bf16* cache, bf16* flat, int B, int H, int Lcap, int L, bool tr) {
+  return cache_flat(st, const_cast<bf16*>(cache), flat, B, H, Lcap, L, tr, 1);
 }
 
 }  // namespace sd
