@@ -64,7 +64,7 @@ typedef struct {
   int32_t max_tgt;   /* longest decoder stream: j <= max_tgt                         */
 } specdec_limits;
 
-enum { SPECDEC_BETA_MAX = 8 }; /* top-beta lists are kept to this depth (paper uses <= 5, Table 4) */
+enum { SPECDEC_ROW_STATS = 8 }; /* floats per row reported by specdec_get_row_stats */
 
 /* ---- life cycle -------------------------------------------------------------------- */
 int specdec_create(specdec_ctx** out, const specdec_limits* limits); /* host only */
@@ -135,7 +135,7 @@ int specdec_draft(specdec_ctx* ctx, int32_t k, int32_t* draft, void* stream);
  * appended after the cached ones), vocabulary projection and log-softmax statistics fused
  * with the acceptance test.  Draft i is accepted iff drafts 1..i-1 were and, on row i-1,
  *   log P(y~) >= log P(beta-th ranked token)   and   log P(top-1) - log P(y~) <= tau.
- * beta = 1, tau = 0 is the strict top-1 rule.  Outputs (device int32 [B]):
+ * beta = 1, tau = 0 is the strict top-1 rule; 1 <= beta <= vocab, tau >= 0.  Outputs (device int32 [B]):
  *   accept_len = number of accepted drafts a (= c - 1),
  *   next_token = the verifier's arg-max token on row a (lowest index among maxima); when all
  *   k drafts are accepted this is the token after the last draft.
@@ -168,9 +168,10 @@ int specdec_get_output(specdec_ctx* ctx, int32_t* tokens, int32_t out_cap, int32
  * cached length hold whatever the last pass wrote there. */
 int specdec_get_cache(specdec_ctx* ctx, specdec_role role, void* k_cache, void* v_cache, int32_t L,
                       void* stream);
-/* Per-row statistics of the latest specdec_verify, device fp32 [B, k+1, 4 + SPECDEC_BETA_MAX]:
- * {max logit, arg-max (as float), log-sum-exp, logit of the draft scored on this row (or
- * -inf on the last row), the SPECDEC_BETA_MAX largest logits in descending order}. */
+/* Per-row statistics of the latest specdec_verify, device fp32 [B, k+1, SPECDEC_ROW_STATS]:
+ * {max logit, arg-max (as float), log-sum-exp, logit z_d of the draft scored on this row (-inf
+ * on the last row), number of logits strictly larger than z_d (as float), 0, 0, 0}.
+ * log P(token) = logit - log-sum-exp. */
 int specdec_get_row_stats(specdec_ctx* ctx, float* stats, void* stream);
 
 /* ---- timing of one kernel kind ----------------------------------------------------------- */

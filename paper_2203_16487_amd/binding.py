@@ -24,8 +24,8 @@ SPECDEC_ERR_HIP = -4
 SPECDEC_ERR_NO_DEVICE = -5
 SPECDEC_VERIFIER = 0
 SPECDEC_DRAFTER = 1
-SPECDEC_BETA_MAX = 8
-ROW_STATS = 4 + SPECDEC_BETA_MAX
+SPECDEC_ROW_STATS = 8
+ROW_STATS = SPECDEC_ROW_STATS
 
 
 class specdec_model_desc(C.Structure):

@@ -42,7 +42,8 @@ struct Model {
   bf16* att = nullptr;       // [Rmax][d]
   bf16* hid = nullptr;       // [Rmax][F]
   float* part = nullptr;     // [Rmax][n_tiles][kPartF]
-  float* row_stats = nullptr;  // [Rmax][4+kTopN]
+  float* row_stats = nullptr;  // [Rmax][kRowStats]
+  float* zd = nullptr;       // [Rmax] logit of the draft each row scores
   // encoder activations, rows = Bmax * Scap
   float* ex = nullptr;
   bf16 *exb = nullptr, *eqkv = nullptr, *eatt = nullptr, *ehid = nullptr;
@@ -110,7 +111,7 @@ inline void prof_end(specdec_ctx* c, hipStream_t st) {
 bool desc_ok(const specdec_model_desc* d) {
   return d && d->enc_layers >= 0 && d->dec_layers >= 1 && d->n_heads >= 1 && d->n_heads <= 32 &&
          d->d_model == 64 * d->n_heads && d->d_ffn >= 64 && d->d_ffn % 64 == 0 && d->d_ffn <= 16384 &&
-         d->vocab >= SPECDEC_BETA_MAX && d->vocab <= (1 << 24) && d->bos_id >= 0 && d->bos_id < d->vocab &&
+         d->vocab >= 8 && d->vocab <= (1 << 24) && d->bos_id >= 0 && d->bos_id < d->vocab &&
          d->eos_id >= 0 && d->eos_id < d->vocab && d->pad_id >= 0 && d->pad_id < d->vocab &&
          d->mask_id >= 0 && d->mask_id < d->vocab;
 }
@@ -193,7 +194,8 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   t.att = cv.take<bf16>(Rmax * D);
   t.hid = cv.take<bf16>(Rmax * F);
   t.part = cv.take<float>(Rmax * n_tiles * sd::kPartF);
-  t.row_stats = cv.take<float>(Rmax * (4 + SPECDEC_BETA_MAX));
+  t.row_stats = cv.take<float>(Rmax * sd::kRowStats);
+  t.zd = cv.take<float>(Rmax);
   t.rm.row_b = cv.take<int>(Rmax);
   t.rm.row_pos = cv.take<int>(Rmax);
   t.rm.row_tok = cv.take<int>(Rmax);
@@ -214,7 +216,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
     m->kv_layer = t.kv_layer; m->xkv_layer = t.xkv_layer;
     m->pe = t.pe; m->kc = t.kc; m->vc = t.vc; m->xk = t.xk; m->xv = t.xv;
     m->x = t.x; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
-    m->part = t.part; m->row_stats = t.row_stats; m->rm = t.rm;
+    m->part = t.part; m->row_stats = t.row_stats; m->zd = t.zd; m->rm = t.rm;
     m->ex = t.ex; m->exb = t.exb; m->eqkv = t.eqkv; m->eatt = t.eatt; m->ehid = t.ehid;
     m->etok = t.etok; m->epos = t.epos;
   }
@@ -238,7 +240,7 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
     sd::AttnArgs a{};
     a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
     a.k = kc; a.k_b = (long)H * Lcap * 64; a.k_h = (long)Lcap * 64; a.k_row = 64;
-    a.v = vc; a.v_b = (long)H * Lcap * 64; a.v_h = (long)Lcap * 64; a.v_row = Lcap;
+    a.v = vc; a.v_b = (long)H * Lcap * 64; a.v_h = (long)Lcap * 64;
     a.o = m.att; a.o_b = (long)T * D; a.o_row = D;
     a.q_count = m.rm.seq_rows; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
     a.T = T; a.H = H; a.B = B;
@@ -248,7 +250,7 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
     LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln1g, L.ln1b, m.xb, R, D));
     LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.xb, D, L.cwq, R, D, D, L.cbq, m.q, D, false));
     a.k = m.xk + m.xkv_layer * l; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64;
-    a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_row = Scap;
+    a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64;
     a.lim_row = nullptr; a.lim_seq = c->st.src_len;
     a.key_split = c->S_cur > 256;
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
@@ -480,7 +482,7 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
   if (k < 1) return fail(c, SPECDEC_ERR_INVALID_ARG, "k = %d", k);
   if (k > c->lim.k_max) return fail(c, SPECDEC_ERR_TOO_LARGE, "k = %d exceeds k_max = %d", k, c->lim.k_max);
   Model& m = c->m[SPECDEC_VERIFIER];
-  if (beta < 1 || beta > SPECDEC_BETA_MAX || beta > m.d.vocab) return fail(c, SPECDEC_ERR_INVALID_ARG, "beta = %d outside [1, %d]", beta, SPECDEC_BETA_MAX);
+  if (beta < 1 || beta > m.d.vocab) return fail(c, SPECDEC_ERR_INVALID_ARG, "beta = %d outside [1, vocab]", beta);
   if (!(tau >= 0.f) || !std::isfinite(tau)) return fail(c, SPECDEC_ERR_INVALID_ARG, "tau must be finite and >= 0");
   if (c->uncached_ub[0] > 0 && !c->trusted[0]) return fail(c, SPECDEC_ERR_BAD_STATE, "verifier cache does not cover the stream: call specdec_prefill or specdec_load_cache");
   hipStream_t st = S(stream);
@@ -489,8 +491,8 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
   rc = decoder_layers(c, m, B, T, st);
   if (rc) return rc;
   const int n_tiles = (m.d.vocab + 127) / 128;
-  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.part, logits));
-  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, n_tiles, R, m.row_stats));
+  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.zd, m.part, logits));
+  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
   LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::accept_rows(st, m.row_stats, c->st, B, k, beta, tau, m.d.pad_id, accept_len, next_token));
   c->last_k = k;
   return SPECDEC_OK;
@@ -575,7 +577,7 @@ int specdec_get_row_stats(specdec_ctx* c, float* stats, void* stream) {
   if (rc) return rc;
   if (!stats) return fail(c, SPECDEC_ERR_INVALID_ARG, "null stats");
   if (c->last_k <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "no verification pass to report");
-  const size_t n = (size_t)c->B * (c->last_k + 1) * (4 + SPECDEC_BETA_MAX);
+  const size_t n = (size_t)c->B * (c->last_k + 1) * SPECDEC_ROW_STATS;
   HIPCHK(c, hipMemcpyAsync(stats, c->m[0].row_stats, n * sizeof(float), hipMemcpyDeviceToDevice, S(stream)));
   return SPECDEC_OK;
 }

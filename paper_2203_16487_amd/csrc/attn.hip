@@ -10,8 +10,8 @@
 // Row i of key tile t stands for key c0 + 8*(i/4) + 4*t + i%4, so that the eight scores a lane
 // holds after the two S^T tiles (q = lane%16, keys c0 + 8*(lane/16) .. +7) are already the B
 // operand of the second product, and its V^T operand is one contiguous 16-byte load.  This is
-// why values are cached transposed ([64][L]).  Both results keep q = lane%16, so the running
-// max / sum of a query live in the lanes that hold its accumulators.
+// why values are cached in blocks of 8 keys (vt_off).  Both results keep q = lane%16, so the
+// running max / sum of a query live in the lanes that hold its accumulators.
 //
 // A query sees keys [0, limit): causal verify rows (limit grows by one per row), the
 // drafter's mask slots (limit = whole block), padded cross / encoder attention (limit = source
@@ -86,9 +86,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   const bf16* vbase = a.v + b * a.v_b + h * a.v_h;
   const int kclamp = max(kmax - 1, 0);
 
-  for (int c0 = kw * 32; c0 < kmax; c0 += kstep * 32) {
+  // operands of one 32-key chunk (8 x 16 B per lane); the next chunk is fetched while the
+  // current one is multiplied, so a wave pays the memory latency once, not once per chunk
+  auto load_chunk = [&](int c0, bf16x8 (&kf)[2][2], bf16x8 (&vf)[4]) {
     // K operands: tile t, row lq  <->  key c0 + 8*(lq/4) + 4*t + lq%4
-    bf16x8 kf[2][2], vf[4];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int key = min(c0 + 8 * (lq >> 2) + 4 * t + (lq & 3), kclamp);
@@ -96,10 +97,18 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
       kf[t][0] = *reinterpret_cast<const bf16x8*>(kp);
       kf[t][1] = *reinterpret_cast<const bf16x8*>(kp + 32);
     }
-    // V^T operands: row e = et*16 + lq, keys c0 + 8g .. +7
+    // V operands: dim e = et*16 + lq, keys c0 + 8g .. +7 (one block of the key-blocked layout)
 #pragma unroll
     for (int et = 0; et < 4; ++et)
-      vf[et] = *reinterpret_cast<const bf16x8*>(vbase + (long)(et * 16 + lq) * a.v_row + c0 + 8 * g);
+      vf[et] = *reinterpret_cast<const bf16x8*>(vbase + vt_off(c0 + 8 * g, et * 16 + lq));
+  };
+  bf16x8 kf[2][2], vf[4], kn[2][2], vn[4];
+  const int cfirst = kw * 32, cstep = kstep * 32;
+  if (cfirst < kmax) load_chunk(cfirst, kf, vf);
+
+  for (int c0 = cfirst; c0 < kmax; c0 += cstep) {
+    const bool more = c0 + cstep < kmax;
+    if (more) load_chunk(c0 + cstep, kn, vn);
     if (c0 + 32 > kmax) {
       const int nvalid = kmax - (c0 + 8 * g);
 #pragma unroll
@@ -146,6 +155,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
         for (int r = 0; r < 4; ++r) oacc[qt][et][r] *= alpha;
         oacc[qt][et] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[et], pf, oacc[qt][et], 0, 0, 0);
       }
+    }
+    if (more) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) { kf[t][0] = kn[t][0]; kf[t][1] = kn[t][1]; }
+#pragma unroll
+      for (int et = 0; et < 4; ++et) vf[et] = vn[et];
     }
   }
 

@@ -17,6 +17,14 @@ constexpr int kHeadDim = 64;   // d_model = 64 * n_heads for every model in the 
 constexpr int kTopN = 8;       // depth of the per-row top lists (SPECDEC_BETA_MAX)
 constexpr float kNegInf = -__builtin_inff();
 
+// Value caches are stored in blocks of 8 keys: element (key, e) of one (sequence, head) lies at
+//   ((key / 8) * 64 + e) * 8 + key % 8
+// so the 8 consecutive keys that one lane feeds to the P.V product are one 16-byte load, and
+// the 64 dims of one key block are 1 KB contiguous.
+__host__ __device__ __forceinline__ long vt_off(int key, int e) {
+  return ((long)(key >> 3) * kHeadDim + e) * 8 + (key & 7);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);

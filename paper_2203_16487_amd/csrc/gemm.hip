@@ -75,8 +75,8 @@ struct EpiBf16 {
 
 // Decoder self-attention projection: columns [0,d) are queries, [d,2d) keys, [2d,3d) values.
 // Keys go straight into the cache row of the token they belong to and values into the
-// transposed value cache: this is the "append" of the KV cache, fused into the projection.
-//   key cache   [B][H][Lcap][64]      value cache [B][H][64][Lcap]
+// key-blocked value cache: this is the "append" of the KV cache, fused into the projection.
+//   key cache   [B][H][Lcap][64]      value cache [B][H][Lcap/8][64][8] (see vt_off)
 struct EpiQkvAppend {
   const bf16* bias;
   bf16* q;
@@ -98,15 +98,15 @@ struct EpiQkvAppend {
     if (part == 1) {
       *reinterpret_cast<bf16x8*>(kc + (((size_t)b * H + h) * Lcap + pos) * kHeadDim + e) = o;
     } else {
-      bf16* dst = vc + (((size_t)b * H + h) * kHeadDim + e) * Lcap + pos;
+      bf16* dst = vc + ((size_t)b * H + h) * Lcap * kHeadDim + vt_off(pos, e);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) dst[(size_t)i * Lcap] = o[i];
+      for (int i = 0; i < 8; ++i) dst[i * 8] = o[i];
     }
   }
 };
 
 // Cross-attention keys/values of the encoder memory: row m = b*S + s.
-//   xk [B][H][Scap][64]     xv [B][H][64][Scap] (transposed like the value cache)
+//   xk [B][H][Scap][64]     xv [B][H][Scap/8][64][8] (blocked like the value cache)
 struct EpiCrossKv {
   const bf16* bias;
   bf16* xk;
@@ -120,9 +120,9 @@ struct EpiCrossKv {
     if (part == 0) {
       *reinterpret_cast<bf16x8*>(xk + (((size_t)b * H + h) * Scap + s) * kHeadDim + e) = o;
     } else {
-      bf16* dst = xv + (((size_t)b * H + h) * kHeadDim + e) * Scap + s;
+      bf16* dst = xv + ((size_t)b * H + h) * Scap * kHeadDim + vt_off(s, e);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) dst[(size_t)i * Scap] = o[i];
+      for (int i = 0; i < 8; ++i) dst[i * 8] = o[i];
     }
   }
 };
@@ -203,17 +203,55 @@ hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, in
 }
 
 // ----------------------------------------------------------------------------- vocabulary
+// Rank test without a sort (paper Eq. 8): the draft is inside the top beta iff fewer than
+// beta logits are strictly larger than its own.  Its logit z_d is needed before the big
+// product is scanned, so a tiny pre-pass computes it -- with the SAME instruction sequence
+// (MFMA 32x32x16, k blocks of 16 in ascending order, same operand roles) that produces that
+// very element in the main kernel.  The two values are therefore bit-identical and the
+// count is exactly the count over the row the main kernel sees.
+//
+// One wave = 32 rows: D[i][j] = x_i . E[draft_j]; the diagonal is kept.
+__global__ __launch_bounds__(64) void draft_logit_kernel(const bf16* __restrict__ A, const bf16* __restrict__ E,
+                                                         int M, int V, int K, const int* __restrict__ row_draft,
+                                                         float* __restrict__ zd_out) {
+  const int lane = threadIdx.x, lrow = lane & 31, lhalf = lane >> 5;
+  const int r = blockIdx.x * 32 + lrow;
+  const int rr = min(r, M - 1);
+  const int t = row_draft[rr];
+  const bool has = (r < M) && t >= 0 && t < V;
+  const bf16* ap = A + (size_t)rr * K + lhalf * 8;
+  const bf16* bp = E + (size_t)(has ? t : 0) * K + lhalf * 8;
+  f32x16 acc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll 8
+  for (int kb = 0; kb < K / 16; ++kb) {
+    bf16x8 a = *reinterpret_cast<const bf16x8*>(ap + kb * 16);
+    bf16x8 b = *reinterpret_cast<const bf16x8*>(bp + kb * 16);
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+  }
+  // element (i, j): j = lane%32, i = 8*(reg/4) + 4*(lane/32) + reg%4; the diagonal j = i sits in
+  // the lane half (j/4)%2, register 4*(j/8) + j%4
+  if (lhalf == ((lrow >> 2) & 1) && r < M) {
+    const int reg = 4 * (lrow >> 3) + (lrow & 3);
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) if (i == reg) v = acc[i];
+    zd_out[r] = has ? v : kNegInf;
+  }
+}
+
 // One block = 128 rows x 128 vocabulary columns.  After the K loop the fp32 tile goes through
 // LDS so that two threads own one row (64 columns each); each scans its columns once for
-// max / arg-max / top list / draft logit and once for the sum of exponentials, the two halves
-// are merged with lane shuffles, and one partial record per (row, tile) is written.  Logits
-// never reach memory unless the caller asks for them.
+// max / arg-max / number of logits above the draft's and once for the sum of exponentials, the
+// two halves are merged with lane shuffles, and one 16-byte partial record per (row, tile) is
+// written.  Logits never reach memory unless the caller asks for them.
 typedef GemmCfg<128, 128, 2> CfgVocab;
 
 __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* __restrict__ A,
                                                                    const bf16* __restrict__ E, int M,
                                                                    int V, int K, int MT, int NT,
-                                                                   const int* __restrict__ row_draft,
+                                                                   const float* __restrict__ zd_row,
                                                                    float* __restrict__ part,
                                                                    float* __restrict__ logits) {
   extern __shared__ __attribute__((aligned(1024))) bf16 smem[];
@@ -229,53 +267,41 @@ __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* _
   const int tid = threadIdx.x;
   const int row = tid >> 1, half = tid & 1;
   const int m = m0 + row;
-  const int tdraft = (m < M) ? row_draft[m] : -1;
-  float best = kNegInf, zd = kNegInf;
-  int besti = 0x7fffffff;
-  float top[kTopN];
-#pragma unroll
-  for (int i = 0; i < kTopN; ++i) top[i] = kNegInf;
+  const float zd = (m < M) ? zd_row[m] : kNegInf;   // -inf on rows that score no draft: count unused
+  float best = kNegInf;
+  int besti = 0x7fffffff, cnt = 0;
   // lane (row, half) visits column half*64 + (j + row + 32*half) % 64 at step j: the 64 lanes
   // of a wave hit 64 different banks
   const int rot = row + 32 * half;
+#pragma unroll 8
   for (int j = 0; j < 64; ++j) {
-    int c = half * 64 + ((j + rot) & 63);
-    int n = n0 + c;
-    float v = cs[cs_off<128>(row, c)];
+    const int c = half * 64 + ((j + rot) & 63);
+    const int n = n0 + c;
+    const float v = cs[cs_off<128>(row, c)];
     if (n < V) {
       if (v > best || (v == best && n < besti)) { best = v; besti = n; }
-      top_insert<kTopN>(top, v);
-      if (n == tdraft) zd = v;
+      cnt += (v > zd) ? 1 : 0;
     }
   }
   float se = 0.f;
+#pragma unroll 8
   for (int j = 0; j < 64; ++j) {
-    int c = half * 64 + ((j + rot) & 63);
+    const int c = half * 64 + ((j + rot) & 63);
     if (n0 + c < V) se += __expf(cs[cs_off<128>(row, c)] - best);
   }
   // merge the two halves of the row (lanes tid and tid^1)
-  float obest = __shfl_xor(best, 1, 64);
-  int obesti = __shfl_xor(besti, 1, 64);
-  float ose = __shfl_xor(se, 1, 64);
-  float ozd = __shfl_xor(zd, 1, 64);
-  float otop[kTopN];
-#pragma unroll
-  for (int i = 0; i < kTopN; ++i) otop[i] = __shfl_xor(top[i], 1, 64);
-  float nb = fmaxf(best, obest);
+  const float obest = __shfl_xor(best, 1, 64);
+  const int obesti = __shfl_xor(besti, 1, 64);
+  const float ose = __shfl_xor(se, 1, 64);
+  const int ocnt = __shfl_xor(cnt, 1, 64);
+  const float nb = fmaxf(best, obest);
   float tot = 0.f;
   if (best > kNegInf) tot += se * __expf(best - nb);
   if (obest > kNegInf) tot += ose * __expf(obest - nb);
-  int nbi = (obest > best || (obest == best && obesti < besti)) ? obesti : besti;
-#pragma unroll
-  for (int i = 0; i < kTopN; ++i) top_insert<kTopN>(top, otop[i]);
+  const int nbi = (obest > best || (obest == best && obesti < besti)) ? obesti : besti;
   if (half == 0 && m < M) {
-    float* p = part + ((size_t)m * NT + nt) * kPartF;
-    p[0] = nb;
-    p[1] = __int_as_float(nbi);
-    p[2] = tot;
-    p[3] = fmaxf(zd, ozd);
-#pragma unroll
-    for (int i = 0; i < kTopN; ++i) p[4 + i] = top[i];
+    f32x4 rec = {nb, __int_as_float(nbi), tot, __int_as_float(cnt + ocnt)};
+    *reinterpret_cast<f32x4*>(part + ((size_t)m * NT + nt) * kPartF) = rec;
   }
   if (logits) {
     for (int idx = tid; idx < 128 * 128; idx += CfgVocab::kThreads) {
@@ -286,7 +312,7 @@ __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* _
 }
 
 hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int V, int K,
-                       const int* row_draft, float* part, float* logits) {
+                       const int* row_draft, float* zd_row, float* part, float* logits) {
   if (M <= 0) return hipSuccess;
   static bool attr_done = false;
   if (!attr_done) {
@@ -295,9 +321,10 @@ hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int 
     if (e != hipSuccess) return e;
     attr_done = true;
   }
+  hipLaunchKernelGGL(draft_logit_kernel, dim3((M + 31) / 32), dim3(64), 0, st, A, E, M, V, K, row_draft, zd_row);
   const int MT = (M + 127) / 128, NT = (V + 127) / 128;
   hipLaunchKernelGGL(vocab_kernel, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
-                     A, E, M, V, K, MT, NT, row_draft, part, logits);
+                     A, E, M, V, K, MT, NT, zd_row, part, logits);
   return hipGetLastError();
 }
 

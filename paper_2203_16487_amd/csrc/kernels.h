@@ -39,21 +39,22 @@ hipError_t gemm_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, 
 hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
                          const bf16* bias, bf16* xk, bf16* xv, int S, int H, int Scap);
 
-// Vocabulary projection fused with per-row statistics.  For every row and every 128-column
-// vocabulary tile one partial record of kPartF floats is written to part[M][n_tiles][kPartF]:
-// {tile max, tile arg-max (int bits), sum exp(z - tile max), logit of column row_draft[m] if
-// it lies in the tile else -inf, the kTopN largest logits of the tile, descending}.
+// Vocabulary projection fused with per-row statistics.  zd_row [M] receives the logit of the
+// draft each row scores (-inf if none).  For every row and every 128-column vocabulary tile one
+// partial record of kPartF floats is written to part[M][n_tiles][kPartF]: {tile max, tile
+// arg-max (int bits), sum exp(z - tile max), number of tile logits > zd_row (int bits)}.
 // logits (optional, fp32 [M, V]) receives the full rows.
-constexpr int kPartF = 12;
+constexpr int kPartF = 4;
+constexpr int kRowStats = 8;   // floats per row of merged statistics
 hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int V, int K,
-                       const int* row_draft, float* part, float* logits);
+                       const int* row_draft, float* zd_row, float* part, float* logits);
 
 // ---- attn.hip ------------------------------------------------------------------------
 struct AttnArgs {
   const bf16* q;  long q_b, q_row;            // q + b*q_b + i*q_row + h*64
   const bf16* k;  long k_b, k_h, k_row;       // keys   [key][64]:  k + b*k_b + h*k_h + key*k_row
-  const bf16* v;  long v_b, v_h, v_row;       // values [64][key]:  v + b*v_b + h*v_h + e*v_row + key
-                                              //   (v_row % 32 == 0: whole 32-key chunks are read)
+  const bf16* v;  long v_b, v_h;              // values, key-blocked (vt_off): v + b*v_b + h*v_h + vt_off(key, e);
+                                              //   whole 32-key chunks are read: capacity % 32 == 0
   bf16* o;        long o_b, o_row;            // o + b*o_b + i*o_row + h*64
   const int* q_count;                         // [B] queries of sequence b (null: T)
   const int* lim_row;                         // [B*T] visible keys per query (null: lim_seq)
@@ -88,8 +89,10 @@ struct SeqState {       // device arrays of the bound state buffer, all [max_bat
 // rows of a verification pass: [u_j, drafts]; also stores the drafts for commit
 hipError_t assemble_verify(hipStream_t st, const SeqState& s, const RowMap& rm, const int* draft,
                            int B, int k, int V);
-// merge the vocabulary partials of every row into row_stats [R][4 + kTopN]
-hipError_t merge_rows(hipStream_t st, const float* part, int n_tiles, int R, float* row_stats);
+// merge the vocabulary partials of every row into row_stats [R][kRowStats] =
+// {max, arg-max, log-sum-exp, draft logit, number of logits above the draft's, 0, 0, 0}
+hipError_t merge_rows(hipStream_t st, const float* part, const float* zd_row, int n_tiles, int R,
+                      float* row_stats);
 // top-beta / tau rule on the merged rows and the leading-accept scan per sequence
 hipError_t accept_rows(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k,
                        int beta, float tau, int pad_id, int* accept_len, int* next_token);
@@ -104,10 +107,10 @@ hipError_t set_src_len(hipStream_t st, const SeqState& s, const int* src_len, in
 hipError_t set_cached(hipStream_t st, const SeqState& s, int role, const int* n, int B, int hi);
 hipError_t get_output(hipStream_t st, const SeqState& s, int* tokens, int out_cap, int* out_len,
                       int* finished, int B, int pad_id);
-// key cache [B][H][Lcap][64] / value cache [B][H][64][Lcap]  <->  flat [B][L][d]
+// key cache [B][H][Lcap][64] / key-blocked value cache  <->  flat [B][L][d]
 hipError_t cache_from_flat(hipStream_t st, bf16* cache, const bf16* flat, int B, int H, int Lcap,
-                           int L, bool transposed);
+                           int L, bool blocked);
 hipError_t cache_to_flat(hipStream_t st, const bf16* cache, bf16* flat, int B, int H, int Lcap,
-                         int L, bool transposed);
+                         int L, bool blocked);
 
 }  // namespace sd

@@ -134,72 +134,56 @@ hipError_t assemble_verify(hipStream_t st, const SeqState& s, const RowMap& rm, 
 
 // ----------------------------------------------------------------------------- acceptance
 // Stage 1, one wave per row: merge the per-tile partials of the vocabulary kernel into
-//   m = max logit, arg-max = lowest column among maxima, LSE, z_d = logit of the scored
-//   draft, s_1 >= s_2 >= ... the kTopN largest logits (with multiplicity).
-__global__ __launch_bounds__(64) void merge_rows_kernel(const float* __restrict__ part, int n_tiles, int R,
+//   m = max logit, arg-max = lowest column among maxima, LSE, and the number of logits that
+//   are strictly larger than the logit z_d of the draft this row scores.
+__global__ __launch_bounds__(64) void merge_rows_kernel(const float* __restrict__ part,
+                                                        const float* __restrict__ zd_row, int n_tiles, int R,
                                                         float* __restrict__ row_stats) {
   const int r = blockIdx.x, lane = threadIdx.x;
   if (r >= R) return;
   const float* pr = part + (size_t)r * n_tiles * kPartF;
-  float m = kNegInf, zd = kNegInf;
-  int am = 0x7fffffff;
-  float top[kTopN];
-#pragma unroll
-  for (int t = 0; t < kTopN; ++t) top[t] = kNegInf;
+  float m = kNegInf;
+  int am = 0x7fffffff, cnt = 0;
   for (int t = lane; t < n_tiles; t += 64) {
-    const float* p = pr + (size_t)t * kPartF;
-    f32x4 p0 = *reinterpret_cast<const f32x4*>(p), p1 = *reinterpret_cast<const f32x4*>(p + 4),
-          p2 = *reinterpret_cast<const f32x4*>(p + 8);
-    float tm = p0[0];
-    int ti = __float_as_int(p0[1]);
+    const f32x4 p = *reinterpret_cast<const f32x4*>(pr + (size_t)t * kPartF);
+    const float tm = p[0];
+    const int ti = __float_as_int(p[1]);
     if (tm > m || (tm == m && ti < am)) { m = tm; am = ti; }
-    zd = fmaxf(zd, p0[3]);
-#pragma unroll
-    for (int q = 0; q < 4; ++q) { top_insert<kTopN>(top, p1[q]); top_insert<kTopN>(top, p2[q]); }
+    cnt += __float_as_int(p[3]);
   }
   const float gm = wave_max(m);
   int cand = (m == gm) ? am : 0x7fffffff;
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) cand = min(cand, __shfl_xor(cand, o, 64));
-  zd = wave_max(zd);
+  for (int o = 32; o > 0; o >>= 1) {
+    cand = min(cand, __shfl_xor(cand, o, 64));
+    cnt += __shfl_xor(cnt, o, 64);
+  }
   float se = 0.f;
   for (int t = lane; t < n_tiles; t += 64) {
-    const float* p = pr + (size_t)t * kPartF;
+    const f32x4 p = *reinterpret_cast<const f32x4*>(pr + (size_t)t * kPartF);
     se += p[2] * __expf(p[0] - gm);
   }
   se = wave_sum(se);
-  const float lse = gm + __logf(se);
-  // global top list: kTopN rounds of "largest head over the lanes, pop it there"
-  float gtop[kTopN];
-  int head = 0;
-#pragma unroll
-  for (int q = 0; q < kTopN; ++q) {
-    float mine = kNegInf;
-#pragma unroll
-    for (int t = 0; t < kTopN; ++t) if (t == head) mine = top[t];
-    const float best = wave_max(mine);
-    gtop[q] = best;
-    const unsigned long long mask = __ballot(mine == best && best > kNegInf);
-    if (mask != 0ull && lane == (int)__builtin_ctzll(mask)) ++head;   // lowest holder pops
-  }
   if (lane == 0) {
-    float* rs = row_stats + (size_t)r * (4 + kTopN);
-    rs[0] = gm; rs[1] = (float)cand; rs[2] = lse; rs[3] = zd;
-#pragma unroll
-    for (int q = 0; q < kTopN; ++q) rs[4 + q] = gtop[q];
+    f32x4 a = {gm, (float)cand, gm + __logf(se), zd_row[r]};
+    f32x4 b = {(float)cnt, 0.f, 0.f, 0.f};
+    float* rs = row_stats + (size_t)r * kRowStats;
+    *reinterpret_cast<f32x4*>(rs) = a;
+    *reinterpret_cast<f32x4*>(rs + 4) = b;
   }
 }
-hipError_t merge_rows(hipStream_t st, const float* part, int n_tiles, int R, float* row_stats) {
+hipError_t merge_rows(hipStream_t st, const float* part, const float* zd_row, int n_tiles, int R, float* row_stats) {
   if (R <= 0) return hipSuccess;
-  hipLaunchKernelGGL(merge_rows_kernel, dim3(R), dim3(64), 0, st, part, n_tiles, R, row_stats);
+  hipLaunchKernelGGL(merge_rows_kernel, dim3(R), dim3(64), 0, st, part, zd_row, n_tiles, R, row_stats);
   return hipGetLastError();
 }
 
-// Stage 2, one thread per sequence (paper Sec. 3.2):
-// Eq. 8:  log P(draft) >= log P(beta-th ranked)   <=>  z_d >= s_beta
+// Stage 2, one thread per sequence (paper Sec. 3.2).  With z_d the draft's logit on its row:
+// Eq. 8:  log P(draft) >= log P(beta-th ranked)   <=>  #{v : z_v > z_d} < beta
 // Eq. 9:  log P(top-1) - log P(draft) <= tau      <=>  m - z_d <= tau
-// (log-softmax subtracts the same LSE from every logit of the row).  a = number of leading
-// rows that pass; next = arg-max of row a.
+// (log-softmax subtracts the same LSE from every logit of the row; a draft tied with the
+// beta-th score passes, as ">=" says).  a = number of leading rows that pass; next = arg-max
+// of row a.
 __global__ void accept_kernel(const float* __restrict__ row_stats, SeqState s, int B, int k, int beta, float tau,
                               int pad_id, int* __restrict__ accept_len, int* __restrict__ next_token) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -207,13 +191,12 @@ __global__ void accept_kernel(const float* __restrict__ row_stats, SeqState s, i
   const int T = k + 1;
   int a = 0;
   for (; a < k; ++a) {
-    const float* rs = row_stats + (size_t)(b * T + a) * (4 + kTopN);
-    const float zd = rs[3];
-    if (!(zd >= rs[4 + beta - 1] && rs[0] - zd <= tau)) break;
+    const float* rs = row_stats + (size_t)(b * T + a) * kRowStats;
+    if (!(rs[4] < (float)beta && rs[0] - rs[3] <= tau)) break;
   }
   const bool fin = s.finished[b] != 0;
   accept_len[b] = fin ? 0 : a;
-  next_token[b] = fin ? pad_id : (int)row_stats[(size_t)(b * T + a) * (4 + kTopN) + 1];
+  next_token[b] = fin ? pad_id : (int)row_stats[(size_t)(b * T + a) * kRowStats + 1];
 }
 hipError_t accept_rows(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k, int beta,
                        float tau, int pad_id, int* accept_len, int* next_token) {
@@ -357,7 +340,7 @@ hipError_t get_output(hipStream_t st, const SeqState& s, int* tokens, int out_ca
 
 // ----------------------------------------------------------------------------- cache layout
 // flat [B][L][H*64]  <->  key cache [B][H][Lcap][64] (16-byte chunks) or transposed value
-// cache [B][H][64][Lcap] (element-wise; only used to load / inspect caches)
+// cache (element-wise; only used to load / inspect caches)
 __global__ void cache_flat_kernel(bf16* cache, bf16* flat, int B, int H, int Lcap, int L, int to_flat) {
   long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
   long n = (long)B * L * H * 8;
@@ -380,7 +363,7 @@ __global__ void cache_flat_t_kernel(bf16* cache, bf16* flat, int B, int H, int L
   int h = (int)(t % H); t /= H;
   int l = (int)(t % L);
   int b = (int)(t / L);
-  bf16* c = cache + (((size_t)b * H + h) * kHeadDim + e) * Lcap + l;
+  bf16* c = cache + ((size_t)b * H + h) * Lcap * kHeadDim + vt_off(l, e);
   bf16* f = flat + (((size_t)b * L + l) * H + h) * kHeadDim + e;
   if (to_flat) *f = *c; else *c = *f;
 }
