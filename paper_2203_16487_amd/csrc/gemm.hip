@@ -27,32 +27,38 @@ __device__ __forceinline__ int cs_off(int row, int col) {
 }
 
 // ----------------------------------------------------------------------------- epilogues
-// Each gets 8 consecutive columns [n, n+8) of row m (n % 8 == 0, inside the matrix).
+// An epilogue handles 8 consecutive columns [n, n+8) of row m (n % 8 == 0, inside the matrix)
+// in two steps: fetch() issues every global read the chunk needs (bias, residual, row
+// bookkeeping), store() consumes them.  The kernel calls fetch() for all chunks of a thread
+// before the first store(), so the reads of a tile cost one memory round trip in total.
 struct EpiF32 {
-  const bf16* bias;
-  const float* resid;
+  const bf16* __restrict__ bias;
+  const float* resid;   // may alias out
   float* out;
   int ldo;
-  __device__ __forceinline__ void operator()(int m, int n, float (&v)[8]) const {
+  struct Pre { bf16x8 b; f32x4 r0, r1; };
+  __device__ __forceinline__ Pre fetch(int m, int n) const {
+    Pre p;
+    p.b = *reinterpret_cast<const bf16x8*>(bias + n);
     const size_t o = (size_t)m * ldo + n;
-    if (bias) {
-      bf16x8 b = *reinterpret_cast<const bf16x8*>(bias + n);
+    if (resid) { p.r0 = *reinterpret_cast<const f32x4*>(resid + o); p.r1 = *reinterpret_cast<const f32x4*>(resid + o + 4); }
+    else { p.r0 = f32x4{0.f, 0.f, 0.f, 0.f}; p.r1 = p.r0; }
+    return p;
+  }
+  __device__ __forceinline__ void store(int m, int n, const float (&v)[8], const Pre& p) const {
+    f32x4 w0, w1;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] += (float)b[i];
+    for (int i = 0; i < 4; ++i) {
+      w0[i] = v[i] + (float)p.b[i] + p.r0[i];
+      w1[i] = v[4 + i] + (float)p.b[4 + i] + p.r1[i];
     }
-    if (resid) {
-      f32x4 r0 = *reinterpret_cast<const f32x4*>(resid + o), r1 = *reinterpret_cast<const f32x4*>(resid + o + 4);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { v[i] += r0[i]; v[4 + i] += r1[i]; }
-    }
-    f32x4 w0 = {v[0], v[1], v[2], v[3]}, w1 = {v[4], v[5], v[6], v[7]};
+    const size_t o = (size_t)m * ldo + n;
     *reinterpret_cast<f32x4*>(out + o) = w0;
     *reinterpret_cast<f32x4*>(out + o + 4) = w1;
   }
 };
 
-__device__ __forceinline__ bf16x8 pack_bias(float (&v)[8], const bf16* bias, int n, bool relu) {
-  bf16x8 b = *reinterpret_cast<const bf16x8*>(bias + n);
+__device__ __forceinline__ bf16x8 pack_bias(const float (&v)[8], const bf16x8& b, bool relu) {
   bf16x8 o;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
@@ -64,12 +70,16 @@ __device__ __forceinline__ bf16x8 pack_bias(float (&v)[8], const bf16* bias, int
 }
 
 struct EpiBf16 {
-  const bf16* bias;
-  bf16* out;
+  const bf16* __restrict__ bias;
+  bf16* __restrict__ out;
   int ldo;
   int relu;
-  __device__ __forceinline__ void operator()(int m, int n, float (&v)[8]) const {
-    *reinterpret_cast<bf16x8*>(out + (size_t)m * ldo + n) = pack_bias(v, bias, n, relu != 0);
+  struct Pre { bf16x8 b; };
+  __device__ __forceinline__ Pre fetch(int m, int n) const {
+    return Pre{*reinterpret_cast<const bf16x8*>(bias + n)};
+  }
+  __device__ __forceinline__ void store(int m, int n, const float (&v)[8], const Pre& p) const {
+    *reinterpret_cast<bf16x8*>(out + (size_t)m * ldo + n) = pack_bias(v, p.b, relu != 0);
   }
 };
 
@@ -78,27 +88,30 @@ struct EpiBf16 {
 // key-blocked value cache: this is the "append" of the KV cache, fused into the projection.
 //   key cache   [B][H][Lcap][64]      value cache [B][H][Lcap/8][64][8] (see vt_off)
 struct EpiQkvAppend {
-  const bf16* bias;
-  bf16* q;
-  bf16* kc;
-  bf16* vc;
-  const int* row_b;
-  const int* row_pos;
+  const bf16* __restrict__ bias;
+  bf16* __restrict__ q;
+  bf16* __restrict__ kc;
+  bf16* __restrict__ vc;
+  const int* __restrict__ row_b;
+  const int* __restrict__ row_pos;
   int d, H, Lcap;
-  __device__ __forceinline__ void operator()(int m, int n, float (&v)[8]) const {
-    bf16x8 o = pack_bias(v, bias, n, false);
+  struct Pre { bf16x8 b; int sb, pos; };
+  __device__ __forceinline__ Pre fetch(int m, int n) const {
+    return Pre{*reinterpret_cast<const bf16x8*>(bias + n), row_b[m], row_pos[m]};
+  }
+  __device__ __forceinline__ void store(int m, int n, const float (&v)[8], const Pre& p) const {
+    const bf16x8 o = pack_bias(v, p.b, false);
     const int part = n / d, c = n - part * d;
     if (part == 0) {
       *reinterpret_cast<bf16x8*>(q + (size_t)m * d + c) = o;
       return;
     }
-    const int b = row_b[m];
-    if (b < 0) return;
-    const int h = c >> 6, e = c & 63, pos = row_pos[m];
+    if (p.sb < 0) return;
+    const int h = c >> 6, e = c & 63;
     if (part == 1) {
-      *reinterpret_cast<bf16x8*>(kc + (((size_t)b * H + h) * Lcap + pos) * kHeadDim + e) = o;
+      *reinterpret_cast<bf16x8*>(kc + (((size_t)p.sb * H + h) * Lcap + p.pos) * kHeadDim + e) = o;
     } else {
-      bf16* dst = vc + ((size_t)b * H + h) * Lcap * kHeadDim + vt_off(pos, e);
+      bf16* dst = vc + ((size_t)p.sb * H + h) * Lcap * kHeadDim + vt_off(p.pos, e);
 #pragma unroll
       for (int i = 0; i < 8; ++i) dst[i * 8] = o[i];
     }
@@ -108,12 +121,16 @@ struct EpiQkvAppend {
 // Cross-attention keys/values of the encoder memory: row m = b*S + s.
 //   xk [B][H][Scap][64]     xv [B][H][Scap/8][64][8] (blocked like the value cache)
 struct EpiCrossKv {
-  const bf16* bias;
-  bf16* xk;
-  bf16* xv;
+  const bf16* __restrict__ bias;
+  bf16* __restrict__ xk;
+  bf16* __restrict__ xv;
   int d, H, S, Scap;
-  __device__ __forceinline__ void operator()(int m, int n, float (&v)[8]) const {
-    bf16x8 o = pack_bias(v, bias, n, false);
+  struct Pre { bf16x8 b; };
+  __device__ __forceinline__ Pre fetch(int m, int n) const {
+    return Pre{*reinterpret_cast<const bf16x8*>(bias + n)};
+  }
+  __device__ __forceinline__ void store(int m, int n, const float (&v)[8], const Pre& p) const {
+    const bf16x8 o = pack_bias(v, p.b, false);
     const int part = n / d, c = n - part * d;
     const int b = m / S, s = m - b * S;
     const int h = c >> 6, e = c & 63;
@@ -137,20 +154,32 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_kernel(const bf16* __restr
   int mt, nt;
   if (!xcd_tile(MT, NT, mt, nt)) return;
   const int m0 = mt * Cfg::kBM, n0 = nt * Cfg::kBN;
+  constexpr int CPR = Cfg::kBN / 8;                          // 8-column chunks per row
+  constexpr int ITER = Cfg::kBM * CPR / Cfg::kThreads;       // chunks per thread
+  static_assert(Cfg::kBM * CPR % Cfg::kThreads == 0, "tile / thread count");
+  // what the epilogue reads from memory is requested before the K loop and arrives under it
+  typename Epi::Pre pre[ITER];
+#pragma unroll
+  for (int it = 0; it < ITER; ++it) {
+    const int idx = it * Cfg::kThreads + threadIdx.x;
+    const int r = idx / CPR, c = (idx - r * CPR) * 8;
+    pre[it] = epi.fetch(min(m0 + r, M - 1), min(n0 + c, N - 8));
+  }
   GemmAcc<Cfg> acc;
   gemm_mainloop<Cfg>(A, lda, W, ldw, M, N, 0, K / GK, m0, n0, smem, acc);
   float* cs = reinterpret_cast<float*>(smem);
   gemm_foreach<Cfg>(acc, 0, 0, [&](int r, int c, float v) { cs[cs_off<Cfg::kBN>(r, c)] = v; });
   __syncthreads();
-  constexpr int CPR = Cfg::kBN / 8;   // 8-column chunks per row
-  for (int idx = threadIdx.x; idx < Cfg::kBM * CPR; idx += Cfg::kThreads) {
+#pragma unroll
+  for (int it = 0; it < ITER; ++it) {
+    const int idx = it * Cfg::kThreads + threadIdx.x;
     const int r = idx / CPR, c = (idx - r * CPR) * 8;
     const int m = m0 + r, n = n0 + c;
     if (m < M && n < N) {
       const float* src = cs + cs_off<Cfg::kBN>(r, c);
       f32x4 a = *reinterpret_cast<const f32x4*>(src), b = *reinterpret_cast<const f32x4*>(src + 4);
-      float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-      epi(m, n, v);
+      const float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+      epi.store(m, n, v, pre[it]);
     }
   }
 }
@@ -248,6 +277,13 @@ __global__ __launch_bounds__(64) void draft_logit_kernel(const bf16* __restrict_
 // written.  Logits never reach memory unless the caller asks for them.
 typedef GemmCfg<128, 128, 2> CfgVocab;
 
+// Staging tile of the vocabulary kernel: [128 rows][32 chunks of 4 columns], chunk ch of row r
+// at chunk (ch & 16) + ((ch & 15) ^ (r & 15) ^ ((ch >> 4) << 3)): the 16 lanes that read one
+// 16-byte chunk each in the same cycle (8 rows x 2 halves) then cover all 64 banks.
+__device__ __forceinline__ int vs_off(int row, int ch) {
+  return row * 128 + (((ch & 16) + ((ch & 15) ^ (row & 15) ^ ((ch >> 4) << 3))) << 2);
+}
+
 __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* __restrict__ A,
                                                                    const bf16* __restrict__ E, int M,
                                                                    int V, int K, int MT, int NT,
@@ -261,7 +297,7 @@ __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* _
   GemmAcc<CfgVocab> acc;
   gemm_mainloop<CfgVocab>(A, K, E, K, M, V, 0, K / GK, m0, n0, smem, acc);
   float* cs = reinterpret_cast<float*>(smem);  // [128][128] fp32 = 64 KB
-  gemm_foreach<CfgVocab>(acc, 0, 0, [&](int r, int c, float v) { cs[cs_off<128>(r, c)] = v; });
+  gemm_foreach<CfgVocab>(acc, 0, 0, [&](int r, int c, float v) { cs[vs_off(r, c >> 2) + (c & 3)] = v; });
   __syncthreads();
 
   const int tid = threadIdx.x;
@@ -270,25 +306,28 @@ __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* _
   const float zd = (m < M) ? zd_row[m] : kNegInf;   // -inf on rows that score no draft: count unused
   float best = kNegInf;
   int besti = 0x7fffffff, cnt = 0;
-  // lane (row, half) visits column half*64 + (j + row + 32*half) % 64 at step j: the 64 lanes
-  // of a wave hit 64 different banks
-  const int rot = row + 32 * half;
-#pragma unroll 8
-  for (int j = 0; j < 64; ++j) {
-    const int c = half * 64 + ((j + rot) & 63);
-    const int n = n0 + c;
-    const float v = cs[cs_off<128>(row, c)];
-    if (n < V) {
-      if (v > best || (v == best && n < besti)) { best = v; besti = n; }
-      cnt += (v > zd) ? 1 : 0;
+  const bool full = n0 + 128 <= V;
+  // thread (row, half) owns columns [half*64, half*64 + 64) of its row: 16 reads of 4 columns
+  f32x4 vals[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) vals[i] = *reinterpret_cast<const f32x4*>(cs + vs_off(row, half * 16 + i));
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int n = n0 + half * 64 + i * 4 + e;   // ascending: ">" keeps the lowest index of a tie
+      const float v = vals[i][e];
+      if (full || n < V) {
+        if (v > best) { best = v; besti = n; }
+        cnt += (v > zd) ? 1 : 0;
+      }
     }
-  }
   float se = 0.f;
-#pragma unroll 8
-  for (int j = 0; j < 64; ++j) {
-    const int c = half * 64 + ((j + rot) & 63);
-    if (n0 + c < V) se += __expf(cs[cs_off<128>(row, c)] - best);
-  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (full || n0 + half * 64 + i * 4 + e < V) se += __expf(vals[i][e] - best);
   // merge the two halves of the row (lanes tid and tid^1)
   const float obest = __shfl_xor(best, 1, 64);
   const int obesti = __shfl_xor(besti, 1, 64);
@@ -306,7 +345,7 @@ __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* _
   if (logits) {
     for (int idx = tid; idx < 128 * 128; idx += CfgVocab::kThreads) {
       int r = idx >> 7, c = idx & 127;
-      if (m0 + r < M && n0 + c < V) logits[(size_t)(m0 + r) * V + n0 + c] = cs[cs_off<128>(r, c)];
+      if (m0 + r < M && n0 + c < V) logits[(size_t)(m0 + r) * V + n0 + c] = cs[vs_off(r, c >> 2) + (c & 3)];
     }
   }
 }
