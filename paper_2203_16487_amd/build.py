@@ -18,7 +18,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspecdec.so")
 SOURCES = ["api.hip", "gemm.hip", "attn.hip", "misc.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-parameter",
+FLAGS = ["--offload-arch=gfx950", "-O3", *os.environ.get("SD_EXTRA_FLAGS", "").split(), "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-parameter",
          # packed-fp32 instruction selection off (device pass only; the host pass
          # reports the feature as unknown, which is harmless)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -240,7 +240,7 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
     sd::AttnArgs a{};
     a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
     a.k = kc; a.k_b = (long)H * Lcap * 64; a.k_h = (long)Lcap * 64; a.k_row = 64;
-    a.v = vc; a.v_b = (long)H * Lcap * 64; a.v_h = (long)Lcap * 64;
+    a.v = vc; a.v_b = (long)H * Lcap * 64; a.v_h = (long)Lcap * 64; a.v_row = 64; a.v_blocked = 0;
     a.o = m.att; a.o_b = (long)T * D; a.o_row = D;
     a.q_count = m.rm.seq_rows; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
     a.T = T; a.H = H; a.B = B;
@@ -250,7 +250,7 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
     LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln1g, L.ln1b, m.xb, R, D));
     LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.xb, D, L.cwq, R, D, D, L.cbq, m.q, D, false));
     a.k = m.xk + m.xkv_layer * l; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64;
-    a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64;
+    a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_blocked = 1;
     a.lim_row = nullptr; a.lim_seq = c->st.src_len;
     a.key_split = c->S_cur > 256;
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
@@ -453,7 +453,7 @@ int specdec_load_cache(specdec_ctx* c, specdec_role role, const void* k_cache, c
   const size_t flat_layer = (size_t)c->B * L_max * m.d.d_model;
   for (int l = 0; l < m.d.dec_layers; ++l) {
     HIPCHK(c, sd::cache_from_flat(S(stream), m.kc + m.kv_layer * l, static_cast<const bf16*>(k_cache) + flat_layer * l, c->B, H, c->Lcap, L_max, false));
-    HIPCHK(c, sd::cache_from_flat(S(stream), m.vc + m.kv_layer * l, static_cast<const bf16*>(v_cache) + flat_layer * l, c->B, H, c->Lcap, L_max, true));
+    HIPCHK(c, sd::cache_from_flat(S(stream), m.vc + m.kv_layer * l, static_cast<const bf16*>(v_cache) + flat_layer * l, c->B, H, c->Lcap, L_max, false));
   }
   HIPCHK(c, sd::set_cached(S(stream), c->st, role, n, c->B, L_max));
   c->trusted[role] = true;
@@ -567,7 +567,7 @@ int specdec_get_cache(specdec_ctx* c, specdec_role role, void* k_cache, void* v_
   const size_t flat_layer = (size_t)c->B * L * m.d.d_model;
   for (int l = 0; l < m.d.dec_layers; ++l) {
     HIPCHK(c, sd::cache_to_flat(S(stream), m.kc + m.kv_layer * l, static_cast<bf16*>(k_cache) + flat_layer * l, c->B, m.d.n_heads, c->Lcap, L, false));
-    HIPCHK(c, sd::cache_to_flat(S(stream), m.vc + m.kv_layer * l, static_cast<bf16*>(v_cache) + flat_layer * l, c->B, m.d.n_heads, c->Lcap, L, true));
+    HIPCHK(c, sd::cache_to_flat(S(stream), m.vc + m.kv_layer * l, static_cast<bf16*>(v_cache) + flat_layer * l, c->B, m.d.n_heads, c->Lcap, L, false));
   }
   return SPECDEC_OK;
 }

@@ -1,8 +1,8 @@
 // Scaled dot-product attention for few queries against a streamed key/value set, on MFMA.
 //
 // A wave owns one (sequence, head) pair and a group of up to 16*NQT queries; it walks the keys
-// in chunks of 32 with an online softmax.  Nothing is staged in LDS: every MFMA operand is a
-// 16-byte global load in exactly the register layout the instruction wants.
+// in chunks of 32 with an online softmax.  Query, key and blocked-value operands are 16-byte
+// global loads in exactly the register layout the instruction wants.
 //
 //   S^T[key][q]  = sum_e K[key][e] Q[q][e]        mfma 16x16x32: A = key rows, B = query rows
 //   O^T[e][q]   += sum_key V^T[e][key] P^T[key][q] mfma 16x16x32: A = V^T rows, B = P (registers)
@@ -10,8 +10,10 @@
 // Row i of key tile t stands for key c0 + 8*(i/4) + 4*t + i%4, so that the eight scores a lane
 // holds after the two S^T tiles (q = lane%16, keys c0 + 8*(lane/16) .. +7) are already the B
 // operand of the second product, and its V^T operand is one contiguous 16-byte load.  This is
-// why values are cached in blocks of 8 keys (vt_off).  Both results keep q = lane%16, so the
-// running max / sum of a query live in the lanes that hold its accumulators.
+// what the key-blocked value layout (vt_off) of the cross-attention values is for; values in
+// row layout (the self-attention cache, appended row by row) are turned around through a
+// wave-private LDS tile instead.  Both results keep q = lane%16, so the running max / sum of
+// a query live in the lanes that hold its accumulators.
 //
 // A query sees keys [0, limit): causal verify rows (limit grows by one per row), the
 // drafter's mask slots (limit = whole block), padded cross / encoder attention (limit = source
@@ -32,10 +34,14 @@ __device__ __forceinline__ bf16x8 zero_tail(bf16x8 v, int nvalid) {
   return o;
 }
 
-template <int NQT>
+constexpr int kVtPitch = 68;   // bf16 per staged value row: 34 banks, so the transposed 2-byte
+                               // reads of the four lane groups (8 rows apart) hit disjoint banks
+
+template <int NQT, bool VBLK>
 __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   __shared__ float Om[4][NQT * 16][kHeadDim + 1];
   __shared__ float Ms[4][NQT * 16], Ls[4][NQT * 16];
+  __shared__ __attribute__((aligned(16))) bf16 Vs[VBLK ? 1 : 4][VBLK ? 1 : 32][kVtPitch];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lq = lane & 15, g = lane >> 4;
@@ -97,10 +103,20 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
       kf[t][0] = *reinterpret_cast<const bf16x8*>(kp);
       kf[t][1] = *reinterpret_cast<const bf16x8*>(kp + 32);
     }
-    // V operands: dim e = et*16 + lq, keys c0 + 8g .. +7 (one block of the key-blocked layout)
+    if (VBLK) {
+      // V operands: dim e = et*16 + lq, keys c0 + 8g .. +7 = one block of the key-blocked layout
 #pragma unroll
-    for (int et = 0; et < 4; ++et)
-      vf[et] = *reinterpret_cast<const bf16x8*>(vbase + vt_off(c0 + 8 * g, et * 16 + lq));
+      for (int et = 0; et < 4; ++et)
+        vf[et] = *reinterpret_cast<const bf16x8*>(vbase + vt_off(c0 + 8 * g, et * 16 + lq));
+    } else {
+      // row layout: fetch 32 whole rows (lane -> row 8*i + lane/8, dims 8*(lane%8) .. +7); they
+      // are turned into operands through LDS when the chunk is used
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = min(c0 + 8 * i + (lane >> 3), kclamp);
+        vf[i] = *reinterpret_cast<const bf16x8*>(vbase + (long)key * a.v_row + (lane & 7) * 8);
+      }
+    }
   };
   bf16x8 kf[2][2], vf[4], kn[2][2], vn[4];
   const int cfirst = kw * 32, cstep = kstep * 32;
@@ -109,6 +125,18 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   for (int c0 = cfirst; c0 < kmax; c0 += cstep) {
     const bool more = c0 + cstep < kmax;
     if (more) load_chunk(c0 + cstep, kn, vn);
+    if (!VBLK) {
+      // wave-private transposition: rows -> LDS -> (dim, 8 consecutive keys) operands
+      // (LDS operations of one wave execute in order, so no barrier is needed; memcpy keeps
+      // the 16-byte store and the 2-byte loads in one alias class for the compiler)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        __builtin_memcpy(&Vs[wave][8 * i + (lane >> 3)][(lane & 7) * 8], &vf[i], 16);
+#pragma unroll
+      for (int et = 0; et < 4; ++et)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) vf[et][i] = Vs[wave][8 * g + i][et * 16 + lq];
+    }
     if (c0 + 32 > kmax) {
       const int nvalid = kmax - (c0 + 8 * g);
 #pragma unroll
@@ -214,16 +242,21 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   }
 }
 
-hipError_t attention(hipStream_t st, const AttnArgs& a) {
-  if (a.B <= 0 || a.T <= 0) return hipSuccess;
+template <bool VBLK>
+static hipError_t attention_launch(hipStream_t st, const AttnArgs& a) {
   const int nqt = a.T <= 16 ? 1 : (a.T <= 32 ? 2 : 4);
   const int qgroups = (a.T + nqt * 16 - 1) / (nqt * 16);
   const long units = (long)a.B * a.H * qgroups;
   const unsigned blocks = (unsigned)(a.key_split ? units : (units + 3) / 4);
-  if (nqt == 1) hipLaunchKernelGGL(attn_kernel<1>, dim3(blocks), dim3(kAttnThreads), 0, st, a);
-  else if (nqt == 2) hipLaunchKernelGGL(attn_kernel<2>, dim3(blocks), dim3(kAttnThreads), 0, st, a);
-  else hipLaunchKernelGGL(attn_kernel<4>, dim3(blocks), dim3(kAttnThreads), 0, st, a);
+  if (nqt == 1) hipLaunchKernelGGL((attn_kernel<1, VBLK>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
+  else if (nqt == 2) hipLaunchKernelGGL((attn_kernel<2, VBLK>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
+  else hipLaunchKernelGGL((attn_kernel<4, VBLK>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
   return hipGetLastError();
+}
+
+hipError_t attention(hipStream_t st, const AttnArgs& a) {
+  if (a.B <= 0 || a.T <= 0) return hipSuccess;
+  return a.v_blocked ? attention_launch<true>(st, a) : attention_launch<false>(st, a);
 }
 
 }  // namespace sd

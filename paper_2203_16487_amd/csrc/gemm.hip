@@ -84,9 +84,8 @@ struct EpiBf16 {
 };
 
 // Decoder self-attention projection: columns [0,d) are queries, [d,2d) keys, [2d,3d) values.
-// Keys go straight into the cache row of the token they belong to and values into the
-// key-blocked value cache: this is the "append" of the KV cache, fused into the projection.
-//   key cache   [B][H][Lcap][64]      value cache [B][H][Lcap/8][64][8] (see vt_off)
+// Keys and values go straight into the cache rows of the token they belong to: this is the
+// "append" of the KV cache, fused into the projection.  Both caches are [B][H][Lcap][64].
 struct EpiQkvAppend {
   const bf16* __restrict__ bias;
   bf16* __restrict__ q;
@@ -108,13 +107,8 @@ struct EpiQkvAppend {
     }
     if (p.sb < 0) return;
     const int h = c >> 6, e = c & 63;
-    if (part == 1) {
-      *reinterpret_cast<bf16x8*>(kc + (((size_t)p.sb * H + h) * Lcap + p.pos) * kHeadDim + e) = o;
-    } else {
-      bf16* dst = vc + ((size_t)p.sb * H + h) * Lcap * kHeadDim + vt_off(p.pos, e);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) dst[i * 8] = o[i];
-    }
+    bf16* cache = (part == 1) ? kc : vc;
+    *reinterpret_cast<bf16x8*>(cache + (((size_t)p.sb * H + h) * Lcap + p.pos) * kHeadDim + e) = o;
   }
 };
 

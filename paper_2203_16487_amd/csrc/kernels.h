@@ -35,7 +35,7 @@ hipError_t gemm_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, 
                            const bf16* bias, bf16* q_out, bf16* kc, bf16* vc, const int* row_b,
                            const int* row_pos, int H, int Lcap);
 // Cross-attention keys/values of the encoder memory, N = 2d: memory rows m = b*S + s ->
-// xk, xv [B][H][Scap][64].
+// xk [B][H][Scap][64], xv key-blocked [B][H][Scap/8][64][8].
 hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
                          const bf16* bias, bf16* xk, bf16* xv, int S, int H, int Scap);
 
@@ -53,8 +53,9 @@ hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int 
 struct AttnArgs {
   const bf16* q;  long q_b, q_row;            // q + b*q_b + i*q_row + h*64
   const bf16* k;  long k_b, k_h, k_row;       // keys   [key][64]:  k + b*k_b + h*k_h + key*k_row
-  const bf16* v;  long v_b, v_h;              // values, key-blocked (vt_off): v + b*v_b + h*v_h + vt_off(key, e);
-                                              //   whole 32-key chunks are read: capacity % 32 == 0
+  const bf16* v;  long v_b, v_h, v_row;       // values: v + b*v_b + h*v_h + ...
+  int v_blocked;                              //   1: key-blocked, + vt_off(key, e); whole 32-key chunks are
+                                              //      read, capacity % 32 == 0      0: rows, + key*v_row + e
   bf16* o;        long o_b, o_row;            // o + b*o_b + i*o_row + h*64
   const int* q_count;                         // [B] queries of sequence b (null: T)
   const int* lim_row;                         // [B*T] visible keys per query (null: lim_seq)
