@@ -163,7 +163,7 @@ def cpu_baseline(desc, B_sample, k, L, src_len, beta, tau, budget_s=20.0):
             committed += a + 1            # commit = a + 1 tokens; rollback = len unchanged here
         reps += 1
         el = time.perf_counter() - t0
-        if el >= budget_s / 2 or reps >= 50:
+        if el >= budget_s / 2 or reps >= 400:
             break
     return {"value": committed / el, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"first {B_sample} of the 128 sequences, verify+accept+commit repeated {reps}x "
