@@ -274,7 +274,7 @@ def commit(seq: SeqState, vst: DecState, drafts, a: int, nxt: int, eos_id: int, 
 
 
 # ----------------------------------------------------------------------------- drafter
-def draft(model: Model, dst: DecState, stream: Sequence[int], k: int) -> List[int]:
+def draft(model: Model, dst: DecState, stream: Sequence[int], k: int, return_logits: bool = False):
     """Spec-Drafter inference (Eq. 7): append k [MASK] tokens to the decoded stream
     and predict all of them in one pass.
 
@@ -293,7 +293,8 @@ def draft(model: Model, dst: DecState, stream: Sequence[int], k: int) -> List[in
     h = decoder_rows(model, dst, new + [model.desc.mask_id] * k, vis)
     dst.len += n
     z = vocab_logits(model, h[n:])
-    return [int(t) for t in np.argmax(z, axis=-1)]
+    toks = [int(t) for t in np.argmax(z, axis=-1)]
+    return (toks, z) if return_logits else toks
 
 
 # ----------------------------------------------------------------------------- decoding loops

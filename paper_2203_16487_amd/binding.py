@@ -64,6 +64,7 @@ EXPORTS = {
     "specdec_get_output": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "specdec_get_cache": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "specdec_get_row_stats": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "specdec_get_memory": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]),
 }
 
 _lib = None
@@ -226,6 +227,10 @@ def specdec_get_output(ctx, tokens, out_len, finished=None):
 
 def specdec_get_cache(ctx, role: int, k_cache, v_cache):
     _check(ctx, lib().specdec_get_cache(ctx, role, _ptr(k_cache), _ptr(v_cache), k_cache.shape[2], _stream()))
+
+
+def specdec_get_memory(ctx, role: int, memory):
+    _check(ctx, lib().specdec_get_memory(ctx, role, _ptr(memory), _stream()))
 
 
 def specdec_get_row_stats(ctx, stats):

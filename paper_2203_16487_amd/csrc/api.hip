@@ -44,6 +44,8 @@ struct Model {
   float* part = nullptr;     // [Rmax][n_tiles][kPartF]
   float* row_stats = nullptr;  // [Rmax][kRowStats]
   float* zd = nullptr;       // [Rmax] logit of the draft each row scores
+  bf16* slots = nullptr;     // [Bmax*k_max][d] final hidden states of the drafter's mask slots
+  int* new_rows = nullptr;   // [Bmax] stream rows of the current prefill / draft pass
   // encoder activations, rows = Bmax * Scap
   float* ex = nullptr;
   bf16 *exb = nullptr, *eqkv = nullptr, *eatt = nullptr, *ehid = nullptr;
@@ -202,8 +204,10 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   t.rm.row_lim = cv.take<int>(Rmax);
   t.rm.row_draft = cv.take<int>(Rmax);
   t.rm.seq_rows = cv.take<int>(Bm);
+  t.slots = cv.take<bf16>(Bm * (size_t)c->lim.k_max * D);
+  t.new_rows = cv.take<int>(Bm);
   if (d->enc_layers > 0) {
-    const size_t Re = Bm * (size_t)c->lim.max_src;
+    const size_t Re = Bm * (size_t)c->Scap;
     t.ex = cv.take<float>(Re * D);
     t.exb = cv.take<bf16>(Re * D);
     t.eqkv = cv.take<bf16>(Re * 3 * D);
@@ -217,6 +221,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
     m->pe = t.pe; m->kc = t.kc; m->vc = t.vc; m->xk = t.xk; m->xv = t.xv;
     m->x = t.x; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
     m->part = t.part; m->row_stats = t.row_stats; m->zd = t.zd; m->rm = t.rm;
+    m->slots = t.slots; m->new_rows = t.new_rows;
     m->ex = t.ex; m->exb = t.exb; m->eqkv = t.eqkv; m->eatt = t.eatt; m->ehid = t.ehid;
     m->etok = t.etok; m->epos = t.epos;
   }
@@ -301,7 +306,7 @@ int specdec_create(specdec_ctx** out, const specdec_limits* lim) {
   c->Tmax = 2 * lim->k_max + 1;
   c->Lcap = (lim->max_tgt + lim->k_max + 1 + 31) & ~31;   // rows of the KV arenas (32-key chunks)
   c->Scap = (lim->max_src + 31) & ~31;
-  c->n_pos = c->Lcap;
+  c->n_pos = c->Lcap > c->Scap ? c->Lcap : c->Scap;
   *out = c;
   return SPECDEC_OK;
 }
@@ -420,10 +425,57 @@ int specdec_set_memory(specdec_ctx* c, specdec_role role, const void* memory, co
   return cross_kv_from(c, c->m[role], static_cast<const bf16*>(memory), c->B, S_max, S(stream));
 }
 
+// Encoder of one model over B*S_max padded rows; leaves the memory (bf16) in m.exb.
+static int encoder_pass(specdec_ctx* c, Model& m, const int32_t* src, int B, int S_max, hipStream_t st) {
+  const int R = B * S_max, D = m.d.d_model, F = m.d.d_ffn, H = m.d.n_heads, Scap = c->Scap;
+  const size_t Re = (size_t)c->lim.max_batch * Scap;
+  bf16* eq = m.eqkv;                 // [R][d]
+  bf16* ek = m.eqkv + Re * D;        // [B][H][Scap][64]
+  bf16* ev = m.eqkv + 2 * Re * D;    // [B][H][Scap/8][64][8]
+  HIPCHK(c, sd::encoder_rows(st, src, m.etok, m.epos, B, S_max, m.d.vocab));
+  LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::embed_rows(st, m.etok, m.epos, m.embed, m.pe, m.ex, m.exb, R, D));
+  for (int l = 0; l < m.d.enc_layers; ++l) {
+    const EncLayer& L = m.enc[l];
+    LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::gemm_enc_qkv(st, m.exb, L.wqkv, R, D, D, L.bqkv, eq, ek, ev, S_max, H, Scap));
+    sd::AttnArgs a{};
+    a.q = eq; a.q_b = (long)S_max * D; a.q_row = D;
+    a.k = ek; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64; a.k_row = 64;
+    a.v = ev; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_row = 64; a.v_blocked = 1;
+    a.o = m.eatt; a.o_b = (long)S_max * D; a.o_row = D;
+    a.q_count = c->st.src_len; a.lim_row = nullptr; a.lim_seq = c->st.src_len;
+    a.T = S_max; a.H = H; a.B = B;
+    a.key_split = S_max > 256;
+    LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.eatt, D, L.wo, R, D, D, L.bo, m.ex, m.ex, D));
+    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.ex, L.ln1g, L.ln1b, m.exb, R, D));
+    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.exb, D, L.w1, R, F, D, L.b1, m.ehid, F, true));
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.ehid, F, L.w2, R, D, F, L.b2, m.ex, m.ex, D));
+    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.ex, L.ln2g, L.ln2b, m.exb, R, D));
+  }
+  return SPECDEC_OK;
+}
+
 int specdec_encode(specdec_ctx* c, const int32_t* src, const int32_t* src_len, int32_t S_max, void* stream) {
-  (void)src; (void)src_len; (void)S_max; (void)stream;
   if (!c) return SPECDEC_ERR_INVALID_ARG;
-  return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_encode: encoder pass not available in this build");
+  if (!c->state_bound || c->B <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "bind state and call specdec_begin first");
+  if (!src || !src_len) return fail(c, SPECDEC_ERR_INVALID_ARG, "null src/src_len");
+  if (S_max < 1) return fail(c, SPECDEC_ERR_INVALID_ARG, "S_max = %d", S_max);
+  if (S_max > c->lim.max_src) return fail(c, SPECDEC_ERR_TOO_LARGE, "S_max = %d exceeds max_src = %d", S_max, c->lim.max_src);
+  int n = 0;
+  for (int r = 0; r < 2; ++r) n += (c->m[r].bound && c->m[r].d.enc_layers > 0) ? 1 : 0;
+  if (n == 0) return fail(c, SPECDEC_ERR_BAD_STATE, "no bound model has an encoder");
+  hipStream_t st = S(stream);
+  HIPCHK(c, sd::set_src_len(st, c->st, src_len, c->B, S_max));
+  c->S_cur = S_max;
+  for (int r = 0; r < 2; ++r) {
+    Model& m = c->m[r];
+    if (!m.bound || m.d.enc_layers == 0) continue;
+    int rc = encoder_pass(c, m, src, c->B, S_max, st);
+    if (rc) return rc;
+    rc = cross_kv_from(c, m, m.exb, c->B, S_max, st);
+    if (rc) return rc;
+  }
+  return SPECDEC_OK;
 }
 
 int specdec_set_stream(specdec_ctx* c, const int32_t* tokens, const int32_t* len, int32_t L_max, void* stream) {
@@ -461,17 +513,53 @@ int specdec_load_cache(specdec_ctx* c, specdec_role role, const void* k_cache, c
 }
 
 int specdec_prefill(specdec_ctx* c, specdec_role role, void* stream) {
-  (void)stream;
   int rc = check_ready(c, role, true);
   if (rc) return rc;
-  return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_prefill: not available in this build");
+  Model& m = c->m[role];
+  hipStream_t st = S(stream);
+  const int T = c->Tmax;
+  while (c->uncached_ub[role] > 0) {
+    HIPCHK(c, sd::assemble_stream(st, c->st, m.rm, role, c->B, T, 0, m.d.mask_id, m.d.pad_id, m.d.vocab, m.new_rows));
+    rc = decoder_layers(c, m, c->B, T, st);
+    if (rc) return rc;
+    HIPCHK(c, sd::advance_cached(st, c->st, role, m.new_rows, c->B));
+    c->uncached_ub[role] -= T;
+  }
+  c->uncached_ub[role] = 0;
+  c->trusted[role] = false;
+  return SPECDEC_OK;
 }
 
 int specdec_draft(specdec_ctx* c, int32_t k, int32_t* draft, void* stream) {
-  (void)k; (void)draft; (void)stream;
   int rc = check_ready(c, SPECDEC_DRAFTER, true);
   if (rc) return rc;
-  return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_draft: not available in this build");
+  if (!draft) return fail(c, SPECDEC_ERR_INVALID_ARG, "null draft");
+  if (k < 1) return fail(c, SPECDEC_ERR_INVALID_ARG, "k = %d", k);
+  if (k > c->lim.k_max) return fail(c, SPECDEC_ERR_TOO_LARGE, "k = %d exceeds k_max = %d", k, c->lim.k_max);
+  Model& m = c->m[SPECDEC_DRAFTER];
+  hipStream_t st = S(stream);
+  // stream tokens the drafter has not ingested yet: at most k_max + 1 fit beside the k slots
+  int ub = c->trusted[1] ? 1 : c->uncached_ub[1];
+  if (ub < 1) ub = 1;
+  if (ub > c->lim.k_max + 1) {
+    rc = specdec_prefill(c, SPECDEC_DRAFTER, stream);
+    if (rc) return rc;
+    ub = 1;
+  }
+  const int B = c->B, T = ub + k;
+  HIPCHK(c, sd::assemble_stream(st, c->st, m.rm, SPECDEC_DRAFTER, B, T, k, m.d.mask_id, m.d.pad_id, m.d.vocab, m.new_rows));
+  rc = decoder_layers(c, m, B, T, st);
+  if (rc) return rc;
+  HIPCHK(c, sd::gather_slots(st, m.xb, m.slots, m.new_rows, B, T, k, m.d.d_model));
+  const int R = B * k, n_tiles = (m.d.vocab + 127) / 128;
+  HIPCHK(c, sd::fill_i32(st, m.rm.row_draft, -1, R));
+  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.zd, m.part, nullptr));
+  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
+  HIPCHK(c, sd::write_drafts(st, m.row_stats, c->st, B, k, m.d.pad_id, draft));
+  HIPCHK(c, sd::advance_cached(st, c->st, SPECDEC_DRAFTER, m.new_rows, B));
+  c->uncached_ub[1] = 0;
+  c->trusted[1] = false;
+  return SPECDEC_OK;
 }
 
 int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, float tau, int32_t* accept_len,
@@ -569,6 +657,17 @@ int specdec_get_cache(specdec_ctx* c, specdec_role role, void* k_cache, void* v_
     HIPCHK(c, sd::cache_to_flat(S(stream), m.kc + m.kv_layer * l, static_cast<bf16*>(k_cache) + flat_layer * l, c->B, m.d.n_heads, c->Lcap, L, false));
     HIPCHK(c, sd::cache_to_flat(S(stream), m.vc + m.kv_layer * l, static_cast<bf16*>(v_cache) + flat_layer * l, c->B, m.d.n_heads, c->Lcap, L, false));
   }
+  return SPECDEC_OK;
+}
+
+int specdec_get_memory(specdec_ctx* c, specdec_role role, void* memory, void* stream) {
+  int rc = check_ready(c, role, true);
+  if (rc) return rc;
+  if (!memory) return fail(c, SPECDEC_ERR_INVALID_ARG, "null memory");
+  Model& m = c->m[role];
+  if (m.d.enc_layers == 0 || !m.exb) return fail(c, SPECDEC_ERR_BAD_STATE, "model has no encoder");
+  const size_t n = (size_t)c->B * c->S_cur * m.d.d_model;
+  HIPCHK(c, hipMemcpyAsync(memory, m.exb, n * sizeof(bf16), hipMemcpyDeviceToDevice, S(stream)));
   return SPECDEC_OK;
 }
 

@@ -138,6 +138,37 @@ struct EpiCrossKv {
   }
 };
 
+// Encoder self-attention projection, N = 3d, row m = b*S + s: queries -> q [M,d]; keys and
+// values of the source go into the same layouts as the cross-attention K/V.
+struct EpiEncQkv {
+  const bf16* __restrict__ bias;
+  bf16* __restrict__ q;
+  bf16* __restrict__ xk;
+  bf16* __restrict__ xv;
+  int d, H, S, Scap;
+  struct Pre { bf16x8 b; };
+  __device__ __forceinline__ Pre fetch(int m, int n) const {
+    return Pre{*reinterpret_cast<const bf16x8*>(bias + n)};
+  }
+  __device__ __forceinline__ void store(int m, int n, const float (&v)[8], const Pre& p) const {
+    const bf16x8 o = pack_bias(v, p.b, false);
+    const int part = n / d, c = n - part * d;
+    if (part == 0) {
+      *reinterpret_cast<bf16x8*>(q + (size_t)m * d + c) = o;
+      return;
+    }
+    const int b = m / S, s = m - b * S;
+    const int h = c >> 6, e = c & 63;
+    if (part == 1) {
+      *reinterpret_cast<bf16x8*>(xk + (((size_t)b * H + h) * Scap + s) * kHeadDim + e) = o;
+    } else {
+      bf16* dst = xv + ((size_t)b * H + h) * Scap * kHeadDim + vt_off(s, e);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) dst[i * 8] = o[i];
+    }
+  }
+};
+
 template <class Cfg, class Epi>
 __global__ __launch_bounds__(Cfg::kThreads) void gemm_kernel(const bf16* __restrict__ A, int lda,
                                                              const bf16* __restrict__ W, int ldw,
@@ -223,6 +254,11 @@ hipError_t gemm_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, 
 hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
                          const bf16* bias, bf16* xk, bf16* xv, int S, int H, int Scap) {
   return launch(st, A, K, W, M, 2 * d, K, EpiCrossKv{bias, xk, xv, d, H, S, Scap});
+}
+
+hipError_t gemm_enc_qkv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
+                        const bf16* bias, bf16* q_out, bf16* ek, bf16* ev, int S, int H, int Scap) {
+  return launch(st, A, K, W, M, 3 * d, K, EpiEncQkv{bias, q_out, ek, ev, d, H, S, Scap});
 }
 
 // ----------------------------------------------------------------------------- vocabulary

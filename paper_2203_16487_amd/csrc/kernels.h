@@ -39,6 +39,11 @@ hipError_t gemm_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, 
 hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
                          const bf16* bias, bf16* xk, bf16* xv, int S, int H, int Scap);
 
+// Encoder self-attention projection, N = 3d, rows m = b*S + s: q -> q_out [M,d], keys ->
+// ek [B][H][Scap][64], values -> ev key-blocked [B][H][Scap/8][64][8].
+hipError_t gemm_enc_qkv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
+                        const bf16* bias, bf16* q_out, bf16* ek, bf16* ev, int S, int H, int Scap);
+
 // Vocabulary projection fused with per-row statistics.  zd_row [M] receives the logit of the
 // draft each row scores (-inf if none).  For every row and every 128-column vocabulary tile one
 // partial record of kPartF floats is written to part[M][n_tiles][kPartF]: {tile max, tile
@@ -90,6 +95,15 @@ struct SeqState {       // device arrays of the bound state buffer, all [max_bat
 // rows of a verification pass: [u_j, drafts]; also stores the drafts for commit
 hipError_t assemble_verify(hipStream_t st, const SeqState& s, const RowMap& rm, const int* draft,
                            int B, int k, int V);
+// rows of a prefill pass (n_mask = 0) or of a drafter pass (stream rows + n_mask [MASK] slots)
+hipError_t assemble_stream(hipStream_t st, const SeqState& s, const RowMap& rm, int role, int B, int T,
+                           int n_mask, int mask_id, int pad_id, int V, int* new_rows);
+hipError_t advance_cached(hipStream_t st, const SeqState& s, int role, const int* new_rows, int B);
+hipError_t gather_slots(hipStream_t st, const bf16* xb, bf16* dst, const int* new_rows, int B, int T,
+                        int k, int d);
+hipError_t write_drafts(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k,
+                        int pad_id, int* draft);
+hipError_t encoder_rows(hipStream_t st, const int* src, int* tok, int* pos, int B, int S, int V);
 // merge the vocabulary partials of every row into row_stats [R][kRowStats] =
 // {max, arg-max, log-sum-exp, draft logit, number of logits above the draft's, 0, 0, 0}
 hipError_t merge_rows(hipStream_t st, const float* part, const float* zd_row, int n_tiles, int R,

@@ -132,6 +132,92 @@ hipError_t assemble_verify(hipStream_t st, const SeqState& s, const RowMap& rm, 
   return hipGetLastError();
 }
 
+// ----------------------------------------------------------------------------- prefill / draft rows
+// One thread per sequence writes the T row slots of its sequence.
+// Prefill (n_mask = 0): the next up to T uncached stream tokens, causal.
+// Draft (Sec. 3.1.3, Eq. 7): the uncached stream tokens (causal) followed by n_mask [MASK]
+// slots; slot s sits at the position of the token it predicts and attends to the whole stream
+// and to all slots.  The slots' keys/values land beyond the valid cache length and are dead
+// after the pass.  new_rows[b] = stream rows of this pass (the amount `cached` advances by).
+__global__ void assemble_stream_kernel(SeqState s, RowMap rm, int role, int B, int T, int n_mask, int mask_id,
+                                       int pad_id, int V, int* __restrict__ new_rows) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int c0 = s.cached[role][b];
+  const int target = s.len[b] + (role == 1 ? 1 : 0);       // drafter also ingests the pending token
+  const int n = max(0, min(target - c0, T - n_mask));
+  const bool masks = n_mask > 0 && c0 + n == target;         // slots only once the stream is ingested
+  const int* u = s.tokens + (size_t)b * s.tok_pitch;
+  for (int i = 0; i < T; ++i) {
+    const int r = b * T + i;
+    int rb = -1, pos = 0, tok = pad_id, lim = 0;
+    if (i < n) {
+      rb = b; pos = c0 + i; tok = min(max(u[c0 + i], 0), V - 1); lim = c0 + i + 1;
+    } else if (masks && i < n + n_mask) {
+      rb = b; pos = c0 + i; tok = mask_id; lim = c0 + n + n_mask;
+    }
+    rm.row_b[r] = rb; rm.row_pos[r] = pos; rm.row_tok[r] = tok; rm.row_lim[r] = lim; rm.row_draft[r] = -1;
+  }
+  rm.seq_rows[b] = n + (masks ? n_mask : 0);
+  new_rows[b] = n;
+}
+hipError_t assemble_stream(hipStream_t st, const SeqState& s, const RowMap& rm, int role, int B, int T,
+                           int n_mask, int mask_id, int pad_id, int V, int* new_rows) {
+  hipLaunchKernelGGL(assemble_stream_kernel, blocks_for(B, 64), dim3(64), 0, st, s, rm, role, B, T, n_mask,
+                     mask_id, pad_id, V, new_rows);
+  return hipGetLastError();
+}
+
+__global__ void advance_cached_kernel(SeqState s, int role, const int* __restrict__ new_rows, int B) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) s.cached[role][b] += new_rows[b];
+}
+hipError_t advance_cached(hipStream_t st, const SeqState& s, int role, const int* new_rows, int B) {
+  hipLaunchKernelGGL(advance_cached_kernel, blocks_for(B, 64), dim3(64), 0, st, s, role, new_rows, B);
+  return hipGetLastError();
+}
+
+// dense [B*k][d] copy of the mask-slot rows (row b*T + new_rows[b] + s) for the vocabulary kernel
+__global__ void gather_slots_kernel(const bf16* __restrict__ xb, bf16* __restrict__ dst,
+                                    const int* __restrict__ new_rows, int B, int T, int k, int d) {
+  const int o = blockIdx.x;              // b*k + s
+  const int b = o / k, sl = o - b * k;
+  const uint4* src = reinterpret_cast<const uint4*>(xb + (size_t)(b * T + new_rows[b] + sl) * d);
+  uint4* out = reinterpret_cast<uint4*>(dst + (size_t)o * d);
+  for (int c = threadIdx.x; c < d / 8; c += blockDim.x) out[c] = src[c];
+}
+hipError_t gather_slots(hipStream_t st, const bf16* xb, bf16* dst, const int* new_rows, int B, int T, int k, int d) {
+  hipLaunchKernelGGL(gather_slots_kernel, dim3(B * k), dim3(64), 0, st, xb, dst, new_rows, B, T, k, d);
+  return hipGetLastError();
+}
+
+// draft[b][s] = arg-max of slot row b*k + s (pad for finished sequences)
+__global__ void write_drafts_kernel(const float* __restrict__ row_stats, SeqState s, int B, int k, int pad_id,
+                                    int* __restrict__ draft) {
+  const int o = blockIdx.x * blockDim.x + threadIdx.x;
+  if (o >= B * k) return;
+  const int b = o / k;
+  draft[o] = s.finished[b] ? pad_id : (int)row_stats[(size_t)o * kRowStats + 1];
+}
+hipError_t write_drafts(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k, int pad_id, int* draft) {
+  hipLaunchKernelGGL(write_drafts_kernel, blocks_for((long)B * k, 128), dim3(128), 0, st, row_stats, s, B, k, pad_id, draft);
+  return hipGetLastError();
+}
+
+// encoder rows: row b*S + s feeds src[b][s] (clamped into the vocabulary) at position s
+__global__ void encoder_rows_kernel(const int* __restrict__ src, int* __restrict__ tok, int* __restrict__ pos,
+                                    long n, int S, int V) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  tok[i] = min(max(src[i], 0), V - 1);
+  pos[i] = (int)(i % S);
+}
+hipError_t encoder_rows(hipStream_t st, const int* src, int* tok, int* pos, int B, int S, int V) {
+  const long n = (long)B * S;
+  hipLaunchKernelGGL(encoder_rows_kernel, blocks_for(n, 256), dim3(256), 0, st, src, tok, pos, n, S, V);
+  return hipGetLastError();
+}
+
 // ----------------------------------------------------------------------------- acceptance
 // Stage 1, one wave per row: merge the per-tile partials of the vocabulary kernel into
 //   m = max logit, arg-max = lowest column among maxima, LSE, and the number of logits that
