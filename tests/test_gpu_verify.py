@@ -144,3 +144,80 @@ def test_config2_batched_base_verifier():
                                   drafts="greedy")
     check_case(case, label="config2")
     assert len(set(case.accept.tolist())) >= 4       # a spread of bifurcation points
+
+
+def test_long_source_and_long_prefix_key_split_paths():
+    """Summarization-shaped sizes on a small model: source 300 (> 256: four waves split the
+    keys of one head and merge through LDS), prefixes up to 270 (self-attention arena > 256)."""
+    desc = synth.ModelDesc(0, 2, 128, 2, 256, 1000, 320, 320).resolved()
+    case = cases.make_verify_case(desc, seed=6, B=4, S=300, k=10, beta=5, tau=3.0, len_lo=200, len_hi=270,
+                                  drafts="greedy", ragged_src=True, std=0.08)
+    check_case(case, label="long")
+
+
+def test_block_sizes_k1_and_k31():
+    """k = 1 (two rows) and k = 31 (32 rows: two 16-query tiles per wave)."""
+    for k, seed in ((1, 7), (31, 8), (25, 9)):
+        case = cases.make_verify_case(small_desc(), seed=seed, B=3, S=6, k=k, beta=3, tau=1.0, len_lo=0, len_hi=9,
+                                      drafts="greedy", ragged_src=True, std=0.08, corrupt_p=0.1)
+        check_case(case, label=f"k={k}")
+
+
+def test_degenerate_inputs():
+    """Source of one token, empty prefix (j = 0, pending = BOS), a batch below max_batch, and a
+    sequence that is already finished (reports accept_len 0 and the pad token)."""
+    import gpu_harness as gh
+    from paper_2203_16487_amd import binding as sd
+    desc = small_desc()
+    case = cases.make_verify_case(desc, seed=10, B=3, S=1, k=4, beta=2, tau=0.5, len_lo=0, len_hi=0,
+                                  drafts="greedy", std=0.08)
+    ses = gh.open_verifier(case, max_batch=7)
+    check_case(case, ses=ses, label="degenerate")
+    # finish sequence 1 by committing EOS, then verify again
+    dev = ses.device
+    acc = torch.zeros(case.B, dtype=torch.int32, device=dev)
+    nxt = torch.tensor([5, desc.eos_id, 6], dtype=torch.int32, device=dev)
+    sd.specdec_commit(ses.ctx, acc, nxt)
+    out = gh.gpu_verify(ses, case, want_logits=False)
+    assert out["accept"][1] == 0 and out["next"][1] == desc.pad_id
+    toks = torch.zeros((case.B, 4), dtype=torch.int32, device=dev)
+    olen = torch.zeros(case.B, dtype=torch.int32, device=dev)
+    fin = torch.zeros(case.B, dtype=torch.int32, device=dev)
+    sd.specdec_get_output(ses.ctx, toks, olen, fin)
+    torch.cuda.synchronize()
+    assert fin.cpu().tolist() == [0, 1, 0] and olen.cpu().tolist() == [1, 1, 1]
+    assert toks[:, 0].cpu().tolist() == [5, desc.eos_id, 6]
+
+
+def test_argument_errors_on_device():
+    import gpu_harness as gh
+    from paper_2203_16487_amd import binding as sd
+    case = cases.make_verify_case(small_desc(), seed=12, B=2, S=4, k=3, beta=1, tau=0.0, len_lo=1, len_hi=3, std=0.08)
+    ses = gh.open_verifier(case)
+    dev = ses.device
+    d = ses.i32(case.drafts)
+    acc = torch.zeros(2, dtype=torch.int32, device=dev)
+    nxt = torch.zeros(2, dtype=torch.int32, device=dev)
+    for kw, code in ((dict(k=4), sd.SPECDEC_ERR_TOO_LARGE), (dict(k=0), sd.SPECDEC_ERR_INVALID_ARG),
+                     (dict(beta=0), sd.SPECDEC_ERR_INVALID_ARG), (dict(tau=-1.0), sd.SPECDEC_ERR_INVALID_ARG),
+                     (dict(tau=float("nan")), sd.SPECDEC_ERR_INVALID_ARG)):
+        args = dict(k=3, beta=1, tau=0.0); args.update(kw)
+        with pytest.raises(sd.SpecDecError) as e:
+            sd.specdec_verify(ses.ctx, d, args["k"], args["beta"], args["tau"], acc, nxt)
+        assert e.value.code == code, kw
+    with pytest.raises(sd.SpecDecError) as e:            # commit without verify
+        sd.specdec_commit(ses.ctx, acc, nxt)
+    assert e.value.code == sd.SPECDEC_ERR_BAD_STATE
+    with pytest.raises(sd.SpecDecError) as e:            # drafter not bound
+        sd.specdec_draft(ses.ctx, 3, d)
+    assert e.value.code == sd.SPECDEC_ERR_BAD_STATE
+    # a stream without cache or prefill is refused
+    sd.specdec_set_stream(ses.ctx, ses.i32(case.tokens), ses.i32(case.lens))
+    with pytest.raises(sd.SpecDecError) as e:
+        sd.specdec_verify(ses.ctx, d, 3, 1, 0.0, acc, nxt)
+    assert e.value.code == sd.SPECDEC_ERR_BAD_STATE
+    # ... and accepted after prefill, with the same result as with the loaded cache
+    cases.run_oracle(case)
+    sd.specdec_prefill(ses.ctx, sd.SPECDEC_VERIFIER)
+    out = gh.gpu_verify(ses, case)
+    assert np.abs(out["logits"] - case.logits).max() <= LOGIT_TOL
