@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -37,6 +38,8 @@ struct Model {
   bf16 *kc = nullptr, *vc = nullptr;   // [Ld][Bmax][H][Lcap][64]
   bf16 *xk = nullptr, *xv = nullptr;   // [Ld][Bmax][H][Scap][64]
   float* x = nullptr;        // [Rmax][d] residual stream
+  float* x2 = nullptr;       // [32][d] second residual buffer of the fused small-batch path
+  bool skinny_ready = false;
   bf16* xb = nullptr;        // [Rmax][d]
   bf16* q = nullptr;         // [Rmax][d]
   bf16* att = nullptr;       // [Rmax][d]
@@ -72,6 +75,7 @@ struct specdec_ctx {
   int prof_kind = SPECDEC_KIND_NONE;
   std::vector<hipEvent_t> prof_ev;
   int prof_used = 0;
+  bool no_skinny = false;   // SPECDEC_NO_SKINNY=1: always take the general kernels
   char err[512] = {0};
 };
 
@@ -181,7 +185,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   Carver cv(base);
   const size_t Bm = c->lim.max_batch, D = d->d_model, F = d->d_ffn, H = d->n_heads;
   const size_t Rmax = Bm * c->Tmax;
-  const size_t n_tiles = (d->vocab + 127) / 128;
+  const size_t n_tiles = (d->vocab + 63) / 64;   // the small-batch path uses 64-column tiles
   Model t;
   t.kv_layer = Bm * H * c->Lcap * 64;
   t.xkv_layer = Bm * H * (size_t)c->Scap * 64;
@@ -191,10 +195,11 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   t.xk = cv.take<bf16>(t.xkv_layer * d->dec_layers);
   t.xv = cv.take<bf16>(t.xkv_layer * d->dec_layers);
   t.x = cv.take<float>(Rmax * D);
+  t.x2 = cv.take<float>(32 * D);
   t.xb = cv.take<bf16>(Rmax * D);
-  t.q = cv.take<bf16>(Rmax * D);
+  t.q = cv.take<bf16>((Rmax > 32 ? Rmax : 32) * D);
   t.att = cv.take<bf16>(Rmax * D);
-  t.hid = cv.take<bf16>(Rmax * F);
+  t.hid = cv.take<bf16>((Rmax > 32 ? Rmax : 32) * F);
   t.part = cv.take<float>(Rmax * n_tiles * sd::kPartF);
   t.row_stats = cv.take<float>(Rmax * sd::kRowStats);
   t.zd = cv.take<float>(Rmax);
@@ -219,7 +224,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   if (m) {
     m->kv_layer = t.kv_layer; m->xkv_layer = t.xkv_layer;
     m->pe = t.pe; m->kc = t.kc; m->vc = t.vc; m->xk = t.xk; m->xv = t.xv;
-    m->x = t.x; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
+    m->x = t.x; m->x2 = t.x2; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
     m->part = t.part; m->row_stats = t.row_stats; m->zd = t.zd; m->rm = t.rm;
     m->slots = t.slots; m->new_rows = t.new_rows;
     m->ex = t.ex; m->exb = t.exb; m->eqkv = t.eqkv; m->eatt = t.eatt; m->ehid = t.ehid;
@@ -268,6 +273,55 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
   return SPECDEC_OK;
 }
 
+// Same pass with the fused small-batch kernels (at most 32 rows).  Returns in `out` where the
+// final hidden state comes from (LayerNorm of the last residual sum).
+bool skinny_ok(const specdec_ctx* c, const Model& m, int R, int T) {
+  return !c->no_skinny && R <= 32 && T <= 32 && sd::skinny_supported(m.d.d_model, m.d.d_ffn) &&
+         c->Lcap <= 256 && c->S_cur <= 256;
+}
+
+int decoder_layers_skinny(specdec_ctx* c, Model& m, int B, int T, hipStream_t st, sd::SkSrc* out) {
+  const int R = B * T, D = m.d.d_model, F = m.d.d_ffn, H = m.d.n_heads;
+  const int Lcap = c->Lcap, Scap = c->Scap;
+  if (!m.skinny_ready) {
+    HIPCHK(c, sd::skinny_init(D));
+    m.skinny_ready = true;
+  }
+  sd::SkSrc cur{0, nullptr, nullptr, nullptr, m.rm.row_tok, m.rm.row_pos, m.embed, m.pe};
+  float* freeb = m.x;       // residual-sum buffer not read by the kernel being launched
+  float* other = m.x2;
+  auto produced = [&](const bf16* g, const bf16* b) {   // freeb now holds the new sum
+    cur = sd::SkSrc{2, freeb, g, b, nullptr, nullptr, nullptr, nullptr};
+    float* t = freeb; freeb = other; other = t;
+  };
+  for (int l = 0; l < m.d.dec_layers; ++l) {
+    const DecLayer& L = m.dec[l];
+    bf16* kc = m.kc + m.kv_layer * l;
+    bf16* vc = m.vc + m.kv_layer * l;
+    LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::skinny_qkv(st, cur, R, D, L.wqkv, L.bqkv, m.q, kc, vc, m.rm.row_b, m.rm.row_pos, H, Lcap));
+    sd::AttnArgs a{};
+    a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
+    a.k = kc; a.k_b = (long)H * Lcap * 64; a.k_h = (long)Lcap * 64; a.k_row = 64;
+    a.v = vc; a.v_b = (long)H * Lcap * 64; a.v_h = (long)Lcap * 64; a.v_row = 64; a.v_blocked = 0;
+    a.o = nullptr; a.o_b = 0; a.o_row = 0;
+    a.q_count = m.rm.seq_rows; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
+    a.T = T; a.H = H; a.B = B; a.key_split = 0;
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_attn_o(st, cur, R, D, a, L.wo, L.bo, freeb));
+    produced(L.ln1g, L.ln1b);
+    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, cur, R, D, L.cwq, D, L.cbq, m.q, false));
+    a.k = m.xk + m.xkv_layer * l; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64;
+    a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_blocked = 1;
+    a.lim_row = nullptr; a.lim_seq = c->st.src_len;
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_attn_o(st, cur, R, D, a, L.cwo, L.cbo, freeb));
+    produced(L.ln2g, L.ln2b);
+    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, cur, R, D, L.w1, F, L.b1, m.hid, true));
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_ffn2(st, cur, R, D, m.hid, F, L.w2, L.b2, freeb));
+    produced(L.ln3g, L.ln3b);
+  }
+  *out = cur;
+  return SPECDEC_OK;
+}
+
 int cross_kv_from(specdec_ctx* c, Model& m, const bf16* memory, int B, int S_max, hipStream_t st) {
   const int D = m.d.d_model;
   for (int l = 0; l < m.d.dec_layers; ++l)
@@ -304,6 +358,7 @@ int specdec_create(specdec_ctx** out, const specdec_limits* lim) {
   if (!c) return SPECDEC_ERR_TOO_LARGE;
   c->lim = *lim;
   c->Tmax = 2 * lim->k_max + 1;
+  if (const char* e = getenv("SPECDEC_NO_SKINNY")) c->no_skinny = (e[0] == '1');
   c->Lcap = (lim->max_tgt + lim->k_max + 1 + 31) & ~31;   // rows of the KV arenas (32-key chunks)
   c->Scap = (lim->max_src + 31) & ~31;
   c->n_pos = c->Lcap > c->Scap ? c->Lcap : c->Scap;
@@ -576,11 +631,20 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
   hipStream_t st = S(stream);
   const int B = c->B, T = k + 1, R = B * T;
   LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::assemble_verify(st, c->st, m.rm, draft, B, k, m.d.vocab));
-  rc = decoder_layers(c, m, B, T, st);
-  if (rc) return rc;
-  const int n_tiles = (m.d.vocab + 127) / 128;
-  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.zd, m.part, logits));
-  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
+  if (skinny_ok(c, m, R, T)) {
+    sd::SkSrc fin{};
+    rc = decoder_layers_skinny(c, m, B, T, st, &fin);
+    if (rc) return rc;
+    const int n_tiles = (m.d.vocab + 63) / 64;
+    LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::skinny_vocab(st, fin, R, m.d.d_model, m.embed, m.d.vocab, m.rm.row_draft, m.zd, m.part, logits));
+    LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
+  } else {
+    rc = decoder_layers(c, m, B, T, st);
+    if (rc) return rc;
+    const int n_tiles = (m.d.vocab + 127) / 128;
+    LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.zd, m.part, logits));
+    LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
+  }
   LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::accept_rows(st, m.row_stats, c->st, B, k, beta, tau, m.d.pad_id, accept_len, next_token));
   c->last_k = k;
   return SPECDEC_OK;

@@ -19,23 +19,11 @@
 // drafter's mask slots (limit = whole block), padded cross / encoder attention (limit = source
 // length).  With key_split the 4 waves of a block share one pair and take every 4th chunk;
 // their partial (max, sum, O) are merged through LDS.
-#include "common.h"
-#include "kernels.h"
+#include "attn_core.h"
 
 namespace sd {
 
 constexpr int kAttnThreads = 256;
-
-__device__ __forceinline__ bf16x8 zero_tail(bf16x8 v, int nvalid) {
-  // keep elements [0, nvalid), zero the rest (values beyond a sequence's keys may be anything)
-  bf16x8 o;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) o[i] = (i < nvalid) ? v[i] : (bf16)0.f;
-  return o;
-}
-
-constexpr int kVtPitch = 68;   // bf16 per staged value row: 34 banks, so the transposed 2-byte
-                               // reads of the four lane groups (8 rows apart) hit disjoint banks
 
 template <int NQT, bool VBLK>
 __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
@@ -58,139 +46,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   const int nq_seq = a.q_count ? a.q_count[b] : a.T;
   const int nq = active_pair ? min(nq_seq - q0, NQT * 16) : 0;
 
-  // this lane's queries: q0 + qt*16 + lq; limits and Q operands (pre-scaled by 1/sqrt(64))
-  int lim[NQT];
-  bf16x8 qf[NQT][2];
-  int kmax = 0;
-#pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    const int qi = qt * 16 + lq;
-    const bool ok = qi < nq;
-    lim[qt] = ok ? (a.lim_row ? a.lim_row[b * a.T + q0 + qi] : a.lim_seq[b]) : 0;
-    kmax = max(kmax, lim[qt]);
-    const bf16* qp = a.q + b * a.q_b + (long)(q0 + (ok ? qi : 0)) * a.q_row + h * kHeadDim + g * 8;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 v = *reinterpret_cast<const bf16x8*>(qp + ks * 32);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = (bf16)((float)v[e] * 0.125f);   // exact: power of two
-      qf[qt][ks] = v;
-    }
-  }
-  kmax = wave_max_i(kmax);
-
   float mrun[NQT], lrun[NQT];
   f32x4 oacc[NQT][4];
-#pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    mrun[qt] = kNegInf; lrun[qt] = 0.f;
-#pragma unroll
-    for (int et = 0; et < 4; ++et) oacc[qt][et] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-
-  const bf16* kbase = a.k + b * a.k_b + h * a.k_h;
-  const bf16* vbase = a.v + b * a.v_b + h * a.v_h;
-  const int kclamp = max(kmax - 1, 0);
-
-  // operands of one 32-key chunk (8 x 16 B per lane); the next chunk is fetched while the
-  // current one is multiplied, so a wave pays the memory latency once, not once per chunk
-  auto load_chunk = [&](int c0, bf16x8 (&kf)[2][2], bf16x8 (&vf)[4]) {
-    // K operands: tile t, row lq  <->  key c0 + 8*(lq/4) + 4*t + lq%4
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int key = min(c0 + 8 * (lq >> 2) + 4 * t + (lq & 3), kclamp);
-      const bf16* kp = kbase + (long)key * a.k_row + g * 8;
-      kf[t][0] = *reinterpret_cast<const bf16x8*>(kp);
-      kf[t][1] = *reinterpret_cast<const bf16x8*>(kp + 32);
-    }
-    if (VBLK) {
-      // V operands: dim e = et*16 + lq, keys c0 + 8g .. +7 = one block of the key-blocked layout
-#pragma unroll
-      for (int et = 0; et < 4; ++et)
-        vf[et] = *reinterpret_cast<const bf16x8*>(vbase + vt_off(c0 + 8 * g, et * 16 + lq));
-    } else {
-      // row layout: fetch 32 whole rows (lane -> row 8*i + lane/8, dims 8*(lane%8) .. +7); they
-      // are turned into operands through LDS when the chunk is used
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = min(c0 + 8 * i + (lane >> 3), kclamp);
-        vf[i] = *reinterpret_cast<const bf16x8*>(vbase + (long)key * a.v_row + (lane & 7) * 8);
-      }
-    }
-  };
-  bf16x8 kf[2][2], vf[4], kn[2][2], vn[4];
-  const int cfirst = kw * 32, cstep = kstep * 32;
-  if (cfirst < kmax) load_chunk(cfirst, kf, vf);
-
-  for (int c0 = cfirst; c0 < kmax; c0 += cstep) {
-    const bool more = c0 + cstep < kmax;
-    if (more) load_chunk(c0 + cstep, kn, vn);
-    if (!VBLK) {
-      // wave-private transposition: rows -> LDS -> (dim, 8 consecutive keys) operands
-      // (LDS operations of one wave execute in order, so no barrier is needed; memcpy keeps
-      // the 16-byte store and the 2-byte loads in one alias class for the compiler)
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        __builtin_memcpy(&Vs[wave][8 * i + (lane >> 3)][(lane & 7) * 8], &vf[i], 16);
-#pragma unroll
-      for (int et = 0; et < 4; ++et)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) vf[et][i] = Vs[wave][8 * g + i][et * 16 + lq];
-    }
-    if (c0 + 32 > kmax) {
-      const int nvalid = kmax - (c0 + 8 * g);
-#pragma unroll
-      for (int et = 0; et < 4; ++et) vf[et] = zero_tail(vf[et], nvalid);
-    }
-#pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) {
-      f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][0], qf[qt][0], s0, 0, 0, 0);
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][1], qf[qt][1], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][0], qf[qt][0], s1, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][1], qf[qt][1], s1, 0, 0, 0);
-      // this lane: query lq of tile qt, keys kb .. kb+7 = {s0[0..3], s1[0..3]}
-      const int kb = c0 + 8 * g;
-      float s[8];
-      float cm = kNegInf;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        s[r] = (kb + r < lim[qt]) ? s0[r] : kNegInf;
-        s[4 + r] = (kb + 4 + r < lim[qt]) ? s1[r] : kNegInf;
-      }
-#pragma unroll
-      for (int r = 0; r < 8; ++r) cm = fmaxf(cm, s[r]);
-      cm = fmaxf(cm, __shfl_xor(cm, 16, 64));
-      cm = fmaxf(cm, __shfl_xor(cm, 32, 64));
-      const float mnew = fmaxf(mrun[qt], cm);
-      const bool any = mnew > kNegInf;
-      const float alpha = any ? __expf(mrun[qt] - mnew) : 1.f;   // exp(-inf) = 0 on first use
-      float ps = 0.f;
-      bf16x8 pf;
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        float p = (any && s[r] > kNegInf) ? __expf(s[r] - mnew) : 0.f;
-        ps += p;
-        pf[r] = (bf16)p;
-      }
-      ps += __shfl_xor(ps, 16, 64);
-      ps += __shfl_xor(ps, 32, 64);
-      lrun[qt] = lrun[qt] * alpha + ps;
-      mrun[qt] = mnew;
-#pragma unroll
-      for (int et = 0; et < 4; ++et) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) oacc[qt][et][r] *= alpha;
-        oacc[qt][et] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[et], pf, oacc[qt][et], 0, 0, 0);
-      }
-    }
-    if (more) {
-#pragma unroll
-      for (int t = 0; t < 2; ++t) { kf[t][0] = kn[t][0]; kf[t][1] = kn[t][1]; }
-#pragma unroll
-      for (int et = 0; et < 4; ++et) vf[et] = vn[et];
-    }
-  }
+  attn_wave<NQT, VBLK>(a, b, h, q0, nq, kw, kstep, Vs[VBLK ? 0 : wave], mrun, lrun, oacc);
 
   // oacc[qt][et][r] = O^T[e = et*16 + 4g + r][q = qt*16 + lq]
   if (!a.key_split) {

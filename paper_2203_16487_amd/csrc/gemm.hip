@@ -191,7 +191,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_kernel(const bf16* __restr
     pre[it] = epi.fetch(min(m0 + r, M - 1), min(n0 + c, N - 8));
   }
   GemmAcc<Cfg> acc;
-  gemm_mainloop<Cfg>(A, lda, W, ldw, M, N, 0, K / GK, m0, n0, smem, acc);
+  gemm_mainloop<Cfg>(A, lda, W, ldw, M, N, 0, K / Cfg::GK, m0, n0, smem, acc);
   float* cs = reinterpret_cast<float*>(smem);
   gemm_foreach<Cfg>(acc, 0, 0, [&](int r, int c, float v) { cs[cs_off<Cfg::kBN>(r, c)] = v; });
   __syncthreads();
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* _
   if (!xcd_tile(MT, NT, mt, nt)) return;
   const int m0 = mt * 128, n0 = nt * 128;
   GemmAcc<CfgVocab> acc;
-  gemm_mainloop<CfgVocab>(A, K, E, K, M, V, 0, K / GK, m0, n0, smem, acc);
+  gemm_mainloop<CfgVocab>(A, K, E, K, M, V, 0, K / CfgVocab::GK, m0, n0, smem, acc);
   float* cs = reinterpret_cast<float*>(smem);  // [128][128] fp32 = 64 KB
   gemm_foreach<CfgVocab>(acc, 0, 0, [&](int r, int c, float v) { cs[vs_off(r, c >> 2) + (c & 3)] = v; });
   __syncthreads();

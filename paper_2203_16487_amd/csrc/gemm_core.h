@@ -12,7 +12,6 @@
 
 namespace sd {
 
-constexpr int GK = 64;               // k extent of one pipeline stage
 constexpr int kGemmThreads = 256;
 
 #define SD_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
@@ -27,24 +26,30 @@ __device__ __forceinline__ void wait_vmcnt() {
 // clobber keeps the compiler from moving LDS accesses across it.
 __device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-// LDS tile rows are 64 bf16 = 8 chunks of 16 B.  Chunk c of row r lives at chunk
-// c ^ ((r >> 1) & 7): 16 consecutive rows reading the same logical chunk touch all 64 banks.
+// LDS tile rows hold GK bf16 (the k extent of one pipeline stage) = GK/8 chunks of 16 B.
+// GK = 64: chunk c of row r lives at chunk c ^ ((r >> 1) & 7); GK = 32: at c ^ ((r >> 2) & 3).
+// Either way 16 consecutive rows reading the same logical chunk touch all 64 banks once.
+template <int GK>
 __device__ __forceinline__ int lds_off(int row, int chunk) {
-  return row * GK + ((chunk ^ ((row >> 1) & 7)) << 3);
+  static_assert(GK == 64 || GK == 32, "stage depth");
+  return GK == 64 ? row * 64 + ((chunk ^ ((row >> 1) & 7)) << 3) : row * 32 + ((chunk ^ ((row >> 2) & 3)) << 3);
 }
 
-template <int BM, int BN, int STAGES, int WAVES_M = 2, int WAVES_N = 2>
+template <int BM, int BN, int STAGES, int WAVES_M = 2, int WAVES_N = 2, int GK_ = 64>
 struct GemmCfg {
+  static constexpr int GK = GK_;
+  static constexpr int kRowsPerLoad = 512 / GK;        // tile rows moved by one global_load_lds
   static constexpr int kBM = BM, kBN = BN, kStages = STAGES;
   static constexpr int kWavesM = WAVES_M, kWavesN = WAVES_N, kWaves = WAVES_M * WAVES_N;
   static constexpr int kThreads = 64 * kWaves;
   static constexpr int kRows = BM + BN;                 // LDS rows per stage (A rows then W rows)
-  static constexpr int kIPW = kRows / 8 / kWaves;       // global_load_lds per wave per stage
+  static constexpr int kIPW = kRows / kRowsPerLoad / kWaves;   // global_load_lds per wave per stage
   static constexpr int kStageElems = kRows * GK;
   static constexpr int kSmemBytes = STAGES * kStageElems * 2;
   static constexpr int kWM = BM / WAVES_M, kWN = BN / WAVES_N;   // wave tile
   static constexpr int kTM = kWM / 32, kTN = kWN / 32;           // MFMA tiles per wave
-  static_assert(kRows % (8 * kWaves) == 0 && kWM % 32 == 0 && kWN % 32 == 0, "tile shape");
+  static_assert(kRows % (kRowsPerLoad * kWaves) == 0 && BM % kRowsPerLoad == 0 && kWM % 32 == 0 && kWN % 32 == 0,
+                "tile shape");
 };
 
 template <class Cfg>
@@ -62,10 +67,10 @@ __device__ __forceinline__ void load_frags(GemmFrag<Cfg>& f, const bf16* sA, con
                                            int wn, int lrow, int lhalf, int kk) {
 #pragma unroll
   for (int i = 0; i < Cfg::kTM; ++i)
-    f.a[i] = *reinterpret_cast<const bf16x8*>(sA + lds_off(wm + i * 32 + lrow, kk * 2 + lhalf));
+    f.a[i] = *reinterpret_cast<const bf16x8*>(sA + lds_off<Cfg::GK>(wm + i * 32 + lrow, kk * 2 + lhalf));
 #pragma unroll
   for (int j = 0; j < Cfg::kTN; ++j)
-    f.b[j] = *reinterpret_cast<const bf16x8*>(sW + lds_off(wn + j * 32 + lrow, kk * 2 + lhalf));
+    f.b[j] = *reinterpret_cast<const bf16x8*>(sW + lds_off<Cfg::GK>(wn + j * 32 + lrow, kk * 2 + lhalf));
 }
 
 template <class Cfg>
@@ -77,15 +82,15 @@ __device__ __forceinline__ void mma_frags(GemmAcc<Cfg>& acc, const GemmFrag<Cfg>
       acc.c[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc.c[i][j], 0, 0, 0);
 }
 
-// Whole K range [k_begin, k_begin + 64*KT) of the block tile at (m0, n0).  Rows beyond M / N
+// Whole K range [k_begin, k_begin + GK*KT) of the block tile at (m0, n0).  Rows beyond M / N
 // are clamped to the last valid row (their products land in outputs that are never stored).
-// Requirements: K % 64 == 0, lda/ldw % 8 == 0, A and W 16-byte aligned, smem 1024-aligned.
+// Requirements: K % GK == 0, lda/ldw % 8 == 0, A and W 16-byte aligned, smem 1024-aligned.
 template <class Cfg>
 __device__ __forceinline__ void gemm_mainloop(const bf16* __restrict__ A, int lda,
                                               const bf16* __restrict__ W, int ldw, int M, int N,
                                               int k_begin, int KT, int m0, int n0, bf16* smem,
                                               GemmAcc<Cfg>& acc) {
-  constexpr int IPW = Cfg::kIPW, STAGES = Cfg::kStages;
+  constexpr int IPW = Cfg::kIPW, STAGES = Cfg::kStages, GK = Cfg::GK, RPL = Cfg::kRowsPerLoad, CPR = GK / 8;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave / Cfg::kWavesN) * Cfg::kWM, wn = (wave % Cfg::kWavesN) * Cfg::kWN;
 #pragma unroll
@@ -95,13 +100,13 @@ __device__ __forceinline__ void gemm_mainloop(const bf16* __restrict__ A, int ld
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc.c[i][j][r] = 0.f;
 
-  // One global_load_lds moves 64 lanes x 16 B = 8 tile rows; lane l lands at row l/8, physical
-  // chunk l%8, so it fetches the logical chunk that the swizzle maps there.
+  // One global_load_lds moves 64 lanes x 16 B = RPL tile rows; lane l lands at row l/CPR,
+  // physical chunk l%CPR, so it fetches the logical chunk that the swizzle maps there.
   const bf16* gptr[IPW];
 #pragma unroll
   for (int i = 0; i < IPW; ++i) {
-    const int row = (wave * IPW + i) * 8 + (lane >> 3);
-    const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+    const int row = (wave * IPW + i) * RPL + lane / CPR;
+    const int chunk = GK == 64 ? ((lane & 7) ^ ((row >> 1) & 7)) : ((lane & 3) ^ ((row >> 2) & 3));
     if (row < Cfg::kBM) {
       gptr[i] = A + (size_t)min(m0 + row, M - 1) * lda + k_begin + chunk * 8;
     } else {
@@ -111,7 +116,7 @@ __device__ __forceinline__ void gemm_mainloop(const bf16* __restrict__ A, int ld
   auto issue = [&](int kt, int slot) {
 #pragma unroll
     for (int i = 0; i < IPW; ++i) {
-      bf16* dst = smem + slot * Cfg::kStageElems + (wave * IPW + i) * 8 * GK;
+      bf16* dst = smem + slot * Cfg::kStageElems + (wave * IPW + i) * 512;
       __builtin_amdgcn_global_load_lds(SD_GLB_PTR(gptr[i] + kt * GK), SD_LDS_PTR(dst), 16, 0, 0);
     }
   };
@@ -132,10 +137,12 @@ __device__ __forceinline__ void gemm_mainloop(const bf16* __restrict__ A, int ld
     load_frags<Cfg>(f0, sA, sW, wm, wn, lrow, lhalf, 0);
     load_frags<Cfg>(f1, sA, sW, wm, wn, lrow, lhalf, 1);
     mma_frags<Cfg>(acc, f0);
-    load_frags<Cfg>(f0, sA, sW, wm, wn, lrow, lhalf, 2);
-    mma_frags<Cfg>(acc, f1);
-    load_frags<Cfg>(f1, sA, sW, wm, wn, lrow, lhalf, 3);
-    mma_frags<Cfg>(acc, f0);
+    if (GK == 64) {
+      load_frags<Cfg>(f0, sA, sW, wm, wn, lrow, lhalf, 2);
+      mma_frags<Cfg>(acc, f1);
+      load_frags<Cfg>(f1, sA, sW, wm, wn, lrow, lhalf, 3);
+      mma_frags<Cfg>(acc, f0);
+    }
     mma_frags<Cfg>(acc, f1);
   }
   block_barrier();   // LDS may be reused by the caller's epilogue

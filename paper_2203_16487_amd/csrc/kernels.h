@@ -71,6 +71,34 @@ struct AttnArgs {
 };
 hipError_t attention(hipStream_t st, const AttnArgs& a);
 
+// ---- skinny.hip: fused kernels for passes of at most 32 rows --------------------------
+// Where a kernel takes its input hidden state from: embedding rows (mode 0), raw fp32 rows
+// (mode 1) or the LayerNorm of fp32 rows (mode 2), all [R][d].
+struct SkSrc {
+  int mode;
+  const float* xs;
+  const bf16* g;
+  const bf16* b;
+  const int* tok;
+  const int* pos;
+  const bf16* E;
+  const float* pe;
+};
+bool skinny_supported(int d, int F);
+hipError_t skinny_init(int d);
+hipError_t skinny_qkv(hipStream_t st, const SkSrc& src, int R, int d, const bf16* W, const bf16* bias, bf16* q,
+                      bf16* kc, bf16* vc, const int* row_b, const int* row_pos, int H, int Lcap);
+// xs_out = hidden(resid) + attention(a) W^T + bias   (every block recomputes the attention)
+hipError_t skinny_attn_o(hipStream_t st, const SkSrc& resid, int R, int d, const AttnArgs& a, const bf16* W,
+                         const bf16* bias, float* xs_out);
+hipError_t skinny_proj(hipStream_t st, const SkSrc& src, int R, int d, const bf16* W, int N, const bf16* bias,
+                       bf16* out, bool relu);
+hipError_t skinny_ffn2(hipStream_t st, const SkSrc& resid, int R, int d, const bf16* hid, int F, const bf16* W,
+                       const bf16* bias, float* xs_out);
+// draft logits + per-row partial records per 64-column vocabulary tile (n_tiles = ceil(V/64))
+hipError_t skinny_vocab(hipStream_t st, const SkSrc& src, int R, int d, const bf16* E, int V, const int* row_draft,
+                        float* zd_row, float* part, float* logits);
+
 // ---- misc.hip ------------------------------------------------------------------------
 hipError_t build_pos_table(hipStream_t st, float* pe, int n_pos, int d);
 hipError_t embed_rows(hipStream_t st, const int* tok, const int* pos, const bf16* E,
