@@ -43,48 +43,79 @@ struct SkLds {
 };
 
 // Hidden state of the R rows = what `src` describes; bf16 copy of all columns -> hb (rows
-// R..31 zero), fp32 copy of columns [n0, n0 + 16) -> hown (for residual adds).
+// R .. nrows-1 zero), fp32 copy of columns [n0, n0 + 16) -> hown (for residual adds).
+// A wave takes rows wave, wave + 4, ...; it requests the data of up to four of them (and the
+// LayerNorm parameters, once) before it reduces any, so the prologue costs one memory round
+// trip however many rows there are.
 template <int PER>
-__device__ __forceinline__ void sk_hidden(const SkSrc& s, int R, bf16* hb, float* hown, int n0, bool want_hb) {
-  constexpr int d = 64 * PER, pitch = d + kSkPad;
+__device__ __forceinline__ void sk_hidden(const SkSrc& s, int R, int nrows, bf16* hb, float* hown, int n0,
+                                          bool want_hb) {
+  constexpr int d = 64 * PER, pitch = d + kSkPad, RU = 4;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  for (int r = wave; r < kSkRows; r += 4) {
-    float v[PER];
-    if (r < R) {
-      if (s.mode == 0) {
-        const bf16* e = s.E + (size_t)s.tok[r] * d;
-        const float* p = s.pe + (size_t)s.pos[r] * d;
-        const float sc = sqrtf((float)d);
+  float gg[PER], bb[PER];
+  if (s.mode == 2) {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) v[i] = (float)e[i * 64 + lane] * sc + p[i * 64 + lane];
-      } else {
+    for (int i = 0; i < PER; ++i) { gg[i] = (float)s.g[i * 64 + lane]; bb[i] = (float)s.b[i * 64 + lane]; }
+  }
+  for (int base = wave; base < nrows; base += 4 * RU) {
+    float v[RU][PER];
+    if (s.mode == 0) {
+      int tok[RU], pos[RU];
 #pragma unroll
-        for (int i = 0; i < PER; ++i) v[i] = s.xs[(size_t)r * d + i * 64 + lane];
-        if (s.mode == 2) {
-          float gg[PER], bb[PER];
+      for (int u = 0; u < RU; ++u) {
+        const int r = min(base + 4 * u, R - 1);
+        tok[u] = s.tok[r]; pos[u] = s.pos[r];
+      }
+      const float sc = sqrtf((float)d);
 #pragma unroll
-          for (int i = 0; i < PER; ++i) { gg[i] = (float)s.g[i * 64 + lane]; bb[i] = (float)s.b[i * 64 + lane]; }
-          float sum = 0.f;
+      for (int u = 0; u < RU; ++u) {
+        const bf16* e = s.E + (size_t)tok[u] * d;
+        const float* p = s.pe + (size_t)pos[u] * d;
 #pragma unroll
-          for (int i = 0; i < PER; ++i) sum += v[i];
-          const float mean = wave_sum(sum) / (float)d;
-          float q = 0.f;
-#pragma unroll
-          for (int i = 0; i < PER; ++i) { float t = v[i] - mean; q += t * t; }
-          const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
-#pragma unroll
-          for (int i = 0; i < PER; ++i) v[i] = (v[i] - mean) * rstd * gg[i] + bb[i];
-        }
+        for (int i = 0; i < PER; ++i) v[u][i] = (float)e[i * 64 + lane] * sc + p[i * 64 + lane];
       }
     } else {
 #pragma unroll
-      for (int i = 0; i < PER; ++i) v[i] = 0.f;
+      for (int u = 0; u < RU; ++u) {
+        const int r = min(base + 4 * u, R - 1);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) v[u][i] = s.xs[(size_t)r * d + i * 64 + lane];
+      }
+      if (s.mode == 2) {
+        float mean[RU], rstd[RU];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+          float sum = 0.f;
+#pragma unroll
+          for (int i = 0; i < PER; ++i) sum += v[u][i];
+          mean[u] = wave_sum(sum) / (float)d;
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+          float q = 0.f;
+#pragma unroll
+          for (int i = 0; i < PER; ++i) { float t = v[u][i] - mean[u]; q += t * t; }
+          rstd[u] = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u)
+#pragma unroll
+          for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean[u]) * rstd[u] * gg[i] + bb[i];
+      }
     }
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int c = i * 64 + lane;
-      if (want_hb) hb[r * pitch + c] = (bf16)v[i];
-      if (c >= n0 && c < n0 + 16) hown[r * 16 + c - n0] = v[i];
+    for (int u = 0; u < RU; ++u) {
+      const int r = base + 4 * u;
+      if (r < nrows) {
+        const bool real = r < R;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+          const int c = i * 64 + lane;
+          const float val = real ? v[u][i] : 0.f;
+          if (want_hb) hb[r * pitch + c] = (bf16)val;
+          if (c >= n0 && c < n0 + 16) hown[r * 16 + c - n0] = val;
+        }
+      }
     }
   }
 }
@@ -168,7 +199,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_qkv_kernel(SkSrc src, int R, co
   const int k0 = wave * (d / 4);
   bf16x8 wf[steps];
   sk_wload<steps>(W, d, n0, 3 * d, k0, wf);
-  sk_hidden<PER>(src, R, L.hb, L.hown, -64, true);
+  sk_hidden<PER>(src, R, TWO ? 32 : 16, L.hb, L.hown, -64, true);
   __syncthreads();
   f32x4 acc[2];
   sk_zero(acc);
@@ -202,19 +233,20 @@ __global__ __launch_bounds__(kSkThreads) void sk_attn_o_kernel(SkSrc resid, int 
   const int k0 = wave * (d / 4);
   bf16x8 wf[steps];
   sk_wload<steps>(W, d, n0, d, k0, wf);
-  sk_hidden<PER>(resid, R, L.hb, L.hown, n0, false);
+  sk_hidden<PER>(resid, R, TWO ? 32 : 16, L.hb, L.hown, n0, false);
   // attention output of every (sequence, head) pair -> hb (bf16 [32][d]); rows >= R zero
-  for (int idx = threadIdx.x; idx < kSkRows * pitch / 8; idx += kSkThreads)
+  for (int idx = threadIdx.x; idx < (TWO ? 32 : 16) * pitch / 8; idx += kSkThreads)
     reinterpret_cast<uint4*>(L.hb)[idx] = make_uint4(0, 0, 0, 0);
   __syncthreads();
   for (int p = wave; p < a.B * a.H; p += 4) {
     const int b = p / a.H, h = p - b * a.H;
-    const int nq = min(a.q_count ? a.q_count[b] : a.T, 32);
-    float mrun[2], lrun[2];
-    f32x4 oacc[2][4];
-    attn_wave<2, VBLK>(a, b, h, 0, nq, 0, 1, L.vs[wave], mrun, lrun, oacc);
+    constexpr int NQT = TWO ? 2 : 1;   // at most 16 rows in all: one query tile
+    const int nq = min(a.q_count ? a.q_count[b] : a.T, 16 * NQT);
+    float mrun[NQT], lrun[NQT];
+    f32x4 oacc[NQT][4];
+    attn_wave<NQT, VBLK>(a, b, h, 0, nq, 0, 1, L.vs[wave], mrun, lrun, oacc);
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < NQT; ++qt) {
       const int qi = qt * 16 + lq;
       if (qi < nq) {
         const float inv = lrun[qt] > 0.f ? 1.f / lrun[qt] : 0.f;
@@ -252,7 +284,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_proj_kernel(SkSrc src, int R, c
   const int k0 = wave * (d / 4);
   bf16x8 wf[steps];
   sk_wload<steps>(W, d, n0, N, k0, wf);
-  sk_hidden<PER>(src, R, L.hb, L.hown, -64, true);
+  sk_hidden<PER>(src, R, TWO ? 32 : 16, L.hb, L.hown, -64, true);
   __syncthreads();
   f32x4 acc[2];
   sk_zero(acc);
@@ -288,7 +320,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_ffn2_kernel(SkSrc resid, int R,
 #pragma unroll
     for (int u = 0; u < S1; ++u) hf[u] = *reinterpret_cast<const bf16x8*>(hp + u * 32);
   }
-  sk_hidden<PER>(resid, R, L.hb, L.hown, n0, false);
+  sk_hidden<PER>(resid, R, TWO ? 32 : 16, L.hb, L.hown, n0, false);
   f32x4 acc[2];
   sk_zero(acc);
   auto getB = [&](int t, int k) {
@@ -319,7 +351,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_draft_logit_kernel(SkSrc src, i
   SkLds<PER> L(sk_smem);
   constexpr int d = 64 * PER, pitch = d + kSkPad;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
-  sk_hidden<PER>(src, R, L.hb, L.hown, -64, true);
+  sk_hidden<PER>(src, R, R > 16 ? 32 : 16, L.hb, L.hown, -64, true);
   __syncthreads();
   if (wave >= 2) return;
   const int t = wave;
@@ -357,7 +389,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_vocab_kernel(SkSrc src, int R, 
   constexpr int steps = d / 32, S1 = steps < kSkW ? steps : kSkW;
   bf16x8 wf[S1];
   sk_wload<S1>(E, d, n0, V, 0, wf);
-  sk_hidden<PER>(src, R, L.hb, L.hown, -64, true);
+  sk_hidden<PER>(src, R, TWO ? 32 : 16, L.hb, L.hown, -64, true);
   __syncthreads();
   f32x4 acc[2];
   sk_zero(acc);
