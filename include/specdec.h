@@ -140,6 +140,10 @@ int specdec_draft(specdec_ctx* ctx, int32_t k, int32_t* draft, void* stream);
  *   next_token = the verifier's arg-max token on row a (lowest index among maxima); when all
  *   k drafts are accepted this is the token after the last draft.
  * Finished sequences report accept_len 0 and next_token pad_id.
+ * Passes of at most 32 rows run as one resident kernel whose workgroups meet at bounded grid
+ * barriers; should a barrier time out (never expected), every sequence reports accept_len -1
+ * and next_token pad_id, specdec_commit then changes nothing, and the condition lasts until
+ * the next specdec_begin.
  * logits_or_null: optional device fp32 [B, k+1, V] receiving every row's logits (parity
  * mode; slow).  Does not change any length: calling it twice gives the same result. */
 int specdec_verify(specdec_ctx* ctx, const int32_t* draft, int32_t k, int32_t beta, float tau,
@@ -192,7 +196,8 @@ typedef enum {
   SPECDEC_KIND_LN = 5,
   SPECDEC_KIND_ACCEPT = 6,
   SPECDEC_KIND_OTHER = 7,
-  SPECDEC_KIND_COUNT = 8
+  SPECDEC_KIND_RESIDENT = 8,   /* whole decoder pass + vocabulary tiles of a small batch, one kernel */
+  SPECDEC_KIND_COUNT = 9
 } specdec_kernel_kind;
 int specdec_profile_select(specdec_ctx* ctx, int32_t kind);
 int specdec_profile_read(specdec_ctx* ctx, double* total_ms /*host*/, int32_t* launches /*host*/);

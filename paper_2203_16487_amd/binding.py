@@ -208,7 +208,7 @@ def specdec_rewind(ctx, length):
     _check(ctx, lib().specdec_rewind(ctx, _ptr(length), _stream()))
 
 
-KIND = dict(none=-1, gemm_f32=0, gemm_bf16=1, gemm_qkv=2, attn=3, vocab=4, ln=5, accept=6, other=7)
+KIND = dict(none=-1, gemm_f32=0, gemm_bf16=1, gemm_qkv=2, attn=3, vocab=4, ln=5, accept=6, other=7, resident=8)
 
 
 def specdec_profile_select(ctx, kind: int):

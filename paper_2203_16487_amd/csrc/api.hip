@@ -40,6 +40,10 @@ struct Model {
   float* x = nullptr;        // [Rmax][d] residual stream
   float* x2 = nullptr;       // [32][d] second residual buffer of the fused small-batch path
   bool skinny_ready = false;
+  sd::RsLayer* rs_layers = nullptr;   // device copy of the decoder layers' pointers (resident kernel)
+  unsigned* rs_bar = nullptr;         // barrier counters + error flag of the resident kernel
+  int rs_parity = 0;
+  int rs_seq = 0;
   bf16* xb = nullptr;        // [Rmax][d]
   bf16* q = nullptr;         // [Rmax][d]
   bf16* att = nullptr;       // [Rmax][d]
@@ -76,6 +80,7 @@ struct specdec_ctx {
   std::vector<hipEvent_t> prof_ev;
   int prof_used = 0;
   bool no_skinny = false;   // SPECDEC_NO_SKINNY=1: always take the general kernels
+  bool resident = false;    // SPECDEC_RESIDENT=1: small batches run the decoder pass as one resident kernel
   char err[512] = {0};
 };
 
@@ -211,6 +216,8 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   t.rm.seq_rows = cv.take<int>(Bm);
   t.slots = cv.take<bf16>(Bm * (size_t)c->lim.k_max * D);
   t.new_rows = cv.take<int>(Bm);
+  t.rs_layers = cv.take<sd::RsLayer>(d->dec_layers);
+  t.rs_bar = cv.take<unsigned>(sd::kRsBarWords);
   if (d->enc_layers > 0) {
     const size_t Re = Bm * (size_t)c->Scap;
     t.ex = cv.take<float>(Re * D);
@@ -226,7 +233,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
     m->pe = t.pe; m->kc = t.kc; m->vc = t.vc; m->xk = t.xk; m->xv = t.xv;
     m->x = t.x; m->x2 = t.x2; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
     m->part = t.part; m->row_stats = t.row_stats; m->zd = t.zd; m->rm = t.rm;
-    m->slots = t.slots; m->new_rows = t.new_rows;
+    m->slots = t.slots; m->new_rows = t.new_rows; m->rs_layers = t.rs_layers; m->rs_bar = t.rs_bar;
     m->ex = t.ex; m->exb = t.exb; m->eqkv = t.eqkv; m->eatt = t.eatt; m->ehid = t.ehid;
     m->etok = t.etok; m->epos = t.epos;
   }
@@ -254,7 +261,7 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
     a.o = m.att; a.o_b = (long)T * D; a.o_row = D;
     a.q_count = m.rm.seq_rows; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
     a.T = T; a.H = H; a.B = B;
-    a.key_split = Lcap > 256;
+    a.key_split = Lcap > 256; a.cap = Lcap;
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.wo, R, D, D, L.bo, m.x, m.x, D));
     LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln1g, L.ln1b, m.xb, R, D));
@@ -262,7 +269,7 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
     a.k = m.xk + m.xkv_layer * l; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64;
     a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_blocked = 1;
     a.lim_row = nullptr; a.lim_seq = c->st.src_len;
-    a.key_split = c->S_cur > 256;
+    a.key_split = c->S_cur > 256; a.cap = Scap;
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.cwo, R, D, D, L.cbo, m.x, m.x, D));
     LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln2g, L.ln2b, m.xb, R, D));
@@ -294,29 +301,41 @@ int decoder_layers_skinny(specdec_ctx* c, Model& m, int B, int T, hipStream_t st
     cur = sd::SkSrc{2, freeb, g, b, nullptr, nullptr, nullptr, nullptr};
     float* t = freeb; freeb = other; other = t;
   };
+#ifdef SD_DEBUG
+  int dbg_left = getenv("SD_DEBUG_STOP") ? atoi(getenv("SD_DEBUG_STOP")) : 1 << 30;
+#define SKDBG if (--dbg_left <= 0) { *out = cur; return SPECDEC_OK; }
+#else
+#define SKDBG
+#endif
   for (int l = 0; l < m.d.dec_layers; ++l) {
     const DecLayer& L = m.dec[l];
     bf16* kc = m.kc + m.kv_layer * l;
     bf16* vc = m.vc + m.kv_layer * l;
     LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::skinny_qkv(st, cur, R, D, L.wqkv, L.bqkv, m.q, kc, vc, m.rm.row_b, m.rm.row_pos, H, Lcap));
+    SKDBG
     sd::AttnArgs a{};
     a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
     a.k = kc; a.k_b = (long)H * Lcap * 64; a.k_h = (long)Lcap * 64; a.k_row = 64;
     a.v = vc; a.v_b = (long)H * Lcap * 64; a.v_h = (long)Lcap * 64; a.v_row = 64; a.v_blocked = 0;
     a.o = nullptr; a.o_b = 0; a.o_row = 0;
     a.q_count = m.rm.seq_rows; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
-    a.T = T; a.H = H; a.B = B; a.key_split = 0;
+    a.T = T; a.H = H; a.B = B; a.key_split = 0; a.cap = Lcap;
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_attn_o(st, cur, R, D, a, L.wo, L.bo, freeb));
     produced(L.ln1g, L.ln1b);
+    SKDBG
     LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, cur, R, D, L.cwq, D, L.cbq, m.q, false));
+    SKDBG
     a.k = m.xk + m.xkv_layer * l; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64;
     a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_blocked = 1;
-    a.lim_row = nullptr; a.lim_seq = c->st.src_len;
+    a.lim_row = nullptr; a.lim_seq = c->st.src_len; a.cap = Scap;
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_attn_o(st, cur, R, D, a, L.cwo, L.cbo, freeb));
     produced(L.ln2g, L.ln2b);
+    SKDBG
     LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, cur, R, D, L.w1, F, L.b1, m.hid, true));
+    SKDBG
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_ffn2(st, cur, R, D, m.hid, F, L.w2, L.b2, freeb));
     produced(L.ln3g, L.ln3b);
+    SKDBG
   }
   *out = cur;
   return SPECDEC_OK;
@@ -359,6 +378,7 @@ int specdec_create(specdec_ctx** out, const specdec_limits* lim) {
   c->lim = *lim;
   c->Tmax = 2 * lim->k_max + 1;
   if (const char* e = getenv("SPECDEC_NO_SKINNY")) c->no_skinny = (e[0] == '1');
+  if (const char* e = getenv("SPECDEC_RESIDENT")) c->resident = (e[0] == '1');
   c->Lcap = (lim->max_tgt + lim->k_max + 1 + 31) & ~31;   // rows of the KV arenas (32-key chunks)
   c->Scap = (lim->max_src + 31) & ~31;
   c->n_pos = c->Lcap > c->Scap ? c->Lcap : c->Scap;
@@ -446,6 +466,17 @@ int specdec_bind_model(specdec_ctx* c, specdec_role role, const specdec_model_de
   }
   carve_model(c, d, workspace, &m);
   HIPCHK(c, sd::build_pos_table(S(stream), m.pe, c->n_pos, d->d_model));
+  {
+    std::vector<sd::RsLayer> rl(d->dec_layers);
+    for (int l = 0; l < d->dec_layers; ++l) {
+      const DecLayer& L = m.dec[l];
+      rl[l] = sd::RsLayer{L.wqkv, L.bqkv, L.wo, L.bo, L.ln1g, L.ln1b, L.cwq, L.cbq, L.cwo, L.cbo, L.ln2g, L.ln2b,
+                          L.w1, L.b1, L.w2, L.b2, L.ln3g, L.ln3b};
+    }
+    HIPCHK(c, hipMemcpy(m.rs_layers, rl.data(), rl.size() * sizeof(sd::RsLayer), hipMemcpyHostToDevice));
+    HIPCHK(c, sd::fill_i32(S(stream), reinterpret_cast<int*>(m.rs_bar), 0, sd::kRsBarWords));
+    m.rs_parity = 0;
+  }
   m.bound = true;
   return SPECDEC_OK;
 }
@@ -458,6 +489,10 @@ int specdec_begin(specdec_ctx* c, int32_t B, int32_t max_new, void* stream) {
   if (B > c->lim.max_batch) return fail(c, SPECDEC_ERR_TOO_LARGE, "B = %d exceeds max_batch = %d", B, c->lim.max_batch);
   const Model& any = c->m[0].bound ? c->m[0] : c->m[1];
   HIPCHK(c, sd::begin_state(S(stream), c->st, B, max_new, c->lim.max_tgt, any.d.bos_id));
+  if (c->m[0].bound) {   // a new run clears the resident kernel's counters and error flag
+    HIPCHK(c, sd::fill_i32(S(stream), reinterpret_cast<int*>(c->m[0].rs_bar), 0, sd::kRsBarWords));
+    c->m[0].rs_parity = 0;
+  }
   c->B = B;
   c->max_new = max_new;
   c->last_k = 0;
@@ -499,7 +534,7 @@ static int encoder_pass(specdec_ctx* c, Model& m, const int32_t* src, int B, int
     a.o = m.eatt; a.o_b = (long)S_max * D; a.o_row = D;
     a.q_count = c->st.src_len; a.lim_row = nullptr; a.lim_seq = c->st.src_len;
     a.T = S_max; a.H = H; a.B = B;
-    a.key_split = S_max > 256;
+    a.key_split = S_max > 256; a.cap = Scap;
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.eatt, D, L.wo, R, D, D, L.bo, m.ex, m.ex, D));
     LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.ex, L.ln1g, L.ln1b, m.exb, R, D));
@@ -631,7 +666,28 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
   hipStream_t st = S(stream);
   const int B = c->B, T = k + 1, R = B * T;
   LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::assemble_verify(st, c->st, m.rm, draft, B, k, m.d.vocab));
-  if (skinny_ok(c, m, R, T)) {
+  const unsigned* failed = nullptr;
+  if (skinny_ok(c, m, R, T) && c->resident) {
+    sd::RsArgs a{};
+    a.R = R; a.T = T; a.B = B; a.H = m.d.n_heads; a.V = m.d.vocab; a.Lcap = c->Lcap; a.Scap = c->Scap;
+    a.n_layers = m.d.dec_layers; a.layers = m.rs_layers;
+    a.row_tok = m.rm.row_tok; a.row_pos = m.rm.row_pos; a.row_b = m.rm.row_b; a.row_lim = m.rm.row_lim;
+    a.row_draft = m.rm.row_draft; a.seq_rows = m.rm.seq_rows; a.src_len = c->st.src_len;
+    a.E = m.embed; a.pe = m.pe; a.xs0 = m.x; a.xs1 = m.x2; a.q = m.q; a.hid = m.hid;
+    a.kc = m.kc; a.vc = m.vc; a.xk = m.xk; a.xv = m.xv; a.kv_layer = m.kv_layer; a.xkv_layer = m.xkv_layer;
+    a.zd = m.zd; a.part = m.part; a.logits = logits;
+    a.bar = m.rs_bar; a.parity = m.rs_parity;
+    m.rs_seq = m.rs_seq >= 0x3fffffff ? 1 : m.rs_seq + 1;
+    a.seq = m.rs_seq;
+#ifdef SD_DEBUG
+    a.stop_after = getenv("SD_DEBUG_STOP") ? atoi(getenv("SD_DEBUG_STOP")) : 1 << 30;
+#endif
+    m.rs_parity ^= 1;
+    LAUNCH(c, SPECDEC_KIND_RESIDENT, st, sd::resident_verify(st, a, m.d.d_model, m.d.d_ffn));
+    const int n_tiles = (m.d.vocab + 63) / 64;
+    LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
+    failed = m.rs_bar + 16;
+  } else if (skinny_ok(c, m, R, T)) {
     sd::SkSrc fin{};
     rc = decoder_layers_skinny(c, m, B, T, st, &fin);
     if (rc) return rc;
@@ -645,7 +701,7 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
     LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.zd, m.part, logits));
     LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
   }
-  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::accept_rows(st, m.row_stats, c->st, B, k, beta, tau, m.d.pad_id, accept_len, next_token));
+  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::accept_rows(st, m.row_stats, c->st, B, k, beta, tau, m.d.pad_id, accept_len, next_token, failed));
   c->last_k = k;
   return SPECDEC_OK;
 }
@@ -746,3 +802,12 @@ int specdec_get_row_stats(specdec_ctx* c, float* stats, void* stream) {
 }
 
 }  // extern "C"
+
+#ifdef SD_DEBUG
+extern "C" int sd_debug_copy(specdec_ctx* c, int which, void* host, size_t bytes) {
+  Model& m = c->m[0];
+  const void* src = which == 0 ? (const void*)m.x : which == 1 ? (const void*)m.x2 : which == 2 ? (const void*)m.q : (const void*)m.hid;
+  (void)hipDeviceSynchronize();
+  return (int)hipMemcpy(host, src, bytes, hipMemcpyDeviceToHost);
+}
+#endif

@@ -114,6 +114,7 @@ static hipError_t attention_launch(hipStream_t st, const AttnArgs& a) {
 
 hipError_t attention(hipStream_t st, const AttnArgs& a) {
   if (a.B <= 0 || a.T <= 0) return hipSuccess;
+  if (a.cap < 32 || a.cap % 32 != 0) return hipErrorInvalidValue;   // whole chunks are read
   return a.v_blocked ? attention_launch<true>(st, a) : attention_launch<false>(st, a);
 }
 

@@ -20,12 +20,52 @@ constexpr int kVtPitch = 68;   // bf16 per staged value row: 34 banks, so the tr
 // key chunks kw, kw + kstep, ... of 32 keys.  Results: running max / sum per query (lane%16
 // of tile qt) and the unnormalised O^T accumulators oacc[qt][et][r] = O^T[e = et*16 + 4*(lane/16)
 // + r][q = qt*16 + lane%16].  Vs: wave-private LDS tile [32][kVtPitch] (row-layout values only).
-template <int NQT, bool VBLK>
+// COHQ / COHKV: queries / keys and row-layout values may have been written by other workgroups
+// of the running kernel (coherent loads, see ld16).
+template <int NQT, bool VBLK, bool COHQ = false, bool COHKV = false>
 __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q0, int nq, int kw, int kstep,
                                           bf16 (*Vs)[kVtPitch], float (&mrun)[NQT], float (&lrun)[NQT],
                                           f32x4 (&oacc)[NQT][4]) {
   const int lane = threadIdx.x & 63;
   const int lq = lane & 15, g = lane >> 4;
+  const bf16* kbase = a.k + b * a.k_b + h * a.k_h;
+  const bf16* vbase = a.v + b * a.v_b + h * a.v_h;
+
+  // operands of one 32-key chunk (8 x 16 B per lane), key rows clamped to `last`; the next
+  // chunk is fetched while the current one is multiplied
+  auto load_chunk = [&](int c0, int last, bf16x8 (&kf)[2][2], bf16x8 (&vf)[4]) {
+    // K operands: tile t, row lq  <->  key c0 + 8*(lq/4) + 4*t + lq%4
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int key = min(c0 + 8 * (lq >> 2) + 4 * t + (lq & 3), last);
+      const bf16* kp = kbase + (long)key * a.k_row + g * 8;
+      kf[t][0] = ld16<COHKV>(kp);
+      kf[t][1] = ld16<COHKV>(kp + 32);
+    }
+    if (VBLK) {
+      // V operands: dim e = et*16 + lq, keys kb .. kb+7 = one block of the key-blocked layout
+      const int kb = min(c0 + 8 * g, a.cap - 8);
+#pragma unroll
+      for (int et = 0; et < 4; ++et)
+        vf[et] = *reinterpret_cast<const bf16x8*>(vbase + vt_off(kb, et * 16 + lq));
+    } else {
+      // row layout: fetch 32 whole rows (lane -> row 8*i + lane/8, dims 8*(lane%8) .. +7); they
+      // are turned into operands through LDS when the chunk is used
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int key = min(c0 + 8 * i + (lane >> 3), last);
+        vf[i] = ld16<COHKV>(vbase + (long)key * a.v_row + (lane & 7) * 8);
+      }
+    }
+  };
+  // The first chunk is requested before the limits are known (its addresses depend on no
+  // loaded value: rows are clamped to the arena, whose every row may be read; keys past a
+  // query's limit are masked by selection and their values zeroed), so limits, queries, keys
+  // and values of a short context arrive in one memory round trip.
+  bf16x8 kf[2][2], vf[4], kn[2][2], vn[4];
+  const int cfirst = kw * 32, cstep = kstep * 32;
+  load_chunk(cfirst, a.cap - 1, kf, vf);
+
   // this lane's queries: q0 + qt*16 + lq; limits and Q operands (pre-scaled by 1/sqrt(64))
   int lim[NQT];
   bf16x8 qf[NQT][2];
@@ -39,7 +79,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
     const bf16* qp = a.q + b * a.q_b + (long)(q0 + (ok ? qi : 0)) * a.q_row + h * kHeadDim + g * 8;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 v = *reinterpret_cast<const bf16x8*>(qp + ks * 32);
+      bf16x8 v = ld16<COHQ>(qp + ks * 32);
 #pragma unroll
       for (int e = 0; e < 8; ++e) v[e] = (bf16)((float)v[e] * 0.125f);   // exact: power of two
       qf[qt][ks] = v;
@@ -54,43 +94,11 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
     for (int et = 0; et < 4; ++et) oacc[qt][et] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  const bf16* kbase = a.k + b * a.k_b + h * a.k_h;
-  const bf16* vbase = a.v + b * a.v_b + h * a.v_h;
   const int kclamp = max(kmax - 1, 0);
-
-  // operands of one 32-key chunk (8 x 16 B per lane); the next chunk is fetched while the
-  // current one is multiplied, so a wave pays the memory latency once, not once per chunk
-  auto load_chunk = [&](int c0, bf16x8 (&kf)[2][2], bf16x8 (&vf)[4]) {
-    // K operands: tile t, row lq  <->  key c0 + 8*(lq/4) + 4*t + lq%4
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int key = min(c0 + 8 * (lq >> 2) + 4 * t + (lq & 3), kclamp);
-      const bf16* kp = kbase + (long)key * a.k_row + g * 8;
-      kf[t][0] = *reinterpret_cast<const bf16x8*>(kp);
-      kf[t][1] = *reinterpret_cast<const bf16x8*>(kp + 32);
-    }
-    if (VBLK) {
-      // V operands: dim e = et*16 + lq, keys c0 + 8g .. +7 = one block of the key-blocked layout
-#pragma unroll
-      for (int et = 0; et < 4; ++et)
-        vf[et] = *reinterpret_cast<const bf16x8*>(vbase + vt_off(c0 + 8 * g, et * 16 + lq));
-    } else {
-      // row layout: fetch 32 whole rows (lane -> row 8*i + lane/8, dims 8*(lane%8) .. +7); they
-      // are turned into operands through LDS when the chunk is used
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int key = min(c0 + 8 * i + (lane >> 3), kclamp);
-        vf[i] = *reinterpret_cast<const bf16x8*>(vbase + (long)key * a.v_row + (lane & 7) * 8);
-      }
-    }
-  };
-  bf16x8 kf[2][2], vf[4], kn[2][2], vn[4];
-  const int cfirst = kw * 32, cstep = kstep * 32;
-  if (cfirst < kmax) load_chunk(cfirst, kf, vf);
 
   for (int c0 = cfirst; c0 < kmax; c0 += cstep) {
     const bool more = c0 + cstep < kmax;
-    if (more) load_chunk(c0 + cstep, kn, vn);
+    if (more) load_chunk(c0 + cstep, kclamp, kn, vn);
     if (!VBLK) {
       // wave-private transposition: rows -> LDS -> (dim, 8 consecutive keys) operands
       // (LDS operations of one wave execute in order, so no barrier is needed; memcpy keeps
@@ -157,7 +165,8 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
       for (int et = 0; et < 4; ++et) vf[et] = vn[et];
     }
   }
-
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) mfma_settle(oacc[qt]);
 }
 
 }  // namespace sd

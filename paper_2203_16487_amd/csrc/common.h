@@ -56,4 +56,52 @@ __device__ __forceinline__ void top_insert(float (&t)[N], float v) {
   }
 }
 
+// Wait states between the last MFMA of a chain and ordinary vector instructions that read its
+// result.  Seen on this toolchain: when a branch separates the two, the required wait states
+// are not always inserted and the last result registers are read before they are written
+// (wrong sums in columns 4g+2, 4g+3 of a 16x16 tile).  The asm statements below consume the
+// accumulators, so they cannot move above the MFMAs, and hold 32 idle issue slots (the longest
+// MFMA needs 19); whatever reads the accumulators afterwards reads settled registers.
+__device__ __forceinline__ void mfma_settle(f32x4& a) { asm volatile("s_nop 15\n\ts_nop 15" : "+v"(a)); }
+__device__ __forceinline__ void mfma_settle(f32x4& a, f32x4& b) {
+  asm volatile("s_nop 15\n\ts_nop 15" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void mfma_settle(f32x4 (&a)[4]) {
+  asm volatile("s_nop 15\n\ts_nop 15" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
+}
+__device__ __forceinline__ void mfma_settle(f32x16& a) { asm volatile("s_nop 15\n\ts_nop 15" : "+v"(a)); }
+
+// Accesses that are coherent among all workgroups of a running kernel: relaxed atomics at
+// device scope go to the coherence point instead of the issuing CU's L1 / XCD's L2, so a
+// value stored this way and acknowledged (s_waitcnt vmcnt(0)) is what a later load of this
+// kind returns, on whichever XCD the two workgroups run.
+__device__ __forceinline__ float ld_coh(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ int ld_coh(const int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bf16x8 ld_coh16(const bf16* p) {   // 16 bytes, 8-byte aligned halves
+  const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
+  unsigned long long u[2];
+  u[0] = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  u[1] = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  bf16x8 v;
+  __builtin_memcpy(&v, u, 16);
+  return v;
+}
+__device__ __forceinline__ void st_coh(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_coh(bf16* p, bf16 v) {
+  unsigned short bits;
+  __builtin_memcpy(&bits, &v, 2);
+  __hip_atomic_store(reinterpret_cast<unsigned short*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <bool COH>
+__device__ __forceinline__ bf16x8 ld16(const bf16* p) {
+  if (COH) return ld_coh16(p);
+  return *reinterpret_cast<const bf16x8*>(p);
+}
+
 }  // namespace sd

@@ -145,6 +145,10 @@ __device__ __forceinline__ void gemm_mainloop(const bf16* __restrict__ A, int ld
     }
     mma_frags<Cfg>(acc, f1);
   }
+#pragma unroll
+  for (int i = 0; i < Cfg::kTM; ++i)
+#pragma unroll
+    for (int j = 0; j < Cfg::kTN; ++j) mfma_settle(acc.c[i][j]);
   block_barrier();   // LDS may be reused by the caller's epilogue
 }
 

@@ -67,6 +67,7 @@ struct AttnArgs {
   const int* lim_seq;                         // [B]  visible keys of every query of b
   int T;                                      // max queries per sequence (q_b = T rows apart)
   int H, B;
+  int cap;                                    // key rows of one (b, h) arena (multiple of 32); any row below it may be read
   int key_split;                              // 1: the 4 waves of a block split one pair's keys
 };
 hipError_t attention(hipStream_t st, const AttnArgs& a);
@@ -85,6 +86,36 @@ struct SkSrc {
   const float* pe;
 };
 bool skinny_supported(int d, int F);
+
+// ---- resident.hip: the whole verification pass of at most 32 rows as one resident kernel ----
+struct RsLayer {
+  const bf16 *wqkv, *bqkv, *wo, *bo, *ln1g, *ln1b;
+  const bf16 *cwq, *cbq, *cwo, *cbo, *ln2g, *ln2b;
+  const bf16 *w1, *b1, *w2, *b2, *ln3g, *ln3b;
+};
+struct RsArgs {
+  int R, T, B, H, V, Lcap, Scap, n_layers;
+  const RsLayer* layers;              // device array [n_layers]
+  const int *row_tok, *row_pos, *row_b, *row_lim, *row_draft, *seq_rows, *src_len;
+  const bf16* E;                      // tied embedding / output matrix [V][d]
+  const float* pe;
+  float *xs0, *xs1;                   // residual-sum buffers [32][d]
+  bf16 *q, *hid;                      // [32][d], [32][F]
+  bf16 *kc, *vc;                      // self K/V arenas, layer stride kv_layer
+  const bf16 *xk, *xv;                // cross K/V arenas, layer stride xkv_layer
+  size_t kv_layer, xkv_layer;
+  float *zd, *part, *logits;          // outputs: draft logits [R], tile records, optional logits
+  unsigned* bar;                      // kRsBarWords words: [0],[1] arrival counters (alternating
+                                      // launches), [16] error flag, [64*(1+h)] wake-up word of helper h
+  int parity;                         // which counter this launch uses (the other one is cleared)
+  int seq;                            // launch number, never 0
+#ifdef SD_DEBUG
+  int stop_after;
+#endif
+};
+constexpr int kRsWorkers = 32;        // workgroups of the resident kernel that run the decoder phases
+constexpr int kRsBarWords = 64 * 226;
+hipError_t resident_verify(hipStream_t st, const RsArgs& a, int d, int F);
 hipError_t skinny_init(int d);
 hipError_t skinny_qkv(hipStream_t st, const SkSrc& src, int R, int d, const bf16* W, const bf16* bias, bf16* q,
                       bf16* kc, bf16* vc, const int* row_b, const int* row_pos, int H, int Lcap);
@@ -137,8 +168,10 @@ hipError_t encoder_rows(hipStream_t st, const int* src, int* tok, int* pos, int 
 hipError_t merge_rows(hipStream_t st, const float* part, const float* zd_row, int n_tiles, int R,
                       float* row_stats);
 // top-beta / tau rule on the merged rows and the leading-accept scan per sequence
+// (fail: optional device flag; when set every sequence reports accept_len -1, next_token pad)
 hipError_t accept_rows(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k,
-                       int beta, float tau, int pad_id, int* accept_len, int* next_token);
+                       int beta, float tau, int pad_id, int* accept_len, int* next_token,
+                       const unsigned* fail = nullptr);
 hipError_t commit_rows(hipStream_t st, const SeqState& s, const int* accept_len,
                        const int* next_token, int B, int eos_id, int* n_active);
 hipError_t begin_state(hipStream_t st, const SeqState& s, int B, int max_new, int max_tgt,

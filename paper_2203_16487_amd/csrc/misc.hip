@@ -271,9 +271,11 @@ hipError_t merge_rows(hipStream_t st, const float* part, const float* zd_row, in
 // beta-th score passes, as ">=" says).  a = number of leading rows that pass; next = arg-max
 // of row a.
 __global__ void accept_kernel(const float* __restrict__ row_stats, SeqState s, int B, int k, int beta, float tau,
-                              int pad_id, int* __restrict__ accept_len, int* __restrict__ next_token) {
+                              int pad_id, int* __restrict__ accept_len, int* __restrict__ next_token,
+                              const unsigned* __restrict__ fail) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
+  if (fail && *fail) { accept_len[b] = -1; next_token[b] = pad_id; return; }
   const int T = k + 1;
   int a = 0;
   for (; a < k; ++a) {
@@ -285,9 +287,9 @@ __global__ void accept_kernel(const float* __restrict__ row_stats, SeqState s, i
   next_token[b] = fin ? pad_id : (int)row_stats[(size_t)(b * T + a) * kRowStats + 1];
 }
 hipError_t accept_rows(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k, int beta,
-                       float tau, int pad_id, int* accept_len, int* next_token) {
+                       float tau, int pad_id, int* accept_len, int* next_token, const unsigned* fail) {
   hipLaunchKernelGGL(accept_kernel, blocks_for(B, 64), dim3(64), 0, st, row_stats, s, B, k, beta, tau, pad_id,
-                     accept_len, next_token);
+                     accept_len, next_token, fail);
   return hipGetLastError();
 }
 
@@ -304,7 +306,8 @@ __global__ void commit_kernel(SeqState s, const int* __restrict__ accept_len, co
   for (int b = threadIdx.x; b < B; b += blockDim.x) {
     if (!s.finished[b]) {
       int a = accept_len[b];
-      a = max(0, min(a, s.k_max));
+      if (a < 0) { ++mine; continue; }   // verification reported a failure: nothing to commit
+      a = min(a, s.k_max);
       int j = s.len[b];
       const int cap = s.cap[b];
       int* u = s.tokens + (size_t)b * s.tok_pitch;

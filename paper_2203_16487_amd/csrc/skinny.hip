@@ -15,174 +15,10 @@
 // before the first MFMA (one memory round trip per kernel), and the 4 partial tiles are summed
 // through LDS in a fixed order.  MFMA 16x16x32: A = 16 weight rows, B = up to 2 x 16 activation
 // rows, so D[n][m]: lane holds row m = lane%16, columns n = 4*(lane/16) + r.
-#include "attn_core.h"
+#include "skinny_core.h"
 
 namespace sd {
 
-constexpr int kSkThreads = 256;
-constexpr int kSkRows = 32;          // activation rows a block can hold (2 MFMA column tiles)
-constexpr int kSkPad = 8;            // bf16 padding of an activation row in LDS (bank spread)
-
-// LDS carve-up (dynamic): hb bf16 [32][d + 8] | hown f32 [32][16] | red f32 [4][16][33] | Vs
-template <int PER>
-struct SkLds {
-  static constexpr int d = 64 * PER;
-  static constexpr int kPitch = d + kSkPad;
-  static constexpr size_t kHb = (size_t)kSkRows * kPitch * 2;
-  static constexpr size_t kOwn = (size_t)kSkRows * 16 * 4;
-  static constexpr size_t kRed = (size_t)4 * 16 * 33 * 4;
-  static constexpr size_t kVs = (size_t)4 * 32 * kVtPitch * 2;
-  static constexpr size_t kBytes = kHb + kOwn + kRed + kVs;
-  bf16* hb; float* hown; float* red; bf16 (*vs)[32][kVtPitch];
-  __device__ explicit SkLds(char* base) {
-    hb = reinterpret_cast<bf16*>(base);
-    hown = reinterpret_cast<float*>(base + kHb);
-    red = reinterpret_cast<float*>(base + kHb + kOwn);
-    vs = reinterpret_cast<bf16 (*)[32][kVtPitch]>(base + kHb + kOwn + kRed);
-  }
-};
-
-// Hidden state of the R rows = what `src` describes; bf16 copy of all columns -> hb (rows
-// R .. nrows-1 zero), fp32 copy of columns [n0, n0 + 16) -> hown (for residual adds).
-// A wave takes rows wave, wave + 4, ...; it requests the data of up to four of them (and the
-// LayerNorm parameters, once) before it reduces any, so the prologue costs one memory round
-// trip however many rows there are.
-template <int PER>
-__device__ __forceinline__ void sk_hidden(const SkSrc& s, int R, int nrows, bf16* hb, float* hown, int n0,
-                                          bool want_hb) {
-  constexpr int d = 64 * PER, pitch = d + kSkPad, RU = 4;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  float gg[PER], bb[PER];
-  if (s.mode == 2) {
-#pragma unroll
-    for (int i = 0; i < PER; ++i) { gg[i] = (float)s.g[i * 64 + lane]; bb[i] = (float)s.b[i * 64 + lane]; }
-  }
-  for (int base = wave; base < nrows; base += 4 * RU) {
-    float v[RU][PER];
-    if (s.mode == 0) {
-      int tok[RU], pos[RU];
-#pragma unroll
-      for (int u = 0; u < RU; ++u) {
-        const int r = min(base + 4 * u, R - 1);
-        tok[u] = s.tok[r]; pos[u] = s.pos[r];
-      }
-      const float sc = sqrtf((float)d);
-#pragma unroll
-      for (int u = 0; u < RU; ++u) {
-        const bf16* e = s.E + (size_t)tok[u] * d;
-        const float* p = s.pe + (size_t)pos[u] * d;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) v[u][i] = (float)e[i * 64 + lane] * sc + p[i * 64 + lane];
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < RU; ++u) {
-        const int r = min(base + 4 * u, R - 1);
-#pragma unroll
-        for (int i = 0; i < PER; ++i) v[u][i] = s.xs[(size_t)r * d + i * 64 + lane];
-      }
-      if (s.mode == 2) {
-        float mean[RU], rstd[RU];
-#pragma unroll
-        for (int u = 0; u < RU; ++u) {
-          float sum = 0.f;
-#pragma unroll
-          for (int i = 0; i < PER; ++i) sum += v[u][i];
-          mean[u] = wave_sum(sum) / (float)d;
-        }
-#pragma unroll
-        for (int u = 0; u < RU; ++u) {
-          float q = 0.f;
-#pragma unroll
-          for (int i = 0; i < PER; ++i) { float t = v[u][i] - mean[u]; q += t * t; }
-          rstd[u] = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
-        }
-#pragma unroll
-        for (int u = 0; u < RU; ++u)
-#pragma unroll
-          for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean[u]) * rstd[u] * gg[i] + bb[i];
-      }
-    }
-#pragma unroll
-    for (int u = 0; u < RU; ++u) {
-      const int r = base + 4 * u;
-      if (r < nrows) {
-        const bool real = r < R;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) {
-          const int c = i * 64 + lane;
-          const float val = real ? v[u][i] : 0.f;
-          if (want_hb) hb[r * pitch + c] = (bf16)val;
-          if (c >= n0 && c < n0 + 16) hown[r * 16 + c - n0] = val;
-        }
-      }
-    }
-  }
-}
-
-// Weight operands of this wave: rows n0 + lane%16 of W, k range [k0, k0 + 32*S).  sk_wload only
-// issues the loads -- kernels call it first thing, so the weights travel while the prologue
-// (LayerNorm, attention) runs; sk_mma consumes them:
-//   acc[t] += W[n0 + i][k] . B_t[j][k],  getB(t, k) = 8 bf16 of activation row t*16 + lane%16 at k.
-// Step counts and the second row tile are compile-time, so the MFMA sequence is straight-line.
-constexpr int kSkW = 16;   // most steps held in registers at a time
-template <int S>
-__device__ __forceinline__ void sk_wload(const bf16* __restrict__ W, int ldw, int n0, int N, int k0,
-                                         bf16x8 (&wf)[S]) {
-  const int lane = threadIdx.x & 63, lq = lane & 15, g = lane >> 4;
-  const bf16* wp = W + (size_t)min(n0 + lq, N - 1) * ldw + k0 + 8 * g;
-#pragma unroll
-  for (int u = 0; u < S; ++u) wf[u] = *reinterpret_cast<const bf16x8*>(wp + u * 32);
-}
-template <int S, bool TWO, class GetB>
-__device__ __forceinline__ void sk_mma(const bf16x8 (&wf)[S], int k0, GetB&& getB, f32x4 (&acc)[2]) {
-  const int g = (threadIdx.x & 63) >> 4;
-#pragma unroll
-  for (int u = 0; u < S; ++u) {
-    const int k = k0 + u * 32 + 8 * g;
-    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], getB(0, k), acc[0], 0, 0, 0);
-    if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], getB(1, k), acc[1], 0, 0, 0);
-  }
-}
-// steps kSkW .. STEPS - 1 of a long k range, kSkW at a time
-template <int STEPS, bool TWO, class GetB>
-__device__ __forceinline__ void sk_mma_tail(const bf16* __restrict__ W, int ldw, int n0, int N, int k0,
-                                            GetB&& getB, f32x4 (&acc)[2]) {
-  if constexpr (STEPS > kSkW) {
-    static_assert(STEPS % kSkW == 0, "long k ranges come in whole batches");
-#pragma unroll 1
-    for (int s0 = kSkW; s0 < STEPS; s0 += kSkW) {
-      bf16x8 wf[kSkW];
-      sk_wload<kSkW>(W, ldw, n0, N, k0 + s0 * 32, wf);
-      sk_mma<kSkW, TWO>(wf, k0 + s0 * 32, getB, acc);
-    }
-  }
-}
-__device__ __forceinline__ void sk_zero(f32x4 (&acc)[2]) {
-  acc[0] = f32x4{0.f, 0.f, 0.f, 0.f};
-  acc[1] = acc[0];
-}
-
-// Sum the 4 waves' partial tiles (fixed order) and hand every output (m, n local) to f.
-template <class F>
-__device__ __forceinline__ void sk_reduce(const f32x4 (&acc)[2], float* red, int R, F&& f) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
-#pragma unroll
-  for (int t = 0; t < 2; ++t)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) red[(wave * 16 + 4 * g + r) * 33 + t * 16 + lq] = acc[t][r];
-  __syncthreads();
-  for (int idx = threadIdx.x; idx < 16 * kSkRows; idx += kSkThreads) {
-    const int m = idx >> 4, n = idx & 15;
-    if (m < R) {
-      float v = red[(0 * 16 + n) * 33 + m];
-      v += red[(1 * 16 + n) * 33 + m];
-      v += red[(2 * 16 + n) * 33 + m];
-      v += red[(3 * 16 + n) * 33 + m];
-      f(m, n, v);
-    }
-  }
-}
 
 // ------------------------------------------------------------------------------------ qkv
 template <int PER, bool TWO>
@@ -221,24 +57,28 @@ __global__ __launch_bounds__(kSkThreads) void sk_qkv_kernel(SkSrc src, int R, co
 // ------------------------------------------------------------------------------------ attention + O
 // resid: hidden state the sublayer started from (its own 16 columns are added back).
 template <int PER, bool VBLK, bool TWO>
-__global__ __launch_bounds__(kSkThreads) void sk_attn_o_kernel(SkSrc resid, int R, AttnArgs a,
-                                                               const bf16* __restrict__ W,
-                                                               const bf16* __restrict__ bias,
-                                                               float* __restrict__ xs_out) {
+__global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resid, int R, AttnArgs a,
+                                                                      const bf16* __restrict__ W,
+                                                                      const bf16* __restrict__ bias,
+                                                                      float* __restrict__ xs_out) {
   extern __shared__ __attribute__((aligned(16))) char sk_smem[];
   SkLds<PER> L(sk_smem);
-  constexpr int d = 64 * PER, pitch = d + kSkPad;
+  constexpr int d = 64 * PER, pitch = d + kSkPad, steps = d / 128;
   const int n0 = blockIdx.x * 16, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
-  constexpr int steps = d / 128;
-  const int k0 = wave * (d / 4);
+  const bool kwave = wave < 4;                 // the four waves that split K of the O-projection
+  const int k0 = (wave & 3) * (d / 4);
   bf16x8 wf[steps];
-  sk_wload<steps>(W, d, n0, d, k0, wf);
-  sk_hidden<PER>(resid, R, TWO ? 32 : 16, L.hb, L.hown, n0, false);
-  // attention output of every (sequence, head) pair -> hb (bf16 [32][d]); rows >= R zero
-  for (int idx = threadIdx.x; idx < (TWO ? 32 : 16) * pitch / 8; idx += kSkThreads)
+  if (kwave) {
+    sk_wload<steps>(W, d, n0, d, k0, wf);
+    // the block's 16 columns of the sublayer's input, for the residual add
+    sk_hidden<PER>(resid, R, TWO ? 32 : 16, L.hb, L.hown, n0, false);
+  }
+  // attention output of every (sequence, head) pair -> hb (bf16 [32][d]); rows >= R zero.
+  // One pair per wave: eight pairs are in flight at once.
+  for (int idx = threadIdx.x; idx < (TWO ? 32 : 16) * pitch / 8; idx += 64 * kSkAttnWaves)
     reinterpret_cast<uint4*>(L.hb)[idx] = make_uint4(0, 0, 0, 0);
   __syncthreads();
-  for (int p = wave; p < a.B * a.H; p += 4) {
+  for (int p = wave; p < a.B * a.H; p += kSkAttnWaves) {
     const int b = p / a.H, h = p - b * a.H;
     constexpr int NQT = TWO ? 2 : 1;   // at most 16 rows in all: one query tile
     const int nq = min(a.q_count ? a.q_count[b] : a.T, 16 * NQT);
@@ -262,8 +102,9 @@ __global__ __launch_bounds__(kSkThreads) void sk_attn_o_kernel(SkSrc resid, int 
   f32x4 acc[2];
   sk_zero(acc);
   const bf16* hb = L.hb;
-  sk_mma<steps, TWO>(wf, k0,
-         [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); }, acc);
+  if (kwave)
+    sk_mma<steps, TWO>(wf, k0,
+           [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); }, acc);
   const float* hown = L.hown;
   sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
     xs_out[(size_t)m * d + n0 + nl] = v + (float)bias[n0 + nl] + hown[m * 16 + nl];
@@ -332,6 +173,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_ffn2_kernel(SkSrc resid, int R,
     if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], getB(1, k0 + u * 32 + 8 * g), acc[1], 0, 0, 0);
   }
   sk_mma_tail<FS, TWO>(W, F, n0, d, k0, getB, acc);
+  mfma_settle(acc[0], acc[1]);
   __syncthreads();
   const float* hown = L.hown;
   sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
@@ -349,30 +191,9 @@ __global__ __launch_bounds__(kSkThreads) void sk_draft_logit_kernel(SkSrc src, i
                                                                     float* __restrict__ zd_out) {
   extern __shared__ __attribute__((aligned(16))) char sk_smem[];
   SkLds<PER> L(sk_smem);
-  constexpr int d = 64 * PER, pitch = d + kSkPad;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
   sk_hidden<PER>(src, R, R > 16 ? 32 : 16, L.hb, L.hown, -64, true);
   __syncthreads();
-  if (wave >= 2) return;
-  const int t = wave;
-  const int row = t * 16 + lq;
-  const int tok = row < R ? row_draft[row] : -1;
-  const bool has = tok >= 0 && tok < V;
-  const bf16* wp = E + (size_t)(has ? tok : 0) * d + 8 * g;
-  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-  for (int s = 0; s < d / 32; ++s) {
-    bf16x8 wf = *reinterpret_cast<const bf16x8*>(wp + s * 32);
-    bf16x8 hf = *reinterpret_cast<const bf16x8*>(L.hb + row * pitch + s * 32 + 8 * g);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, hf, acc, 0, 0, 0);
-  }
-  // D[i][j]: this lane holds j = lq, i = 4g + r; diagonal i = j  <=>  g == lq/4, r = lq%4
-  if (g == (lq >> 2) && row < R) {
-    float v = 0.f;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) if (r == (lq & 3)) v = acc[r];
-    zd_out[row] = has ? v : kNegInf;
-  }
+  sk_draft_logit<PER>(L.hb, R, E, V, row_draft, [&](int row, float v) { zd_out[row] = v; });
 }
 
 // One block = 64 vocabulary columns (16 per wave, whole K per wave), one partial record per row.
@@ -384,7 +205,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_vocab_kernel(SkSrc src, int R, 
   extern __shared__ __attribute__((aligned(16))) char sk_smem[];
   SkLds<PER> L(sk_smem);
   constexpr int d = 64 * PER, pitch = d + kSkPad;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15;
   const int n0 = blockIdx.x * 64 + wave * 16;
   constexpr int steps = d / 32, S1 = steps < kSkW ? steps : kSkW;
   bf16x8 wf[S1];
@@ -397,62 +218,10 @@ __global__ __launch_bounds__(kSkThreads) void sk_vocab_kernel(SkSrc src, int R, 
   auto getB = [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); };
   sk_mma<S1, TWO>(wf, 0, getB, acc);
   sk_mma_tail<steps, TWO>(E, d, n0, V, 0, getB, acc);
-  // this lane: rows m = t*16 + lq, columns n0 + 4g + r
-  float* red = L.red;   // [4 waves][32 rows][4]: max, arg-max, sum-exp, count
+  float zd[2];
 #pragma unroll
-  for (int t = 0; t < 2; ++t) {
-    const int m = t * 16 + lq;
-    const float zd = m < R ? zd_row[m] : kNegInf;
-    float best = kNegInf;
-    int besti = 0x7fffffff, cnt = 0;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int n = n0 + 4 * g + r;
-      const float v = acc[t][r];
-      if (n < V) {
-        if (v > best) { best = v; besti = n; }
-        cnt += (v > zd) ? 1 : 0;
-        if (logits && m < R) logits[(size_t)m * V + n] = v;
-      }
-    }
-#pragma unroll
-    for (int o = 16; o <= 32; o <<= 1) {
-      const float ob = __shfl_xor(best, o, 64);
-      const int oi = __shfl_xor(besti, o, 64);
-      if (ob > best || (ob == best && oi < besti)) { best = ob; besti = oi; }
-      cnt += __shfl_xor(cnt, o, 64);
-    }
-    float se = 0.f;
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-      if (n0 + 4 * g + r < V) se += __expf(acc[t][r] - best);
-    se += __shfl_xor(se, 16, 64);
-    se += __shfl_xor(se, 32, 64);
-    if (g == 0) {
-      float* p = red + (wave * 32 + m) * 4;
-      p[0] = best; p[1] = __int_as_float(besti); p[2] = se; p[3] = __int_as_float(cnt);
-    }
-  }
-  __syncthreads();
-  if (threadIdx.x < kSkRows && (int)threadIdx.x < R) {
-    const int m = threadIdx.x;
-    float best = kNegInf, tot = 0.f;
-    int besti = 0x7fffffff, cnt = 0;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float* p = red + (w * 32 + m) * 4;
-      const int bi = __float_as_int(p[1]);
-      if (p[0] > best || (p[0] == best && bi < besti)) { best = p[0]; besti = bi; }
-      cnt += __float_as_int(p[3]);
-    }
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float* p = red + (w * 32 + m) * 4;
-      if (p[0] > kNegInf) tot += p[2] * __expf(p[0] - best);
-    }
-    f32x4 rec = {best, __int_as_float(besti), tot, __int_as_float(cnt)};
-    *reinterpret_cast<f32x4*>(part + ((size_t)m * n_tiles + blockIdx.x) * kPartF) = rec;
-  }
+  for (int t = 0; t < 2; ++t) zd[t] = (t * 16 + lq < R) ? zd_row[t * 16 + lq] : kNegInf;
+  sk_vocab_tile(acc, n0, V, R, zd, L.red, part, n_tiles, blockIdx.x, logits);
 }
 
 // ------------------------------------------------------------------------------------ launchers
@@ -518,11 +287,11 @@ hipError_t skinny_qkv(hipStream_t st, const SkSrc& src, int R, int d, const bf16
 hipError_t skinny_attn_o(hipStream_t st, const SkSrc& resid, int R, int d, const AttnArgs& a, const bf16* W,
                          const bf16* bias, float* xs_out) {
   if (a.v_blocked) {
-    SK_DISPATCH(d, SK_ROWS(R, hipLaunchKernelGGL((sk_attn_o_kernel<PER, true, TWO>), dim3(d / 16), dim3(kSkThreads),
-                                                 SkLds<PER>::kBytes, st, resid, R, a, W, bias, xs_out)));
+    SK_DISPATCH(d, SK_ROWS(R, hipLaunchKernelGGL((sk_attn_o_kernel<PER, true, TWO>), dim3(d / 16),
+                                                 dim3(64 * kSkAttnWaves), SkLds<PER>::kBytes, st, resid, R, a, W, bias, xs_out)));
   } else {
-    SK_DISPATCH(d, SK_ROWS(R, hipLaunchKernelGGL((sk_attn_o_kernel<PER, false, TWO>), dim3(d / 16), dim3(kSkThreads),
-                                                 SkLds<PER>::kBytes, st, resid, R, a, W, bias, xs_out)));
+    SK_DISPATCH(d, SK_ROWS(R, hipLaunchKernelGGL((sk_attn_o_kernel<PER, false, TWO>), dim3(d / 16),
+                                                 dim3(64 * kSkAttnWaves), SkLds<PER>::kBytes, st, resid, R, a, W, bias, xs_out)));
   }
   return hipGetLastError();
 }

@@ -1,0 +1,285 @@
+// Building blocks of the small-batch (at most 32 rows) decoder kernels: LDS carve-up, the
+// hidden-state prologue, K-split weight-streaming products on MFMA 16x16x32 and their
+// reduction.  Used by the per-projection kernels and by the single resident kernel.
+#pragma once
+#include "attn_core.h"
+
+namespace sd {
+
+#ifndef SK_HID_T
+#define SK_HID_T(i)
+#endif
+
+constexpr int kSkThreads = 256;
+constexpr int kSkRows = 32;          // activation rows a block can hold (2 MFMA column tiles)
+constexpr int kSkAttnWaves = 8;      // waves of the attention + O kernel (one (sequence, head) pair each)
+constexpr int kSkPad = 8;            // bf16 padding of an activation row in LDS (bank spread)
+
+// LDS carve-up (dynamic): hb bf16 [32][d + 8] | hown f32 [2][32][16] | red f32 [4][16][33] | Vs
+template <int PER>
+struct SkLds {
+  static constexpr int d = 64 * PER;
+  static constexpr int kPitch = d + kSkPad;
+  static constexpr size_t kHb = (size_t)kSkRows * kPitch * 2;
+  static constexpr size_t kOwn = (size_t)2 * kSkRows * 16 * 4;
+  static constexpr size_t kRed = (size_t)4 * 16 * 33 * 4;
+  static constexpr size_t kVs = (size_t)kSkAttnWaves * 32 * kVtPitch * 2;
+  static constexpr size_t kBytes = kHb + kOwn + kRed + kVs;
+  bf16* hb; float* hown; float* red; bf16 (*vs)[32][kVtPitch];
+  __device__ explicit SkLds(char* base) {
+    hb = reinterpret_cast<bf16*>(base);
+    hown = reinterpret_cast<float*>(base + kHb);
+    red = reinterpret_cast<float*>(base + kHb + kOwn);
+    vs = reinterpret_cast<bf16 (*)[32][kVtPitch]>(base + kHb + kOwn + kRed);
+  }
+};
+
+// Hidden state of the R rows = what `src` describes; bf16 copy of all columns -> hb (rows
+// R .. nrows-1 zero), fp32 copy of columns [n0, n0 + 16) -> hown (for residual adds).
+// A wave takes rows wave, wave + 4, ...; it requests the data of up to four of them (and the
+// LayerNorm parameters, once) before it reduces any, so the prologue costs one memory round
+// trip however many rows there are.
+// COH: the fp32 rows were written by other workgroups of the running kernel.  n0b: a second
+// 16-column residual slice (slot 1 of hown, [2][32][16]); negative: none.
+template <int PER, bool COH = false>
+__device__ __forceinline__ void sk_hidden(const SkSrc& s, int R, int nrows, bf16* hb, float* hown, int n0,
+                                          bool want_hb, int n0b = -64) {
+  constexpr int d = 64 * PER, pitch = d + kSkPad, RU = 4;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float gg[PER], bb[PER];
+  SK_HID_T(110);
+  if (s.mode == 2) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) { gg[i] = (float)s.g[i * 64 + lane]; bb[i] = (float)s.b[i * 64 + lane]; }
+  }
+  for (int base = wave; base < nrows; base += 4 * RU) {
+    float v[RU][PER];
+    if (s.mode == 0) {
+      int tok[RU], pos[RU];
+#pragma unroll
+      for (int u = 0; u < RU; ++u) {
+        const int r = min(base + 4 * u, R - 1);
+        tok[u] = s.tok[r]; pos[u] = s.pos[r];
+      }
+      const float sc = sqrtf((float)d);
+#pragma unroll
+      for (int u = 0; u < RU; ++u) {
+        const bf16* e = s.E + (size_t)tok[u] * d;
+        const float* p = s.pe + (size_t)pos[u] * d;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) v[u][i] = (float)e[i * 64 + lane] * sc + p[i * 64 + lane];
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < RU; ++u) {
+        const int r = min(base + 4 * u, R - 1);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) v[u][i] = COH ? ld_coh(s.xs + (size_t)r * d + i * 64 + lane) : s.xs[(size_t)r * d + i * 64 + lane];
+      }
+      SK_HID_T(111);
+      if (s.mode == 2) {
+        float mean[RU], rstd[RU];
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+          float sum = 0.f;
+#pragma unroll
+          for (int i = 0; i < PER; ++i) sum += v[u][i];
+          mean[u] = wave_sum(sum) / (float)d;
+        }
+        SK_HID_T(112);
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+          float q = 0.f;
+#pragma unroll
+          for (int i = 0; i < PER; ++i) { float t = v[u][i] - mean[u]; q += t * t; }
+          rstd[u] = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u)
+#pragma unroll
+          for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean[u]) * rstd[u] * gg[i] + bb[i];
+        SK_HID_T(113);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < RU; ++u) {
+      const int r = base + 4 * u;
+      if (r < nrows) {
+        const bool real = r < R;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+          const int c = i * 64 + lane;
+          const float val = real ? v[u][i] : 0.f;
+          if (want_hb) hb[r * pitch + c] = (bf16)val;
+          if (c >= n0 && c < n0 + 16) hown[r * 16 + c - n0] = val;
+          if (c >= n0b && c < n0b + 16) hown[kSkRows * 16 + r * 16 + c - n0b] = val;
+        }
+      }
+    }
+  }
+}
+
+// Weight operands of this wave: rows n0 + lane%16 of W, k range [k0, k0 + 32*S).  sk_wload only
+// issues the loads -- kernels call it first thing, so the weights travel while the prologue
+// (LayerNorm, attention) runs; sk_mma consumes them:
+//   acc[t] += W[n0 + i][k] . B_t[j][k],  getB(t, k) = 8 bf16 of activation row t*16 + lane%16 at k.
+// Step counts and the second row tile are compile-time, so the MFMA sequence is straight-line.
+constexpr int kSkW = 16;   // most steps held in registers at a time
+template <int S>
+__device__ __forceinline__ void sk_wload(const bf16* __restrict__ W, int ldw, int n0, int N, int k0,
+                                         bf16x8 (&wf)[S]) {
+  const int lane = threadIdx.x & 63, lq = lane & 15, g = lane >> 4;
+  const bf16* wp = W + (size_t)min(n0 + lq, N - 1) * ldw + k0 + 8 * g;
+#pragma unroll
+  for (int u = 0; u < S; ++u) wf[u] = *reinterpret_cast<const bf16x8*>(wp + u * 32);
+}
+template <int S, bool TWO, class GetB>
+__device__ __forceinline__ void sk_mma(const bf16x8 (&wf)[S], int k0, GetB&& getB, f32x4 (&acc)[2]) {
+  const int g = (threadIdx.x & 63) >> 4;
+#pragma unroll
+  for (int u = 0; u < S; ++u) {
+    const int k = k0 + u * 32 + 8 * g;
+    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], getB(0, k), acc[0], 0, 0, 0);
+    if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], getB(1, k), acc[1], 0, 0, 0);
+  }
+  mfma_settle(acc[0], acc[1]);
+}
+// steps kSkW .. STEPS - 1 of a long k range, kSkW at a time
+template <int STEPS, bool TWO, class GetB>
+__device__ __forceinline__ void sk_mma_tail(const bf16* __restrict__ W, int ldw, int n0, int N, int k0,
+                                            GetB&& getB, f32x4 (&acc)[2]) {
+  if constexpr (STEPS > kSkW) {
+    static_assert(STEPS % kSkW == 0, "long k ranges come in whole batches");
+#pragma unroll 1
+    for (int s0 = kSkW; s0 < STEPS; s0 += kSkW) {
+      bf16x8 wf[kSkW];
+      sk_wload<kSkW>(W, ldw, n0, N, k0 + s0 * 32, wf);
+      sk_mma<kSkW, TWO>(wf, k0 + s0 * 32, getB, acc);
+    }
+  }
+}
+__device__ __forceinline__ void sk_zero(f32x4 (&acc)[2]) {
+  acc[0] = f32x4{0.f, 0.f, 0.f, 0.f};
+  acc[1] = acc[0];
+}
+
+// Sum the 4 waves' partial tiles (fixed order) and hand every output (m, n local) to f.
+template <class F>
+__device__ __forceinline__ void sk_reduce(const f32x4 (&acc)[2], float* red, int R, F&& f) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
+  if (wave < 4) {   // (a block may have more waves than the four that split K)
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) red[(wave * 16 + 4 * g + r) * 33 + t * 16 + lq] = acc[t][r];
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < 16 * kSkRows && threadIdx.x < kSkThreads; idx += kSkThreads) {
+    const int m = idx >> 4, n = idx & 15;
+    if (m < R) {
+      float v = red[(0 * 16 + n) * 33 + m];
+      v += red[(1 * 16 + n) * 33 + m];
+      v += red[(2 * 16 + n) * 33 + m];
+      v += red[(3 * 16 + n) * 33 + m];
+      f(m, n, v);
+    }
+  }
+}
+
+// Logit of the draft each row scores: D[i][j] = E[draft of row 16t+i] . h[16t+j] (wave t < 2)
+// with the same instruction and k order as the vocabulary projection, hence bit-identical to
+// the element the projection produces for that (row, column); the diagonal is kept.
+template <int PER, class Out>
+__device__ __forceinline__ void sk_draft_logit(const bf16* hb, int R, const bf16* __restrict__ E, int V,
+                                               const int* __restrict__ row_draft, Out&& out) {
+  constexpr int d = 64 * PER, pitch = d + kSkPad;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
+  if (wave >= 2) return;
+  const int t = wave;
+  const int row = t * 16 + lq;
+  const int tok = row < R ? row_draft[row] : -1;
+  const bool has = tok >= 0 && tok < V;
+  const bf16* wp = E + (size_t)(has ? tok : 0) * d + 8 * g;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
+  for (int s = 0; s < d / 32; ++s) {
+    bf16x8 wf = *reinterpret_cast<const bf16x8*>(wp + s * 32);
+    bf16x8 hf = *reinterpret_cast<const bf16x8*>(hb + row * pitch + s * 32 + 8 * g);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, hf, acc, 0, 0, 0);
+  }
+  mfma_settle(acc);
+  // D[i][j]: this lane holds j = lq, i = 4g + r; diagonal i = j  <=>  g == lq/4, r = lq%4
+  if (g == (lq >> 2) && row < R) {
+    float v = 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) if (r == (lq & 3)) v = acc[r];
+    out(row, has ? v : kNegInf);
+  }
+}
+
+// Row statistics of one 64-column vocabulary tile (16 columns per wave: acc of this wave,
+// first column n0): per row the maximum, its lowest index, sum exp(z - max) and the number of
+// logits above the row's draft logit zd[t] (row t*16 + lane%16); one record per row -> part.
+__device__ __forceinline__ void sk_vocab_tile(const f32x4 (&acc)[2], int n0, int V, int R, const float (&zd_t)[2],
+                                              float* red, float* __restrict__ part, int n_tiles, int tile,
+                                              float* __restrict__ logits) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
+  // this lane: rows m = t*16 + lq, columns n0 + 4g + r
+  // red: [4 waves][32 rows][4]: max, arg-max, sum-exp, count
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int m = t * 16 + lq;
+    const float zd = zd_t[t];
+    float best = kNegInf;
+    int besti = 0x7fffffff, cnt = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int n = n0 + 4 * g + r;
+      const float v = acc[t][r];
+      if (n < V) {
+        if (v > best) { best = v; besti = n; }
+        cnt += (v > zd) ? 1 : 0;
+        if (logits && m < R) logits[(size_t)m * V + n] = v;
+      }
+    }
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+      const float ob = __shfl_xor(best, o, 64);
+      const int oi = __shfl_xor(besti, o, 64);
+      if (ob > best || (ob == best && oi < besti)) { best = ob; besti = oi; }
+      cnt += __shfl_xor(cnt, o, 64);
+    }
+    float se = 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (n0 + 4 * g + r < V) se += __expf(acc[t][r] - best);
+    se += __shfl_xor(se, 16, 64);
+    se += __shfl_xor(se, 32, 64);
+    if (g == 0) {
+      float* p = red + (wave * 32 + m) * 4;
+      p[0] = best; p[1] = __int_as_float(besti); p[2] = se; p[3] = __int_as_float(cnt);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < kSkRows && (int)threadIdx.x < R) {
+    const int m = threadIdx.x;
+    float best = kNegInf, tot = 0.f;
+    int besti = 0x7fffffff, cnt = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float* p = red + (w * 32 + m) * 4;
+      const int bi = __float_as_int(p[1]);
+      if (p[0] > best || (p[0] == best && bi < besti)) { best = p[0]; besti = bi; }
+      cnt += __float_as_int(p[3]);
+    }
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float* p = red + (w * 32 + m) * 4;
+      if (p[0] > kNegInf) tot += p[2] * __expf(p[0] - best);
+    }
+    f32x4 rec = {best, __int_as_float(besti), tot, __int_as_float(cnt)};
+    *reinterpret_cast<f32x4*>(part + ((size_t)m * n_tiles + tile) * kPartF) = rec;
+  }
+}
+
+}  // namespace sd

@@ -221,3 +221,36 @@ def test_argument_errors_on_device():
     sd.specdec_prefill(ses.ctx, sd.SPECDEC_VERIFIER)
     out = gh.gpu_verify(ses, case)
     assert np.abs(out["logits"] - case.logits).max() <= LOGIT_TOL
+
+
+def test_small_batch_paths_agree(monkeypatch):
+    """The three implementations of a pass of at most 32 rows -- general kernels, fused
+    per-projection kernels (the default) and the single resident kernel (opt-in) -- give the
+    same logits to the last bit on the fused paths and match the oracle on all three; the
+    fused paths also cover d = 512 with two 16-row tiles (B = 2, k = 10)."""
+    import gpu_harness as gh
+    case = cases.make_verify_case(small_desc(), seed=21, B=3, S=9, k=4, beta=3, tau=1.0, len_lo=0, len_hi=12,
+                                  drafts="greedy", ragged_src=True, std=0.08)
+    cases.run_oracle(case)
+    desc2 = synth.base_verifier(max_src=32, max_tgt=64, enc_layers=0)
+    case2 = cases.make_verify_case(desc2, seed=22, B=2, S=24, k=10, beta=3, tau=1.0, len_lo=3, len_hi=20,
+                                   drafts="greedy", ragged_src=True)
+    cases.run_oracle(case2)
+    for cs in (case, case2):
+        outs = {}
+        for tag, env in (("general", {"SPECDEC_NO_SKINNY": "1"}), ("fused", {}), ("resident", {"SPECDEC_RESIDENT": "1"})):
+            monkeypatch.delenv("SPECDEC_NO_SKINNY", raising=False)
+            monkeypatch.delenv("SPECDEC_RESIDENT", raising=False)
+            for k_, v_ in env.items():
+                monkeypatch.setenv(k_, v_)
+            ses = gh.open_verifier(cs)
+            outs[tag] = gh.gpu_verify(ses, cs)
+            ses.close()
+            err = np.abs(outs[tag]["logits"] - cs.logits).max()
+            print(f"[paths {tag}] logits max-abs err {err:.3e}")
+            assert err <= LOGIT_TOL
+            exact, excused, bad = cases.compare_decisions(cs, outs[tag]["accept"], outs[tag]["next"])
+            assert not bad, (tag, bad)
+        assert np.array_equal(outs["fused"]["logits"], outs["resident"]["logits"])
+        assert np.array_equal(outs["fused"]["accept"], outs["resident"]["accept"])
+        assert np.array_equal(outs["fused"]["next"], outs["resident"]["next"])
