@@ -301,18 +301,11 @@ int decoder_layers_skinny(specdec_ctx* c, Model& m, int B, int T, hipStream_t st
     cur = sd::SkSrc{2, freeb, g, b, nullptr, nullptr, nullptr, nullptr};
     float* t = freeb; freeb = other; other = t;
   };
-#ifdef SD_DEBUG
-  int dbg_left = getenv("SD_DEBUG_STOP") ? atoi(getenv("SD_DEBUG_STOP")) : 1 << 30;
-#define SKDBG if (--dbg_left <= 0) { *out = cur; return SPECDEC_OK; }
-#else
-#define SKDBG
-#endif
   for (int l = 0; l < m.d.dec_layers; ++l) {
     const DecLayer& L = m.dec[l];
     bf16* kc = m.kc + m.kv_layer * l;
     bf16* vc = m.vc + m.kv_layer * l;
     LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::skinny_qkv(st, cur, R, D, L.wqkv, L.bqkv, m.q, kc, vc, m.rm.row_b, m.rm.row_pos, H, Lcap));
-    SKDBG
     sd::AttnArgs a{};
     a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
     a.k = kc; a.k_b = (long)H * Lcap * 64; a.k_h = (long)Lcap * 64; a.k_row = 64;
@@ -322,20 +315,15 @@ int decoder_layers_skinny(specdec_ctx* c, Model& m, int B, int T, hipStream_t st
     a.T = T; a.H = H; a.B = B; a.key_split = 0; a.cap = Lcap;
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_attn_o(st, cur, R, D, a, L.wo, L.bo, freeb));
     produced(L.ln1g, L.ln1b);
-    SKDBG
     LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, cur, R, D, L.cwq, D, L.cbq, m.q, false));
-    SKDBG
     a.k = m.xk + m.xkv_layer * l; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64;
     a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_blocked = 1;
     a.lim_row = nullptr; a.lim_seq = c->st.src_len; a.cap = Scap;
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_attn_o(st, cur, R, D, a, L.cwo, L.cbo, freeb));
     produced(L.ln2g, L.ln2b);
-    SKDBG
     LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, cur, R, D, L.w1, F, L.b1, m.hid, true));
-    SKDBG
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_ffn2(st, cur, R, D, m.hid, F, L.w2, L.b2, freeb));
     produced(L.ln3g, L.ln3b);
-    SKDBG
   }
   *out = cur;
   return SPECDEC_OK;
@@ -679,9 +667,6 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
     a.bar = m.rs_bar; a.parity = m.rs_parity;
     m.rs_seq = m.rs_seq >= 0x3fffffff ? 1 : m.rs_seq + 1;
     a.seq = m.rs_seq;
-#ifdef SD_DEBUG
-    a.stop_after = getenv("SD_DEBUG_STOP") ? atoi(getenv("SD_DEBUG_STOP")) : 1 << 30;
-#endif
     m.rs_parity ^= 1;
     LAUNCH(c, SPECDEC_KIND_RESIDENT, st, sd::resident_verify(st, a, m.d.d_model, m.d.d_ffn));
     const int n_tiles = (m.d.vocab + 63) / 64;
@@ -802,12 +787,3 @@ int specdec_get_row_stats(specdec_ctx* c, float* stats, void* stream) {
 }
 
 }  // extern "C"
-
-#ifdef SD_DEBUG
-extern "C" int sd_debug_copy(specdec_ctx* c, int which, void* host, size_t bytes) {
-  Model& m = c->m[0];
-  const void* src = which == 0 ? (const void*)m.x : which == 1 ? (const void*)m.x2 : which == 2 ? (const void*)m.q : (const void*)m.hid;
-  (void)hipDeviceSynchronize();
-  return (int)hipMemcpy(host, src, bytes, hipMemcpyDeviceToHost);
-}
-#endif

@@ -109,9 +109,6 @@ struct RsArgs {
                                       // launches), [16] error flag, [64*(1+h)] wake-up word of helper h
   int parity;                         // which counter this launch uses (the other one is cleared)
   int seq;                            // launch number, never 0
-#ifdef SD_DEBUG
-  int stop_after;
-#endif
 };
 constexpr int kRsWorkers = 32;        // workgroups of the resident kernel that run the decoder phases
 constexpr int kRsBarWords = 64 * 226;

@@ -22,18 +22,8 @@
 // per-projection kernels do.
 #include <hip/hip_runtime.h>
 
-#include <cstdlib>
 #include <type_traits>
 
-#ifdef SD_DEBUG
-namespace sd { __device__ unsigned long long rs_times[128]; }
-using sd::rs_times;
-#define RS_T(i) do { const int i_ = (i); if (blockIdx.x == 0 && threadIdx.x == 0 && i_ < 128) rs_times[i_] = __builtin_amdgcn_s_memrealtime(); } while (0)
-extern "C" int sd_debug_times(unsigned long long* out) { return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(rs_times), sizeof(rs_times)); }
-#else
-#define RS_T(i)
-#endif
-#define SK_HID_T(i) RS_T(i)
 #include "skinny_core.h"
 
 namespace sd {
@@ -41,11 +31,6 @@ namespace sd {
 constexpr unsigned kRsSpinMax = 1u << 20;
 constexpr int kRsHelpers = 224;   // most workgroups that only do vocabulary tiles
 constexpr int kRsFlagPitch = 64;  // words between two helpers' wake-up words (256 bytes)
-#if defined(SD_DEBUG) && !defined(RS_NO_STOP)
-#define RS_DBG_STOP if (++dbg_phase >= A.stop_after) return
-#else
-#define RS_DBG_STOP
-#endif
 
 
 struct RsState {
@@ -155,11 +140,8 @@ __device__ __forceinline__ void rs_project(const SkLds<PER>& L, const SkSrc& src
   const int wave = threadIdx.x >> 6, lq = threadIdx.x & 15;
   const int k0 = wave * (P::d / 4);
   if (w >= P::nvb) return;
-  if (N == P::d) RS_T(100);
   sk_hidden<PER, true>(src, R, TWO ? 32 : 16, L.hb, L.hown, -64, true);
-  if (N == P::d) RS_T(101);
   __syncthreads();
-  if (N == P::d) RS_T(102);
   const bf16* hb = L.hb;
   auto getB = [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); };
   auto slice = [&](auto ic) {
@@ -168,12 +150,9 @@ __device__ __forceinline__ void rs_project(const SkLds<PER>& L, const SkSrc& src
     if (vb >= P::nvb) return;
     f32x4 acc[2];
     rs_slice_mma<PER, N, TWO, I>(pre, W, vb, k0, getB, acc);
-    if (N == P::d) RS_T(103);
     const int n0 = vb * 16;
     sk_reduce(acc, L.red, R, [&](int m, int nl, float v) { epi(m, n0 + nl, v); });
-    if (N == P::d) RS_T(104);
     __syncthreads();   // red is reused by the next slice
-    if (N == P::d) RS_T(105);
   };
   static_assert(P::NSL <= 8, "slices per workgroup");
   slice(std::integral_constant<int, 0>{});
@@ -409,9 +388,6 @@ __global__ __launch_bounds__(kSkThreads) void rs_verify_kernel(RsArgs A) {
   RsState bar{A.bar + A.parity, err, 0u, flag};
   if (w == 0 && threadIdx.x == 0) __hip_atomic_store(A.bar + (1 - A.parity), 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
-  int ts = 0;
-  (void)ts;
-  RS_T(ts++);
   SkSrc cur{0, nullptr, nullptr, nullptr, A.row_tok, A.row_pos, A.E, A.pe};
   float* freeb = A.xs0;
   float* other = A.xs1;
@@ -435,12 +411,9 @@ __global__ __launch_bounds__(kSkThreads) void rs_verify_kernel(RsArgs A) {
       bf16* cache = (part == 1) ? kc : vc;
       st_coh(cache + (((size_t)b * A.H + (c >> 6)) * A.Lcap + A.row_pos[m]) * kHeadDim + (c & 63), (bf16)v);
     });
-    RS_T(ts++);
     rs_arrive(bar);
     rs_prefetch_proj<PER, d>(pre, Ly.wo, w);
     if (!rs_wait(bar)) return;
-    RS_T(ts++);
-    RS_DBG_STOP;
     // self-attention + O
     AttnArgs a{};
     a.q = A.q; a.q_b = (long)A.T * d; a.q_row = d;
@@ -450,53 +423,38 @@ __global__ __launch_bounds__(kSkThreads) void rs_verify_kernel(RsArgs A) {
     a.T = A.T; a.H = A.H; a.B = A.B; a.key_split = 0; a.cap = A.Lcap;
     rs_attn_o<PER, false, TWO>(L, cur, R, a, Ly.wo, Ly.bo, freeb, w, pre);
     produced(Ly.ln1g, Ly.ln1b);
-    RS_T(ts++);
     rs_arrive(bar);
     rs_prefetch_proj<PER, d>(pre, Ly.cwq, w);
     if (!rs_wait(bar)) return;
-    RS_T(ts++);
-    RS_DBG_STOP;
     // cross-attention Q
     rs_project<PER, d, TWO>(L, cur, R, Ly.cwq, w, pre, [&](int m, int n, float v) {
       st_coh(A.q + (size_t)m * d + n, (bf16)(v + (float)Ly.cbq[n]));
     });
-    RS_T(ts++);
     rs_arrive(bar);
     rs_prefetch_proj<PER, d>(pre, Ly.cwo, w);
     if (!rs_wait(bar)) return;
-    RS_T(ts++);
-    RS_DBG_STOP;
     // cross-attention + O
     a.k = A.xk + A.xkv_layer * l; a.k_b = (long)A.H * A.Scap * 64; a.k_h = (long)A.Scap * 64;
     a.v = A.xv + A.xkv_layer * l; a.v_b = a.k_b; a.v_h = a.k_h; a.v_blocked = 1;
     a.lim_row = nullptr; a.lim_seq = A.src_len; a.cap = A.Scap;
     rs_attn_o<PER, true, TWO>(L, cur, R, a, Ly.cwo, Ly.cbo, freeb, w, pre);
     produced(Ly.ln2g, Ly.ln2b);
-    RS_T(ts++);
     rs_arrive(bar);
     rs_prefetch_proj<PER, F>(pre, Ly.w1, w);
     if (!rs_wait(bar)) return;
-    RS_T(ts++);
-    RS_DBG_STOP;
     // FFN1
     rs_project<PER, F, TWO>(L, cur, R, Ly.w1, w, pre, [&](int m, int n, float v) {
       st_coh(A.hid + (size_t)m * F + n, (bf16)fmaxf(v + (float)Ly.b1[n], 0.f));
     });
-    RS_T(ts++);
     rs_arrive(bar);
     rs_prefetch_ffn2<PER, FS>(pre, Ly.w2, w);
     if (!rs_wait(bar)) return;
-    RS_T(ts++);
-    RS_DBG_STOP;
     // FFN2
     rs_ffn2<PER, FS, TWO>(L, cur, R, A.hid, Ly.w2, Ly.b2, freeb, w, pre);
     produced(Ly.ln3g, Ly.ln3b);
-    RS_T(ts++);
     rs_arrive(bar);
     if (l + 1 < A.n_layers) rs_prefetch_proj<PER, 3 * d>(pre, A.layers[l + 1].wqkv, w);
     if (!rs_wait(bar)) return;
-    RS_T(ts++);
-    RS_DBG_STOP;
   }
   // the final residual sum is visible everywhere: wake the vocabulary helpers, each through a
   // word of its own (one hot word polled by every helper would saturate its memory channel)
@@ -535,10 +493,7 @@ static hipError_t rs_launch(hipStream_t st, const RsArgs& A) {
     ready = true;
   }
   const int n_tiles = (A.V + 63) / 64;
-  int helpers = n_tiles < kRsHelpers ? n_tiles : kRsHelpers;
-#ifdef SD_DEBUG
-  if (getenv("RS_HELPERS")) helpers = atoi(getenv("RS_HELPERS"));
-#endif
+  const int helpers = n_tiles < kRsHelpers ? n_tiles : kRsHelpers;
   hipLaunchKernelGGL((rs_verify_kernel<PER, FS, TWO>), dim3(kRsWorkers + helpers), dim3(kSkThreads), lds, st, A);
   return hipGetLastError();
 }

@@ -68,10 +68,13 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
   const bool kwave = wave < 4;                 // the four waves that split K of the O-projection
   const int k0 = (wave & 3) * (d / 4);
   bf16x8 wf[steps];
+  // the block's 16 columns of the sublayer's input (for the residual add) are requested now
+  // and normalised after the attention, whose own requests travel at the same time
+  SkHidden<PER> hs;
   if (kwave) {
     sk_wload<steps>(W, d, n0, d, k0, wf);
-    // the block's 16 columns of the sublayer's input, for the residual add
-    sk_hidden<PER>(resid, R, TWO ? 32 : 16, L.hb, L.hown, n0, false);
+    hs.params(resid);
+    hs.load(resid, R, wave);
   }
   // attention output of every (sequence, head) pair -> hb (bf16 [32][d]); rows >= R zero.
   // One pair per wave: eight pairs are in flight at once.
@@ -96,6 +99,13 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
 #pragma unroll
           for (int r = 0; r < 4; ++r) op[et * 16 + 4 * g + r] = (bf16)(oacc[qt][et][r] * inv);
       }
+    }
+  }
+  if (kwave) {
+    hs.finish(resid, R, TWO ? 32 : 16, wave, L.hb, L.hown, n0, false, -64);
+    if (TWO) {
+      hs.load(resid, R, wave + 16);
+      hs.finish(resid, R, 32, wave + 16, L.hb, L.hown, n0, false, -64);
     }
   }
   __syncthreads();

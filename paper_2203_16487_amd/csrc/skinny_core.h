@@ -6,10 +6,6 @@
 
 namespace sd {
 
-#ifndef SK_HID_T
-#define SK_HID_T(i)
-#endif
-
 constexpr int kSkThreads = 256;
 constexpr int kSkRows = 32;          // activation rows a block can hold (2 MFMA column tiles)
 constexpr int kSkAttnWaves = 8;      // waves of the attention + O kernel (one (sequence, head) pair each)
@@ -42,18 +38,22 @@ struct SkLds {
 // COH: the fp32 rows were written by other workgroups of the running kernel.  n0b: a second
 // 16-column residual slice (slot 1 of hown, [2][32][16]); negative: none.
 template <int PER, bool COH = false>
-__device__ __forceinline__ void sk_hidden(const SkSrc& s, int R, int nrows, bf16* hb, float* hown, int n0,
-                                          bool want_hb, int n0b = -64) {
-  constexpr int d = 64 * PER, pitch = d + kSkPad, RU = 4;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+struct SkHidden {
+  static constexpr int d = 64 * PER, pitch = d + kSkPad, RU = 4;
   float gg[PER], bb[PER];
-  SK_HID_T(110);
-  if (s.mode == 2) {
+  float v[RU][PER];
+
+  // LayerNorm parameters of this lane's columns (once per kernel)
+  __device__ __forceinline__ void params(const SkSrc& s) {
+    const int lane = threadIdx.x & 63;
+    if (s.mode == 2) {
 #pragma unroll
-    for (int i = 0; i < PER; ++i) { gg[i] = (float)s.g[i * 64 + lane]; bb[i] = (float)s.b[i * 64 + lane]; }
+      for (int i = 0; i < PER; ++i) { gg[i] = (float)s.g[i * 64 + lane]; bb[i] = (float)s.b[i * 64 + lane]; }
+    }
   }
-  for (int base = wave; base < nrows; base += 4 * RU) {
-    float v[RU][PER];
+  // request rows base, base + 4, base + 8, base + 12 (clamped to R - 1): nothing is waited for
+  __device__ __forceinline__ void load(const SkSrc& s, int R, int base) {
+    const int lane = threadIdx.x & 63;
     if (s.mode == 0) {
       int tok[RU], pos[RU];
 #pragma unroll
@@ -74,32 +74,35 @@ __device__ __forceinline__ void sk_hidden(const SkSrc& s, int R, int nrows, bf16
       for (int u = 0; u < RU; ++u) {
         const int r = min(base + 4 * u, R - 1);
 #pragma unroll
-        for (int i = 0; i < PER; ++i) v[u][i] = COH ? ld_coh(s.xs + (size_t)r * d + i * 64 + lane) : s.xs[(size_t)r * d + i * 64 + lane];
+        for (int i = 0; i < PER; ++i)
+          v[u][i] = COH ? ld_coh(s.xs + (size_t)r * d + i * 64 + lane) : s.xs[(size_t)r * d + i * 64 + lane];
       }
-      SK_HID_T(111);
-      if (s.mode == 2) {
-        float mean[RU], rstd[RU];
+    }
+  }
+  // normalise the requested rows and write them out
+  __device__ __forceinline__ void finish(const SkSrc& s, int R, int nrows, int base, bf16* hb, float* hown, int n0,
+                                         bool want_hb, int n0b) {
+    const int lane = threadIdx.x & 63;
+    if (s.mode == 2) {
+      float mean[RU], rstd[RU];
 #pragma unroll
-        for (int u = 0; u < RU; ++u) {
-          float sum = 0.f;
+      for (int u = 0; u < RU; ++u) {
+        float sum = 0.f;
 #pragma unroll
-          for (int i = 0; i < PER; ++i) sum += v[u][i];
-          mean[u] = wave_sum(sum) / (float)d;
-        }
-        SK_HID_T(112);
-#pragma unroll
-        for (int u = 0; u < RU; ++u) {
-          float q = 0.f;
-#pragma unroll
-          for (int i = 0; i < PER; ++i) { float t = v[u][i] - mean[u]; q += t * t; }
-          rstd[u] = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
-        }
-#pragma unroll
-        for (int u = 0; u < RU; ++u)
-#pragma unroll
-          for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean[u]) * rstd[u] * gg[i] + bb[i];
-        SK_HID_T(113);
+        for (int i = 0; i < PER; ++i) sum += v[u][i];
+        mean[u] = wave_sum(sum) / (float)d;
       }
+#pragma unroll
+      for (int u = 0; u < RU; ++u) {
+        float q = 0.f;
+#pragma unroll
+        for (int i = 0; i < PER; ++i) { float t = v[u][i] - mean[u]; q += t * t; }
+        rstd[u] = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+      }
+#pragma unroll
+      for (int u = 0; u < RU; ++u)
+#pragma unroll
+        for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean[u]) * rstd[u] * gg[i] + bb[i];
     }
 #pragma unroll
     for (int u = 0; u < RU; ++u) {
@@ -116,6 +119,18 @@ __device__ __forceinline__ void sk_hidden(const SkSrc& s, int R, int nrows, bf16
         }
       }
     }
+  }
+};
+
+template <int PER, bool COH = false>
+__device__ __forceinline__ void sk_hidden(const SkSrc& s, int R, int nrows, bf16* hb, float* hown, int n0,
+                                          bool want_hb, int n0b = -64) {
+  const int wave = (threadIdx.x >> 6) & 3;
+  SkHidden<PER, COH> hs;
+  hs.params(s);
+  for (int base = wave; base < nrows; base += 16) {
+    hs.load(s, R, base);
+    hs.finish(s, R, nrows, base, hb, hown, n0, want_hb, n0b);
   }
 }
 
