@@ -39,6 +39,15 @@ PEAK_HBM_GBS = 8000.0
 PEAK_BF16_TFLOPS = 2500.0
 SEED = 0
 
+# HBM-side bytes per launch of each kernel kind on this workload, from two rocprofv3 --pmc runs of
+# this script (FETCH_SIZE, then WRITE_SIZE; averages over the kind's launches), each scaled by
+# what the same counter reads for a plain 256 MiB device copy (`--copy-calibration`): FETCH_SIZE
+# reads 0.5 per KiB copied, WRITE_SIZE 1.0.  Summary and commands:
+# profiles/loop_iteration_batch128.hbm_traffic.md.  Offline measurements, not taken in this run.
+MEASURED_TRAFFIC_BYTES = {
+    "gemm_f32": {"fetch": 2.0 * 27041.9 * 1024, "write": 1.0 * 5595.4 * 1024},
+}
+
 
 def _force_prefix(sd, ses, desc, B, k, L, prefix):
     """Decode state with a given stream, built by the library itself: the tokens are forced
@@ -202,6 +211,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch1", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain device-to-device copy of 256 MiB, five times (reference for scaling "
+                         "rocprofv3's FETCH_SIZE / WRITE_SIZE counters), and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (sequences are independent; more GPUs would "
@@ -215,6 +227,15 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     sd.lib()   # fails loudly if the HIP library is missing
+    if args.copy_calibration:
+        src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4, "copies": 5}))
+        return
 
     B, k, L, beta, tau, S_max = 128, 10, 64, 3, 1.0, 128
     vdesc = synth.big_verifier(max_src=S_max, max_tgt=128, enc_layers=6)
@@ -278,7 +299,11 @@ def main():
     peak, unit, scale = (PEAK_BF16_TFLOPS, "TFLOP/s", 1e12) if bound == "mfma" else (PEAK_HBM_GBS, "GB/s", 1e9)
     roof = {"bound": bound, "kernel": dominant, "achieved": amount / avg_s / scale, "peak": peak, "unit": unit,
             "frac": amount / avg_s / scale / peak, "traffic": None, "avg_launch_us": avg_s * 1e6,
-            "launches_timed": n}
+            "launches_timed": n, "algorithmic_per_launch": amount}
+    if dominant in MEASURED_TRAFFIC_BYTES:
+        t = MEASURED_TRAFFIC_BYTES[dominant]
+        roof["traffic"] = t["fetch"] + t["write"]
+        roof["traffic_unit"] = "bytes per launch (rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, copy-calibrated, offline)"
 
     Rv, Rd = B * (k + 1), tokens_per_step + B * k
     step_flops = (Rv * dec_flops_per_row(vdesc) + 2.0 * Rv * vdesc.vocab * vdesc.d_model +
