@@ -227,7 +227,8 @@ def test_small_batch_paths_agree(monkeypatch):
     """The three implementations of a pass of at most 32 rows -- general kernels, fused
     per-projection kernels (the default) and the single resident kernel (opt-in) -- give the
     same logits to the last bit on the fused paths and match the oracle on all three; the
-    fused paths also cover d = 512 with two 16-row tiles (B = 2, k = 10)."""
+    fused paths also cover d = 512 with two 16-row tiles (B = 2, k = 10) and d = 1024 with one and
+    two tiles."""
     import gpu_harness as gh
     case = cases.make_verify_case(small_desc(), seed=21, B=3, S=9, k=4, beta=3, tau=1.0, len_lo=0, len_hi=12,
                                   drafts="greedy", ragged_src=True, std=0.08)
@@ -236,7 +237,14 @@ def test_small_batch_paths_agree(monkeypatch):
     case2 = cases.make_verify_case(desc2, seed=22, B=2, S=24, k=10, beta=3, tau=1.0, len_lo=3, len_hi=20,
                                    drafts="greedy", ragged_src=True)
     cases.run_oracle(case2)
-    for cs in (case, case2):
+    # big verifier (d = 1024, F = 4096: two output slices per resident workgroup, long FFN2 k range)
+    desc3 = synth.big_verifier(max_src=48, max_tgt=64, enc_layers=0)
+    case3 = cases.make_verify_case(desc3, seed=23, B=2, S=40, k=10, beta=3, tau=1.0, len_lo=5, len_hi=30,
+                                   drafts="greedy", ragged_src=True)
+    cases.run_oracle(case3)
+    case4 = cases.make_verify_case(desc3, seed=24, B=1, S=33, k=10, beta=3, tau=1.0, len_lo=17, len_hi=17)
+    cases.run_oracle(case4)
+    for cs in (case, case2, case3, case4):
         outs = {}
         for tag, env in (("general", {"SPECDEC_NO_SKINNY": "1"}), ("fused", {}), ("resident", {"SPECDEC_RESIDENT": "1"})):
             monkeypatch.delenv("SPECDEC_NO_SKINNY", raising=False)
