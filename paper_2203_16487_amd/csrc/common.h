@@ -41,21 +41,6 @@ __device__ __forceinline__ int wave_max_i(int v) {
   return v;
 }
 
-// Insert v into a descending list t[0..N) (keeps the N largest, duplicates kept).
-template <int N>
-__device__ __forceinline__ void top_insert(float (&t)[N], float v) {
-  if (v > t[N - 1]) {
-    t[N - 1] = v;
-#pragma unroll
-    for (int i = N - 1; i > 0; --i) {
-      float hi = fmaxf(t[i - 1], t[i]);
-      float lo = fminf(t[i - 1], t[i]);
-      t[i - 1] = hi;
-      t[i] = lo;
-    }
-  }
-}
-
 // Wait states between the last MFMA of a chain and ordinary vector instructions that read its
 // result.  Seen on this toolchain: when a branch separates the two, the required wait states
 // are not always inserted and the last result registers are read before they are written

@@ -283,12 +283,12 @@ __global__ __launch_bounds__(64) void draft_logit_kernel(const bf16* __restrict_
   f32x16 acc;
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll 8
   for (int kb = 0; kb < K / 16; ++kb) {
     bf16x8 a = *reinterpret_cast<const bf16x8*>(ap + kb * 16);
     bf16x8 b = *reinterpret_cast<const bf16x8*>(bp + kb * 16);
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
   }
+  mfma_settle(acc);
   // element (i, j): j = lane%32, i = 8*(reg/4) + 4*(lane/32) + reg%4; the diagonal j = i sits in
   // the lane half (j/4)%2, register 4*(j/8) + j%4
   if (lhalf == ((lrow >> 2) & 1) && r < M) {
