@@ -135,15 +135,19 @@ int specdec_draft(specdec_ctx* ctx, int32_t k, int32_t* draft, void* stream);
  * appended after the cached ones), vocabulary projection and log-softmax statistics fused
  * with the acceptance test.  Draft i is accepted iff drafts 1..i-1 were and, on row i-1,
  *   log P(y~) >= log P(beta-th ranked token)   and   log P(top-1) - log P(y~) <= tau.
- * beta = 1, tau = 0 is the strict top-1 rule; 1 <= beta <= vocab, tau >= 0.  Outputs (device int32 [B]):
+ * beta = 1, tau = 0 is the strict top-1 rule; 0 <= k <= k_max, 1 <= beta <= vocab, tau >= 0.
+ * Outputs (device int32 [B]):
  *   accept_len = number of accepted drafts a (= c - 1),
  *   next_token = the verifier's arg-max token on row a (lowest index among maxima); when all
  *   k drafts are accepted this is the token after the last draft.
  * Finished sequences report accept_len 0 and next_token pad_id.
- * Passes of at most 32 rows run as one resident kernel whose workgroups meet at bounded grid
- * barriers; should a barrier time out (never expected), every sequence reports accept_len -1
- * and next_token pad_id, specdec_commit then changes nothing, and the condition lasts until
- * the next specdec_begin.
+ * k = 0 (draft may be null) is one plain autoregressive step: accept_len = 0 and next_token is
+ * the verifier's greedy token (the baseline of Sec. 2 on the same kernels).
+ * With SPECDEC_RESIDENT=1 in the environment when the context is created, passes of at most 32
+ * rows run as one resident kernel whose workgroups meet at bounded grid barriers; should a
+ * barrier time out (never expected), every sequence reports accept_len -1 and next_token
+ * pad_id, specdec_commit then changes nothing, and the condition lasts until the next
+ * specdec_begin.
  * logits_or_null: optional device fp32 [B, k+1, V] receiving every row's logits (parity
  * mode; slow).  Does not change any length: calling it twice gives the same result. */
 int specdec_verify(specdec_ctx* ctx, const int32_t* draft, int32_t k, int32_t beta, float tau,

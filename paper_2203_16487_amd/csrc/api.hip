@@ -71,7 +71,7 @@ struct specdec_ctx {
   Model m[2];
   int B = 0;          // batch of the current begin()
   int max_new = 0;
-  int last_k = 0;     // k of the latest verify (0: none)
+  int last_T = 0;     // rows per sequence (k + 1) of the latest verify (0: none)
   int S_cur = 0;      // S_max of the current memory
   int uncached_ub[2] = {0, 0};
   bool trusted[2] = {false, false};
@@ -483,7 +483,7 @@ int specdec_begin(specdec_ctx* c, int32_t B, int32_t max_new, void* stream) {
   }
   c->B = B;
   c->max_new = max_new;
-  c->last_k = 0;
+  c->last_T = 0;
   c->uncached_ub[0] = 0;
   c->uncached_ub[1] = 1;
   c->trusted[0] = c->trusted[1] = false;
@@ -566,7 +566,7 @@ int specdec_set_stream(specdec_ctx* c, const int32_t* tokens, const int32_t* len
   c->uncached_ub[0] = L_max;
   c->uncached_ub[1] = L_max + 1;
   c->trusted[0] = c->trusted[1] = false;
-  c->last_k = 0;
+  c->last_T = 0;
   return SPECDEC_OK;
 }
 
@@ -644,8 +644,8 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
                    int32_t* next_token, float* logits, void* stream) {
   int rc = check_ready(c, SPECDEC_VERIFIER, true);
   if (rc) return rc;
-  if (!draft || !accept_len || !next_token) return fail(c, SPECDEC_ERR_INVALID_ARG, "null draft/accept_len/next_token");
-  if (k < 1) return fail(c, SPECDEC_ERR_INVALID_ARG, "k = %d", k);
+  if (!accept_len || !next_token || (!draft && k > 0)) return fail(c, SPECDEC_ERR_INVALID_ARG, "null draft/accept_len/next_token");
+  if (k < 0) return fail(c, SPECDEC_ERR_INVALID_ARG, "k = %d", k);
   if (k > c->lim.k_max) return fail(c, SPECDEC_ERR_TOO_LARGE, "k = %d exceeds k_max = %d", k, c->lim.k_max);
   Model& m = c->m[SPECDEC_VERIFIER];
   if (beta < 1 || beta > m.d.vocab) return fail(c, SPECDEC_ERR_INVALID_ARG, "beta = %d outside [1, vocab]", beta);
@@ -687,7 +687,7 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
     LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
   }
   LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::accept_rows(st, m.row_stats, c->st, B, k, beta, tau, m.d.pad_id, accept_len, next_token, failed));
-  c->last_k = k;
+  c->last_T = k + 1;
   return SPECDEC_OK;
 }
 
@@ -695,9 +695,9 @@ int specdec_commit(specdec_ctx* c, const int32_t* accept_len, const int32_t* nex
   int rc = check_ready(c, SPECDEC_VERIFIER, false);
   if (rc) return rc;
   if (!accept_len || !next_token) return fail(c, SPECDEC_ERR_INVALID_ARG, "null accept_len/next_token");
-  if (c->last_k <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_commit without a preceding specdec_verify");
+  if (c->last_T <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_commit without a preceding specdec_verify");
   HIPCHK(c, sd::commit_rows(S(stream), c->st, accept_len, next_token, c->B, c->m[0].d.eos_id, n_active));
-  c->last_k = 0;
+  c->last_T = 0;
   c->uncached_ub[1] += c->lim.k_max + 1;
   return SPECDEC_OK;
 }
@@ -707,7 +707,7 @@ int specdec_rewind(specdec_ctx* c, const int32_t* len, void* stream) {
   if (!c->state_bound || c->B <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "begin not called");
   if (!len) return fail(c, SPECDEC_ERR_INVALID_ARG, "null len");
   HIPCHK(c, sd::rewind_state(S(stream), c->st, len, c->B));
-  c->last_k = 0;
+  c->last_T = 0;
   return SPECDEC_OK;
 }
 
@@ -780,8 +780,8 @@ int specdec_get_row_stats(specdec_ctx* c, float* stats, void* stream) {
   int rc = check_ready(c, SPECDEC_VERIFIER, false);
   if (rc) return rc;
   if (!stats) return fail(c, SPECDEC_ERR_INVALID_ARG, "null stats");
-  if (c->last_k <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "no verification pass to report");
-  const size_t n = (size_t)c->B * (c->last_k + 1) * SPECDEC_ROW_STATS;
+  if (c->last_T <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "no verification pass to report");
+  const size_t n = (size_t)c->B * c->last_T * SPECDEC_ROW_STATS;
   HIPCHK(c, hipMemcpyAsync(stats, c->m[0].row_stats, n * sizeof(float), hipMemcpyDeviceToDevice, S(stream)));
   return SPECDEC_OK;
 }

@@ -198,3 +198,56 @@ def test_config3_drafter_pass():
     assert worst <= 3e-2
     ex = check_drafts(dr.cpu().numpy(), o_tok, o_log, "config3")
     print(f"[config3] drafts match ({ex} near-tie excused)")
+
+
+def test_autoregressive_baseline_k0():
+    """k = 0: verification degenerates to one plain autoregressive step per call (Sec. 2, the
+    baseline SpecDec is measured against).  The oracle follows in lock step with dec_step; the
+    whole output must equal the oracle's greedy decoding unless a near-tie was excused.  B = 40
+    takes the general kernels, B = 5 the fused small-batch ones."""
+    for B in (5, 40):
+        (vd, vb, vm), _ = make_models(seed=31)
+        row = synth.bf16_bits_to_f32(vb["embed"][vd.eos_id]) * 2.0          # make EOS reachable
+        vb["embed"][vd.eos_id] = synth.f32_to_bf16_bits(row)
+        vm.w["embed"][vd.eos_id] = synth.bf16_bits_to_f32(vb["embed"][vd.eos_id])
+        S_max, max_new = 12, 14
+        src_len = synth.random_lengths(31, "src_len", B, 2, S_max)
+        src = synth.random_tokens(31, "src", (B, S_max), vd)
+        ses = open_session(B, 4, S_max, 64, ver=(vd, vb))
+        dev = ses.device
+        sd.specdec_begin(ses.ctx, B, max_new)
+        sd.specdec_encode(ses.ctx, ses.i32(src), ses.i32(src_len))
+        mems = [orc.encode(vm, list(src[b, :src_len[b]])) for b in range(B)]
+        sts = [orc.new_state(vm, mems[b], max_new + 2) for b in range(B)]
+        streams = [[vd.bos_id] for _ in range(B)]
+        done = [False] * B
+        acc = torch.zeros(B, dtype=torch.int32, device=dev)
+        nxt = torch.zeros(B, dtype=torch.int32, device=dev)
+        nact = torch.zeros(1, dtype=torch.int32, device=dev)
+        excused = 0
+        for it in range(max_new + 1):
+            sd.specdec_verify(ses.ctx, None, 0, 1, 0.0, acc, nxt)
+            sd.specdec_commit(ses.ctx, acc, nxt, nact)
+            torch.cuda.synchronize()
+            g_acc, g_nxt = acc.cpu().numpy(), nxt.cpu().numpy()
+            assert (g_acc == 0).all()
+            for b in range(B):
+                if done[b]:
+                    assert g_nxt[b] == vd.pad_id
+                    continue
+                z = orc.dec_step(vm, sts[b], streams[b][-1])
+                t = int(np.argmax(z))
+                if t != int(g_nxt[b]):
+                    assert near_tie(z), (B, it, b, t, int(g_nxt[b]))
+                    excused += 1
+                streams[b].append(int(g_nxt[b]))
+                if int(g_nxt[b]) == vd.eos_id or len(streams[b]) - 1 >= max_new:
+                    done[b] = True
+            if int(nact.item()) == 0:
+                break
+        assert all(done)
+        if excused == 0:
+            for b in range(B):
+                assert streams[b][1:] == orc.greedy_decode(vm, mems[b], max_new)
+        print(f"[ar baseline B={B}] greedy decoding reproduced ({excused} near-ties excused)")
+        ses.close()

@@ -198,7 +198,7 @@ def test_argument_errors_on_device():
     d = ses.i32(case.drafts)
     acc = torch.zeros(2, dtype=torch.int32, device=dev)
     nxt = torch.zeros(2, dtype=torch.int32, device=dev)
-    for kw, code in ((dict(k=4), sd.SPECDEC_ERR_TOO_LARGE), (dict(k=0), sd.SPECDEC_ERR_INVALID_ARG),
+    for kw, code in ((dict(k=4), sd.SPECDEC_ERR_TOO_LARGE), (dict(k=-1), sd.SPECDEC_ERR_INVALID_ARG),
                      (dict(beta=0), sd.SPECDEC_ERR_INVALID_ARG), (dict(tau=-1.0), sd.SPECDEC_ERR_INVALID_ARG),
                      (dict(tau=float("nan")), sd.SPECDEC_ERR_INVALID_ARG)):
         args = dict(k=3, beta=1, tau=0.0); args.update(kw)
