@@ -88,3 +88,12 @@ def test_bind_model_argument_checks_without_gpu():
             assert L.specdec_bind_model(ctx, 0, C.byref(d), ptrs, n, C.c_void_p(4096), 1 << 40, None) == sd.SPECDEC_ERR_NO_DEVICE
     finally:
         sd.specdec_destroy(ctx)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message (this build is one-GPU only)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr
