@@ -630,8 +630,7 @@ int specdec_draft(specdec_ctx* c, int32_t k, int32_t* draft, void* stream) {
   if (rc) return rc;
   HIPCHK(c, sd::gather_slots(st, m.xb, m.slots, m.new_rows, B, T, k, m.d.d_model));
   const int R = B * k, n_tiles = (m.d.vocab + 127) / 128;
-  HIPCHK(c, sd::fill_i32(st, m.rm.row_draft, -1, R));
-  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.zd, m.part, nullptr));
+  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, m.d.d_model, nullptr, m.zd, m.part, nullptr));
   LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
   HIPCHK(c, sd::write_drafts(st, m.row_stats, c->st, B, k, m.d.pad_id, draft));
   HIPCHK(c, sd::advance_cached(st, c->st, SPECDEC_DRAFTER, m.new_rows, B));

@@ -390,7 +390,12 @@ hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int 
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(draft_logit_kernel, dim3((M + 31) / 32), dim3(64), 0, st, A, E, M, V, K, row_draft, zd_row);
+  if (row_draft) {
+    hipLaunchKernelGGL(draft_logit_kernel, dim3((M + 31) / 32), dim3(64), 0, st, A, E, M, V, K, row_draft, zd_row);
+  } else {   // no row scores a draft (drafter pass): every count is taken against -inf and unused
+    hipError_t e = fill_i32(st, reinterpret_cast<int*>(zd_row), (int)0xff800000u, M);
+    if (e != hipSuccess) return e;
+  }
   const int MT = (M + 127) / 128, NT = (V + 127) / 128;
   hipLaunchKernelGGL(vocab_kernel, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
                      A, E, M, V, K, MT, NT, zd_row, part, logits);

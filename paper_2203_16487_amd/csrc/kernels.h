@@ -48,7 +48,8 @@ hipError_t gemm_enc_qkv(hipStream_t st, const bf16* A, const bf16* W, int M, int
 // draft each row scores (-inf if none).  For every row and every 128-column vocabulary tile one
 // partial record of kPartF floats is written to part[M][n_tiles][kPartF]: {tile max, tile
 // arg-max (int bits), sum exp(z - tile max), number of tile logits > zd_row (int bits)}.
-// logits (optional, fp32 [M, V]) receives the full rows.
+// logits (optional, fp32 [M, V]) receives the full rows.  row_draft may be null: no row scores a
+// draft (the pre-pass is skipped, zd_row is filled with -inf).
 constexpr int kPartF = 4;
 constexpr int kRowStats = 8;   // floats per row of merged statistics
 hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int V, int K,
