@@ -283,10 +283,29 @@ __global__ __launch_bounds__(64) void draft_logit_kernel(const bf16* __restrict_
   f32x16 acc;
 #pragma unroll
   for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-  for (int kb = 0; kb < K / 16; ++kb) {
-    bf16x8 a = *reinterpret_cast<const bf16x8*>(ap + kb * 16);
-    bf16x8 b = *reinterpret_cast<const bf16x8*>(bp + kb * 16);
-    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+  // operands of 16 k-blocks are requested together (one memory round trip per 256 columns of K
+  // instead of one per block); the accumulation order stays k-ascending
+  constexpr int U = 16;
+  const int nkb = K / 16;
+  for (int kb0 = 0; kb0 < nkb; kb0 += U) {
+    bf16x8 a[U], b[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int kb = min(kb0 + u, nkb - 1);
+      a[u] = *reinterpret_cast<const bf16x8*>(ap + kb * 16);
+      b[u] = *reinterpret_cast<const bf16x8*>(bp + kb * 16);
+    }
+    if (kb0 + U <= nkb) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[u], acc, 0, 0, 0);
+    } else {
+      for (int u = 0; u < nkb - kb0; ++u) {
+        bf16x8 au = a[0], bu = b[0];
+#pragma unroll
+        for (int v = 1; v < U; ++v) if (v == u) { au = a[v]; bu = b[v]; }
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(au, bu, acc, 0, 0, 0);
+      }
+    }
   }
   mfma_settle(acc);
   // element (i, j): j = lane%32, i = 8*(reg/4) + 4*(lane/32) + reg%4; the diagonal j = i sits in
