@@ -124,3 +124,34 @@ def test_config5_summarization_loop_full_size():
     attention; self-attention arena beyond 256 rows); 2 sequences recomputed by the oracle."""
     run_full_size("config5", B=32, k=10, beta=5, tau=3.0, S_max=1024, src_lo=1024, max_tgt=256,
                   len_lo=200, len_hi=245, sample=[3, 31])
+
+
+def test_config3_drafter_pass_full_size():
+    """Spec-Drafter pass at its full batch: B=64, source 128, 32 tokens decoded, k=10 mask slots;
+    the whole batch on the GPU (encoder, prefill, draft), 3 sequences recomputed by the oracle."""
+    dd = synth.spec_drafter(max_src=128, max_tgt=64)
+    db = synth.make_weights(dd, 0, tag="drafter")
+    dm = orc.Model(dd, synth.weights_f32(db))
+    B, S, k, L = 64, 128, 10, 32
+    src = synth.random_tokens(0, "src", (B, S), dd)
+    src_len = np.full(B, S, np.int32)
+    toks = synth.random_tokens(0, "prefix", (B, L + 1), dd)
+    toks[:, 0] = dd.bos_id
+    lens = np.full(B, L, np.int32)
+    ses = dl.open_session(B, k, S, 64, dr=(dd, db))
+    sd.specdec_begin(ses.ctx, B, 100)
+    sd.specdec_encode(ses.ctx, ses.i32(src), ses.i32(src_len))
+    sd.specdec_set_stream(ses.ctx, ses.i32(toks), ses.i32(lens))
+    sd.specdec_prefill(ses.ctx, sd.SPECDEC_DRAFTER)
+    dr = torch.full((B, k), -1, dtype=torch.int32, device=ses.device)
+    sd.specdec_draft(ses.ctx, k, dr)
+    torch.cuda.synchronize()
+    g = dr.cpu().numpy()
+    assert (g >= 0).all() and (g < dd.vocab).all()
+    excused = 0
+    for b in (0, 31, 63):
+        dst = orc.new_state(dm, orc.encode(dm, list(src[b])), 64)
+        t, z = orc.draft(dm, dst, [int(x) for x in toks[b]], k, return_logits=True)
+        excused += dl.check_drafts(g[b:b + 1], [t], [z], f"config3 full {b}")
+    print(f"[config3 full] drafts of 3 sampled sequences match ({excused} near-ties excused)")
+    ses.close()
