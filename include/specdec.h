@@ -83,7 +83,8 @@ int specdec_bind_state(specdec_ctx* ctx, void* state /*device*/, size_t bytes);
 /* Per-model workspace (KV arenas, cross-attention K/V, activations, position table). */
 int specdec_workspace_bytes(const specdec_ctx* ctx, const specdec_model_desc* desc, size_t* out);
 /* weights: (host) array of n_weights (device) pointers in the order above.  The workspace
- * is (device), 256-byte aligned.  Builds the position table on `stream`. */
+ * is (device), 256-byte aligned.  Builds the position table on `stream`; also copies a small
+ * table of layer pointers into the workspace with a synchronous host-to-device copy. */
 int specdec_bind_model(specdec_ctx* ctx, specdec_role role, const specdec_model_desc* desc,
                        const void* const* weights, int32_t n_weights, void* workspace,
                        size_t workspace_bytes, void* stream);
