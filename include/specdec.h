@@ -84,7 +84,11 @@ int specdec_bind_state(specdec_ctx* ctx, void* state /*device*/, size_t bytes);
 int specdec_workspace_bytes(const specdec_ctx* ctx, const specdec_model_desc* desc, size_t* out);
 /* weights: (host) array of n_weights (device) pointers in the order above.  The workspace
  * is (device), 256-byte aligned.  Builds the position table on `stream`; also copies a small
- * table of layer pointers into the workspace with a synchronous host-to-device copy. */
+ * table of layer pointers into the workspace with a synchronous host-to-device copy.
+ * The weight tensors are used in place and must hold their final values when this is called:
+ * kernels on `stream` read them here to derive, into the workspace, the per-column vectors with
+ * which each decoder LayerNorm is folded into the projections around it (sums of gain x weight
+ * and shift x weight over the input dimension).  Bind again after changing weights. */
 int specdec_bind_model(specdec_ctx* ctx, specdec_role role, const specdec_model_desc* desc,
                        const void* const* weights, int32_t n_weights, void* workspace,
                        size_t workspace_bytes, void* stream);

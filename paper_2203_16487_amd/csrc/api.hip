@@ -26,6 +26,13 @@ struct DecLayer {
   const bf16 *w1, *b1, *w2, *b2, *ln3g, *ln3b;
 };
 
+// LayerNorm folded into the projections that read its output: ln3 of the layer below -> wqkv
+// (unused in layer 0), ln1 -> cwq, ln2 -> w1.
+struct LnFolds {
+  sd::LnFold qkv, cq, w1;
+  const float *vo, *vco, *v2;   // column vectors of the three residual sums (wo, cwo, w2), [3][d] each
+};
+
 struct Model {
   bool bound = false;
   bool has_memory = false;
@@ -45,6 +52,9 @@ struct Model {
   int rs_parity = 0;
   int rs_seq = 0;
   bf16* xb = nullptr;        // [Rmax][d]
+  float* lnp[2] = {nullptr, nullptr};   // [rows][d/64 rounded up to even][2] chunk pairs of the two latest residual sums
+  float* fold = nullptr;     // per decoder layer: cs and bf vectors of wqkv, cwq, w1 (LayerNorm folded)
+  std::vector<LnFolds> folds;
   bf16* q = nullptr;         // [Rmax][d]
   bf16* att = nullptr;       // [Rmax][d]
   bf16* hid = nullptr;       // [Rmax][F]
@@ -80,6 +90,7 @@ struct specdec_ctx {
   std::vector<hipEvent_t> prof_ev;
   int prof_used = 0;
   bool no_skinny = false;   // SPECDEC_NO_SKINNY=1: always take the general kernels
+  bool no_ln_fold = false;  // SPECDEC_NO_LN_FOLD=1: LayerNorm as a pass of its own between the GEMMs
   bool resident = false;    // SPECDEC_RESIDENT=1: small batches run the decoder pass as one resident kernel
   char err[512] = {0};
 };
@@ -202,6 +213,9 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   t.x = cv.take<float>(Rmax * D);
   t.x2 = cv.take<float>(32 * D);
   t.xb = cv.take<bf16>(Rmax * D);
+  t.lnp[0] = cv.take<float>(Rmax * (D / 64 + 1) * 2);
+  t.lnp[1] = cv.take<float>(Rmax * (D / 64 + 1) * 2);
+  t.fold = cv.take<float>((size_t)d->dec_layers * (2 * (3 * D + D + F) + 9 * D));
   t.q = cv.take<bf16>((Rmax > 32 ? Rmax : 32) * D);
   t.att = cv.take<bf16>(Rmax * D);
   t.hid = cv.take<bf16>((Rmax > 32 ? Rmax : 32) * F);
@@ -231,6 +245,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   if (m) {
     m->kv_layer = t.kv_layer; m->xkv_layer = t.xkv_layer;
     m->pe = t.pe; m->kc = t.kc; m->vc = t.vc; m->xk = t.xk; m->xv = t.xv;
+    m->lnp[0] = t.lnp[0]; m->lnp[1] = t.lnp[1]; m->fold = t.fold;
     m->x = t.x; m->x2 = t.x2; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
     m->part = t.part; m->row_stats = t.row_stats; m->zd = t.zd; m->rm = t.rm;
     m->slots = t.slots; m->new_rows = t.new_rows; m->rs_layers = t.rs_layers; m->rs_bar = t.rs_bar;
@@ -248,12 +263,29 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
   const int R = B * T, D = m.d.d_model, F = m.d.d_ffn, H = m.d.n_heads;
   const int Lcap = c->Lcap, Scap = c->Scap;
   LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::embed_rows(st, m.rm.row_tok, m.rm.row_pos, m.embed, m.pe, m.x, m.xb, R, D));
+  // LayerNorm folded into the GEMMs on both sides of it: m.x holds the un-normalised sum, m.xb
+  // that sum times the gain, `pend` the LayerNorm still to be applied to them.
+  const bool fold = !c->no_ln_fold;
+  const float* pend = nullptr;   // chunk pairs of the sum in m.x (null: m.x is the residual itself)
+  int flip = 0;
+  auto sum = [&](const bf16* A, int K, const bf16* W, const float* vecs) {
+    float* out = m.lnp[flip];
+    hipError_t e = sd::gemm_ln_sum(st, A, K, W, R, D, K, vecs, pend ? pend : m.lnp[flip ^ 1], pend != nullptr, m.x, m.xb, out);
+    pend = out;
+    flip ^= 1;
+    return e;
+  };
   for (int l = 0; l < m.d.dec_layers; ++l) {
     const DecLayer& L = m.dec[l];
     bf16* kc = m.kc + m.kv_layer * l;
     bf16* vc = m.vc + m.kv_layer * l;
-    LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::gemm_qkv_append(st, m.xb, L.wqkv, R, D, D, L.bqkv, m.q, kc, vc, m.rm.row_b,
-                                  m.rm.row_pos, H, Lcap));
+    if (fold && l > 0) {
+      LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::gemm_ln_qkv_append(st, m.xb, L.wqkv, R, D, m.folds[l].qkv, pend, m.q, kc,
+                                       vc, m.rm.row_b, m.rm.row_pos, H, Lcap));
+    } else {
+      LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::gemm_qkv_append(st, m.xb, L.wqkv, R, D, D, L.bqkv, m.q, kc, vc, m.rm.row_b,
+                                    m.rm.row_pos, H, Lcap));
+    }
     sd::AttnArgs a{};
     a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
     a.k = kc; a.k_b = (long)H * Lcap * 64; a.k_h = (long)Lcap * 64; a.k_row = 64;
@@ -263,19 +295,32 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
     a.T = T; a.H = H; a.B = B;
     a.key_split = Lcap > 256; a.cap = Lcap;
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
-    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.wo, R, D, D, L.bo, m.x, m.x, D));
-    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln1g, L.ln1b, m.xb, R, D));
-    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.xb, D, L.cwq, R, D, D, L.cbq, m.q, D, false));
+    if (fold) {
+      LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sum(m.att, D, L.wo, m.folds[l].vo));
+      LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_ln_bf16(st, m.xb, L.cwq, R, D, D, m.folds[l].cq, pend, m.q, D, false));
+    } else {
+      LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.wo, R, D, D, L.bo, m.x, m.x, D));
+      LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln1g, L.ln1b, m.xb, R, D));
+      LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.xb, D, L.cwq, R, D, D, L.cbq, m.q, D, false));
+    }
     a.k = m.xk + m.xkv_layer * l; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64;
     a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_blocked = 1;
     a.lim_row = nullptr; a.lim_seq = c->st.src_len;
     a.key_split = c->S_cur > 256; a.cap = Scap;
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
-    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.cwo, R, D, D, L.cbo, m.x, m.x, D));
-    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln2g, L.ln2b, m.xb, R, D));
-    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.xb, D, L.w1, R, F, D, L.b1, m.hid, F, true));
-    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.hid, F, L.w2, R, D, F, L.b2, m.x, m.x, D));
-    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln3g, L.ln3b, m.xb, R, D));
+    if (fold) {
+      LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sum(m.att, D, L.cwo, m.folds[l].vco));
+      LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_ln_bf16(st, m.xb, L.w1, R, F, D, m.folds[l].w1, pend, m.hid, F, true));
+      LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sum(m.hid, F, L.w2, m.folds[l].v2));
+      if (l + 1 == m.d.dec_layers)   // the vocabulary projection reads the normalised rows themselves
+        LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln3g, L.ln3b, m.xb, R, D));
+    } else {
+      LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.cwo, R, D, D, L.cbo, m.x, m.x, D));
+      LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln2g, L.ln2b, m.xb, R, D));
+      LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.xb, D, L.w1, R, F, D, L.b1, m.hid, F, true));
+      LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.hid, F, L.w2, R, D, F, L.b2, m.x, m.x, D));
+      LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln3g, L.ln3b, m.xb, R, D));
+    }
   }
   return SPECDEC_OK;
 }
@@ -366,6 +411,7 @@ int specdec_create(specdec_ctx** out, const specdec_limits* lim) {
   c->lim = *lim;
   c->Tmax = 2 * lim->k_max + 1;
   if (const char* e = getenv("SPECDEC_NO_SKINNY")) c->no_skinny = (e[0] == '1');
+  if (const char* e = getenv("SPECDEC_NO_LN_FOLD")) c->no_ln_fold = (e[0] == '1');
   if (const char* e = getenv("SPECDEC_RESIDENT")) c->resident = (e[0] == '1');
   c->Lcap = (lim->max_tgt + lim->k_max + 1 + 31) & ~31;   // rows of the KV arenas (32-key chunks)
   c->Scap = (lim->max_src + 31) & ~31;
@@ -454,6 +500,28 @@ int specdec_bind_model(specdec_ctx* c, specdec_role role, const specdec_model_de
   }
   carve_model(c, d, workspace, &m);
   HIPCHK(c, sd::build_pos_table(S(stream), m.pe, c->n_pos, d->d_model));
+  {
+    const int D = d->d_model, F = d->d_ffn;
+    float* f = m.fold;
+    auto vec2 = [&](int n) { sd::LnFold o{f, f + n}; f += 2 * n; return o; };
+    m.folds.resize(d->dec_layers);
+    for (int l = 0; l < d->dec_layers; ++l) {
+      const DecLayer& L = m.dec[l];
+      LnFolds& o = m.folds[l];
+      o.qkv = vec2(3 * D); o.cq = vec2(D); o.w1 = vec2(F);
+      float* v = f;
+      f += 9 * D;
+      o.vo = v; o.vco = v + 3 * D; o.v2 = v + 6 * D;
+      const bf16* g0 = l > 0 ? m.dec[l - 1].ln3g : nullptr;
+      const bf16* b0 = l > 0 ? m.dec[l - 1].ln3b : nullptr;
+      HIPCHK(c, sd::ln_sum_vecs(S(stream), L.bo, g0, b0, L.ln1g, D, v));
+      HIPCHK(c, sd::ln_sum_vecs(S(stream), L.cbo, L.ln1g, L.ln1b, L.ln2g, D, v + 3 * D));
+      HIPCHK(c, sd::ln_sum_vecs(S(stream), L.b2, L.ln2g, L.ln2b, L.ln3g, D, v + 6 * D));
+      if (l > 0) HIPCHK(c, sd::ln_fold(S(stream), L.wqkv, m.dec[l - 1].ln3g, m.dec[l - 1].ln3b, L.bqkv, 3 * D, D, o.qkv));
+      HIPCHK(c, sd::ln_fold(S(stream), L.cwq, L.ln1g, L.ln1b, L.cbq, D, D, o.cq));
+      HIPCHK(c, sd::ln_fold(S(stream), L.w1, L.ln2g, L.ln2b, L.b1, F, D, o.w1));
+    }
+  }
   {
     std::vector<sd::RsLayer> rl(d->dec_layers);
     for (int l = 0; l < d->dec_layers; ++l) {

@@ -261,6 +261,339 @@ hipError_t gemm_enc_qkv(hipStream_t st, const bf16* A, const bf16* W, int M, int
   return launch(st, A, K, W, M, 3 * d, K, EpiEncQkv{bias, q_out, ek, ev, d, H, S, Scap});
 }
 
+// ----------------------------------------------------------------------------- LayerNorm folded into the GEMMs
+// Post-LN blocks: x' = LN(y), y = x + sublayer(x).  Instead of a pass of its own over y, the
+// normalisation is split between the GEMM that produces y and the GEMMs that consume x':
+//   producer (EpiLnSum)   writes y (fp32), bf16(y * g) and, for every 64-column chunk of every row,
+//                         the pair {sum, sum of squared deviations from the chunk mean};
+//   consumer (EpiLn*)     multiplies bf16(y * g) by the unchanged weights and finishes
+//                         LN(y) W^T + b = rstd * (acc - mean * cs) + bf,
+//                         cs[n] = sum_k g[k] W[n][k],  bf[n] = b[n] + sum_k beta[k] W[n][k]
+//                         (both fp32, derived once per model by ln_fold);
+//   the residual x' that the next producer adds is recomputed there from y, mean, rstd, g, beta.
+// mean and rstd of a row come from its chunk pairs, merged with the parallel-variance formula;
+// eps = 1e-5 and the biased variance, as in layer_norm.  Epilogues run with every wave of the
+// chip at the same point and nothing to overlap with, so they are written for few instructions:
+// per row {rstd, -mean * rstd}, per column folded constants, fused multiply-adds.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// Sums over aligned groups of 2, 4 or 8 neighbouring lanes with DPP moves (no LDS round trip):
+// swap within pairs, swap pairs within quads, mirror within groups of 8.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+template <int LANES>
+__device__ __forceinline__ float group_sum(float v) {
+  static_assert(LANES == 2 || LANES == 4 || LANES == 8, "group size");
+  v += dpp_move<0xB1>(v);                     // quad_perm [1,0,3,2]
+  if (LANES >= 4) v += dpp_move<0x4E>(v);     // quad_perm [2,3,0,1]
+  if (LANES >= 8) v += dpp_move<0x141>(v);    // row_half_mirror: lane i <-> 7 - i
+  return v;
+}
+
+// Chunk pairs of a row lie together, [M][pitch] pairs with pitch = chunks rounded up to even, so a
+// thread fetches two pairs per 16-byte load.
+__host__ __device__ __forceinline__ int ln_pitch(int chunks) { return (chunks + 1) & ~1; }
+
+template <class Cfg>
+struct LnRows {
+  static constexpr int TPR = Cfg::kThreads / Cfg::kBM;   // threads that share one tile row
+  static constexpr int NL = 16 / TPR;                    // 16-byte loads per thread (d <= 2048)
+  static_assert(TPR == 2 || TPR == 4, "threads per row");
+  f32x4 p[NL];                                           // pairs 2q, 2q+1 for q = j + i * TPR
+  // Loads sit behind conditions on kernel arguments only (no lane takes a branch of its own).
+  __device__ __forceinline__ void request(const f32x2* part, int chunks, int m0, int M) {
+    const int r = threadIdx.x / TPR, j = threadIdx.x % TPR;
+    const int pitch = ln_pitch(chunks);
+    const f32x4* src = reinterpret_cast<const f32x4*>(part + (size_t)min(m0 + r, M - 1) * pitch);
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      p[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (2 * i * TPR < chunks) p[i] = src[min(j + i * TPR, pitch / 2 - 1)];
+    }
+  }
+  // rowstat [BM][2] in LDS: {rstd, -mean * rstd}; {1, 0} when there is nothing to normalise
+  __device__ __forceinline__ void finish(int chunks, bool identity, float* rowstat) const {
+    const int r = threadIdx.x / TPR, j = threadIdx.x % TPR;
+    const float inv_d = __builtin_amdgcn_rcpf((float)(64 * chunks));   // d = 2^6 * chunks: exact for powers of two
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      if (2 * i * TPR >= chunks) continue;
+      const int c = 2 * (j + i * TPR);
+      s += (c < chunks ? p[i][0] : 0.f) + (c + 1 < chunks ? p[i][2] : 0.f);
+    }
+    s = group_sum<TPR>(s);
+    const float mean = s * inv_d;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      if (2 * i * TPR >= chunks) continue;
+      const int c = 2 * (j + i * TPR);
+      const float d0 = p[i][0] * (1.0f / 64.0f) - mean, d1 = p[i][2] * (1.0f / 64.0f) - mean;
+      q += (c < chunks ? p[i][1] + 64.0f * d0 * d0 : 0.f) + (c + 1 < chunks ? p[i][3] + 64.0f * d1 * d1 : 0.f);
+    }
+    q = group_sum<TPR>(q);
+    if (j == 0) {
+      const float rstd = identity ? 1.f : 1.0f / sqrtf(q * inv_d + 1e-5f);
+      rowstat[2 * r] = rstd;
+      rowstat[2 * r + 1] = identity ? 0.f : -mean * rstd;
+    }
+  }
+};
+
+// Producer.  x holds the previous sum y_prev (or the plain residual when has_prev is 0) and
+// receives the new sum in place.  Column vectors (LnSumVecs, fp32 [3][d]):
+//   0: gain of the LayerNorm pending on x (1 without one)
+//   1: its shift (0 without one) + this GEMM's bias
+//   2: gain of the LayerNorm that follows
+struct EpiLnSum {
+  static constexpr int kVec = 3;
+  const float* __restrict__ vecs;
+  const f32x2* ln_in;              // chunk pairs of y_prev
+  f32x2* ln_out;                   // chunk pairs of the new sum
+  float* x;
+  bf16* __restrict__ xg;           // bf16(y * next gain)
+  int ld, chunks;
+  int has_prev;                    // 0: x is the residual itself
+  __device__ __forceinline__ const float* vec(int i) const { return vecs + i * ld; }
+  __device__ __forceinline__ bool identity() const { return has_prev == 0; }
+  struct Pre { f32x4 r0, r1; };
+  __device__ __forceinline__ Pre fetch(int m, int n) const {
+    const size_t o = (size_t)m * ld + n;
+    return Pre{*reinterpret_cast<const f32x4*>(x + o), *reinterpret_cast<const f32x4*>(x + o + 4)};
+  }
+  // called by every lane (live = inside the matrix): the chunk sums cross lanes
+  __device__ __forceinline__ void store(int m, int n, bool live, const float (&v)[8], const Pre& p,
+                                        float rstd, float nmr, const float (&cv)[kVec][8]) const {
+    float y[8], s = 0.f, ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float r = i < 4 ? p.r0[i] : p.r1[i - 4];
+      y[i] = v[i] + __builtin_fmaf(__builtin_fmaf(r, rstd, nmr), cv[0][i], cv[1][i]);
+      s += y[i];
+      ss = __builtin_fmaf(y[i], y[i], ss);
+    }
+    s = group_sum<8>(s);     // 8 lanes = one 64-column chunk
+    ss = group_sum<8>(ss);
+    if (!live) return;
+    const size_t o = (size_t)m * ld + n;
+    *reinterpret_cast<f32x4*>(x + o) = f32x4{y[0], y[1], y[2], y[3]};
+    *reinterpret_cast<f32x4*>(x + o + 4) = f32x4{y[4], y[5], y[6], y[7]};
+    bf16x8 g;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) g[i] = (bf16)(y[i] * cv[2][i]);
+    *reinterpret_cast<bf16x8*>(xg + o) = g;
+    // squared deviations from the chunk mean = sum y^2 - (sum y)^2 / 64, never below 0
+    if ((n & 63) == 0) ln_out[(size_t)m * ln_pitch(chunks) + (n >> 6)] = f32x2{s, fmaxf(ss - s * s * (1.0f / 64.0f), 0.f)};
+  }
+};
+
+// rstd * (acc - mean * cs) + bf on 8 columns: cv[0] = cs, cv[1] = bf
+__device__ __forceinline__ bf16x8 ln_finish(const float (&v)[8], float rstd, float nmr, const float (&cv)[2][8],
+                                            bool relu) {
+  bf16x8 o;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float t = __builtin_fmaf(v[i], rstd, __builtin_fmaf(nmr, cv[0][i], cv[1][i]));
+    if (relu) t = fmaxf(t, 0.f);
+    o[i] = (bf16)t;
+  }
+  return o;
+}
+
+struct EpiLnBf16 {
+  static constexpr int kVec = 2;
+  const float* __restrict__ cs;
+  const float* __restrict__ bf;
+  const f32x2* ln_in;
+  bf16* __restrict__ out;
+  int ldo, chunks, relu;
+  __device__ __forceinline__ const float* vec(int i) const { return i == 0 ? cs : bf; }
+  __device__ __forceinline__ bool identity() const { return false; }
+  struct Pre {};
+  __device__ __forceinline__ Pre fetch(int, int) const { return Pre{}; }
+  __device__ __forceinline__ void store(int m, int n, bool live, const float (&v)[8], const Pre&,
+                                        float rstd, float nmr, const float (&cv)[kVec][8]) const {
+    if (live) *reinterpret_cast<bf16x8*>(out + (size_t)m * ldo + n) = ln_finish(v, rstd, nmr, cv, relu != 0);
+  }
+};
+
+struct EpiLnQkvAppend {
+  static constexpr int kVec = 2;
+  const float* __restrict__ cs;
+  const float* __restrict__ bf;
+  const f32x2* ln_in;
+  int chunks;
+  bf16* __restrict__ q;
+  bf16* __restrict__ kc;
+  bf16* __restrict__ vc;
+  const int* __restrict__ row_b;
+  const int* __restrict__ row_pos;
+  int d, H, Lcap;
+  __device__ __forceinline__ const float* vec(int i) const { return i == 0 ? cs : bf; }
+  __device__ __forceinline__ bool identity() const { return false; }
+  struct Pre { int sb, pos; };
+  __device__ __forceinline__ Pre fetch(int m, int) const { return Pre{row_b[m], row_pos[m]}; }
+  __device__ __forceinline__ void store(int m, int n, bool live, const float (&v)[8], const Pre& p,
+                                        float rstd, float nmr, const float (&cv)[kVec][8]) const {
+    if (!live) return;
+    const bf16x8 o = ln_finish(v, rstd, nmr, cv, false);
+    const int part = n / d, cc = n - part * d;
+    if (part == 0) {
+      *reinterpret_cast<bf16x8*>(q + (size_t)m * d + cc) = o;
+      return;
+    }
+    if (p.sb < 0) return;
+    const int h = cc >> 6, e = cc & 63;
+    bf16* cache = (part == 1) ? kc : vc;
+    *reinterpret_cast<bf16x8*>(cache + (((size_t)p.sb * H + h) * Lcap + p.pos) * kHeadDim + e) = o;
+  }
+};
+
+template <class Cfg, int VEC>
+constexpr int ln_smem_bytes() { return Cfg::kSmemBytes + (2 * Cfg::kBM + VEC * Cfg::kBN) * 4; }
+
+template <class Cfg, class Epi>
+__global__ __launch_bounds__(Cfg::kThreads) void gemm_ln_kernel(const bf16* __restrict__ A, int lda,
+                                                                const bf16* __restrict__ W, int ldw,
+                                                                int M, int N, int K, int MT, int NT,
+                                                                Epi epi) {
+  extern __shared__ __attribute__((aligned(1024))) bf16 smem[];
+  static_assert(Cfg::kSmemBytes >= Cfg::kBM * Cfg::kBN * 4, "staging tile must fit in the ring");
+  static_assert(Cfg::kThreads >= Epi::kVec * Cfg::kBN / 4, "one thread per 4 entries of the column vectors");
+  float* rowstat = reinterpret_cast<float*>(reinterpret_cast<char*>(smem) + Cfg::kSmemBytes);   // [BM][2]
+  float* colv = rowstat + 2 * Cfg::kBM;                                                          // [kVec][BN]
+  int mt, nt;
+  if (!xcd_tile(MT, NT, mt, nt)) return;
+  const int m0 = mt * Cfg::kBM, n0 = nt * Cfg::kBN;
+  constexpr int CPR = Cfg::kBN / 8;                    // 8-column pieces per tile row
+  constexpr int RPI = Cfg::kThreads / CPR;             // tile rows covered by one pass of the block
+  constexpr int ITER = Cfg::kBM / RPI;
+  static_assert(Cfg::kThreads % CPR == 0 && Cfg::kBM % RPI == 0, "tile / thread count");
+  // a thread keeps its 8 columns in every pass: what depends on the column alone is computed once
+  const int tr = threadIdx.x / CPR, tc = (threadIdx.x % CPR) * 8;
+  const int n = n0 + tc;
+  // everything the epilogue reads is requested here and arrives under the K loop
+  LnRows<Cfg> rows;
+  rows.request(epi.ln_in, epi.chunks, m0, M);
+  constexpr int QPV = Cfg::kBN / 4;   // 16-byte pieces per column vector of the tile
+  const bool vec_thread = threadIdx.x < Epi::kVec * QPV;
+  f32x4 cvec = {0.f, 0.f, 0.f, 0.f};
+  if (vec_thread) cvec = *reinterpret_cast<const f32x4*>(epi.vec(threadIdx.x / QPV) + min(n0 + (int)(threadIdx.x % QPV) * 4, N - 4));
+  typename Epi::Pre pre[ITER];
+#pragma unroll
+  for (int it = 0; it < ITER; ++it) pre[it] = epi.fetch(min(m0 + it * RPI + tr, M - 1), min(n, N - 8));
+  GemmAcc<Cfg> acc;
+  gemm_mainloop<Cfg>(A, lda, W, ldw, M, N, 0, K / Cfg::GK, m0, n0, smem, acc);
+  float* cs = reinterpret_cast<float*>(smem);
+  gemm_foreach<Cfg>(acc, 0, 0, [&](int r, int c, float v) { cs[cs_off<Cfg::kBN>(r, c)] = v; });
+  rows.finish(epi.chunks, epi.identity(), rowstat);
+  if (vec_thread) *reinterpret_cast<f32x4*>(colv + threadIdx.x * 4) = cvec;
+  __syncthreads();
+  float cv[Epi::kVec][8];
+#pragma unroll
+  for (int i = 0; i < Epi::kVec; ++i) {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(colv + i * Cfg::kBN + tc);
+    const f32x4 b = *reinterpret_cast<const f32x4*>(colv + i * Cfg::kBN + tc + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { cv[i][e] = a[e]; cv[i][4 + e] = b[e]; }
+  }
+#pragma unroll
+  for (int it = 0; it < ITER; ++it) {
+    const int r = it * RPI + tr, m = m0 + r;
+    const float* src = cs + cs_off<Cfg::kBN>(r, tc);
+    const f32x4 a = *reinterpret_cast<const f32x4*>(src), b = *reinterpret_cast<const f32x4*>(src + 4);
+    const f32x2 st = *reinterpret_cast<const f32x2*>(rowstat + 2 * r);
+    const float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+    epi.store(m, n, m < M && n < N, v, pre[it], st[0], st[1], cv);
+  }
+}
+
+template <class Cfg, class Epi>
+static hipError_t launch_ln_cfg(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
+                                const Epi& epi) {
+  constexpr int kBytes = ln_smem_bytes<Cfg, Epi::kVec>();
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ln_kernel<Cfg, Epi>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int MT = (M + Cfg::kBM - 1) / Cfg::kBM, NT = (N + Cfg::kBN - 1) / Cfg::kBN;
+  hipLaunchKernelGGL((gemm_ln_kernel<Cfg, Epi>), dim3(xcd_grid(MT, NT)), dim3(Cfg::kThreads), kBytes, st,
+                     A, lda, W, K, M, N, K, MT, NT, epi);
+  return hipGetLastError();
+}
+template <class Epi>
+static hipError_t launch_ln(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
+                            const Epi& epi) {
+  if (M <= 0 || N <= 0) return hipSuccess;
+  const long wide_tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+  if (wide_tiles >= 200) return launch_ln_cfg<CfgWide>(st, A, lda, W, M, N, K, epi);
+  return launch_ln_cfg<CfgSmall>(st, A, lda, W, M, N, K, epi);
+}
+
+hipError_t gemm_ln_sum(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int d, int K,
+                       const float* vecs, const float* ln_in, bool has_prev, float* x, bf16* xg, float* ln_out) {
+  return launch_ln(st, A, lda, W, M, d, K,
+                   EpiLnSum{vecs, reinterpret_cast<const f32x2*>(ln_in), reinterpret_cast<f32x2*>(ln_out), x, xg, d,
+                            d / 64, has_prev ? 1 : 0});
+}
+hipError_t gemm_ln_bf16(hipStream_t st, const bf16* A, const bf16* W, int M, int N, int d, const LnFold& f,
+                        const float* ln_in, bf16* out, int ldo, bool relu) {
+  return launch_ln(st, A, d, W, M, N, d,
+                   EpiLnBf16{f.cs, f.bf, reinterpret_cast<const f32x2*>(ln_in), out, ldo, d / 64, relu ? 1 : 0});
+}
+hipError_t gemm_ln_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, int d, const LnFold& f,
+                              const float* ln_in, bf16* q_out, bf16* kc, bf16* vc, const int* row_b,
+                              const int* row_pos, int H, int Lcap) {
+  return launch_ln(st, A, d, W, M, 3 * d, d,
+                   EpiLnQkvAppend{f.cs, f.bf, reinterpret_cast<const f32x2*>(ln_in), d / 64, q_out, kc, vc, row_b,
+                                  row_pos, d, H, Lcap});
+}
+
+// cs[n] = sum_k g[k] W[n][k],  bf[n] = b[n] + sum_k beta[k] W[n][k]; one wave per column n
+__global__ __launch_bounds__(256) void ln_fold_kernel(const bf16* __restrict__ W, const bf16* __restrict__ g,
+                                                      const bf16* __restrict__ beta, const bf16* __restrict__ b,
+                                                      int N, int K, float* __restrict__ cs, float* __restrict__ bf) {
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (n >= N) return;
+  const bf16* w = W + (size_t)n * K;
+  float s = 0.f, t = 0.f;
+  for (int k = lane; k < K; k += 64) {
+    const float wk = (float)w[k];
+    s += (float)g[k] * wk;
+    t += (float)beta[k] * wk;
+  }
+  s = wave_sum(s);
+  t = wave_sum(t);
+  if (lane == 0) { cs[n] = s; bf[n] = (float)b[n] + t; }
+}
+hipError_t ln_fold(hipStream_t st, const bf16* W, const bf16* g, const bf16* beta, const bf16* b, int N, int K,
+                   const LnFold& out) {
+  hipLaunchKernelGGL(ln_fold_kernel, dim3((N + 3) / 4), dim3(256), 0, st, W, g, beta, b, N, K,
+                     const_cast<float*>(out.cs), const_cast<float*>(out.bf));
+  return hipGetLastError();
+}
+
+__global__ void ln_sum_vecs_kernel(const bf16* __restrict__ bias, const bf16* __restrict__ gp,
+                                   const bf16* __restrict__ bp, const bf16* __restrict__ gn, int d,
+                                   float* __restrict__ out) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= d) return;
+  out[n] = gp ? (float)gp[n] : 1.f;
+  out[d + n] = (float)bias[n] + (bp ? (float)bp[n] : 0.f);
+  out[2 * d + n] = (float)gn[n];
+}
+hipError_t ln_sum_vecs(hipStream_t st, const bf16* bias, const bf16* g_prev, const bf16* b_prev, const bf16* g_next,
+                       int d, float* out) {
+  hipLaunchKernelGGL(ln_sum_vecs_kernel, dim3((d + 255) / 256), dim3(256), 0, st, bias, g_prev, b_prev, g_next, d, out);
+  return hipGetLastError();
+}
+
 // ----------------------------------------------------------------------------- vocabulary
 // Rank test without a sort (paper Eq. 8): the draft is inside the top beta iff fewer than
 // beta logits are strictly larger than its own.  Its logit z_d is needed before the big

@@ -44,6 +44,35 @@ hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, in
 hipError_t gemm_enc_qkv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
                         const bf16* bias, bf16* q_out, bf16* ek, bf16* ev, int S, int H, int Scap);
 
+// ---- LayerNorm folded into the GEMM around it (post-LN blocks) ----
+// y = residual sum of a sub-layer, LN(y) = (y - mean) * rstd * g + beta.  The GEMM that forms y
+// also writes bf16(y * g) and, per row and 64-column chunk, the pair {sum, squared deviations
+// from the chunk mean} ("chunk pairs", fp32 [M][pitch][2], pitch = d/64 rounded up to even); the GEMMs that consume LN(y) multiply
+// bf16(y * g) and finish with rstd * (acc - mean * cs) + bf.
+struct LnFold {          // per consuming weight matrix W [N,d] with bias b, for one LayerNorm (g, beta)
+  const float* cs;       // [N]  sum_k g[k] W[n][k]
+  const float* bf;       // [N]  b[n] + sum_k beta[k] W[n][k]
+};
+hipError_t ln_fold(hipStream_t st, const bf16* W, const bf16* g, const bf16* beta, const bf16* b, int N, int K,
+                   const LnFold& out);
+// The column vectors of one producing GEMM, fp32 [3][d] in one piece: gain of the LayerNorm
+// pending on the residual (1 when g_prev is null), its shift (0 when null) + the GEMM's bias,
+// gain of the LayerNorm that follows.
+hipError_t ln_sum_vecs(hipStream_t st, const bf16* bias, const bf16* g_prev, const bf16* b_prev, const bf16* g_next,
+                       int d, float* out);
+// x [M,d] += A W^T + bias, where the residual already in x is LN_prev(x) if has_prev (chunk pairs of
+// x in ln_in; without has_prev ln_in is still read, and ignored: pass any chunk-pair buffer);
+// also xg = bf16(x_new * g_next) and the chunk pairs of x_new -> ln_out (a buffer other than ln_in).
+hipError_t gemm_ln_sum(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int d, int K,
+                       const float* vecs, const float* ln_in, bool has_prev, float* x, bf16* xg, float* ln_out);
+// out bf16 [M,ldo] = act(LN(y) W^T + b) from A = bf16(y * g) [M,d] and the chunk pairs of y
+hipError_t gemm_ln_bf16(hipStream_t st, const bf16* A, const bf16* W, int M, int N, int d, const LnFold& f,
+                        const float* ln_in, bf16* out, int ldo, bool relu);
+// gemm_qkv_append on LN(y)
+hipError_t gemm_ln_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, int d, const LnFold& f,
+                              const float* ln_in, bf16* q_out, bf16* kc, bf16* vc, const int* row_b,
+                              const int* row_pos, int H, int Lcap);
+
 // Vocabulary projection fused with per-row statistics.  zd_row [M] receives the logit of the
 // draft each row scores (-inf if none).  For every row and every 128-column vocabulary tile one
 // partial record of kPartF floats is written to part[M][n_tiles][kPartF]: {tile max, tile

@@ -224,11 +224,12 @@ def test_argument_errors_on_device():
 
 
 def test_small_batch_paths_agree(monkeypatch):
-    """The three implementations of a pass of at most 32 rows -- general kernels, fused
-    per-projection kernels (the default) and the single resident kernel (opt-in) -- give the
-    same logits to the last bit on the fused paths and match the oracle on all three; the
-    fused paths also cover d = 512 with two 16-row tiles (B = 2, k = 10) and d = 1024 with one and
-    two tiles."""
+    """The implementations of a pass of at most 32 rows -- general kernels with LayerNorm folded
+    into the GEMMs around it (what larger batches run), general kernels with LayerNorm as a
+    pass of its own, fused per-projection kernels (the default at this size) and the single
+    resident kernel (opt-in) -- all match the oracle, and the two fused paths give the same
+    logits to the last bit; the cases cover d = 128, d = 512 with two 16-row tiles (B = 2,
+    k = 10) and d = 1024 with one and two tiles."""
     import gpu_harness as gh
     case = cases.make_verify_case(small_desc(), seed=21, B=3, S=9, k=4, beta=3, tau=1.0, len_lo=0, len_hi=12,
                                   drafts="greedy", ragged_src=True, std=0.08)
@@ -246,9 +247,11 @@ def test_small_batch_paths_agree(monkeypatch):
     cases.run_oracle(case4)
     for cs in (case, case2, case3, case4):
         outs = {}
-        for tag, env in (("general", {"SPECDEC_NO_SKINNY": "1"}), ("fused", {}), ("resident", {"SPECDEC_RESIDENT": "1"})):
-            monkeypatch.delenv("SPECDEC_NO_SKINNY", raising=False)
-            monkeypatch.delenv("SPECDEC_RESIDENT", raising=False)
+        for tag, env in (("general", {"SPECDEC_NO_SKINNY": "1"}),
+                         ("general, separate LayerNorm", {"SPECDEC_NO_SKINNY": "1", "SPECDEC_NO_LN_FOLD": "1"}),
+                         ("fused", {}), ("resident", {"SPECDEC_RESIDENT": "1"})):
+            for name in ("SPECDEC_NO_SKINNY", "SPECDEC_RESIDENT", "SPECDEC_NO_LN_FOLD"):
+                monkeypatch.delenv(name, raising=False)
             for k_, v_ in env.items():
                 monkeypatch.setenv(k_, v_)
             ses = gh.open_verifier(cs)
