@@ -72,6 +72,19 @@ def test_small_several_tiles_ragged_tail():
     check_case(case, label="tiles")
 
 
+def test_odd_and_maximal_widths():
+    """Model widths that are no power of two, and the widest one allowed: d = 192 and d = 320 (3 and 5
+    heads: an odd number of 64-column LayerNorm chunks per row, F not a multiple of 128) and d = 2048
+    (32 heads, 32 chunks).  R = 55 / 24 rows: the general kernels with LayerNorm folded into the GEMMs."""
+    for d, H, F, B, k, seed, std in ((192, 3, 320, 5, 10, 31, 0.05), (320, 5, 448, 5, 10, 32, 0.04),
+                                     (2048, 32, 256, 4, 5, 33, 0.02)):
+        desc = synth.ModelDesc(0, 2, d, H, F, 777, 16, 48).resolved()
+        case = cases.make_verify_case(desc, seed=seed, B=B, S=11, k=k, beta=3, tau=1.0, len_lo=0, len_hi=20,
+                                      drafts="greedy", ragged_src=True, std=std)
+        ses, _ = check_case(case, label=f"d={d}")
+        ses.close()
+
+
 def test_kv_append_rollback_and_idempotence():
     import gpu_harness as gh
     from paper_2203_16487_amd import binding as sd
