@@ -257,12 +257,15 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
 
 inline hipStream_t S(void* s) { return static_cast<hipStream_t>(s); }
 
-// Embedding + every decoder layer over the R = B*T rows described by m.rm.
-// Leaves the final hidden states in m.x (fp32) and m.xb (bf16).
-int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
+// Embedding (unless the caller's row assembly has already written it to m.x / m.xb) + every
+// decoder layer over the R = B*T rows described by m.rm.  Leaves the final hidden states in
+// m.x (fp32) and m.xb (bf16); with slot_k > 0 (drafter pass) only those of the slot_k mask-slot
+// rows per sequence are needed, and they go to m.slots [B*slot_k][d] (bf16) instead.
+int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st, bool embedded = false, int slot_k = 0) {
   const int R = B * T, D = m.d.d_model, F = m.d.d_ffn, H = m.d.n_heads;
   const int Lcap = c->Lcap, Scap = c->Scap;
-  LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::embed_rows(st, m.rm.row_tok, m.rm.row_pos, m.embed, m.pe, m.x, m.xb, R, D));
+  if (!embedded)
+    LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::embed_rows(st, m.rm.row_tok, m.rm.row_pos, m.embed, m.pe, m.x, m.xb, R, D));
   // LayerNorm folded into the GEMMs on both sides of it: m.x holds the un-normalised sum, m.xb
   // that sum times the gain, `pend` the LayerNorm still to be applied to them.
   const bool fold = !c->no_ln_fold;
@@ -312,8 +315,12 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
       LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sum(m.att, D, L.cwo, m.folds[l].vco));
       LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_ln_bf16(st, m.xb, L.w1, R, F, D, m.folds[l].w1, pend, m.hid, F, true));
       LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sum(m.hid, F, L.w2, m.folds[l].v2));
-      if (l + 1 == m.d.dec_layers)   // the vocabulary projection reads the normalised rows themselves
-        LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln3g, L.ln3b, m.xb, R, D));
+      if (l + 1 == m.d.dec_layers) {   // the vocabulary projection reads the normalised rows themselves
+        if (slot_k > 0)
+          LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm_slots(st, m.x, L.ln3g, L.ln3b, m.slots, m.new_rows, B, T, slot_k, D));
+        else
+          LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln3g, L.ln3b, m.xb, R, D));
+      }
     } else {
       LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.cwo, R, D, D, L.cbo, m.x, m.x, D));
       LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln2g, L.ln2b, m.xb, R, D));
@@ -322,6 +329,7 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st) {
       LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln3g, L.ln3b, m.xb, R, D));
     }
   }
+  if (slot_k > 0 && !fold) HIPCHK(c, sd::gather_slots(st, m.xb, m.slots, m.new_rows, B, T, slot_k, D));
   return SPECDEC_OK;
 }
 
@@ -665,8 +673,9 @@ int specdec_prefill(specdec_ctx* c, specdec_role role, void* stream) {
   hipStream_t st = S(stream);
   const int T = c->Tmax;
   while (c->uncached_ub[role] > 0) {
-    HIPCHK(c, sd::assemble_stream(st, c->st, m.rm, role, c->B, T, 0, m.d.mask_id, m.d.pad_id, m.d.vocab, m.new_rows));
-    rc = decoder_layers(c, m, c->B, T, st);
+    LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::assemble_embed_stream(st, c->st, m.rm, role, c->B, T, 0, m.d.mask_id, m.d.pad_id, m.d.vocab,
+                                        m.new_rows, m.embed, m.pe, m.x, m.xb, m.d.d_model));
+    rc = decoder_layers(c, m, c->B, T, st, true);
     if (rc) return rc;
     HIPCHK(c, sd::advance_cached(st, c->st, role, m.new_rows, c->B));
     c->uncached_ub[role] -= T;
@@ -693,15 +702,13 @@ int specdec_draft(specdec_ctx* c, int32_t k, int32_t* draft, void* stream) {
     ub = 1;
   }
   const int B = c->B, T = ub + k;
-  HIPCHK(c, sd::assemble_stream(st, c->st, m.rm, SPECDEC_DRAFTER, B, T, k, m.d.mask_id, m.d.pad_id, m.d.vocab, m.new_rows));
-  rc = decoder_layers(c, m, B, T, st);
+  LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::assemble_embed_stream(st, c->st, m.rm, SPECDEC_DRAFTER, B, T, k, m.d.mask_id, m.d.pad_id,
+                                      m.d.vocab, m.new_rows, m.embed, m.pe, m.x, m.xb, m.d.d_model));
+  rc = decoder_layers(c, m, B, T, st, true, k);
   if (rc) return rc;
-  HIPCHK(c, sd::gather_slots(st, m.xb, m.slots, m.new_rows, B, T, k, m.d.d_model));
   const int R = B * k, n_tiles = (m.d.vocab + 127) / 128;
-  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, m.d.d_model, nullptr, m.zd, m.part, nullptr));
-  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
-  HIPCHK(c, sd::write_drafts(st, m.row_stats, c->st, B, k, m.d.pad_id, draft));
-  HIPCHK(c, sd::advance_cached(st, c->st, SPECDEC_DRAFTER, m.new_rows, B));
+  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, m.d.d_model, nullptr, nullptr, m.part, nullptr));
+  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_drafts(st, m.part, n_tiles, m.row_stats, c->st, B, k, m.d.pad_id, m.new_rows, draft));
   c->uncached_ub[1] = 0;
   c->trusted[1] = false;
   return SPECDEC_OK;
@@ -720,9 +727,15 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
   if (c->uncached_ub[0] > 0 && !c->trusted[0]) return fail(c, SPECDEC_ERR_BAD_STATE, "verifier cache does not cover the stream: call specdec_prefill or specdec_load_cache");
   hipStream_t st = S(stream);
   const int B = c->B, T = k + 1, R = B * T;
-  LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::assemble_verify(st, c->st, m.rm, draft, B, k, m.d.vocab));
+  const bool small = skinny_ok(c, m, R, T);   // the small-batch kernels embed the rows themselves
+  if (small)
+    LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::assemble_verify(st, c->st, m.rm, draft, B, k, m.d.vocab));
+  else
+    LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::assemble_embed_verify(st, c->st, m.rm, draft, B, k, m.d.vocab, m.embed, m.pe, m.x, m.xb,
+                                        m.d.d_model));
   const unsigned* failed = nullptr;
-  if (skinny_ok(c, m, R, T) && c->resident) {
+  int n_tiles = (m.d.vocab + 63) / 64;   // per-row partial records of the vocabulary kernel that ran
+  if (small && c->resident) {
     sd::RsArgs a{};
     a.R = R; a.T = T; a.B = B; a.H = m.d.n_heads; a.V = m.d.vocab; a.Lcap = c->Lcap; a.Scap = c->Scap;
     a.n_layers = m.d.dec_layers; a.layers = m.rs_layers;
@@ -736,24 +749,20 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
     a.seq = m.rs_seq;
     m.rs_parity ^= 1;
     LAUNCH(c, SPECDEC_KIND_RESIDENT, st, sd::resident_verify(st, a, m.d.d_model, m.d.d_ffn));
-    const int n_tiles = (m.d.vocab + 63) / 64;
-    LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
     failed = m.rs_bar + 16;
-  } else if (skinny_ok(c, m, R, T)) {
+  } else if (small) {
     sd::SkSrc fin{};
     rc = decoder_layers_skinny(c, m, B, T, st, &fin);
     if (rc) return rc;
-    const int n_tiles = (m.d.vocab + 63) / 64;
     LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::skinny_vocab(st, fin, R, m.d.d_model, m.embed, m.d.vocab, m.rm.row_draft, m.zd, m.part, logits));
-    LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
   } else {
-    rc = decoder_layers(c, m, B, T, st);
+    rc = decoder_layers(c, m, B, T, st, true);
     if (rc) return rc;
-    const int n_tiles = (m.d.vocab + 127) / 128;
+    n_tiles = (m.d.vocab + 127) / 128;
     LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.zd, m.part, logits));
-    LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_rows(st, m.part, m.zd, n_tiles, R, m.row_stats));
   }
-  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::accept_rows(st, m.row_stats, c->st, B, k, beta, tau, m.d.pad_id, accept_len, next_token, failed));
+  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_accept(st, m.part, m.zd, n_tiles, m.row_stats, c->st, B, k, beta, tau, m.d.pad_id,
+                                      accept_len, next_token, failed));
   c->last_T = k + 1;
   return SPECDEC_OK;
 }

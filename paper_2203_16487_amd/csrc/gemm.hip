@@ -685,7 +685,7 @@ __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* _
   const int tid = threadIdx.x;
   const int row = tid >> 1, half = tid & 1;
   const int m = m0 + row;
-  const float zd = (m < M) ? zd_row[m] : kNegInf;   // -inf on rows that score no draft: count unused
+  const float zd = (zd_row && m < M) ? zd_row[m] : kNegInf;   // -inf on rows that score no draft: count unused
   float best = kNegInf;
   int besti = 0x7fffffff, cnt = 0;
   const bool full = n0 + 128 <= V;
@@ -742,15 +742,12 @@ hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int 
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  if (row_draft) {
+  // without row_draft no row scores a draft (drafter pass): every count is taken against -inf, unused
+  if (row_draft)
     hipLaunchKernelGGL(draft_logit_kernel, dim3((M + 31) / 32), dim3(64), 0, st, A, E, M, V, K, row_draft, zd_row);
-  } else {   // no row scores a draft (drafter pass): every count is taken against -inf and unused
-    hipError_t e = fill_i32(st, reinterpret_cast<int*>(zd_row), (int)0xff800000u, M);
-    if (e != hipSuccess) return e;
-  }
   const int MT = (M + 127) / 128, NT = (V + 127) / 128;
   hipLaunchKernelGGL(vocab_kernel, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
-                     A, E, M, V, K, MT, NT, zd_row, part, logits);
+                     A, E, M, V, K, MT, NT, row_draft ? zd_row : nullptr, part, logits);
   return hipGetLastError();
 }
 

@@ -78,7 +78,7 @@ hipError_t gemm_ln_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int 
 // partial record of kPartF floats is written to part[M][n_tiles][kPartF]: {tile max, tile
 // arg-max (int bits), sum exp(z - tile max), number of tile logits > zd_row (int bits)}.
 // logits (optional, fp32 [M, V]) receives the full rows.  row_draft may be null: no row scores a
-// draft (the pre-pass is skipped, zd_row is filled with -inf).
+// draft (the pre-pass is skipped, zd_row is left untouched and may be null; counts are against -inf).
 constexpr int kPartF = 4;
 constexpr int kRowStats = 8;   // floats per row of merged statistics
 hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int V, int K,
@@ -164,6 +164,9 @@ hipError_t embed_rows(hipStream_t st, const int* tok, const int* pos, const bf16
 // x <- LayerNorm(x) * g + b in place (fp32), xb <- bf16(x)
 hipError_t layer_norm(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R,
                       int d);
+// dst [B*k][d] bf16 <- LayerNorm of the mask-slot rows b*T + new_rows[b] + s of x (x unchanged)
+hipError_t layer_norm_slots(hipStream_t st, const float* x, const bf16* g, const bf16* b, bf16* dst,
+                            const int* new_rows, int B, int T, int k, int d);
 hipError_t fill_i32(hipStream_t st, int* p, int v, long n);
 
 struct SeqState {       // device arrays of the bound state buffer, all [max_batch] unless noted
@@ -184,21 +187,30 @@ hipError_t assemble_verify(hipStream_t st, const SeqState& s, const RowMap& rm, 
 // rows of a prefill pass (n_mask = 0) or of a drafter pass (stream rows + n_mask [MASK] slots)
 hipError_t assemble_stream(hipStream_t st, const SeqState& s, const RowMap& rm, int role, int B, int T,
                            int n_mask, int mask_id, int pad_id, int V, int* new_rows);
+// assemble_verify / assemble_stream and embed_rows of the same rows in one launch
+hipError_t assemble_embed_verify(hipStream_t st, const SeqState& s, const RowMap& rm, const int* draft, int B, int k,
+                                 int V, const bf16* E, const float* pe, float* x, bf16* xb, int d);
+hipError_t assemble_embed_stream(hipStream_t st, const SeqState& s, const RowMap& rm, int role, int B, int T,
+                                 int n_mask, int mask_id, int pad_id, int V, int* new_rows, const bf16* E,
+                                 const float* pe, float* x, bf16* xb, int d);
 hipError_t advance_cached(hipStream_t st, const SeqState& s, int role, const int* new_rows, int B);
 hipError_t gather_slots(hipStream_t st, const bf16* xb, bf16* dst, const int* new_rows, int B, int T,
                         int k, int d);
-hipError_t write_drafts(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k,
-                        int pad_id, int* draft);
 hipError_t encoder_rows(hipStream_t st, const int* src, int* tok, int* pos, int B, int S, int V);
 // merge the vocabulary partials of every row into row_stats [R][kRowStats] =
 // {max, arg-max, log-sum-exp, draft logit, number of logits above the draft's, 0, 0, 0}
 hipError_t merge_rows(hipStream_t st, const float* part, const float* zd_row, int n_tiles, int R,
                       float* row_stats);
-// top-beta / tau rule on the merged rows and the leading-accept scan per sequence
+// merge_rows of the B*(k+1) rows of a verification pass, then the top-beta / tau rule on them and
+// the leading-accept scan per sequence, in one launch (k + 1 <= 32)
 // (fail: optional device flag; when set every sequence reports accept_len -1, next_token pad)
-hipError_t accept_rows(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k,
-                       int beta, float tau, int pad_id, int* accept_len, int* next_token,
-                       const unsigned* fail = nullptr);
+hipError_t merge_accept(hipStream_t st, const float* part, const float* zd_row, int n_tiles, float* row_stats,
+                        const SeqState& s, int B, int k, int beta, float tau, int pad_id, int* accept_len,
+                        int* next_token, const unsigned* fail = nullptr);
+// merge_rows of the B*k mask-slot rows of a drafter pass, draft[b][s] = their arg-max (pad for
+// finished sequences), and cached[drafter][b] += new_rows[b]
+hipError_t merge_drafts(hipStream_t st, const float* part, int n_tiles, float* row_stats, const SeqState& s, int B,
+                        int k, int pad_id, const int* new_rows, int* draft);
 hipError_t commit_rows(hipStream_t st, const SeqState& s, const int* accept_len,
                        const int* next_token, int B, int eos_id, int* n_active);
 hipError_t begin_state(hipStream_t st, const SeqState& s, int B, int max_new, int max_tgt,

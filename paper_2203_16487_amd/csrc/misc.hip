@@ -25,18 +25,33 @@ hipError_t build_pos_table(hipStream_t st, float* pe, int n_pos, int d) {
 
 // ----------------------------------------------------------------------------- embedding
 // x[r] = E[tok[r]] * sqrt(d) + PE[pos[r]]  (fp32) and its bf16 copy
-__global__ void embed_kernel(const int* __restrict__ tok, const int* __restrict__ pos,
-                             const bf16* __restrict__ E, const float* __restrict__ pe,
-                             float* __restrict__ x, bf16* __restrict__ xb, int R, int d, float scale) {
-  int r = blockIdx.x;
-  if (r >= R) return;
-  const bf16* e = E + (size_t)tok[r] * d;
-  const float* p = pe + (size_t)pos[r] * d;
-  for (int c = threadIdx.x; c < d; c += blockDim.x) {
-    float v = (float)e[c] * scale + p[c];
-    x[(size_t)r * d + c] = v;
-    xb[(size_t)r * d + c] = (bf16)v;
+// One block per row, 8 columns per thread and step (d % 64 == 0).
+__device__ __forceinline__ void embed_row(const bf16* __restrict__ e, const float* __restrict__ p,
+                                          float* __restrict__ xr, bf16* __restrict__ xbr, int d, float scale) {
+  for (int c = threadIdx.x * 8; c < d; c += blockDim.x * 8) {
+    const bf16x8 ev = *reinterpret_cast<const bf16x8*>(e + c);
+    const f32x4 p0 = *reinterpret_cast<const f32x4*>(p + c), p1 = *reinterpret_cast<const f32x4*>(p + c + 4);
+    f32x4 v0, v1;
+    bf16x8 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v0[i] = (float)ev[i] * scale + p0[i];
+      v1[i] = (float)ev[4 + i] * scale + p1[i];
+      o[i] = (bf16)v0[i];
+      o[4 + i] = (bf16)v1[i];
+    }
+    *reinterpret_cast<f32x4*>(xr + c) = v0;
+    *reinterpret_cast<f32x4*>(xr + c + 4) = v1;
+    *reinterpret_cast<bf16x8*>(xbr + c) = o;
   }
+}
+__global__ __launch_bounds__(128) void embed_kernel(const int* __restrict__ tok, const int* __restrict__ pos,
+                                                    const bf16* __restrict__ E, const float* __restrict__ pe,
+                                                    float* __restrict__ x, bf16* __restrict__ xb, int R, int d,
+                                                    float scale) {
+  const int r = blockIdx.x;
+  if (r >= R) return;
+  embed_row(E + (size_t)tok[r] * d, pe + (size_t)pos[r] * d, x + (size_t)r * d, xb + (size_t)r * d, d, scale);
 }
 hipError_t embed_rows(hipStream_t st, const int* tok, const int* pos, const bf16* E,
                       const float* pe, float* x, bf16* xb, int R, int d) {
@@ -80,6 +95,57 @@ __global__ __launch_bounds__(256) void ln_kernel(float* __restrict__ x, const bf
     xb[(size_t)r * d + c] = (bf16)y;
   }
 }
+// The same on the drafter's mask-slot rows only: output row o = b*k + s is the LayerNorm of row
+// b*T + new_rows[b] + s of x, written (bf16 only) to the dense [B*k][d] operand of the
+// vocabulary kernel.
+template <int PER>
+__global__ __launch_bounds__(256) void ln_slots_kernel(const float* __restrict__ x, const bf16* __restrict__ g,
+                                                       const bf16* __restrict__ bta, bf16* __restrict__ dst,
+                                                       const int* __restrict__ new_rows, int B, int T, int k) {
+  constexpr int d = 64 * PER;
+  const int lane = threadIdx.x & 63;
+  const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (o >= B * k) return;
+  const int b = o / k, sl = o - b * k;
+  const float* xr = x + (size_t)(b * T + new_rows[b] + sl) * d;
+  float v[PER], gg[PER], bb[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) v[i] = xr[i * 64 + lane];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) { gg[i] = (float)g[i * 64 + lane]; bb[i] = (float)bta[i * 64 + lane]; }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) s += v[i];
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) { float t = v[i] - mean; q += t * t; }
+  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+#pragma unroll
+  for (int i = 0; i < PER; ++i)
+    dst[(size_t)o * d + i * 64 + lane] = (bf16)((v[i] - mean) * rstd * gg[i] + bb[i]);
+}
+template <int PER>
+static hipError_t ln_slots_launch(hipStream_t st, const float* x, const bf16* g, const bf16* b, bf16* dst,
+                                  const int* new_rows, int B, int T, int k) {
+  hipLaunchKernelGGL(ln_slots_kernel<PER>, dim3((B * k + 3) / 4), dim3(256), 0, st, x, g, b, dst, new_rows, B, T, k);
+  return hipGetLastError();
+}
+hipError_t layer_norm_slots(hipStream_t st, const float* x, const bf16* g, const bf16* b, bf16* dst,
+                            const int* new_rows, int B, int T, int k, int d) {
+  if (B <= 0 || k <= 0) return hipSuccess;
+  switch (d / 64) {
+#define SD_LN_CASE(P) case P: return ln_slots_launch<P>(st, x, g, b, dst, new_rows, B, T, k);
+    SD_LN_CASE(1) SD_LN_CASE(2) SD_LN_CASE(3) SD_LN_CASE(4) SD_LN_CASE(5) SD_LN_CASE(6) SD_LN_CASE(7) SD_LN_CASE(8)
+    SD_LN_CASE(9) SD_LN_CASE(10) SD_LN_CASE(11) SD_LN_CASE(12) SD_LN_CASE(13) SD_LN_CASE(14) SD_LN_CASE(15)
+    SD_LN_CASE(16) SD_LN_CASE(17) SD_LN_CASE(18) SD_LN_CASE(19) SD_LN_CASE(20) SD_LN_CASE(21) SD_LN_CASE(22)
+    SD_LN_CASE(23) SD_LN_CASE(24) SD_LN_CASE(25) SD_LN_CASE(26) SD_LN_CASE(27) SD_LN_CASE(28) SD_LN_CASE(29)
+    SD_LN_CASE(30) SD_LN_CASE(31) SD_LN_CASE(32)
+#undef SD_LN_CASE
+    default: return hipErrorInvalidValue;
+  }
+}
+
 template <int PER>
 static hipError_t ln_launch(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R) {
   hipLaunchKernelGGL(ln_kernel<PER>, dim3((R + 3) / 4), dim3(256), 0, st, x, g, b, xb, R);
@@ -131,6 +197,36 @@ hipError_t assemble_verify(hipStream_t st, const SeqState& s, const RowMap& rm, 
   hipLaunchKernelGGL(assemble_verify_kernel, blocks_for((long)B * (k + 1), 128), dim3(128), 0, st, s, rm, draft, B, k, V);
   return hipGetLastError();
 }
+// The same, one block per row, followed by the row's embedding (embed_rows).
+__global__ __launch_bounds__(128) void assemble_embed_verify_kernel(SeqState s, RowMap rm,
+                                                                    const int* __restrict__ draft, int B, int k, int V,
+                                                                    const bf16* __restrict__ E,
+                                                                    const float* __restrict__ pe,
+                                                                    float* __restrict__ x, bf16* __restrict__ xb, int d,
+                                                                    float scale) {
+  const int idx = blockIdx.x, T = k + 1;
+  const int b = idx / T, i = idx - b * T;
+  const int j = s.len[b];
+  int tok = (i == 0) ? s.tokens[(size_t)b * s.tok_pitch + j] : draft[b * k + i - 1];
+  tok = min(max(tok, 0), V - 1);
+  if (threadIdx.x == 0) {
+    rm.row_b[idx] = b;
+    rm.row_pos[idx] = j + i;
+    rm.row_tok[idx] = tok;
+    rm.row_lim[idx] = j + i + 1;
+    rm.row_draft[idx] = (i < k) ? draft[b * k + i] : -1;
+    if (i < k) s.last_draft[b * s.k_max + i] = draft[b * k + i];
+    if (i == 0) rm.seq_rows[b] = T;
+  }
+  embed_row(E + (size_t)tok * d, pe + (size_t)(j + i) * d, x + (size_t)idx * d, xb + (size_t)idx * d, d, scale);
+}
+hipError_t assemble_embed_verify(hipStream_t st, const SeqState& s, const RowMap& rm, const int* draft, int B, int k,
+                                 int V, const bf16* E, const float* pe, float* x, bf16* xb, int d) {
+  if (B <= 0) return hipSuccess;
+  hipLaunchKernelGGL(assemble_embed_verify_kernel, dim3(B * (k + 1)), dim3(128), 0, st, s, rm, draft, B, k, V, E, pe,
+                     x, xb, d, sqrtf((float)d));
+  return hipGetLastError();
+}
 
 // ----------------------------------------------------------------------------- prefill / draft rows
 // One thread per sequence writes the T row slots of its sequence.
@@ -167,6 +263,43 @@ hipError_t assemble_stream(hipStream_t st, const SeqState& s, const RowMap& rm, 
                      mask_id, pad_id, V, new_rows);
   return hipGetLastError();
 }
+// The same, one block per row, followed by the row's embedding (embed_rows).
+__global__ __launch_bounds__(128) void assemble_embed_stream_kernel(SeqState s, RowMap rm, int role, int B, int T,
+                                                                    int n_mask, int mask_id, int pad_id, int V,
+                                                                    int* __restrict__ new_rows,
+                                                                    const bf16* __restrict__ E,
+                                                                    const float* __restrict__ pe,
+                                                                    float* __restrict__ x, bf16* __restrict__ xb, int d,
+                                                                    float scale) {
+  const int r = blockIdx.x;
+  const int b = r / T, i = r - b * T;
+  const int c0 = s.cached[role][b];
+  const int target = s.len[b] + (role == 1 ? 1 : 0);
+  const int n = max(0, min(target - c0, T - n_mask));
+  const bool masks = n_mask > 0 && c0 + n == target;
+  int rb = -1, pos = 0, tok = pad_id, lim = 0;
+  if (i < n) {
+    rb = b; pos = c0 + i; tok = min(max(s.tokens[(size_t)b * s.tok_pitch + c0 + i], 0), V - 1); lim = c0 + i + 1;
+  } else if (masks && i < n + n_mask) {
+    rb = b; pos = c0 + i; tok = mask_id; lim = c0 + n + n_mask;
+  }
+  if (threadIdx.x == 0) {
+    rm.row_b[r] = rb; rm.row_pos[r] = pos; rm.row_tok[r] = tok; rm.row_lim[r] = lim; rm.row_draft[r] = -1;
+    if (i == 0) {
+      rm.seq_rows[b] = n + (masks ? n_mask : 0);
+      new_rows[b] = n;
+    }
+  }
+  embed_row(E + (size_t)tok * d, pe + (size_t)pos * d, x + (size_t)r * d, xb + (size_t)r * d, d, scale);
+}
+hipError_t assemble_embed_stream(hipStream_t st, const SeqState& s, const RowMap& rm, int role, int B, int T,
+                                 int n_mask, int mask_id, int pad_id, int V, int* new_rows, const bf16* E,
+                                 const float* pe, float* x, bf16* xb, int d) {
+  if (B <= 0 || T <= 0) return hipSuccess;
+  hipLaunchKernelGGL(assemble_embed_stream_kernel, dim3(B * T), dim3(128), 0, st, s, rm, role, B, T, n_mask, mask_id,
+                     pad_id, V, new_rows, E, pe, x, xb, d, sqrtf((float)d));
+  return hipGetLastError();
+}
 
 __global__ void advance_cached_kernel(SeqState s, int role, const int* __restrict__ new_rows, int B) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
@@ -191,19 +324,6 @@ hipError_t gather_slots(hipStream_t st, const bf16* xb, bf16* dst, const int* ne
   return hipGetLastError();
 }
 
-// draft[b][s] = arg-max of slot row b*k + s (pad for finished sequences)
-__global__ void write_drafts_kernel(const float* __restrict__ row_stats, SeqState s, int B, int k, int pad_id,
-                                    int* __restrict__ draft) {
-  const int o = blockIdx.x * blockDim.x + threadIdx.x;
-  if (o >= B * k) return;
-  const int b = o / k;
-  draft[o] = s.finished[b] ? pad_id : (int)row_stats[(size_t)o * kRowStats + 1];
-}
-hipError_t write_drafts(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k, int pad_id, int* draft) {
-  hipLaunchKernelGGL(write_drafts_kernel, blocks_for((long)B * k, 128), dim3(128), 0, st, row_stats, s, B, k, pad_id, draft);
-  return hipGetLastError();
-}
-
 // encoder rows: row b*S + s feeds src[b][s] (clamped into the vocabulary) at position s
 __global__ void encoder_rows_kernel(const int* __restrict__ src, int* __restrict__ tok, int* __restrict__ pos,
                                     long n, int S, int V) {
@@ -222,12 +342,11 @@ hipError_t encoder_rows(hipStream_t st, const int* src, int* tok, int* pos, int 
 // Stage 1, one wave per row: merge the per-tile partials of the vocabulary kernel into
 //   m = max logit, arg-max = lowest column among maxima, LSE, and the number of logits that
 //   are strictly larger than the logit z_d of the draft this row scores.
-__global__ __launch_bounds__(64) void merge_rows_kernel(const float* __restrict__ part,
-                                                        const float* __restrict__ zd_row, int n_tiles, int R,
-                                                        float* __restrict__ row_stats) {
-  const int r = blockIdx.x, lane = threadIdx.x;
-  if (r >= R) return;
-  const float* pr = part + (size_t)r * n_tiles * kPartF;
+struct RowMerge {
+  float m, lse;
+  int arg, cnt;
+};
+__device__ __forceinline__ RowMerge merge_row(const float* __restrict__ pr, int n_tiles, int lane) {
   float m = kNegInf;
   int am = 0x7fffffff, cnt = 0;
   for (int t = lane; t < n_tiles; t += 64) {
@@ -250,13 +369,20 @@ __global__ __launch_bounds__(64) void merge_rows_kernel(const float* __restrict_
     se += p[2] * __expf(p[0] - gm);
   }
   se = wave_sum(se);
-  if (lane == 0) {
-    f32x4 a = {gm, (float)cand, gm + __logf(se), zd_row[r]};
-    f32x4 b = {(float)cnt, 0.f, 0.f, 0.f};
-    float* rs = row_stats + (size_t)r * kRowStats;
-    *reinterpret_cast<f32x4*>(rs) = a;
-    *reinterpret_cast<f32x4*>(rs + 4) = b;
-  }
+  return RowMerge{gm, gm + __logf(se), cand, cnt};
+}
+__device__ __forceinline__ void store_row_stats(float* rs, const RowMerge& r, float zd) {
+  *reinterpret_cast<f32x4*>(rs) = f32x4{r.m, (float)r.arg, r.lse, zd};
+  *reinterpret_cast<f32x4*>(rs + 4) = f32x4{(float)r.cnt, 0.f, 0.f, 0.f};
+}
+
+__global__ __launch_bounds__(64) void merge_rows_kernel(const float* __restrict__ part,
+                                                        const float* __restrict__ zd_row, int n_tiles, int R,
+                                                        float* __restrict__ row_stats) {
+  const int r = blockIdx.x, lane = threadIdx.x;
+  if (r >= R) return;
+  const RowMerge res = merge_row(part + (size_t)r * n_tiles * kPartF, n_tiles, lane);
+  if (lane == 0) store_row_stats(row_stats + (size_t)r * kRowStats, res, zd_row ? zd_row[r] : kNegInf);
 }
 hipError_t merge_rows(hipStream_t st, const float* part, const float* zd_row, int n_tiles, int R, float* row_stats) {
   if (R <= 0) return hipSuccess;
@@ -264,32 +390,75 @@ hipError_t merge_rows(hipStream_t st, const float* part, const float* zd_row, in
   return hipGetLastError();
 }
 
-// Stage 2, one thread per sequence (paper Sec. 3.2).  With z_d the draft's logit on its row:
+// Stage 2, per sequence (paper Sec. 3.2).  With z_d the draft's logit on its row:
 // Eq. 8:  log P(draft) >= log P(beta-th ranked)   <=>  #{v : z_v > z_d} < beta
 // Eq. 9:  log P(top-1) - log P(draft) <= tau      <=>  m - z_d <= tau
 // (log-softmax subtracts the same LSE from every logit of the row; a draft tied with the
 // beta-th score passes, as ">=" says).  a = number of leading rows that pass; next = arg-max
 // of row a.
-__global__ void accept_kernel(const float* __restrict__ row_stats, SeqState s, int B, int k, int beta, float tau,
-                              int pad_id, int* __restrict__ accept_len, int* __restrict__ next_token,
-                              const unsigned* __restrict__ fail) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= B) return;
-  if (fail && *fail) { accept_len[b] = -1; next_token[b] = pad_id; return; }
+//
+// Both stages in one launch: a block per sequence, its 16 waves merge the k + 1 <= 32 rows (two
+// rounds at most), then one thread scans them.
+constexpr int kMergeWaves = 16;
+__global__ __launch_bounds__(64 * kMergeWaves) void merge_accept_kernel(const float* __restrict__ part,
+                                                           const float* __restrict__ zd_row, int n_tiles,
+                                                           float* __restrict__ row_stats, SeqState s, int k,
+                                                           int beta, float tau, int pad_id,
+                                                           int* __restrict__ accept_len,
+                                                           int* __restrict__ next_token,
+                                                           const unsigned* __restrict__ fail) {
+  __shared__ float sm[32], szd[32];
+  __shared__ int sarg[32], scnt[32];
+  const int b = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int T = k + 1;
-  int a = 0;
-  for (; a < k; ++a) {
-    const float* rs = row_stats + (size_t)(b * T + a) * kRowStats;
-    if (!(rs[4] < (float)beta && rs[0] - rs[3] <= tau)) break;
+  for (int i = wave; i < T; i += kMergeWaves) {
+    const int r = b * T + i;
+    const RowMerge res = merge_row(part + (size_t)r * n_tiles * kPartF, n_tiles, lane);
+    if (lane == 0) {
+      const float zd = zd_row[r];
+      store_row_stats(row_stats + (size_t)r * kRowStats, res, zd);
+      sm[i] = res.m; szd[i] = zd; sarg[i] = res.arg; scnt[i] = res.cnt;
+    }
   }
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  if (fail && *fail) { accept_len[b] = -1; next_token[b] = pad_id; return; }
+  int a = 0;
+  for (; a < k; ++a)
+    if (!(scnt[a] < beta && sm[a] - szd[a] <= tau)) break;
   const bool fin = s.finished[b] != 0;
   accept_len[b] = fin ? 0 : a;
-  next_token[b] = fin ? pad_id : (int)row_stats[(size_t)(b * T + a) * kRowStats + 1];
+  next_token[b] = fin ? pad_id : sarg[a];
 }
-hipError_t accept_rows(hipStream_t st, const float* row_stats, const SeqState& s, int B, int k, int beta,
-                       float tau, int pad_id, int* accept_len, int* next_token, const unsigned* fail) {
-  hipLaunchKernelGGL(accept_kernel, blocks_for(B, 64), dim3(64), 0, st, row_stats, s, B, k, beta, tau, pad_id,
-                     accept_len, next_token, fail);
+hipError_t merge_accept(hipStream_t st, const float* part, const float* zd_row, int n_tiles, float* row_stats,
+                        const SeqState& s, int B, int k, int beta, float tau, int pad_id, int* accept_len,
+                        int* next_token, const unsigned* fail) {
+  if (B <= 0) return hipSuccess;
+  if (k + 1 > 32) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(merge_accept_kernel, dim3(B), dim3(64 * kMergeWaves), 0, st, part, zd_row, n_tiles, row_stats, s, k, beta,
+                     tau, pad_id, accept_len, next_token, fail);
+  return hipGetLastError();
+}
+
+// Drafter: merge the slot rows, draft[b][s] = arg-max of slot row b*k + s (pad for finished
+// sequences); the first B blocks also advance the drafter's cached length by the stream rows
+// this pass ingested.
+__global__ __launch_bounds__(64) void merge_drafts_kernel(const float* __restrict__ part, int n_tiles,
+                                                          float* __restrict__ row_stats, SeqState s, int B, int k,
+                                                          int pad_id, const int* __restrict__ new_rows,
+                                                          int* __restrict__ draft) {
+  const int o = blockIdx.x, lane = threadIdx.x;
+  const RowMerge res = merge_row(part + (size_t)o * n_tiles * kPartF, n_tiles, lane);
+  if (lane != 0) return;
+  store_row_stats(row_stats + (size_t)o * kRowStats, res, kNegInf);
+  draft[o] = s.finished[o / k] ? pad_id : res.arg;
+  if (o < B) s.cached[1][o] += new_rows[o];
+}
+hipError_t merge_drafts(hipStream_t st, const float* part, int n_tiles, float* row_stats, const SeqState& s, int B,
+                        int k, int pad_id, const int* new_rows, int* draft) {
+  if (B <= 0 || k <= 0) return hipSuccess;
+  hipLaunchKernelGGL(merge_drafts_kernel, dim3(B * k), dim3(64), 0, st, part, n_tiles, row_stats, s, B, k, pad_id,
+                     new_rows, draft);
   return hipGetLastError();
 }
 
