@@ -473,25 +473,34 @@ __global__ void commit_kernel(SeqState s, const int* __restrict__ accept_len, co
   __syncthreads();
   int mine = 0;
   for (int b = threadIdx.x; b < B; b += blockDim.x) {
-    if (!s.finished[b]) {
-      int a = accept_len[b];
-      if (a < 0) { ++mine; continue; }   // verification reported a failure: nothing to commit
-      a = min(a, s.k_max);
-      int j = s.len[b];
-      const int cap = s.cap[b];
-      int* u = s.tokens + (size_t)b * s.tok_pitch;
-      int fin = 0;
-      for (int i = 0; i <= a && !fin; ++i) {
-        if (j >= cap) { fin = 1; break; }
-        int t = (i < a) ? s.last_draft[b * s.k_max + i] : next_token[b];
-        u[++j] = t;
-        if (t == eos_id || j >= cap) fin = 1;
+    // two memory round trips per sequence: the scalars, then every token that may be appended
+    const int fin0 = s.finished[b], a0 = accept_len[b], j0 = s.len[b], cap = s.cap[b], nt = next_token[b];
+    if (fin0) continue;
+    if (a0 < 0) { ++mine; continue; }   // verification reported a failure: nothing to commit
+    const int a = min(a0, s.k_max);
+    int t[32];                           // k_max <= 31
+#pragma unroll
+    for (int i = 0; i < 31; ++i) t[i] = (i < a) ? s.last_draft[b * s.k_max + i] : 0;
+    t[31] = 0;
+    int j = j0;
+    int* u = s.tokens + (size_t)b * s.tok_pitch;
+    int fin = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      if (i <= a && !fin) {
+        if (j >= cap) {
+          fin = 1;
+        } else {
+          const int tok = (i < a) ? t[i] : nt;
+          u[++j] = tok;
+          if (tok == eos_id || j >= cap) fin = 1;
+        }
       }
-      s.len[b] = j;
-      s.cached[0][b] = j;   // the verifier's rows of the kept tokens are now valid cache
-      s.finished[b] = fin;
-      if (!fin) ++mine;
     }
+    s.len[b] = j;
+    s.cached[0][b] = j;   // the verifier's rows of the kept tokens are now valid cache
+    s.finished[b] = fin;
+    if (!fin) ++mine;
   }
   if (mine) atomicAdd(&active, mine);
   __syncthreads();
