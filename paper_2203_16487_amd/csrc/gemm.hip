@@ -666,6 +666,9 @@ __device__ __forceinline__ int vs_off(int row, int ch) {
   return row * 128 + (((ch & 16) + ((ch & 15) ^ (row & 15) ^ ((ch >> 4) << 3))) << 2);
 }
 
+// ARGMAX: rows that score no draft and whose log-sum-exp nobody reads (the drafter's slots):
+// only max / arg-max are formed; the record's sum is 0 and its count 0.
+template <bool ARGMAX>
 __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* __restrict__ A,
                                                                    const bf16* __restrict__ E, int M,
                                                                    int V, int K, int MT, int NT,
@@ -701,15 +704,17 @@ __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* _
       const float v = vals[i][e];
       if (full || n < V) {
         if (v > best) { best = v; besti = n; }
-        cnt += (v > zd) ? 1 : 0;
+        if (!ARGMAX) cnt += (v > zd) ? 1 : 0;
       }
     }
   float se = 0.f;
+  if (!ARGMAX) {
 #pragma unroll
-  for (int i = 0; i < 16; ++i)
+    for (int i = 0; i < 16; ++i)
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (full || n0 + half * 64 + i * 4 + e < V) se += __expf(vals[i][e] - best);
+      for (int e = 0; e < 4; ++e)
+        if (full || n0 + half * 64 + i * 4 + e < V) se += __expf(vals[i][e] - best);
+  }
   // merge the two halves of the row (lanes tid and tid^1)
   const float obest = __shfl_xor(best, 1, 64);
   const int obesti = __shfl_xor(besti, 1, 64);
@@ -737,8 +742,11 @@ hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int 
   if (M <= 0) return hipSuccess;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_kernel<false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, CfgVocab::kSmemBytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_kernel<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, CfgVocab::kSmemBytes);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
@@ -746,8 +754,12 @@ hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int 
   if (row_draft)
     hipLaunchKernelGGL(draft_logit_kernel, dim3((M + 31) / 32), dim3(64), 0, st, A, E, M, V, K, row_draft, zd_row);
   const int MT = (M + 127) / 128, NT = (V + 127) / 128;
-  hipLaunchKernelGGL(vocab_kernel, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
-                     A, E, M, V, K, MT, NT, row_draft ? zd_row : nullptr, part, logits);
+  if (row_draft || logits)
+    hipLaunchKernelGGL(vocab_kernel<false>, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
+                       A, E, M, V, K, MT, NT, row_draft ? zd_row : nullptr, part, logits);
+  else
+    hipLaunchKernelGGL(vocab_kernel<true>, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
+                       A, E, M, V, K, MT, NT, nullptr, part, logits);
   return hipGetLastError();
 }
 
