@@ -228,6 +228,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   t.rm.row_lim = cv.take<int>(Rmax);
   t.rm.row_draft = cv.take<int>(Rmax);
   t.rm.seq_rows = cv.take<int>(Bm);
+  t.rm.row_start = cv.take<int>(Bm + 1);
   t.slots = cv.take<bf16>(Bm * (size_t)c->lim.k_max * D);
   t.new_rows = cv.take<int>(Bm);
   t.rs_layers = cv.take<sd::RsLayer>(d->dec_layers);
@@ -261,9 +262,14 @@ inline hipStream_t S(void* s) { return static_cast<hipStream_t>(s); }
 // decoder layer over the R = B*T rows described by m.rm.  Leaves the final hidden states in
 // m.x (fp32) and m.xb (bf16); with slot_k > 0 (drafter pass) only those of the slot_k mask-slot
 // rows per sequence are needed, and they go to m.slots [B*slot_k][d] (bf16) instead.
-int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st, bool embedded = false, int slot_k = 0) {
+// packed: the rows of the pass were assembled without padding (m.rm.row_start); R = B*T is then
+// only the bound the grids are sized for, and tiles beyond the rows in use return at once.
+int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st, bool embedded = false, int slot_k = 0,
+                   bool packed = false) {
   const int R = B * T, D = m.d.d_model, F = m.d.d_ffn, H = m.d.n_heads;
   const int Lcap = c->Lcap, Scap = c->Scap;
+  const int* m_real = packed ? m.rm.row_start + B : nullptr;
+  const int* row_start = packed ? m.rm.row_start : nullptr;
   if (!embedded)
     LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::embed_rows(st, m.rm.row_tok, m.rm.row_pos, m.embed, m.pe, m.x, m.xb, R, D));
   // LayerNorm folded into the GEMMs on both sides of it: m.x holds the un-normalised sum, m.xb
@@ -273,7 +279,8 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st, bool 
   int flip = 0;
   auto sum = [&](const bf16* A, int K, const bf16* W, const float* vecs) {
     float* out = m.lnp[flip];
-    hipError_t e = sd::gemm_ln_sum(st, A, K, W, R, D, K, vecs, pend ? pend : m.lnp[flip ^ 1], pend != nullptr, m.x, m.xb, out);
+    hipError_t e = sd::gemm_ln_sum(st, A, K, W, R, D, K, vecs, pend ? pend : m.lnp[flip ^ 1], pend != nullptr, m.x, m.xb, out,
+                                   m_real);
     pend = out;
     flip ^= 1;
     return e;
@@ -284,23 +291,23 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st, bool 
     bf16* vc = m.vc + m.kv_layer * l;
     if (fold && l > 0) {
       LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::gemm_ln_qkv_append(st, m.xb, L.wqkv, R, D, m.folds[l].qkv, pend, m.q, kc,
-                                       vc, m.rm.row_b, m.rm.row_pos, H, Lcap));
+                                       vc, m.rm.row_b, m.rm.row_pos, H, Lcap, m_real));
     } else {
       LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::gemm_qkv_append(st, m.xb, L.wqkv, R, D, D, L.bqkv, m.q, kc, vc, m.rm.row_b,
-                                    m.rm.row_pos, H, Lcap));
+                                    m.rm.row_pos, H, Lcap, m_real));
     }
     sd::AttnArgs a{};
     a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
     a.k = kc; a.k_b = (long)H * Lcap * 64; a.k_h = (long)Lcap * 64; a.k_row = 64;
     a.v = vc; a.v_b = (long)H * Lcap * 64; a.v_h = (long)Lcap * 64; a.v_row = 64; a.v_blocked = 0;
     a.o = m.att; a.o_b = (long)T * D; a.o_row = D;
-    a.q_count = m.rm.seq_rows; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
+    a.q_count = m.rm.seq_rows; a.q_off = row_start; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
     a.T = T; a.H = H; a.B = B;
     a.key_split = Lcap > 256; a.cap = Lcap;
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
     if (fold) {
       LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sum(m.att, D, L.wo, m.folds[l].vo));
-      LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_ln_bf16(st, m.xb, L.cwq, R, D, D, m.folds[l].cq, pend, m.q, D, false));
+      LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_ln_bf16(st, m.xb, L.cwq, R, D, D, m.folds[l].cq, pend, m.q, D, false, m_real));
     } else {
       LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.att, D, L.wo, R, D, D, L.bo, m.x, m.x, D));
       LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln1g, L.ln1b, m.xb, R, D));
@@ -313,11 +320,11 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st, bool 
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
     if (fold) {
       LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sum(m.att, D, L.cwo, m.folds[l].vco));
-      LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_ln_bf16(st, m.xb, L.w1, R, F, D, m.folds[l].w1, pend, m.hid, F, true));
+      LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_ln_bf16(st, m.xb, L.w1, R, F, D, m.folds[l].w1, pend, m.hid, F, true, m_real));
       LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sum(m.hid, F, L.w2, m.folds[l].v2));
       if (l + 1 == m.d.dec_layers) {   // the vocabulary projection reads the normalised rows themselves
         if (slot_k > 0)
-          LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm_slots(st, m.x, L.ln3g, L.ln3b, m.slots, m.new_rows, B, T, slot_k, D));
+          LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm_slots(st, m.x, L.ln3g, L.ln3b, m.slots, m.new_rows, row_start, B, T, slot_k, D));
         else
           LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln3g, L.ln3b, m.xb, R, D));
       }
@@ -329,7 +336,7 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st, bool 
       LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.x, L.ln3g, L.ln3b, m.xb, R, D));
     }
   }
-  if (slot_k > 0 && !fold) HIPCHK(c, sd::gather_slots(st, m.xb, m.slots, m.new_rows, B, T, slot_k, D));
+  if (slot_k > 0 && !fold) HIPCHK(c, sd::gather_slots(st, m.xb, m.slots, m.new_rows, row_start, B, T, slot_k, D));
   return SPECDEC_OK;
 }
 
@@ -674,7 +681,7 @@ int specdec_prefill(specdec_ctx* c, specdec_role role, void* stream) {
   const int T = c->Tmax;
   while (c->uncached_ub[role] > 0) {
     LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::assemble_embed_stream(st, c->st, m.rm, role, c->B, T, 0, m.d.mask_id, m.d.pad_id, m.d.vocab,
-                                        m.new_rows, m.embed, m.pe, m.x, m.xb, m.d.d_model));
+                                        m.new_rows, m.embed, m.pe, m.x, m.xb, m.d.d_model, false));
     rc = decoder_layers(c, m, c->B, T, st, true);
     if (rc) return rc;
     HIPCHK(c, sd::advance_cached(st, c->st, role, m.new_rows, c->B));
@@ -702,9 +709,12 @@ int specdec_draft(specdec_ctx* c, int32_t k, int32_t* draft, void* stream) {
     ub = 1;
   }
   const int B = c->B, T = ub + k;
+  // rows packed sequence after sequence: a sequence brings 1 .. k_max + 1 new stream rows, the
+  // grids are sized for the most (the GEMMs with LayerNorm folded in know how to stop early)
+  const bool packed = !c->no_ln_fold;
   LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::assemble_embed_stream(st, c->st, m.rm, SPECDEC_DRAFTER, B, T, k, m.d.mask_id, m.d.pad_id,
-                                      m.d.vocab, m.new_rows, m.embed, m.pe, m.x, m.xb, m.d.d_model));
-  rc = decoder_layers(c, m, B, T, st, true, k);
+                                      m.d.vocab, m.new_rows, m.embed, m.pe, m.x, m.xb, m.d.d_model, packed));
+  rc = decoder_layers(c, m, B, T, st, true, k, packed);
   if (rc) return rc;
   const int R = B * k, n_tiles = (m.d.vocab + 127) / 128;
   LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, m.d.d_model, nullptr, nullptr, m.part, nullptr));

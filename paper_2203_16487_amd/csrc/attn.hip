@@ -49,6 +49,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   float mrun[NQT], lrun[NQT];
   f32x4 oacc[NQT][4];
   attn_wave<NQT, VBLK>(a, b, h, q0, nq, kw, kstep, Vs[VBLK ? 0 : wave], mrun, lrun, oacc);
+  bf16* obase = a.q_off ? a.o + (long)(active_pair ? a.q_off[b] : 0) * a.o_row : a.o + b * a.o_b;
 
   // oacc[qt][et][r] = O^T[e = et*16 + 4g + r][q = qt*16 + lq]
   if (!a.key_split) {
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
       const int qi = qt * 16 + lq;
       if (qi < nq) {
         const float inv = lrun[qt] > 0.f ? 1.f / lrun[qt] : 0.f;
-        bf16* op = a.o + b * a.o_b + (long)(q0 + qi) * a.o_row + h * kHeadDim;
+        bf16* op = obase + (long)(q0 + qi) * a.o_row + h * kHeadDim;
 #pragma unroll
         for (int et = 0; et < 4; ++et) {
           bf16x4 w;
@@ -95,7 +96,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
         L += Ls[w][qi] * f;
         O += Om[w][qi][e] * f;
       }
-      a.o[b * a.o_b + (long)(q0 + qi) * a.o_row + h * kHeadDim + e] = (bf16)(L > 0.f ? O / L : 0.f);
+      obase[(long)(q0 + qi) * a.o_row + h * kHeadDim + e] = (bf16)(L > 0.f ? O / L : 0.f);
     }
   }
 }

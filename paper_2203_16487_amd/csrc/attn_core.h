@@ -70,13 +70,15 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
   int lim[NQT];
   bf16x8 qf[NQT][2];
   int kmax = 0;
+  const bf16* qbase = a.q_off ? a.q + (long)a.q_off[b] * a.q_row : a.q + b * a.q_b;
+  const int lbase = a.q_off ? a.q_off[b] : b * a.T;
 #pragma unroll
   for (int qt = 0; qt < NQT; ++qt) {
     const int qi = qt * 16 + lq;
     const bool ok = qi < nq;
-    lim[qt] = ok ? (a.lim_row ? a.lim_row[b * a.T + q0 + qi] : a.lim_seq[b]) : 0;
+    lim[qt] = ok ? (a.lim_row ? a.lim_row[lbase + q0 + qi] : a.lim_seq[b]) : 0;
     kmax = max(kmax, lim[qt]);
-    const bf16* qp = a.q + b * a.q_b + (long)(q0 + (ok ? qi : 0)) * a.q_row + h * kHeadDim + g * 8;
+    const bf16* qp = qbase + (long)(q0 + (ok ? qi : 0)) * a.q_row + h * kHeadDim + g * 8;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
       bf16x8 v = ld16<COHQ>(qp + ks * 32);

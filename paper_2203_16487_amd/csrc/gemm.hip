@@ -173,12 +173,16 @@ template <class Cfg, class Epi>
 __global__ __launch_bounds__(Cfg::kThreads) void gemm_kernel(const bf16* __restrict__ A, int lda,
                                                              const bf16* __restrict__ W, int ldw,
                                                              int M, int N, int K, int MT, int NT,
-                                                             Epi epi) {
+                                                             Epi epi, const int* __restrict__ m_real) {
   extern __shared__ __attribute__((aligned(1024))) bf16 smem[];
   static_assert(Cfg::kSmemBytes >= Cfg::kBM * Cfg::kBN * 4, "staging tile must fit in the ring");
   int mt, nt;
   if (!xcd_tile(MT, NT, mt, nt)) return;
   const int m0 = mt * Cfg::kBM, n0 = nt * Cfg::kBN;
+  if (m_real) {   // only the leading *m_real rows hold data (same value for the whole grid)
+    M = min(M, *m_real);
+    if (m0 >= M) return;
+  }
   constexpr int CPR = Cfg::kBN / 8;                          // 8-column chunks per row
   constexpr int ITER = Cfg::kBM * CPR / Cfg::kThreads;       // chunks per thread
   static_assert(Cfg::kBM * CPR % Cfg::kThreads == 0, "tile / thread count");
@@ -214,7 +218,7 @@ typedef GemmCfg<64, 64, 4> CfgSmall;       // 64 KB LDS; many tiles for narrow o
 
 template <class Cfg, class Epi>
 static hipError_t launch_cfg(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
-                             const Epi& epi) {
+                             const Epi& epi, const int* m_real) {
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<Cfg, Epi>),
@@ -224,18 +228,18 @@ static hipError_t launch_cfg(hipStream_t st, const bf16* A, int lda, const bf16*
   }
   const int MT = (M + Cfg::kBM - 1) / Cfg::kBM, NT = (N + Cfg::kBN - 1) / Cfg::kBN;
   hipLaunchKernelGGL((gemm_kernel<Cfg, Epi>), dim3(xcd_grid(MT, NT)), dim3(Cfg::kThreads), Cfg::kSmemBytes, st,
-                     A, lda, W, K, M, N, K, MT, NT, epi);
+                     A, lda, W, K, M, N, K, MT, NT, epi, m_real);
   return hipGetLastError();
 }
 
 template <class Epi>
 static hipError_t launch(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
-                         const Epi& epi) {
+                         const Epi& epi, const int* m_real = nullptr) {
   if (M <= 0 || N <= 0) return hipSuccess;
   // enough 128x128 tiles to give every CU one?  else take 64x64 tiles
   const long wide_tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
-  if (wide_tiles >= 200) return launch_cfg<CfgWide>(st, A, lda, W, M, N, K, epi);
-  return launch_cfg<CfgSmall>(st, A, lda, W, M, N, K, epi);
+  if (wide_tiles >= 200) return launch_cfg<CfgWide>(st, A, lda, W, M, N, K, epi, m_real);
+  return launch_cfg<CfgSmall>(st, A, lda, W, M, N, K, epi, m_real);
 }
 
 hipError_t gemm_f32(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
@@ -248,8 +252,8 @@ hipError_t gemm_bf16(hipStream_t st, const bf16* A, int lda, const bf16* W, int 
 }
 hipError_t gemm_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
                            const bf16* bias, bf16* q_out, bf16* kc, bf16* vc, const int* row_b,
-                           const int* row_pos, int H, int Lcap) {
-  return launch(st, A, K, W, M, 3 * d, K, EpiQkvAppend{bias, q_out, kc, vc, row_b, row_pos, d, H, Lcap});
+                           const int* row_pos, int H, int Lcap, const int* m_real) {
+  return launch(st, A, K, W, M, 3 * d, K, EpiQkvAppend{bias, q_out, kc, vc, row_b, row_pos, d, H, Lcap}, m_real);
 }
 hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
                          const bf16* bias, bf16* xk, bf16* xv, int S, int H, int Scap) {
@@ -459,7 +463,7 @@ template <class Cfg, class Epi>
 __global__ __launch_bounds__(Cfg::kThreads) void gemm_ln_kernel(const bf16* __restrict__ A, int lda,
                                                                 const bf16* __restrict__ W, int ldw,
                                                                 int M, int N, int K, int MT, int NT,
-                                                                Epi epi) {
+                                                                Epi epi, const int* __restrict__ m_real) {
   extern __shared__ __attribute__((aligned(1024))) bf16 smem[];
   static_assert(Cfg::kSmemBytes >= Cfg::kBM * Cfg::kBN * 4, "staging tile must fit in the ring");
   static_assert(Cfg::kThreads >= Epi::kVec * Cfg::kBN / 4, "one thread per 4 entries of the column vectors");
@@ -468,6 +472,10 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_ln_kernel(const bf16* __re
   int mt, nt;
   if (!xcd_tile(MT, NT, mt, nt)) return;
   const int m0 = mt * Cfg::kBM, n0 = nt * Cfg::kBN;
+  if (m_real) {   // only the leading *m_real rows hold data (same value for the whole grid)
+    M = min(M, *m_real);
+    if (m0 >= M) return;
+  }
   constexpr int CPR = Cfg::kBN / 8;                    // 8-column pieces per tile row
   constexpr int RPI = Cfg::kThreads / CPR;             // tile rows covered by one pass of the block
   constexpr int ITER = Cfg::kBM / RPI;
@@ -513,7 +521,7 @@ __global__ __launch_bounds__(Cfg::kThreads) void gemm_ln_kernel(const bf16* __re
 
 template <class Cfg, class Epi>
 static hipError_t launch_ln_cfg(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
-                                const Epi& epi) {
+                                const Epi& epi, const int* m_real) {
   constexpr int kBytes = ln_smem_bytes<Cfg, Epi::kVec>();
   static bool attr_done = false;
   if (!attr_done) {
@@ -524,35 +532,36 @@ static hipError_t launch_ln_cfg(hipStream_t st, const bf16* A, int lda, const bf
   }
   const int MT = (M + Cfg::kBM - 1) / Cfg::kBM, NT = (N + Cfg::kBN - 1) / Cfg::kBN;
   hipLaunchKernelGGL((gemm_ln_kernel<Cfg, Epi>), dim3(xcd_grid(MT, NT)), dim3(Cfg::kThreads), kBytes, st,
-                     A, lda, W, K, M, N, K, MT, NT, epi);
+                     A, lda, W, K, M, N, K, MT, NT, epi, m_real);
   return hipGetLastError();
 }
 template <class Epi>
 static hipError_t launch_ln(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
-                            const Epi& epi) {
+                            const Epi& epi, const int* m_real) {
   if (M <= 0 || N <= 0) return hipSuccess;
   const long wide_tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
-  if (wide_tiles >= 200) return launch_ln_cfg<CfgWide>(st, A, lda, W, M, N, K, epi);
-  return launch_ln_cfg<CfgSmall>(st, A, lda, W, M, N, K, epi);
+  if (wide_tiles >= 200) return launch_ln_cfg<CfgWide>(st, A, lda, W, M, N, K, epi, m_real);
+  return launch_ln_cfg<CfgSmall>(st, A, lda, W, M, N, K, epi, m_real);
 }
 
 hipError_t gemm_ln_sum(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int d, int K,
-                       const float* vecs, const float* ln_in, bool has_prev, float* x, bf16* xg, float* ln_out) {
+                       const float* vecs, const float* ln_in, bool has_prev, float* x, bf16* xg, float* ln_out,
+                       const int* m_real) {
   return launch_ln(st, A, lda, W, M, d, K,
                    EpiLnSum{vecs, reinterpret_cast<const f32x2*>(ln_in), reinterpret_cast<f32x2*>(ln_out), x, xg, d,
-                            d / 64, has_prev ? 1 : 0});
+                            d / 64, has_prev ? 1 : 0}, m_real);
 }
 hipError_t gemm_ln_bf16(hipStream_t st, const bf16* A, const bf16* W, int M, int N, int d, const LnFold& f,
-                        const float* ln_in, bf16* out, int ldo, bool relu) {
+                        const float* ln_in, bf16* out, int ldo, bool relu, const int* m_real) {
   return launch_ln(st, A, d, W, M, N, d,
-                   EpiLnBf16{f.cs, f.bf, reinterpret_cast<const f32x2*>(ln_in), out, ldo, d / 64, relu ? 1 : 0});
+                   EpiLnBf16{f.cs, f.bf, reinterpret_cast<const f32x2*>(ln_in), out, ldo, d / 64, relu ? 1 : 0}, m_real);
 }
 hipError_t gemm_ln_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, int d, const LnFold& f,
                               const float* ln_in, bf16* q_out, bf16* kc, bf16* vc, const int* row_b,
-                              const int* row_pos, int H, int Lcap) {
+                              const int* row_pos, int H, int Lcap, const int* m_real) {
   return launch_ln(st, A, d, W, M, 3 * d, d,
                    EpiLnQkvAppend{f.cs, f.bf, reinterpret_cast<const f32x2*>(ln_in), d / 64, q_out, kc, vc, row_b,
-                                  row_pos, d, H, Lcap});
+                                  row_pos, d, H, Lcap}, m_real);
 }
 
 // cs[n] = sum_k g[k] W[n][k],  bf[n] = b[n] + sum_k beta[k] W[n][k]; one wave per column n

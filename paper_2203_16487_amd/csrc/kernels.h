@@ -12,7 +12,9 @@ typedef __bf16 bf16;
 // Row bookkeeping of one decoder pass.  Row r belongs to sequence row_b[r] (-1 = padding
 // row: computed but never stored into a cache), sits at stream position row_pos[r], feeds
 // token row_tok[r], may attend to self-attention keys [0, row_lim[r]) and scores draft token
-// row_draft[r] (-1 = none).  Rows of sequence b are b*T .. b*T + seq_rows[b] - 1.
+// row_draft[r] (-1 = none).  Rows of sequence b are b*T .. b*T + seq_rows[b] - 1, or, in a
+// packed pass, row_start[b] .. row_start[b] + seq_rows[b] - 1 with row_start the running sum of
+// seq_rows (row_start[B] = number of rows of the pass): no padding rows between sequences.
 struct RowMap {
   int* row_b;
   int* row_pos;
@@ -20,6 +22,7 @@ struct RowMap {
   int* row_lim;
   int* row_draft;
   int* seq_rows;
+  int* row_start;   // [B + 1]
 };
 
 // ---- gemm.hip: C = A W^T (+bias) with different epilogues; A [M,K] bf16, W [N,K] bf16 ----
@@ -33,7 +36,7 @@ hipError_t gemm_bf16(hipStream_t st, const bf16* A, int lda, const bf16* W, int 
 // caches [B][H][Lcap][64] at sequence row_b[r], position row_pos[r] (the KV append).
 hipError_t gemm_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
                            const bf16* bias, bf16* q_out, bf16* kc, bf16* vc, const int* row_b,
-                           const int* row_pos, int H, int Lcap);
+                           const int* row_pos, int H, int Lcap, const int* m_real = nullptr);
 // Cross-attention keys/values of the encoder memory, N = 2d: memory rows m = b*S + s ->
 // xk [B][H][Scap][64], xv key-blocked [B][H][Scap/8][64][8].
 hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
@@ -63,15 +66,19 @@ hipError_t ln_sum_vecs(hipStream_t st, const bf16* bias, const bf16* g_prev, con
 // x [M,d] += A W^T + bias, where the residual already in x is LN_prev(x) if has_prev (chunk pairs of
 // x in ln_in; without has_prev ln_in is still read, and ignored: pass any chunk-pair buffer);
 // also xg = bf16(x_new * g_next) and the chunk pairs of x_new -> ln_out (a buffer other than ln_in).
+// m_real (all three; device, nullable): number of leading rows that hold data; row tiles at or
+// beyond it are skipped and rows beyond it are neither computed on nor stored (M stays the
+// upper bound the grid is sized for).
 hipError_t gemm_ln_sum(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int d, int K,
-                       const float* vecs, const float* ln_in, bool has_prev, float* x, bf16* xg, float* ln_out);
+                       const float* vecs, const float* ln_in, bool has_prev, float* x, bf16* xg, float* ln_out,
+                       const int* m_real = nullptr);
 // out bf16 [M,ldo] = act(LN(y) W^T + b) from A = bf16(y * g) [M,d] and the chunk pairs of y
 hipError_t gemm_ln_bf16(hipStream_t st, const bf16* A, const bf16* W, int M, int N, int d, const LnFold& f,
-                        const float* ln_in, bf16* out, int ldo, bool relu);
+                        const float* ln_in, bf16* out, int ldo, bool relu, const int* m_real = nullptr);
 // gemm_qkv_append on LN(y)
 hipError_t gemm_ln_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, int d, const LnFold& f,
                               const float* ln_in, bf16* q_out, bf16* kc, bf16* vc, const int* row_b,
-                              const int* row_pos, int H, int Lcap);
+                              const int* row_pos, int H, int Lcap, const int* m_real = nullptr);
 
 // Vocabulary projection fused with per-row statistics.  zd_row [M] receives the logit of the
 // draft each row scores (-inf if none).  For every row and every 128-column vocabulary tile one
@@ -94,7 +101,9 @@ struct AttnArgs {
                                               //      read, capacity % 32 == 0      0: rows, + key*v_row + e
   bf16* o;        long o_b, o_row;            // o + b*o_b + i*o_row + h*64
   const int* q_count;                         // [B] queries of sequence b (null: T)
-  const int* lim_row;                         // [B*T] visible keys per query (null: lim_seq)
+  const int* q_off;                           // [B] first query / output / lim_row row of sequence b (null: b*T,
+                                              //     addressed through q_b / o_b); rows are q_row / o_row apart
+  const int* lim_row;                         // [rows] visible keys per query (null: lim_seq)
   const int* lim_seq;                         // [B]  visible keys of every query of b
   int T;                                      // max queries per sequence (q_b = T rows apart)
   int H, B;
@@ -165,9 +174,10 @@ hipError_t embed_rows(hipStream_t st, const int* tok, const int* pos, const bf16
 // x <- LayerNorm(x) * g + b in place (fp32), xb <- bf16(x)
 hipError_t layer_norm(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R,
                       int d);
-// dst [B*k][d] bf16 <- LayerNorm of the mask-slot rows b*T + new_rows[b] + s of x (x unchanged)
+// dst [B*k][d] bf16 <- LayerNorm of the mask-slot rows first(b) + new_rows[b] + s of x (x unchanged),
+// first(b) = row_start[b], or b*T when row_start is null
 hipError_t layer_norm_slots(hipStream_t st, const float* x, const bf16* g, const bf16* b, bf16* dst,
-                            const int* new_rows, int B, int T, int k, int d);
+                            const int* new_rows, const int* row_start, int B, int T, int k, int d);
 hipError_t fill_i32(hipStream_t st, int* p, int v, long n);
 
 struct SeqState {       // device arrays of the bound state buffer, all [max_batch] unless noted
@@ -191,12 +201,13 @@ hipError_t assemble_stream(hipStream_t st, const SeqState& s, const RowMap& rm, 
 // assemble_verify / assemble_stream and embed_rows of the same rows in one launch
 hipError_t assemble_embed_verify(hipStream_t st, const SeqState& s, const RowMap& rm, const int* draft, int B, int k,
                                  int V, const bf16* E, const float* pe, float* x, bf16* xb, int d);
+// packed: rows of the sequences follow each other without padding (RowMap::row_start is written)
 hipError_t assemble_embed_stream(hipStream_t st, const SeqState& s, const RowMap& rm, int role, int B, int T,
                                  int n_mask, int mask_id, int pad_id, int V, int* new_rows, const bf16* E,
-                                 const float* pe, float* x, bf16* xb, int d);
+                                 const float* pe, float* x, bf16* xb, int d, bool packed);
 hipError_t advance_cached(hipStream_t st, const SeqState& s, int role, const int* new_rows, int B);
-hipError_t gather_slots(hipStream_t st, const bf16* xb, bf16* dst, const int* new_rows, int B, int T,
-                        int k, int d);
+hipError_t gather_slots(hipStream_t st, const bf16* xb, bf16* dst, const int* new_rows, const int* row_start, int B,
+                        int T, int k, int d);
 hipError_t encoder_rows(hipStream_t st, const int* src, int* tok, int* pos, int B, int S, int V);
 // merge the vocabulary partials of every row into row_stats [R][kRowStats] =
 // {max, arg-max, log-sum-exp, draft logit, number of logits above the draft's, 0, 0, 0}

@@ -101,13 +101,14 @@ __global__ __launch_bounds__(256) void ln_kernel(float* __restrict__ x, const bf
 template <int PER>
 __global__ __launch_bounds__(256) void ln_slots_kernel(const float* __restrict__ x, const bf16* __restrict__ g,
                                                        const bf16* __restrict__ bta, bf16* __restrict__ dst,
-                                                       const int* __restrict__ new_rows, int B, int T, int k) {
+                                                       const int* __restrict__ new_rows,
+                                                       const int* __restrict__ row_start, int B, int T, int k) {
   constexpr int d = 64 * PER;
   const int lane = threadIdx.x & 63;
   const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (o >= B * k) return;
   const int b = o / k, sl = o - b * k;
-  const float* xr = x + (size_t)(b * T + new_rows[b] + sl) * d;
+  const float* xr = x + (size_t)((row_start ? row_start[b] : b * T) + new_rows[b] + sl) * d;
   float v[PER], gg[PER], bb[PER];
 #pragma unroll
   for (int i = 0; i < PER; ++i) v[i] = xr[i * 64 + lane];
@@ -127,15 +128,16 @@ __global__ __launch_bounds__(256) void ln_slots_kernel(const float* __restrict__
 }
 template <int PER>
 static hipError_t ln_slots_launch(hipStream_t st, const float* x, const bf16* g, const bf16* b, bf16* dst,
-                                  const int* new_rows, int B, int T, int k) {
-  hipLaunchKernelGGL(ln_slots_kernel<PER>, dim3((B * k + 3) / 4), dim3(256), 0, st, x, g, b, dst, new_rows, B, T, k);
+                                  const int* new_rows, const int* row_start, int B, int T, int k) {
+  hipLaunchKernelGGL(ln_slots_kernel<PER>, dim3((B * k + 3) / 4), dim3(256), 0, st, x, g, b, dst, new_rows, row_start,
+                     B, T, k);
   return hipGetLastError();
 }
 hipError_t layer_norm_slots(hipStream_t st, const float* x, const bf16* g, const bf16* b, bf16* dst,
-                            const int* new_rows, int B, int T, int k, int d) {
+                            const int* new_rows, const int* row_start, int B, int T, int k, int d) {
   if (B <= 0 || k <= 0) return hipSuccess;
   switch (d / 64) {
-#define SD_LN_CASE(P) case P: return ln_slots_launch<P>(st, x, g, b, dst, new_rows, B, T, k);
+#define SD_LN_CASE(P) case P: return ln_slots_launch<P>(st, x, g, b, dst, new_rows, row_start, B, T, k);
     SD_LN_CASE(1) SD_LN_CASE(2) SD_LN_CASE(3) SD_LN_CASE(4) SD_LN_CASE(5) SD_LN_CASE(6) SD_LN_CASE(7) SD_LN_CASE(8)
     SD_LN_CASE(9) SD_LN_CASE(10) SD_LN_CASE(11) SD_LN_CASE(12) SD_LN_CASE(13) SD_LN_CASE(14) SD_LN_CASE(15)
     SD_LN_CASE(16) SD_LN_CASE(17) SD_LN_CASE(18) SD_LN_CASE(19) SD_LN_CASE(20) SD_LN_CASE(21) SD_LN_CASE(22)
@@ -263,7 +265,24 @@ hipError_t assemble_stream(hipStream_t st, const SeqState& s, const RowMap& rm, 
                      mask_id, pad_id, V, new_rows);
   return hipGetLastError();
 }
-// The same, one block per row, followed by the row's embedding (embed_rows).
+// The same, one block per row, followed by the row's embedding (embed_rows).  PACKED: the rows
+// of the sequences follow each other without padding; a block finds its sequence's first row as
+// the sum of the row counts of the sequences before it (each thread derives some of them from the
+// state, as the block does for its own), and blocks beyond their sequence's rows do nothing.
+struct StreamRows {
+  int c0, n, rows;
+  bool masks;
+};
+__device__ __forceinline__ StreamRows stream_rows(const SeqState& s, int role, int b, int T, int n_mask) {
+  StreamRows r;
+  r.c0 = s.cached[role][b];
+  const int target = s.len[b] + (role == 1 ? 1 : 0);       // drafter also ingests the pending token
+  r.n = max(0, min(target - r.c0, T - n_mask));
+  r.masks = n_mask > 0 && r.c0 + r.n == target;             // slots only once the stream is ingested
+  r.rows = r.n + (r.masks ? n_mask : 0);
+  return r;
+}
+template <bool PACKED>
 __global__ __launch_bounds__(128) void assemble_embed_stream_kernel(SeqState s, RowMap rm, int role, int B, int T,
                                                                     int n_mask, int mask_id, int pad_id, int V,
                                                                     int* __restrict__ new_rows,
@@ -271,33 +290,50 @@ __global__ __launch_bounds__(128) void assemble_embed_stream_kernel(SeqState s, 
                                                                     const float* __restrict__ pe,
                                                                     float* __restrict__ x, bf16* __restrict__ xb, int d,
                                                                     float scale) {
-  const int r = blockIdx.x;
-  const int b = r / T, i = r - b * T;
-  const int c0 = s.cached[role][b];
-  const int target = s.len[b] + (role == 1 ? 1 : 0);
-  const int n = max(0, min(target - c0, T - n_mask));
-  const bool masks = n_mask > 0 && c0 + n == target;
+  __shared__ int wsum[2];
+  const int b = blockIdx.x / T, i = blockIdx.x - b * T;
+  const StreamRows me = stream_rows(s, role, b, T, n_mask);
+  int first = b * T;
+  if (PACKED) {
+    int part = 0;
+    for (int o = threadIdx.x; o < b; o += 128) part += stream_rows(s, role, o, T, n_mask).rows;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = part;
+    __syncthreads();
+    first = wsum[0] + wsum[1];
+  }
+  if (threadIdx.x == 0 && i == 0) {
+    rm.seq_rows[b] = me.rows;
+    new_rows[b] = me.n;
+    if (PACKED) {
+      rm.row_start[b] = first;
+      if (b == B - 1) rm.row_start[B] = first + me.rows;
+    }
+  }
+  if (PACKED && i >= me.rows) return;
+  const int r = first + i;
   int rb = -1, pos = 0, tok = pad_id, lim = 0;
-  if (i < n) {
-    rb = b; pos = c0 + i; tok = min(max(s.tokens[(size_t)b * s.tok_pitch + c0 + i], 0), V - 1); lim = c0 + i + 1;
-  } else if (masks && i < n + n_mask) {
-    rb = b; pos = c0 + i; tok = mask_id; lim = c0 + n + n_mask;
+  if (i < me.n) {
+    rb = b; pos = me.c0 + i; tok = min(max(s.tokens[(size_t)b * s.tok_pitch + me.c0 + i], 0), V - 1); lim = me.c0 + i + 1;
+  } else if (me.masks && i < me.n + n_mask) {
+    rb = b; pos = me.c0 + i; tok = mask_id; lim = me.c0 + me.n + n_mask;
   }
   if (threadIdx.x == 0) {
     rm.row_b[r] = rb; rm.row_pos[r] = pos; rm.row_tok[r] = tok; rm.row_lim[r] = lim; rm.row_draft[r] = -1;
-    if (i == 0) {
-      rm.seq_rows[b] = n + (masks ? n_mask : 0);
-      new_rows[b] = n;
-    }
   }
   embed_row(E + (size_t)tok * d, pe + (size_t)pos * d, x + (size_t)r * d, xb + (size_t)r * d, d, scale);
 }
 hipError_t assemble_embed_stream(hipStream_t st, const SeqState& s, const RowMap& rm, int role, int B, int T,
                                  int n_mask, int mask_id, int pad_id, int V, int* new_rows, const bf16* E,
-                                 const float* pe, float* x, bf16* xb, int d) {
+                                 const float* pe, float* x, bf16* xb, int d, bool packed) {
   if (B <= 0 || T <= 0) return hipSuccess;
-  hipLaunchKernelGGL(assemble_embed_stream_kernel, dim3(B * T), dim3(128), 0, st, s, rm, role, B, T, n_mask, mask_id,
-                     pad_id, V, new_rows, E, pe, x, xb, d, sqrtf((float)d));
+  if (packed)
+    hipLaunchKernelGGL(assemble_embed_stream_kernel<true>, dim3(B * T), dim3(128), 0, st, s, rm, role, B, T, n_mask,
+                       mask_id, pad_id, V, new_rows, E, pe, x, xb, d, sqrtf((float)d));
+  else
+    hipLaunchKernelGGL(assemble_embed_stream_kernel<false>, dim3(B * T), dim3(128), 0, st, s, rm, role, B, T, n_mask,
+                       mask_id, pad_id, V, new_rows, E, pe, x, xb, d, sqrtf((float)d));
   return hipGetLastError();
 }
 
@@ -312,15 +348,18 @@ hipError_t advance_cached(hipStream_t st, const SeqState& s, int role, const int
 
 // dense [B*k][d] copy of the mask-slot rows (row b*T + new_rows[b] + s) for the vocabulary kernel
 __global__ void gather_slots_kernel(const bf16* __restrict__ xb, bf16* __restrict__ dst,
-                                    const int* __restrict__ new_rows, int B, int T, int k, int d) {
+                                    const int* __restrict__ new_rows, const int* __restrict__ row_start, int B, int T,
+                                    int k, int d) {
   const int o = blockIdx.x;              // b*k + s
   const int b = o / k, sl = o - b * k;
-  const uint4* src = reinterpret_cast<const uint4*>(xb + (size_t)(b * T + new_rows[b] + sl) * d);
+  const int first = row_start ? row_start[b] : b * T;
+  const uint4* src = reinterpret_cast<const uint4*>(xb + (size_t)(first + new_rows[b] + sl) * d);
   uint4* out = reinterpret_cast<uint4*>(dst + (size_t)o * d);
   for (int c = threadIdx.x; c < d / 8; c += blockDim.x) out[c] = src[c];
 }
-hipError_t gather_slots(hipStream_t st, const bf16* xb, bf16* dst, const int* new_rows, int B, int T, int k, int d) {
-  hipLaunchKernelGGL(gather_slots_kernel, dim3(B * k), dim3(64), 0, st, xb, dst, new_rows, B, T, k, d);
+hipError_t gather_slots(hipStream_t st, const bf16* xb, bf16* dst, const int* new_rows, const int* row_start, int B,
+                        int T, int k, int d) {
+  hipLaunchKernelGGL(gather_slots_kernel, dim3(B * k), dim3(64), 0, st, xb, dst, new_rows, row_start, B, T, k, d);
   return hipGetLastError();
 }
 
