@@ -164,6 +164,15 @@ def test_loop_relaxed():
     assert any(s.stream[-1] == 2 for s in seqs) or True
 
 
+def test_loop_relaxed_separate_layernorm(monkeypatch):
+    """The same loop with LayerNorm run as a pass of its own (SPECDEC_NO_LN_FOLD=1): the drafter pass
+    then keeps T rows per sequence (padding rows between sequences) instead of packing them."""
+    monkeypatch.setenv("SPECDEC_NO_LN_FOLD", "1")
+    *_, seqs, stats = run_loop(seed=23, beta=3, tau=1.0, B=7, k=5)
+    print(f"[loop relaxed, separate LayerNorm] {stats}")
+    assert stats["committed"] == sum(len(s.stream) - 1 for s in seqs)
+
+
 def test_config3_drafter_pass():
     """Spec-Drafter shape: 12-layer encoder, 2-layer decoder, d=512, V=32768; reduced batch for
     the CPU oracle (B=6 of the 64; source 128; 32 cached + 1 pending; k=10)."""
