@@ -195,12 +195,11 @@ struct SeqState {       // device arrays of the bound state buffer, all [max_bat
 // rows of a verification pass: [u_j, drafts]; also stores the drafts for commit
 hipError_t assemble_verify(hipStream_t st, const SeqState& s, const RowMap& rm, const int* draft,
                            int B, int k, int V);
-// rows of a prefill pass (n_mask = 0) or of a drafter pass (stream rows + n_mask [MASK] slots)
-hipError_t assemble_stream(hipStream_t st, const SeqState& s, const RowMap& rm, int role, int B, int T,
-                           int n_mask, int mask_id, int pad_id, int V, int* new_rows);
-// assemble_verify / assemble_stream and embed_rows of the same rows in one launch
+// assemble_verify and embed_rows of the same rows in one launch
 hipError_t assemble_embed_verify(hipStream_t st, const SeqState& s, const RowMap& rm, const int* draft, int B, int k,
                                  int V, const bf16* E, const float* pe, float* x, bf16* xb, int d);
+// rows of a prefill pass (n_mask = 0) or of a drafter pass (stream rows + n_mask [MASK] slots),
+// embedded in the same launch; new_rows[b] = stream rows of sequence b in this pass;
 // packed: rows of the sequences follow each other without padding (RowMap::row_start is written)
 hipError_t assemble_embed_stream(hipStream_t st, const SeqState& s, const RowMap& rm, int role, int B, int T,
                                  int n_mask, int mask_id, int pad_id, int V, int* new_rows, const bf16* E,
@@ -209,18 +208,16 @@ hipError_t advance_cached(hipStream_t st, const SeqState& s, int role, const int
 hipError_t gather_slots(hipStream_t st, const bf16* xb, bf16* dst, const int* new_rows, const int* row_start, int B,
                         int T, int k, int d);
 hipError_t encoder_rows(hipStream_t st, const int* src, int* tok, int* pos, int B, int S, int V);
-// merge the vocabulary partials of every row into row_stats [R][kRowStats] =
-// {max, arg-max, log-sum-exp, draft logit, number of logits above the draft's, 0, 0, 0}
-hipError_t merge_rows(hipStream_t st, const float* part, const float* zd_row, int n_tiles, int R,
-                      float* row_stats);
-// merge_rows of the B*(k+1) rows of a verification pass, then the top-beta / tau rule on them and
-// the leading-accept scan per sequence, in one launch (k + 1 <= 32)
+// Merges the vocabulary partials of each of the B*(k+1) rows of a verification pass into
+// row_stats [R][kRowStats] = {max, arg-max, log-sum-exp, draft logit, number of logits above the
+// draft's, 0, 0, 0}, then applies the top-beta / tau rule and the leading-accept scan per
+// sequence, in one launch (k + 1 <= 32)
 // (fail: optional device flag; when set every sequence reports accept_len -1, next_token pad)
 hipError_t merge_accept(hipStream_t st, const float* part, const float* zd_row, int n_tiles, float* row_stats,
                         const SeqState& s, int B, int k, int beta, float tau, int pad_id, int* accept_len,
                         int* next_token, const unsigned* fail = nullptr);
-// merge_rows of the B*k mask-slot rows of a drafter pass, draft[b][s] = their arg-max (pad for
-// finished sequences), and cached[drafter][b] += new_rows[b]
+// the same merge for the B*k mask-slot rows of a drafter pass, draft[b][s] = their arg-max (pad
+// for finished sequences), and cached[drafter][b] += new_rows[b]
 hipError_t merge_drafts(hipStream_t st, const float* part, int n_tiles, float* row_stats, const SeqState& s, int B,
                         int k, int pad_id, const int* new_rows, int* draft);
 hipError_t commit_rows(hipStream_t st, const SeqState& s, const int* accept_len,

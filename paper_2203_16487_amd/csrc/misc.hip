@@ -231,41 +231,13 @@ hipError_t assemble_embed_verify(hipStream_t st, const SeqState& s, const RowMap
 }
 
 // ----------------------------------------------------------------------------- prefill / draft rows
-// One thread per sequence writes the T row slots of its sequence.
+// Each sequence owns up to T row slots of the pass.
 // Prefill (n_mask = 0): the next up to T uncached stream tokens, causal.
 // Draft (Sec. 3.1.3, Eq. 7): the uncached stream tokens (causal) followed by n_mask [MASK]
 // slots; slot s sits at the position of the token it predicts and attends to the whole stream
 // and to all slots.  The slots' keys/values land beyond the valid cache length and are dead
 // after the pass.  new_rows[b] = stream rows of this pass (the amount `cached` advances by).
-__global__ void assemble_stream_kernel(SeqState s, RowMap rm, int role, int B, int T, int n_mask, int mask_id,
-                                       int pad_id, int V, int* __restrict__ new_rows) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= B) return;
-  const int c0 = s.cached[role][b];
-  const int target = s.len[b] + (role == 1 ? 1 : 0);       // drafter also ingests the pending token
-  const int n = max(0, min(target - c0, T - n_mask));
-  const bool masks = n_mask > 0 && c0 + n == target;         // slots only once the stream is ingested
-  const int* u = s.tokens + (size_t)b * s.tok_pitch;
-  for (int i = 0; i < T; ++i) {
-    const int r = b * T + i;
-    int rb = -1, pos = 0, tok = pad_id, lim = 0;
-    if (i < n) {
-      rb = b; pos = c0 + i; tok = min(max(u[c0 + i], 0), V - 1); lim = c0 + i + 1;
-    } else if (masks && i < n + n_mask) {
-      rb = b; pos = c0 + i; tok = mask_id; lim = c0 + n + n_mask;
-    }
-    rm.row_b[r] = rb; rm.row_pos[r] = pos; rm.row_tok[r] = tok; rm.row_lim[r] = lim; rm.row_draft[r] = -1;
-  }
-  rm.seq_rows[b] = n + (masks ? n_mask : 0);
-  new_rows[b] = n;
-}
-hipError_t assemble_stream(hipStream_t st, const SeqState& s, const RowMap& rm, int role, int B, int T,
-                           int n_mask, int mask_id, int pad_id, int V, int* new_rows) {
-  hipLaunchKernelGGL(assemble_stream_kernel, blocks_for(B, 64), dim3(64), 0, st, s, rm, role, B, T, n_mask,
-                     mask_id, pad_id, V, new_rows);
-  return hipGetLastError();
-}
-// The same, one block per row, followed by the row's embedding (embed_rows).  PACKED: the rows
+// One block per row: the row's bookkeeping, then its embedding (embed_rows).  PACKED: the rows
 // of the sequences follow each other without padding; a block finds its sequence's first row as
 // the sum of the row counts of the sequences before it (each thread derives some of them from the
 // state, as the block does for its own), and blocks beyond their sequence's rows do nothing.
@@ -413,20 +385,6 @@ __device__ __forceinline__ RowMerge merge_row(const float* __restrict__ pr, int 
 __device__ __forceinline__ void store_row_stats(float* rs, const RowMerge& r, float zd) {
   *reinterpret_cast<f32x4*>(rs) = f32x4{r.m, (float)r.arg, r.lse, zd};
   *reinterpret_cast<f32x4*>(rs + 4) = f32x4{(float)r.cnt, 0.f, 0.f, 0.f};
-}
-
-__global__ __launch_bounds__(64) void merge_rows_kernel(const float* __restrict__ part,
-                                                        const float* __restrict__ zd_row, int n_tiles, int R,
-                                                        float* __restrict__ row_stats) {
-  const int r = blockIdx.x, lane = threadIdx.x;
-  if (r >= R) return;
-  const RowMerge res = merge_row(part + (size_t)r * n_tiles * kPartF, n_tiles, lane);
-  if (lane == 0) store_row_stats(row_stats + (size_t)r * kRowStats, res, zd_row ? zd_row[r] : kNegInf);
-}
-hipError_t merge_rows(hipStream_t st, const float* part, const float* zd_row, int n_tiles, int R, float* row_stats) {
-  if (R <= 0) return hipSuccess;
-  hipLaunchKernelGGL(merge_rows_kernel, dim3(R), dim3(64), 0, st, part, zd_row, n_tiles, R, row_stats);
-  return hipGetLastError();
 }
 
 // Stage 2, per sequence (paper Sec. 3.2).  With z_d the draft's logit on its row:
