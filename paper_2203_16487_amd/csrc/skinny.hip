@@ -69,13 +69,12 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
   const int k0 = (wave & 3) * (d / 4);
   bf16x8 wf[steps];
   // the block's 16 columns of the sublayer's input (for the residual add) are requested now
-  // and normalised after the attention, whose own requests travel at the same time
-  SkHidden<PER> hs;
-  if (kwave) {
-    sk_wload<steps>(W, d, n0, d, k0, wf);
-    hs.params(resid);
-    hs.load(resid, R, wave);
-  }
+  // (rows wave, wave + 8, ... of every wave) and normalised after the attention, whose own
+  // requests travel at the same time
+  SkHidden<PER, false, 4, kSkAttnWaves> hs;
+  if (kwave) sk_wload<steps>(W, d, n0, d, k0, wf);
+  hs.params(resid);
+  hs.load(resid, R, wave);
   // attention output of every (sequence, head) pair -> hb (bf16 [32][d]); rows >= R zero.
   // One pair per wave: eight pairs are in flight at once.
   for (int idx = threadIdx.x; idx < (TWO ? 32 : 16) * pitch / 8; idx += 64 * kSkAttnWaves)
@@ -101,13 +100,7 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
       }
     }
   }
-  if (kwave) {
-    hs.finish(resid, R, TWO ? 32 : 16, wave, L.hb, L.hown, n0, false, -64);
-    if (TWO) {
-      hs.load(resid, R, wave + 16);
-      hs.finish(resid, R, 32, wave + 16, L.hb, L.hown, n0, false, -64);
-    }
-  }
+  hs.finish(resid, R, TWO ? 32 : 16, wave, L.hb, L.hown, n0, false, -64);
   __syncthreads();
   f32x4 acc[2];
   sk_zero(acc);

@@ -32,33 +32,83 @@ struct SkLds {
 
 // Hidden state of the R rows = what `src` describes; bf16 copy of all columns -> hb (rows
 // R .. nrows-1 zero), fp32 copy of columns [n0, n0 + 16) -> hown (for residual adds).
-// A wave takes rows wave, wave + 4, ...; it requests the data of up to four of them (and the
+// A wave takes rows base, base + STRIDE, ...; it requests the data of RU of them (and the
 // LayerNorm parameters, once) before it reduces any, so the prologue costs one memory round
-// trip however many rows there are.
+// trip for RU rows per wave.
 // COH: the fp32 rows were written by other workgroups of the running kernel.  n0b: a second
 // 16-column residual slice (slot 1 of hown, [2][32][16]); negative: none.
-template <int PER, bool COH = false>
+// A lane holds VEC consecutive columns per 64*VEC-column group (VEC = 4 when d % 256 == 0), so a
+// row is fetched with 16-byte loads: the prologue's cost is the number of load instructions
+// the CU has to issue, not their bytes.
+template <int PER, bool COH = false, int RU = 4, int STRIDE = 4>
 struct SkHidden {
-  static constexpr int d = 64 * PER, pitch = d + kSkPad, RU = 4;
+  static constexpr int d = 64 * PER, pitch = d + kSkPad;
+  static constexpr int VEC = PER % 4 == 0 ? 4 : (PER % 2 == 0 ? 2 : 1);
+  static constexpr int NV = PER / VEC;                      // vector loads per row and lane
   float gg[PER], bb[PER];
   float v[RU][PER];
+  // column of element i of this lane
+  __device__ __forceinline__ static int col(int i, int lane) { return (i / VEC) * (64 * VEC) + lane * VEC + i % VEC; }
+
+  template <class T>
+  __device__ __forceinline__ static void load_vec(const T* p, float* out) {   // VEC values -> fp32
+    if constexpr (sizeof(T) == 4) {
+      if constexpr (VEC == 4) {
+        f32x4 t;
+        if (COH) {
+          const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
+          unsigned long long u[2] = {__hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                                     __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)};
+          __builtin_memcpy(&t, u, 16);
+        } else {
+          t = *reinterpret_cast<const f32x4*>(p);
+        }
+        out[0] = t[0]; out[1] = t[1]; out[2] = t[2]; out[3] = t[3];
+      } else if constexpr (VEC == 2) {
+        float t[2];
+        if (COH) {
+          unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+          __builtin_memcpy(t, &u, 8);
+        } else {
+          __builtin_memcpy(t, p, 8);
+        }
+        out[0] = t[0]; out[1] = t[1];
+      } else {
+        out[0] = COH ? ld_coh(p) : p[0];
+      }
+    } else {   // bf16 (read-only data: never written by the running kernel)
+      if constexpr (VEC == 4) {
+        const bf16x4 t = *reinterpret_cast<const bf16x4*>(p);
+        out[0] = (float)t[0]; out[1] = (float)t[1]; out[2] = (float)t[2]; out[3] = (float)t[3];
+      } else if constexpr (VEC == 2) {
+        const bf16x2 t = *reinterpret_cast<const bf16x2*>(p);
+        out[0] = (float)t[0]; out[1] = (float)t[1];
+      } else {
+        out[0] = (float)p[0];
+      }
+    }
+  }
 
   // LayerNorm parameters of this lane's columns (once per kernel)
   __device__ __forceinline__ void params(const SkSrc& s) {
     const int lane = threadIdx.x & 63;
     if (s.mode == 2) {
 #pragma unroll
-      for (int i = 0; i < PER; ++i) { gg[i] = (float)s.g[i * 64 + lane]; bb[i] = (float)s.b[i * 64 + lane]; }
+      for (int j = 0; j < NV; ++j) {
+        load_vec(s.g + col(j * VEC, lane), gg + j * VEC);
+        load_vec(s.b + col(j * VEC, lane), bb + j * VEC);
+      }
     }
   }
-  // request rows base, base + 4, base + 8, base + 12 (clamped to R - 1): nothing is waited for
+  // request rows base, base + STRIDE, ... (RU rows, clamped to R - 1): nothing is waited for
   __device__ __forceinline__ void load(const SkSrc& s, int R, int base) {
     const int lane = threadIdx.x & 63;
     if (s.mode == 0) {
       int tok[RU], pos[RU];
 #pragma unroll
       for (int u = 0; u < RU; ++u) {
-        const int r = min(base + 4 * u, R - 1);
+        const int r = min(base + STRIDE * u, R - 1);
         tok[u] = s.tok[r]; pos[u] = s.pos[r];
       }
       const float sc = sqrtf((float)d);
@@ -67,15 +117,20 @@ struct SkHidden {
         const bf16* e = s.E + (size_t)tok[u] * d;
         const float* p = s.pe + (size_t)pos[u] * d;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) v[u][i] = (float)e[i * 64 + lane] * sc + p[i * 64 + lane];
+        for (int j = 0; j < NV; ++j) {
+          float ev[VEC], pv[VEC];
+          load_vec(e + col(j * VEC, lane), ev);
+          SkHidden<PER, false, RU, STRIDE>::load_vec(p + col(j * VEC, lane), pv);
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) v[u][j * VEC + i] = ev[i] * sc + pv[i];
+        }
       }
     } else {
 #pragma unroll
       for (int u = 0; u < RU; ++u) {
-        const int r = min(base + 4 * u, R - 1);
+        const int r = min(base + STRIDE * u, R - 1);
 #pragma unroll
-        for (int i = 0; i < PER; ++i)
-          v[u][i] = COH ? ld_coh(s.xs + (size_t)r * d + i * 64 + lane) : s.xs[(size_t)r * d + i * 64 + lane];
+        for (int j = 0; j < NV; ++j) load_vec(s.xs + (size_t)r * d + col(j * VEC, lane), v[u] + j * VEC);
       }
     }
   }
@@ -106,16 +161,30 @@ struct SkHidden {
     }
 #pragma unroll
     for (int u = 0; u < RU; ++u) {
-      const int r = base + 4 * u;
+      const int r = base + STRIDE * u;
       if (r < nrows) {
         const bool real = r < R;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) {
-          const int c = i * 64 + lane;
-          const float val = real ? v[u][i] : 0.f;
-          if (want_hb) hb[r * pitch + c] = (bf16)val;
-          if (c >= n0 && c < n0 + 16) hown[r * 16 + c - n0] = val;
-          if (c >= n0b && c < n0b + 16) hown[kSkRows * 16 + r * 16 + c - n0b] = val;
+        for (int j = 0; j < NV; ++j) {
+          const int c0 = col(j * VEC, lane);
+          float val[VEC];
+#pragma unroll
+          for (int i = 0; i < VEC; ++i) val[i] = real ? v[u][j * VEC + i] : 0.f;
+          if (want_hb) {
+            bf16 packed[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) packed[i] = (bf16)val[i];
+            __builtin_memcpy(hb + r * pitch + c0, packed, 2 * VEC);   // 2*VEC-byte aligned: pitch, c0 multiples of VEC
+          }
+          // the 16-column slices start at multiples of 16, so a lane's VEC columns are in or out together
+          if (c0 >= n0 && c0 < n0 + 16) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) hown[r * 16 + c0 - n0 + i] = val[i];
+          }
+          if (c0 >= n0b && c0 < n0b + 16) {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) hown[kSkRows * 16 + r * 16 + c0 - n0b + i] = val[i];
+          }
         }
       }
     }
@@ -126,6 +195,13 @@ template <int PER, bool COH = false>
 __device__ __forceinline__ void sk_hidden(const SkSrc& s, int R, int nrows, bf16* hb, float* hown, int n0,
                                           bool want_hb, int n0b = -64) {
   const int wave = (threadIdx.x >> 6) & 3;
+  if (PER <= 8 && nrows > 16) {   // eight rows per wave at once: still one round trip for 32 rows
+    SkHidden<PER, COH, 8> hs;
+    hs.params(s);
+    hs.load(s, R, wave);
+    hs.finish(s, R, nrows, wave, hb, hown, n0, want_hb, n0b);
+    return;
+  }
   SkHidden<PER, COH> hs;
   hs.params(s);
   for (int base = wave; base < nrows; base += 16) {
