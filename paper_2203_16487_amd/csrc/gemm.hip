@@ -281,18 +281,13 @@ hipError_t gemm_enc_qkv(hipStream_t st, const bf16* A, const bf16* W, int M, int
 // per row {rstd, -mean * rstd}, per column folded constants, fused multiply-adds.
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-// Sums over aligned groups of 2, 4 or 8 neighbouring lanes with DPP moves (no LDS round trip):
-// swap within pairs, swap pairs within quads, mirror within groups of 8.
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
-}
+// Sums over aligned groups of 2, 4 or 8 neighbouring lanes with DPP moves (no LDS round trip).
 template <int LANES>
 __device__ __forceinline__ float group_sum(float v) {
   static_assert(LANES == 2 || LANES == 4 || LANES == 8, "group size");
-  v += dpp_move<0xB1>(v);                     // quad_perm [1,0,3,2]
-  if (LANES >= 4) v += dpp_move<0x4E>(v);     // quad_perm [2,3,0,1]
-  if (LANES >= 8) v += dpp_move<0x141>(v);    // row_half_mirror: lane i <-> 7 - i
+  v += dpp_f<kDppSwap1>(v);
+  if (LANES >= 4) v += dpp_f<kDppSwap2>(v);
+  if (LANES >= 8) v += dpp_f<kDppHalfMirror>(v);
   return v;
 }
 

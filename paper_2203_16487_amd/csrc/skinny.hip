@@ -71,7 +71,7 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
   // the block's 16 columns of the sublayer's input (for the residual add) are requested now
   // (rows wave, wave + 8, ... of every wave) and normalised after the attention, whose own
   // requests travel at the same time
-  SkHidden<PER, false, 4, kSkAttnWaves> hs;
+  SkHidden<PER, false, TWO ? 4 : 2, kSkAttnWaves> hs;
   if (kwave) sk_wload<steps>(W, d, n0, d, k0, wf);
   hs.params(resid);
   hs.load(resid, R, wave);
