@@ -255,6 +255,8 @@ __device__ __forceinline__ void sk_zero(f32x4 (&acc)[2]) {
 }
 
 // Sum the 4 waves' partial tiles (fixed order) and hand every output (m, n local) to f.
+// Thread t < 256 gets column n = t % 16 of rows m = t / 16 and t / 16 + 16 (callers prefetch what
+// their f reads from memory for exactly these).
 template <class F>
 __device__ __forceinline__ void sk_reduce(const f32x4 (&acc)[2], float* red, int R, F&& f) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
