@@ -206,9 +206,11 @@ __global__ __launch_bounds__(kSkThreads) void sk_draft_logit_kernel(SkSrc src, i
                                                                     float* __restrict__ zd_out) {
   extern __shared__ __attribute__((aligned(16))) char sk_smem[];
   SkLds<PER> L(sk_smem);
+  SkDraft<PER> dr;
+  sk_draft_fetch<PER>(dr, R, E, V, row_draft);
   sk_hidden<PER>(src, R, R > 16 ? 32 : 16, L.hb, L.hown, -64, true);
   __syncthreads();
-  sk_draft_logit<PER>(L.hb, R, E, V, row_draft, [&](int row, float v) { zd_out[row] = v; });
+  sk_draft_logit<PER>(dr, L.hb, R, [&](int row, float v) { zd_out[row] = v; });
 }
 
 // One block = 64 vocabulary columns (16 per wave, whole K per wave), one partial record per row.

@@ -282,23 +282,40 @@ __device__ __forceinline__ void sk_reduce(const f32x4 (&acc)[2], float* red, int
 // Logit of the draft each row scores: D[i][j] = E[draft of row 16t+i] . h[16t+j] (wave t < 2)
 // with the same instruction and k order as the vocabulary projection, hence bit-identical to
 // the element the projection produces for that (row, column); the diagonal is kept.
+// Two parts: sk_draft_fetch requests the embedding rows of the drafts (first the draft ids,
+// then the rows: two round trips that run while the caller's prologue does), sk_draft_logit
+// multiplies once the hidden rows are in LDS.
+template <int PER>
+struct SkDraft {
+  static constexpr int kSteps = 2 * PER;   // d / 32
+  bf16x8 wf[kSteps];
+  bool has;
+};
+template <int PER>
+__device__ __forceinline__ void sk_draft_fetch(SkDraft<PER>& dr, int R, const bf16* __restrict__ E, int V,
+                                               const int* __restrict__ row_draft) {
+  constexpr int d = 64 * PER;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
+  dr.has = false;
+  if (wave >= 2) return;
+  const int row = wave * 16 + lq;
+  const int tok = row_draft[min(row, R - 1)];
+  dr.has = row < R && tok >= 0 && tok < V;
+  const bf16* wp = E + (size_t)(dr.has ? tok : 0) * d + 8 * g;
+#pragma unroll
+  for (int s = 0; s < SkDraft<PER>::kSteps; ++s) dr.wf[s] = *reinterpret_cast<const bf16x8*>(wp + s * 32);
+}
 template <int PER, class Out>
-__device__ __forceinline__ void sk_draft_logit(const bf16* hb, int R, const bf16* __restrict__ E, int V,
-                                               const int* __restrict__ row_draft, Out&& out) {
+__device__ __forceinline__ void sk_draft_logit(const SkDraft<PER>& dr, const bf16* hb, int R, Out&& out) {
   constexpr int d = 64 * PER, pitch = d + kSkPad;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
   if (wave >= 2) return;
-  const int t = wave;
-  const int row = t * 16 + lq;
-  const int tok = row < R ? row_draft[row] : -1;
-  const bool has = tok >= 0 && tok < V;
-  const bf16* wp = E + (size_t)(has ? tok : 0) * d + 8 * g;
+  const int row = wave * 16 + lq;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 8
-  for (int s = 0; s < d / 32; ++s) {
-    bf16x8 wf = *reinterpret_cast<const bf16x8*>(wp + s * 32);
+#pragma unroll
+  for (int s = 0; s < SkDraft<PER>::kSteps; ++s) {
     bf16x8 hf = *reinterpret_cast<const bf16x8*>(hb + row * pitch + s * 32 + 8 * g);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, hf, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dr.wf[s], hf, acc, 0, 0, 0);
   }
   mfma_settle(acc);
   // D[i][j]: this lane holds j = lq, i = 4g + r; diagonal i = j  <=>  g == lq/4, r = lq%4
@@ -306,7 +323,7 @@ __device__ __forceinline__ void sk_draft_logit(const bf16* hb, int R, const bf16
     float v = 0.f;
 #pragma unroll
     for (int r = 0; r < 4; ++r) if (r == (lq & 3)) v = acc[r];
-    out(row, has ? v : kNegInf);
+    out(row, dr.has ? v : kNegInf);
   }
 }
 
