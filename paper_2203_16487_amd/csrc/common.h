@@ -66,6 +66,10 @@ __device__ __forceinline__ int wave_max_i(int v) {
   return v;
 }
 
+// Workgroup barrier that orders LDS traffic only: __syncthreads() also waits for every global
+// load in flight (vmcnt(0)), which serialises requests a kernel issued early on purpose.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Wait states between the last MFMA of a chain and ordinary vector instructions that read its
 // result.  Seen on this toolchain: when a branch separates the two, the required wait states
 // are not always inserted and the last result registers are read before they are written

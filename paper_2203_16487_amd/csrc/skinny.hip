@@ -77,6 +77,10 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
   const bool kwave = wave < 4;                 // the four waves that split K of the O-projection
   const int k0 = (wave & 3) * (d / 4);
   bf16x8 wf[steps];
+  // hb receives the attention output of every (sequence, head) pair; rows beyond R stay zero
+  for (int idx = threadIdx.x; idx < (TWO ? 32 : 16) * pitch / 8; idx += 64 * kSkAttnWaves)
+    reinterpret_cast<uint4*>(L.hb)[idx] = make_uint4(0, 0, 0, 0);
+  lds_barrier();   // (not __syncthreads: nothing below may wait for the requests that follow)
   // the block's 16 columns of the sublayer's input (for the residual add) are requested now
   // (rows wave, wave + 8, ... of every wave) and normalised after the attention, whose own
   // requests travel at the same time
@@ -85,11 +89,7 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
   const float bias_n = (float)bias[n0 + (threadIdx.x & 15)];   // for the epilogue (sk_reduce: column threadIdx % 16)
   hs.params(resid);
   hs.load(resid, R, wave);
-  // attention output of every (sequence, head) pair -> hb (bf16 [32][d]); rows >= R zero.
   // One pair per wave: eight pairs are in flight at once.
-  for (int idx = threadIdx.x; idx < (TWO ? 32 : 16) * pitch / 8; idx += 64 * kSkAttnWaves)
-    reinterpret_cast<uint4*>(L.hb)[idx] = make_uint4(0, 0, 0, 0);
-  __syncthreads();
   for (int p = wave; p < a.B * a.H; p += kSkAttnWaves) {
     const int b = p / a.H, h = p - b * a.H;
     constexpr int NQT = TWO ? 2 : 1;   // at most 16 rows in all: one query tile
