@@ -37,7 +37,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_qkv_kernel(SkSrc src, int R, co
   sk_wload<steps>(W, d, n0, 3 * d, k0, wf);
   // what the epilogue reads from memory for this thread's outputs (sk_reduce: column
   // threadIdx % 16, rows threadIdx / 16 and + 16) is requested now, not after the product
-  const float bias_n = (float)bias[n0 + (threadIdx.x & 15)];
+  const bf16 bias_n = bias[n0 + (threadIdx.x & 15)];
   int rb[2], rp[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_qkv_kernel(SkSrc src, int R, co
          [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); }, acc);
   sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
     const int n = n0 + nl;
-    v += bias_n;
+    v += (float)bias_n;
     const int part = n / d, c = n - part * d;
     if (part == 0) { q[(size_t)m * d + c] = (bf16)v; return; }
     const int b = rb[m >> 4];
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
   // requests travel at the same time
   SkHidden<PER, false, TWO ? 4 : 2, kSkAttnWaves> hs;
   if (kwave) sk_wload<steps>(W, d, n0, d, k0, wf);
-  const float bias_n = (float)bias[n0 + (threadIdx.x & 15)];   // for the epilogue (sk_reduce: column threadIdx % 16)
+  const bf16 bias_n = bias[n0 + (threadIdx.x & 15)];   // for the epilogue (sk_reduce: column threadIdx % 16)
   hs.params(resid);
   hs.load(resid, R, wave);
   // One pair per wave: eight pairs are in flight at once.
@@ -120,7 +120,7 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
            [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); }, acc);
   const float* hown = L.hown;
   sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
-    xs_out[(size_t)m * d + n0 + nl] = v + bias_n + hown[m * 16 + nl];
+    xs_out[(size_t)m * d + n0 + nl] = v + (float)bias_n + hown[m * 16 + nl];
   });
 }
 
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_proj_kernel(SkSrc src, int R, c
   const int k0 = wave * (d / 4);
   bf16x8 wf[steps];
   sk_wload<steps>(W, d, n0, N, k0, wf);
-  const float bias_n = (float)bias[min(n0 + (int)(threadIdx.x & 15), N - 1)];   // for the epilogue (column threadIdx % 16)
+  const bf16 bias_n = bias[min(n0 + (int)(threadIdx.x & 15), N - 1)];   // for the epilogue (column threadIdx % 16)
   sk_hidden<PER>(src, R, TWO ? 32 : 16, L.hb, L.hown, -64, true);
   __syncthreads();
   f32x4 acc[2];
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_proj_kernel(SkSrc src, int R, c
          [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); }, acc);
   sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
     if (n0 + nl < N) {
-      v += bias_n;
+      v += (float)bias_n;
       if (relu) v = fmaxf(v, 0.f);
       out[(size_t)m * N + n0 + nl] = (bf16)v;
     }
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_ffn2_kernel(SkSrc resid, int R,
   const int k0 = wave * (F / 4);
   bf16x8 wf[S1], hf[S1];
   sk_wload<S1>(W, F, n0, d, k0, wf);
-  const float bias_n = (float)bias[n0 + (threadIdx.x & 15)];   // for the epilogue (sk_reduce: column threadIdx % 16)
+  const bf16 bias_n = bias[n0 + (threadIdx.x & 15)];   // for the epilogue (sk_reduce: column threadIdx % 16)
   // first-tile activations of the same k range, straight from memory (same operand layout)
   {
     const bf16* hp = hid + (size_t)min(lq, R - 1) * F + k0 + 8 * g;
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_ffn2_kernel(SkSrc resid, int R,
   __syncthreads();
   const float* hown = L.hown;
   sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
-    xs_out[(size_t)m * d + n0 + nl] = v + bias_n + hown[m * 16 + nl];
+    xs_out[(size_t)m * d + n0 + nl] = v + (float)bias_n + hown[m * 16 + nl];
   });
 }
 

@@ -45,7 +45,7 @@ struct SkHidden {
   static constexpr int d = 64 * PER, pitch = d + kSkPad;
   static constexpr int VEC = PER % 4 == 0 ? 4 : (PER % 2 == 0 ? 2 : 1);
   static constexpr int NV = PER / VEC;                      // vector loads per row and lane
-  float gg[PER], bb[PER];
+  bf16 gg[PER], bb[PER];   // kept as loaded: a conversion here would wait for the load inside the branch
   float v[RU][PER];
   // column of element i of this lane
   __device__ __forceinline__ static int col(int i, int lane) { return (i / VEC) * (64 * VEC) + lane * VEC + i % VEC; }
@@ -90,14 +90,14 @@ struct SkHidden {
     }
   }
 
-  // LayerNorm parameters of this lane's columns (once per kernel)
+  // LayerNorm parameters of this lane's columns (once per kernel): requested, not waited for
   __device__ __forceinline__ void params(const SkSrc& s) {
     const int lane = threadIdx.x & 63;
     if (s.mode == 2) {
 #pragma unroll
       for (int j = 0; j < NV; ++j) {
-        load_vec(s.g + col(j * VEC, lane), gg + j * VEC);
-        load_vec(s.b + col(j * VEC, lane), bb + j * VEC);
+        __builtin_memcpy(gg + j * VEC, s.g + col(j * VEC, lane), 2 * VEC);
+        __builtin_memcpy(bb + j * VEC, s.b + col(j * VEC, lane), 2 * VEC);
       }
     }
   }
@@ -157,7 +157,7 @@ struct SkHidden {
 #pragma unroll
       for (int u = 0; u < RU; ++u)
 #pragma unroll
-        for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean[u]) * rstd[u] * gg[i] + bb[i];
+        for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean[u]) * rstd[u] * (float)gg[i] + (float)bb[i];
     }
 #pragma unroll
     for (int u = 0; u < RU; ++u) {
