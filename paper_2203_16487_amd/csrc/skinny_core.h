@@ -45,8 +45,17 @@ struct SkHidden {
   static constexpr int d = 64 * PER, pitch = d + kSkPad;
   static constexpr int VEC = PER % 4 == 0 ? 4 : (PER % 2 == 0 ? 2 : 1);
   static constexpr int NV = PER / VEC;                      // vector loads per row and lane
-  bf16 gg[PER], bb[PER];   // kept as loaded: a conversion here would wait for the load inside the branch
+  // LayerNorm parameters exactly as loaded (whole 2*VEC-byte words): taking them apart where
+  // they are requested would make the kernel wait for them there
+  template <int N> struct RawT { typedef unsigned short type; };
+  template <> struct RawT<2> { typedef unsigned type; };
+  template <> struct RawT<4> { typedef unsigned long long type; };
+  typedef typename RawT<VEC>::type RawV;
+  RawV gg[NV], bb[NV];
   float v[RU][PER];
+  __device__ __forceinline__ static float raw_at(const RawV (&p)[NV], int i) {
+    return __builtin_bit_cast(float, (unsigned)((p[i / VEC] >> (16 * (i % VEC))) & 0xffffu) << 16);   // bf16 -> fp32
+  }
   // column of element i of this lane
   __device__ __forceinline__ static int col(int i, int lane) { return (i / VEC) * (64 * VEC) + lane * VEC + i % VEC; }
 
@@ -96,8 +105,8 @@ struct SkHidden {
     if (s.mode == 2) {
 #pragma unroll
       for (int j = 0; j < NV; ++j) {
-        __builtin_memcpy(gg + j * VEC, s.g + col(j * VEC, lane), 2 * VEC);
-        __builtin_memcpy(bb + j * VEC, s.b + col(j * VEC, lane), 2 * VEC);
+        gg[j] = *reinterpret_cast<const RawV*>(s.g + col(j * VEC, lane));
+        bb[j] = *reinterpret_cast<const RawV*>(s.b + col(j * VEC, lane));
       }
     }
   }
@@ -157,7 +166,7 @@ struct SkHidden {
 #pragma unroll
       for (int u = 0; u < RU; ++u)
 #pragma unroll
-        for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean[u]) * rstd[u] * (float)gg[i] + (float)bb[i];
+        for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean[u]) * rstd[u] * raw_at(gg, i) + raw_at(bb, i);
     }
 #pragma unroll
     for (int u = 0; u < RU; ++u) {
