@@ -77,10 +77,8 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
   const bool kwave = wave < 4;                 // the four waves that split K of the O-projection
   const int k0 = (wave & 3) * (d / 4);
   bf16x8 wf[steps];
-  // hb receives the attention output of every (sequence, head) pair; rows beyond R stay zero
-  for (int idx = threadIdx.x; idx < (TWO ? 32 : 16) * pitch / 8; idx += 64 * kSkAttnWaves)
-    reinterpret_cast<uint4*>(L.hb)[idx] = make_uint4(0, 0, 0, 0);
-  lds_barrier();   // (not __syncthreads: nothing below may wait for the requests that follow)
+  // hb receives the attention output of every (sequence, head) pair.  Its rows beyond R are
+  // left as they are: an activation row only feeds its own output row, and those are dropped.
   // the block's 16 columns of the sublayer's input (for the residual add) are requested now
   // (rows wave, wave + 8, ... of every wave) and normalised after the attention, whose own
   // requests travel at the same time

@@ -30,8 +30,10 @@ struct SkLds {
   }
 };
 
-// Hidden state of the R rows = what `src` describes; bf16 copy of all columns -> hb (rows
-// R .. nrows-1 zero), fp32 copy of columns [n0, n0 + 16) -> hown (for residual adds).
+// Hidden state of the R rows = what `src` describes; bf16 copy of all columns -> hb, fp32 copy
+// of columns [n0, n0 + 16) -> hown (for residual adds).  Rows R .. nrows-1 of hb / hown are not
+// written: in the products that follow an activation row only feeds its own output row, and
+// every consumer drops output rows >= R.
 // A wave takes rows base, base + STRIDE, ...; it requests the data of RU of them (and the
 // LayerNorm parameters, once) before it reduces any, so the prologue costs one memory round
 // trip for RU rows per wave.
@@ -137,63 +139,81 @@ struct SkHidden {
     } else {
 #pragma unroll
       for (int u = 0; u < RU; ++u) {
-        const int r = min(base + STRIDE * u, R - 1);
+        const int r = base + STRIDE * u;
+        if (r < R) {   // (same for the whole wave)
 #pragma unroll
-        for (int j = 0; j < NV; ++j) load_vec(s.xs + (size_t)r * d + col(j * VEC, lane), v[u] + j * VEC);
+          for (int j = 0; j < NV; ++j) load_vec(s.xs + (size_t)r * d + col(j * VEC, lane), v[u] + j * VEC);
+        }
       }
     }
   }
-  // normalise the requested rows and write them out
+  // normalise the requested rows and write them out (rows >= R: nothing, see above)
   __device__ __forceinline__ void finish(const SkSrc& s, int R, int nrows, int base, bf16* hb, float* hown, int n0,
                                          bool want_hb, int n0b) {
     const int lane = threadIdx.x & 63;
+    const int rmax = min(R, nrows);
     if (s.mode == 2) {
-      float mean[RU], rstd[RU];
+      if (base + STRIDE * 2 < rmax) {
+        // more than two rows of this wave are in use: all RU are reduced (the unused ones on
+        // whatever their registers hold; they are not written), one kind of reduction after the
+        // other, so that the independent reductions overlap
+        float mean[RU], rstd[RU];
 #pragma unroll
-      for (int u = 0; u < RU; ++u) {
-        float sum = 0.f;
+        for (int u = 0; u < RU; ++u) {
+          float sum = 0.f;
 #pragma unroll
-        for (int i = 0; i < PER; ++i) sum += v[u][i];
-        mean[u] = wave_sum(sum) / (float)d;
+          for (int i = 0; i < PER; ++i) sum += v[u][i];
+          mean[u] = wave_sum(sum) / (float)d;
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+          float q = 0.f;
+#pragma unroll
+          for (int i = 0; i < PER; ++i) { float t = v[u][i] - mean[u]; q += t * t; }
+          rstd[u] = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+        }
+#pragma unroll
+        for (int u = 0; u < RU; ++u)
+#pragma unroll
+          for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean[u]) * rstd[u] * raw_at(gg, i) + raw_at(bb, i);
+      } else {
+#pragma unroll
+        for (int u = 0; u < RU; ++u) {
+          if (base + STRIDE * u >= rmax) continue;   // (same for the whole wave)
+          float sum = 0.f;
+#pragma unroll
+          for (int i = 0; i < PER; ++i) sum += v[u][i];
+          const float mean = wave_sum(sum) / (float)d;
+          float q = 0.f;
+#pragma unroll
+          for (int i = 0; i < PER; ++i) { float t = v[u][i] - mean; q += t * t; }
+          const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+#pragma unroll
+          for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean) * rstd * raw_at(gg, i) + raw_at(bb, i);
+        }
       }
-#pragma unroll
-      for (int u = 0; u < RU; ++u) {
-        float q = 0.f;
-#pragma unroll
-        for (int i = 0; i < PER; ++i) { float t = v[u][i] - mean[u]; q += t * t; }
-        rstd[u] = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
-      }
-#pragma unroll
-      for (int u = 0; u < RU; ++u)
-#pragma unroll
-        for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean[u]) * rstd[u] * raw_at(gg, i) + raw_at(bb, i);
     }
 #pragma unroll
     for (int u = 0; u < RU; ++u) {
       const int r = base + STRIDE * u;
-      if (r < nrows) {
-        const bool real = r < R;
+      if (r >= rmax) continue;
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
-          const int c0 = col(j * VEC, lane);
-          float val[VEC];
+      for (int j = 0; j < NV; ++j) {
+        const int c0 = col(j * VEC, lane);
+        if (want_hb) {
+          bf16 packed[VEC];
 #pragma unroll
-          for (int i = 0; i < VEC; ++i) val[i] = real ? v[u][j * VEC + i] : 0.f;
-          if (want_hb) {
-            bf16 packed[VEC];
+          for (int i = 0; i < VEC; ++i) packed[i] = (bf16)v[u][j * VEC + i];
+          __builtin_memcpy(hb + r * pitch + c0, packed, 2 * VEC);   // 2*VEC-byte aligned: pitch, c0 multiples of VEC
+        }
+        // the 16-column slices start at multiples of 16, so a lane's VEC columns are in or out together
+        if (c0 >= n0 && c0 < n0 + 16) {
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) packed[i] = (bf16)val[i];
-            __builtin_memcpy(hb + r * pitch + c0, packed, 2 * VEC);   // 2*VEC-byte aligned: pitch, c0 multiples of VEC
-          }
-          // the 16-column slices start at multiples of 16, so a lane's VEC columns are in or out together
-          if (c0 >= n0 && c0 < n0 + 16) {
+          for (int i = 0; i < VEC; ++i) hown[r * 16 + c0 - n0 + i] = v[u][j * VEC + i];
+        }
+        if (c0 >= n0b && c0 < n0b + 16) {
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) hown[r * 16 + c0 - n0 + i] = val[i];
-          }
-          if (c0 >= n0b && c0 < n0b + 16) {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) hown[kSkRows * 16 + r * 16 + c0 - n0b + i] = val[i];
-          }
+          for (int i = 0; i < VEC; ++i) hown[kSkRows * 16 + r * 16 + c0 - n0b + i] = v[u][j * VEC + i];
         }
       }
     }
