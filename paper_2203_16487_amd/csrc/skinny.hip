@@ -195,26 +195,13 @@ __global__ __launch_bounds__(kSkThreads) void sk_ffn2_kernel(SkSrc resid, int R,
 }
 
 // ------------------------------------------------------------------------------------ vocabulary
-// Draft logits first (one block, one wave per 16 rows): D[i][j] = E[draft of row 16t+i] . h[16t+j]
-// with the same instruction and k order as the projection below, hence bit-identical to the
-// element the projection produces for that (row, column); the diagonal is kept.
-template <int PER>
-__global__ __launch_bounds__(kSkThreads) void sk_draft_logit_kernel(SkSrc src, int R, const bf16* __restrict__ E,
-                                                                    int V, const int* __restrict__ row_draft,
-                                                                    float* __restrict__ zd_out) {
-  extern __shared__ __attribute__((aligned(16))) char sk_smem[];
-  SkLds<PER> L(sk_smem);
-  SkDraft<PER> dr;
-  sk_draft_fetch<PER>(dr, R, E, V, row_draft);
-  sk_hidden<PER>(src, R, R > 16 ? 32 : 16, L.hb, L.hown, -64, true);
-  __syncthreads();
-  sk_draft_logit<PER>(dr, L.hb, R, [&](int row, float v) { zd_out[row] = v; });
-}
-
-// One block = 64 vocabulary columns (16 per wave, whole K per wave), one partial record per row.
+// Every block first forms the draft logits itself (waves 0 and 1, the sk_draft_logit sequence on
+// its own copy of the hidden rows: the same bits in every block, and the bits its own tile would
+// hold for that column), so the rank counts need no launch of their own before this one.
 template <int PER, bool TWO>
 __global__ __launch_bounds__(kSkThreads) void sk_vocab_kernel(SkSrc src, int R, const bf16* __restrict__ E, int V,
-                                                              const float* __restrict__ zd_row,
+                                                              const int* __restrict__ row_draft,
+                                                              float* __restrict__ zd_out,
                                                               float* __restrict__ part, int n_tiles,
                                                               float* __restrict__ logits) {
   extern __shared__ __attribute__((aligned(16))) char sk_smem[];
@@ -225,19 +212,25 @@ __global__ __launch_bounds__(kSkThreads) void sk_vocab_kernel(SkSrc src, int R, 
   constexpr int steps = d / 32, S1 = steps < kSkW ? steps : kSkW;
   bf16x8 wf[S1];
   sk_wload<S1>(E, d, n0, V, 0, wf);
-  float zd[2];   // requested now: the draft logits come from the kernel just before this one
-#pragma unroll
-  for (int t = 0; t < 2; ++t) zd[t] = zd_row[min(t * 16 + lq, R - 1)];
+  SkDraft<PER> dr;
+  sk_draft_fetch<PER>(dr, R, E, V, row_draft);
   sk_hidden<PER>(src, R, TWO ? 32 : 16, L.hb, L.hown, -64, true);
   __syncthreads();
+  float* zds = L.hown;   // [32] (the residual slices are not used by this kernel)
+  sk_draft_logit<PER>(dr, L.hb, R, [&](int row, float v) {
+    zds[row] = v;
+    if (blockIdx.x == 0) zd_out[row] = v;
+  });
   f32x4 acc[2];
   sk_zero(acc);
   const bf16* hb = L.hb;
   auto getB = [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); };
   sk_mma<S1, TWO>(wf, 0, getB, acc);
   sk_mma_tail<steps, TWO>(E, d, n0, V, 0, getB, acc);
+  __syncthreads();
+  float zd[2];
 #pragma unroll
-  for (int t = 0; t < 2; ++t) zd[t] = (t * 16 + lq < R) ? zd[t] : kNegInf;
+  for (int t = 0; t < 2; ++t) zd[t] = (t * 16 + lq < R) ? zds[t * 16 + lq] : kNegInf;
   sk_vocab_tile(acc, n0, V, R, zd, L.red, part, n_tiles, blockIdx.x, logits);
 }
 
@@ -289,7 +282,6 @@ hipError_t skinny_init(int d) {
   SK_DISPATCH(d, {
     if ((e = sk_init_rows<PER, false>()) != hipSuccess) return e;
     if ((e = sk_init_rows<PER, true>()) != hipSuccess) return e;
-    if ((e = sk_attr<PER>(sk_draft_logit_kernel<PER>)) != hipSuccess) return e;
   });
   return e;
 }
@@ -329,10 +321,8 @@ hipError_t skinny_vocab(hipStream_t st, const SkSrc& src, int R, int d, const bf
                         float* zd_row, float* part, float* logits) {
   const int n_tiles = (V + 63) / 64;
   SK_DISPATCH(d, {
-    hipLaunchKernelGGL(sk_draft_logit_kernel<PER>, dim3(1), dim3(kSkThreads), SkLds<PER>::kBytes, st, src, R, E, V,
-                       row_draft, zd_row);
     SK_ROWS(R, hipLaunchKernelGGL((sk_vocab_kernel<PER, TWO>), dim3(n_tiles), dim3(kSkThreads), SkLds<PER>::kBytes,
-                                  st, src, R, E, V, zd_row, part, n_tiles, logits));
+                                  st, src, R, E, V, row_draft, zd_row, part, n_tiles, logits));
   });
   return hipGetLastError();
 }
