@@ -358,14 +358,32 @@ struct RowMerge {
   int arg, cnt;
 };
 __device__ __forceinline__ RowMerge merge_row(const float* __restrict__ pr, int n_tiles, int lane) {
+  constexpr int kHeld = 8;   // records per lane kept in registers: one pass over memory up to 512 tiles
+  const bool held = n_tiles <= 64 * kHeld;
+  f32x4 rec[kHeld];
   float m = kNegInf;
   int am = 0x7fffffff, cnt = 0;
-  for (int t = lane; t < n_tiles; t += 64) {
-    const f32x4 p = *reinterpret_cast<const f32x4*>(pr + (size_t)t * kPartF);
-    const float tm = p[0];
-    const int ti = __float_as_int(p[1]);
-    if (tm > m || (tm == m && ti < am)) { m = tm; am = ti; }
-    cnt += __float_as_int(p[3]);
+  if (held) {
+#pragma unroll
+    for (int i = 0; i < kHeld; ++i)   // (clamped, so that no load sits behind a lane's own branch)
+      rec[i] = *reinterpret_cast<const f32x4*>(pr + (size_t)min(lane + 64 * i, n_tiles - 1) * kPartF);
+#pragma unroll
+    for (int i = 0; i < kHeld; ++i) {
+      if (lane + 64 * i < n_tiles) {
+        const float tm = rec[i][0];
+        const int ti = __float_as_int(rec[i][1]);
+        if (tm > m || (tm == m && ti < am)) { m = tm; am = ti; }
+        cnt += __float_as_int(rec[i][3]);
+      }
+    }
+  } else {
+    for (int t = lane; t < n_tiles; t += 64) {
+      const f32x4 p = *reinterpret_cast<const f32x4*>(pr + (size_t)t * kPartF);
+      const float tm = p[0];
+      const int ti = __float_as_int(p[1]);
+      if (tm > m || (tm == m && ti < am)) { m = tm; am = ti; }
+      cnt += __float_as_int(p[3]);
+    }
   }
   const float gm = wave_max(m);
   int cand = (m == gm) ? am : 0x7fffffff;
@@ -375,9 +393,15 @@ __device__ __forceinline__ RowMerge merge_row(const float* __restrict__ pr, int 
     cnt += __shfl_xor(cnt, o, 64);
   }
   float se = 0.f;
-  for (int t = lane; t < n_tiles; t += 64) {
-    const f32x4 p = *reinterpret_cast<const f32x4*>(pr + (size_t)t * kPartF);
-    se += p[2] * __expf(p[0] - gm);
+  if (held) {
+#pragma unroll
+    for (int i = 0; i < kHeld; ++i)
+      if (lane + 64 * i < n_tiles) se += rec[i][2] * __expf(rec[i][0] - gm);
+  } else {
+    for (int t = lane; t < n_tiles; t += 64) {
+      const f32x4 p = *reinterpret_cast<const f32x4*>(pr + (size_t)t * kPartF);
+      se += p[2] * __expf(p[0] - gm);
+    }
   }
   se = wave_sum(se);
   return RowMerge{gm, gm + __logf(se), cand, cnt};
