@@ -85,6 +85,17 @@ def test_odd_and_maximal_widths():
         ses.close()
 
 
+def test_large_vocabulary_many_tiles():
+    """V = 70001: more vocabulary tiles per row than the row merge holds in registers (547 tiles of
+    128 columns on the general path, 1094 of 64 on the small-batch path), ragged last tile."""
+    desc = synth.ModelDesc(0, 1, 128, 2, 256, 70001, 16, 48).resolved()
+    for B, k, seed in ((2, 4, 41), (9, 4, 42)):   # 10 rows: small-batch kernels; 45 rows: general kernels
+        case = cases.make_verify_case(desc, seed=seed, B=B, S=9, k=k, beta=3, tau=1.0, len_lo=0, len_hi=12,
+                                      drafts="greedy", ragged_src=True, std=0.08)
+        ses, _ = check_case(case, label=f"V=70001 B={B}")
+        ses.close()
+
+
 def test_kv_append_rollback_and_idempotence():
     import gpu_harness as gh
     from paper_2203_16487_amd import binding as sd
