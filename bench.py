@@ -223,6 +223,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-batch1", action="store_true")
+    ap.add_argument("--batch1-only", action="store_true",
+                    help="run only the single-sequence verify step (the `batch1` object of the usual line) and "
+                         "print it: the command behind profiles/verify_step_batch1.kernel_stats.md")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device-to-device copy of 256 MiB, five times (reference for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters), and exit")
@@ -239,6 +242,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     sd.lib()   # fails loudly if the HIP library is missing
+    if args.batch1_only:
+        print(json.dumps({"batch1": batch1_latency(sd, synth, torch, steps=args.steps)}))
+        return
     if args.copy_calibration:
         src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
