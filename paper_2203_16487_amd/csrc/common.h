@@ -3,6 +3,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// operands of __builtin_amdgcn_global_load_lds (global memory -> LDS without a register stop)
+#define SD_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
+#define SD_GLB_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
+
 namespace sd {
 
 typedef __bf16 bf16;

@@ -14,8 +14,6 @@ namespace sd {
 
 constexpr int kGemmThreads = 256;
 
-#define SD_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
-#define SD_GLB_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {

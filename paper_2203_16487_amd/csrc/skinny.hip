@@ -154,44 +154,88 @@ __global__ __launch_bounds__(kSkThreads) void sk_proj_kernel(SkSrc src, int R, c
 }
 
 // ------------------------------------------------------------------------------------ FFN2
-// xs_out = hidden(resid) + hid W2^T + bias; hid bf16 [R][F] is read straight from memory
+// xs_out = hidden(resid) + hid W2^T + bias, hid bf16 [R][F].
+// STAGED (whenever it fits: everything but 32 rows of F = 4096): the R rows of hid go to LDS
+// first, one global->LDS request of 1 KB per wave, row and 512 columns -- R * F / 512 requests per
+// block instead of one 16-byte register load per wave, k step and row tile; the products then read
+// both row tiles from LDS.  Otherwise the first tile's operands come straight from memory into
+// registers and the second tile's inside the loop.
+template <int FS, bool TWO>
+struct SkFfn2Lds {
+  static constexpr int F = 128 * FS, kPitch = F + kSkPad, kRowsMax = TWO ? 32 : 16;
+  static constexpr size_t kHid = (size_t)kRowsMax * kPitch * 2;
+  static constexpr size_t kOwn = (size_t)2 * kSkRows * 16 * 4, kRed = (size_t)4 * 16 * 33 * 4;
+  static constexpr size_t kBytes = kHid + kOwn + kRed;
+  static constexpr bool kStaged = kBytes <= 150 * 1024 && F % 512 == 0;   // whole 512-column requests
+};
+template <int PER, int FS, bool TWO>
+constexpr size_t sk_ffn2_lds_bytes() {
+  return SkFfn2Lds<FS, TWO>::kStaged ? SkFfn2Lds<FS, TWO>::kBytes : SkLds<PER>::kBytes;
+}
+
 template <int PER, int FS, bool TWO>   // FS = F / 128 = k steps per wave
 __global__ __launch_bounds__(kSkThreads) void sk_ffn2_kernel(SkSrc resid, int R, const bf16* __restrict__ hid,
                                                              const bf16* __restrict__ W,
                                                              const bf16* __restrict__ bias,
                                                              float* __restrict__ xs_out) {
   extern __shared__ __attribute__((aligned(16))) char sk_smem[];
-  SkLds<PER> L(sk_smem);
+  typedef SkFfn2Lds<FS, TWO> FL;
   constexpr int d = 64 * PER, F = 128 * FS, S1 = FS < kSkW ? FS : kSkW;
   const int n0 = blockIdx.x * 16, wave = threadIdx.x >> 6, lq = threadIdx.x & 15, g = (threadIdx.x & 63) >> 4;
   const int k0 = wave * (F / 4);
-  bf16x8 wf[S1], hf[S1];
-  sk_wload<S1>(W, F, n0, d, k0, wf);
   const bf16 bias_n = bias[n0 + (threadIdx.x & 15)];   // for the epilogue (sk_reduce: column threadIdx % 16)
-  // first-tile activations of the same k range, straight from memory (same operand layout)
-  {
-    const bf16* hp = hid + (size_t)min(lq, R - 1) * F + k0 + 8 * g;
-#pragma unroll
-    for (int u = 0; u < S1; ++u) hf[u] = *reinterpret_cast<const bf16x8*>(hp + u * 32);
-  }
-  sk_hidden<PER>(resid, R, TWO ? 32 : 16, L.hb, L.hown, n0, false);
   f32x4 acc[2];
   sk_zero(acc);
-  auto getB = [&](int t, int k) {
-    return *reinterpret_cast<const bf16x8*>(hid + (size_t)min(t * 16 + lq, R - 1) * F + k);
-  };
+  if constexpr (FL::kStaged) {
+    bf16* hidl = reinterpret_cast<bf16*>(sk_smem);
+    float* hown = reinterpret_cast<float*>(sk_smem + FL::kHid);
+    float* red = reinterpret_cast<float*>(sk_smem + FL::kHid + FL::kOwn);
+    bf16x8 wf[S1];
+    sk_wload<S1>(W, F, n0, d, k0, wf);
+    // one request = 64 lanes x 16 B = 512 columns of a row; wave w takes columns 512 w, 512 (w + 4), ...
+    for (int r = 0; r < R; ++r)
+      for (int c = wave * 512; c < F; c += 4 * 512)
+        __builtin_amdgcn_global_load_lds(SD_GLB_PTR(hid + (size_t)r * F + c + (threadIdx.x & 63) * 8),
+                                         SD_LDS_PTR(hidl + r * FL::kPitch + c), 16, 0, 0);
+    sk_hidden<PER>(resid, R, TWO ? 32 : 16, nullptr, hown, n0, false);
+    __syncthreads();   // (waits for the requests above as well)
+    auto getB = [&](int t, int k) {
+      return *reinterpret_cast<const bf16x8*>(hidl + (t * 16 + lq) * FL::kPitch + k);
+    };
+    sk_mma<S1, TWO>(wf, k0, getB, acc);
+    sk_mma_tail<FS, TWO>(W, F, n0, d, k0, getB, acc);
+    mfma_settle(acc[0], acc[1]);
+    __syncthreads();
+    sk_reduce(acc, red, R, [&](int m, int nl, float v) {
+      xs_out[(size_t)m * d + n0 + nl] = v + (float)bias_n + hown[m * 16 + nl];
+    });
+  } else {
+    SkLds<PER> L(sk_smem);
+    bf16x8 wf[S1], hf[S1];
+    sk_wload<S1>(W, F, n0, d, k0, wf);
+    // first-tile activations of the same k range, straight from memory (same operand layout)
+    {
+      const bf16* hp = hid + (size_t)min(lq, R - 1) * F + k0 + 8 * g;
 #pragma unroll
-  for (int u = 0; u < S1; ++u) {
-    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], hf[u], acc[0], 0, 0, 0);
-    if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], getB(1, k0 + u * 32 + 8 * g), acc[1], 0, 0, 0);
+      for (int u = 0; u < S1; ++u) hf[u] = *reinterpret_cast<const bf16x8*>(hp + u * 32);
+    }
+    sk_hidden<PER>(resid, R, TWO ? 32 : 16, L.hb, L.hown, n0, false);
+    auto getB = [&](int t, int k) {
+      return *reinterpret_cast<const bf16x8*>(hid + (size_t)min(t * 16 + lq, R - 1) * F + k);
+    };
+#pragma unroll
+    for (int u = 0; u < S1; ++u) {
+      acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], hf[u], acc[0], 0, 0, 0);
+      if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], getB(1, k0 + u * 32 + 8 * g), acc[1], 0, 0, 0);
+    }
+    sk_mma_tail<FS, TWO>(W, F, n0, d, k0, getB, acc);
+    mfma_settle(acc[0], acc[1]);
+    __syncthreads();
+    const float* hown = L.hown;
+    sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
+      xs_out[(size_t)m * d + n0 + nl] = v + (float)bias_n + hown[m * 16 + nl];
+    });
   }
-  sk_mma_tail<FS, TWO>(W, F, n0, d, k0, getB, acc);
-  mfma_settle(acc[0], acc[1]);
-  __syncthreads();
-  const float* hown = L.hown;
-  sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
-    xs_out[(size_t)m * d + n0 + nl] = v + (float)bias_n + hown[m * 16 + nl];
-  });
 }
 
 // ------------------------------------------------------------------------------------ vocabulary
@@ -270,9 +314,12 @@ static hipError_t sk_init_rows() {
   if ((e = sk_attr<PER>(sk_attn_o_kernel<PER, false, TWO>)) != hipSuccess) return e;
   if ((e = sk_attr<PER>(sk_attn_o_kernel<PER, true, TWO>)) != hipSuccess) return e;
   if ((e = sk_attr<PER>(sk_proj_kernel<PER, TWO>)) != hipSuccess) return e;
-  if ((e = sk_attr<PER>(sk_ffn2_kernel<PER, 2, TWO>)) != hipSuccess) return e;
-  if ((e = sk_attr<PER>(sk_ffn2_kernel<PER, 16, TWO>)) != hipSuccess) return e;
-  if ((e = sk_attr<PER>(sk_ffn2_kernel<PER, 32, TWO>)) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(sk_ffn2_kernel<PER, 2, TWO>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)sk_ffn2_lds_bytes<PER, 2, TWO>())) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(sk_ffn2_kernel<PER, 16, TWO>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)sk_ffn2_lds_bytes<PER, 16, TWO>())) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(sk_ffn2_kernel<PER, 32, TWO>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)sk_ffn2_lds_bytes<PER, 32, TWO>())) != hipSuccess) return e;
   if ((e = sk_attr<PER>(sk_vocab_kernel<PER, TWO>)) != hipSuccess) return e;
   return hipSuccess;
 }
@@ -313,8 +360,8 @@ hipError_t skinny_proj(hipStream_t st, const SkSrc& src, int R, int d, const bf1
 hipError_t skinny_ffn2(hipStream_t st, const SkSrc& resid, int R, int d, const bf16* hid, int F, const bf16* W,
                        const bf16* bias, float* xs_out) {
   SK_DISPATCH(d, SK_FFN(F, SK_ROWS(R, hipLaunchKernelGGL((sk_ffn2_kernel<PER, FS, TWO>), dim3(d / 16),
-                                                         dim3(kSkThreads), SkLds<PER>::kBytes, st, resid, R, hid, W,
-                                                         bias, xs_out))));
+                                                         dim3(kSkThreads), (sk_ffn2_lds_bytes<PER, FS, TWO>()), st, resid,
+                                                         R, hid, W, bias, xs_out))));
   return hipGetLastError();
 }
 hipError_t skinny_vocab(hipStream_t st, const SkSrc& src, int R, int d, const bf16* E, int V, const int* row_draft,
