@@ -336,7 +336,7 @@ hipError_t skinny_init(int d) {
 hipError_t skinny_qkv(hipStream_t st, const SkSrc& src, int R, int d, const bf16* W, const bf16* bias, bf16* q,
                       bf16* kc, bf16* vc, const int* row_b, const int* row_pos, int H, int Lcap) {
   SK_DISPATCH(d, SK_ROWS(R, hipLaunchKernelGGL((sk_qkv_kernel<PER, TWO>), dim3(3 * d / 16), dim3(kSkThreads),
-                                               SkLds<PER>::kBytes, st, src, R, W, bias, q, kc, vc, row_b, row_pos,
+                                               SkLds<PER>::kBytesNoAttn, st, src, R, W, bias, q, kc, vc, row_b, row_pos,
                                                H, Lcap)));
   return hipGetLastError();
 }
@@ -354,7 +354,7 @@ hipError_t skinny_attn_o(hipStream_t st, const SkSrc& resid, int R, int d, const
 hipError_t skinny_proj(hipStream_t st, const SkSrc& src, int R, int d, const bf16* W, int N, const bf16* bias,
                        bf16* out, bool relu) {
   SK_DISPATCH(d, SK_ROWS(R, hipLaunchKernelGGL((sk_proj_kernel<PER, TWO>), dim3((N + 15) / 16), dim3(kSkThreads),
-                                               SkLds<PER>::kBytes, st, src, R, W, N, bias, out, relu ? 1 : 0)));
+                                               SkLds<PER>::kBytesNoAttn, st, src, R, W, N, bias, out, relu ? 1 : 0)));
   return hipGetLastError();
 }
 hipError_t skinny_ffn2(hipStream_t st, const SkSrc& resid, int R, int d, const bf16* hid, int F, const bf16* W,
@@ -368,7 +368,7 @@ hipError_t skinny_vocab(hipStream_t st, const SkSrc& src, int R, int d, const bf
                         float* zd_row, float* part, float* logits) {
   const int n_tiles = (V + 63) / 64;
   SK_DISPATCH(d, {
-    SK_ROWS(R, hipLaunchKernelGGL((sk_vocab_kernel<PER, TWO>), dim3(n_tiles), dim3(kSkThreads), SkLds<PER>::kBytes,
+    SK_ROWS(R, hipLaunchKernelGGL((sk_vocab_kernel<PER, TWO>), dim3(n_tiles), dim3(kSkThreads), SkLds<PER>::kBytesNoAttn,
                                   st, src, R, E, V, row_draft, zd_row, part, n_tiles, logits));
   });
   return hipGetLastError();

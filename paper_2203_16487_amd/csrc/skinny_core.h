@@ -21,6 +21,7 @@ struct SkLds {
   static constexpr size_t kRed = (size_t)4 * 16 * 33 * 4;
   static constexpr size_t kVs = (size_t)kSkAttnWaves * 32 * kVtPitch * 2;
   static constexpr size_t kBytes = kHb + kOwn + kRed + kVs;
+  static constexpr size_t kBytesNoAttn = kHb + kOwn + kRed;   // kernels without attention: Vs (last) left out
   bf16* hb; float* hown; float* red; bf16 (*vs)[32][kVtPitch];
   __device__ explicit SkLds(char* base) {
     hb = reinterpret_cast<bf16*>(base);
