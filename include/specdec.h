@@ -65,11 +65,22 @@ typedef struct {
 } specdec_limits;
 
 enum { SPECDEC_ROW_STATS = 8 }; /* floats per row reported by specdec_get_row_stats */
+enum { SPECDEC_COUNTERS = 8 };  /* int32 words reported by specdec_get_counters */
+
+/* Kernel-path switches of a context (specdec_configure), value 0 or 1. */
+typedef enum {
+  SPECDEC_OPT_SMALL_BATCH_KERNELS = 0, /* default 1: passes of at most 32 rows use the fused small-batch kernels */
+  SPECDEC_OPT_LN_FOLD = 1,             /* default 1: decoder LayerNorms folded into the projections around them  */
+  SPECDEC_OPT_RESIDENT = 2             /* default 0: passes of at most 32 rows run as ONE resident kernel        */
+} specdec_option;
 
 /* ---- life cycle -------------------------------------------------------------------- */
 int specdec_create(specdec_ctx** out, const specdec_limits* limits); /* host only */
 void specdec_destroy(specdec_ctx* ctx);
 const char* specdec_last_error(const specdec_ctx* ctx); /* (host) valid until the next call */
+/* Chooses between kernel paths that compute the same pass (all are parity-tested against each other);
+ * takes effect from the next specdec_verify / specdec_draft / specdec_prefill.  Host only. */
+int specdec_configure(specdec_ctx* ctx, int32_t option, int32_t value);
 
 /* Number of weight tensors of a model and the shape of tensor idx (cols = 1 for vectors). */
 int specdec_num_weights(const specdec_model_desc* desc, int32_t* out);
@@ -101,8 +112,7 @@ int specdec_begin(specdec_ctx* ctx, int32_t B, int32_t max_new, void* stream);
 
 /* Encoder pass of every bound model over src (device int32 [B, S_max], right-padded;
  * src_len device int32 [B], 1 <= src_len <= S_max <= max_src), then the cross-attention
- * keys/values of every decoder layer, computed once per input (Sec. 3.1.2: the encoder is
- * forwarded only once). */
+ * keys/values of every decoder layer.  Runs once per input, not per iteration (Sec. 3.1.2). */
 int specdec_encode(specdec_ctx* ctx, const int32_t* src, const int32_t* src_len, int32_t S_max,
                    void* stream);
 
@@ -119,9 +129,19 @@ int specdec_set_stream(specdec_ctx* ctx, const int32_t* tokens, const int32_t* l
                        void* stream);
 /* Load self-attention keys/values of u_0..u_{n-1} for one model: k_cache, v_cache device
  * bf16 [dec_layers, B, L_max, d]; n device int32 [B] (n <= j for the verifier, n <= j+1 for
- * the drafter).  Rows at and beyond n are ignored. */
+ * the drafter).  Rows at and beyond n are ignored.  The caller vouches that the loaded rows
+ * cover the stream (n = j for the verifier, n >= j for the drafter); the device checks it:
+ * until specdec_prefill has cached the rest, specdec_verify reports accept_len -1 / next_token
+ * pad_id for a sequence with n < j, and specdec_draft returns pad_id drafts for a sequence with
+ * more than one uncached stream token. */
 int specdec_load_cache(specdec_ctx* ctx, specdec_role role, const void* k_cache,
                        const void* v_cache, const int32_t* n, int32_t L_max, void* stream);
+
+/* One call for "decoding resumes from this prefix": specdec_set_stream(tokens, len, L_max) followed
+ * by specdec_load_cache(role, k_cache, v_cache, n = len, L_max).  The streams are shared by both
+ * models, so the other model has nothing cached afterwards (load its cache, or prefill it). */
+int specdec_set_prefix(specdec_ctx* ctx, specdec_role role, const int32_t* tokens, const int32_t* len,
+                       int32_t L_max, const void* k_cache, const void* v_cache, void* stream);
 
 /* Cache the keys/values of every stream token a model has not cached yet (u_0..u_{j-1} for
  * the verifier, u_0..u_j for the drafter) with causal decoder passes of up to k_max+1 rows
@@ -132,8 +152,9 @@ int specdec_prefill(specdec_ctx* ctx, specdec_role role, void* stream);
 /* Spec-Drafter inference (Sec. 3.1.3, Eq. 7): append k [MASK] slots to the stream, one
  * non-autoregressive decoder pass, argmax per slot -> draft device int32 [B, k].  Stream
  * tokens the drafter has not cached yet are processed (causally) in the same pass and
- * cached; mask slots attend to the whole stream and to all k slots. */
-int specdec_draft(specdec_ctx* ctx, int32_t k, int32_t* draft, void* stream);
+ * cached; mask slots attend to the whole stream and to all k slots.
+ * logits_or_null: optional device fp32 [B, k, V] receiving the slots' logits (parity mode; slow). */
+int specdec_draft(specdec_ctx* ctx, int32_t k, int32_t* draft, float* logits_or_null, void* stream);
 
 /* Verification (Sec. 2 Eq. 1-3; Sec. 3.2 Eq. 8-10): one KV-cached pass of the verifier's
  * decoder over rows [u_j, y~_{j+1}, .., y~_{j+k}] (causal; keys/values of the rows are
@@ -148,7 +169,7 @@ int specdec_draft(specdec_ctx* ctx, int32_t k, int32_t* draft, void* stream);
  * Finished sequences report accept_len 0 and next_token pad_id.
  * k = 0 (draft may be null) is one plain autoregressive step: accept_len = 0 and next_token is
  * the verifier's greedy token (the baseline of Sec. 2 on the same kernels).
- * With SPECDEC_RESIDENT=1 in the environment when the context is created, passes of at most 32
+ * With SPECDEC_OPT_RESIDENT set (specdec_configure), passes of at most 32
  * rows run as one resident kernel whose workgroups meet at bounded grid barriers; should a
  * barrier time out (never expected), every sequence reports accept_len -1 and next_token
  * pad_id, specdec_commit then changes nothing, and the condition lasts until the next
@@ -189,6 +210,15 @@ int specdec_get_memory(specdec_ctx* ctx, specdec_role role, void* memory, void* 
  * on the last row), number of logits strictly larger than z_d (as float), 0, 0, 0}.
  * log P(token) = logit - log-sum-exp. */
 int specdec_get_row_stats(specdec_ctx* ctx, float* stats, void* stream);
+/* The same for the k mask-slot rows of the latest specdec_draft, device fp32 [B, k, SPECDEC_ROW_STATS]:
+ * {max logit, arg-max (as float), log-sum-exp (finite only if that pass wrote logits), -inf, 0, 0, 0, 0}. */
+int specdec_get_draft_stats(specdec_ctx* ctx, float* stats, void* stream);
+/* Counters since specdec_begin, device int32 [SPECDEC_COUNTERS]: {specdec_commit calls, tokens
+ * appended by them, sequences finished at the latest commit, verification rows (up to and including
+ * the bifurcation row, summed over specdec_verify calls) whose tau test had a margin
+ * |tau - (log P(top-1) - log P(draft))| <= 1e-2, 0, 0, 0, 0}.  Mean tokens per iteration (the paper's
+ * Tok., Sec. 3.1.1 Eq. 4) = tokens appended / (commits x B). */
+int specdec_get_counters(specdec_ctx* ctx, int32_t* counters, void* stream);
 
 /* ---- timing of one kernel kind ----------------------------------------------------------- */
 /* While a kind is selected every launch of that kernel is bracketed by a pair of HIP events

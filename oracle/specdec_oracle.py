@@ -16,7 +16,7 @@ What follows the paper, and where:
   * strict acceptance / bifurcation position c                 (Sec. 2, Eq. 1, 3)
   * relaxed top-beta / tau acceptance                          (Sec. 3.2, Eq. 8-10)
   * Spec-Drafter inference: prefix + k [MASK] slots, argmax    (Sec. 3.1.3, Eq. 7)
-  * loop "until the termination condition is met"              (Sec. 2, last line)
+  * loop: draft, verify, commit until EOS or the length cap    (Sec. 2)
   * Tok. = accepted tokens per iteration                       (Sec. 3.1.1, Eq. 4)
 
 The paper names the architecture only as a 6+6 Transformer-base of 512/2048
@@ -278,7 +278,7 @@ def draft(model: Model, dst: DecState, stream: Sequence[int], k: int, return_log
     """Spec-Drafter inference (Eq. 7): append k [MASK] tokens to the decoded stream
     and predict all of them in one pass.
 
-    Reading of 'conditioned on the leftward context ... in a mask-predict manner':
+    Prefix-LM reading of Eq. 7 (the slots are predicted from the decoded prefix and the source):
     committed rows attend causally among themselves (so their K/V never changes and
     is cached once); the k mask rows attend to every committed row and to all k mask
     rows.  Mask slot i sits at the position of the token it predicts.  Committed

@@ -26,6 +26,10 @@ SPECDEC_VERIFIER = 0
 SPECDEC_DRAFTER = 1
 SPECDEC_ROW_STATS = 8
 ROW_STATS = SPECDEC_ROW_STATS
+SPECDEC_COUNTERS = 8
+SPECDEC_OPT_SMALL_BATCH_KERNELS = 0
+SPECDEC_OPT_LN_FOLD = 1
+SPECDEC_OPT_RESIDENT = 2
 
 
 class specdec_model_desc(C.Structure):
@@ -54,7 +58,11 @@ EXPORTS = {
     "specdec_set_stream": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "specdec_load_cache": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "specdec_prefill": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
-    "specdec_draft": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]),
+    "specdec_draft": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "specdec_configure": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
+    "specdec_set_prefix": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "specdec_get_draft_stats": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "specdec_get_counters": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "specdec_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p]),
     "specdec_commit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -191,8 +199,25 @@ def specdec_prefill(ctx, role: int):
     _check(ctx, lib().specdec_prefill(ctx, role, _stream()))
 
 
-def specdec_draft(ctx, k: int, draft):
-    _check(ctx, lib().specdec_draft(ctx, k, _ptr(draft), _stream()))
+def specdec_draft(ctx, k: int, draft, logits=None):
+    _check(ctx, lib().specdec_draft(ctx, k, _ptr(draft), _ptr(logits), _stream()))
+
+
+def specdec_configure(ctx, option: int, value: int):
+    _check(ctx, lib().specdec_configure(ctx, option, value))
+
+
+def specdec_set_prefix(ctx, role: int, tokens, length, k_cache, v_cache):
+    _check(ctx, lib().specdec_set_prefix(ctx, role, _ptr(tokens), _ptr(length), tokens.shape[1] - 1, _ptr(k_cache),
+                                         _ptr(v_cache), _stream()))
+
+
+def specdec_get_draft_stats(ctx, stats):
+    _check(ctx, lib().specdec_get_draft_stats(ctx, _ptr(stats), _stream()))
+
+
+def specdec_get_counters(ctx, counters):
+    _check(ctx, lib().specdec_get_counters(ctx, _ptr(counters), _stream()))
 
 
 def specdec_verify(ctx, draft, k: int, beta: int, tau: float, accept_len, next_token, logits=None):
@@ -242,14 +267,17 @@ class Session:
     """Owns the context and the torch tensors (weights, workspaces, state) it points into.
     Allocation and pointer marshalling only."""
 
-    def __init__(self, max_batch: int, k_max: int, max_src: int, max_tgt: int, device="cuda:0"):
+    def __init__(self, max_batch: int, k_max: int, max_src: int, max_tgt: int, device="cuda:0", fill: int = 0):
+        """fill: byte the state and workspace buffers hold before they are bound (the header lets the
+        caller pass any buffer: 0xFF makes every untouched bf16 / fp32 word a NaN)."""
         import torch
         self.torch = torch
         self.device = torch.device(device)
         self.ctx = specdec_create(max_batch, k_max, max_src, max_tgt)
         self.limits = (max_batch, k_max, max_src, max_tgt)
         self._keep = []
-        self.state = torch.zeros(specdec_state_bytes(self.ctx), dtype=torch.uint8, device=self.device)
+        self.fill = int(fill)
+        self.state = torch.full((specdec_state_bytes(self.ctx),), self.fill, dtype=torch.uint8, device=self.device)
         specdec_bind_state(self.ctx, self.state)
         self.desc: Dict[int, object] = {}
 
@@ -264,7 +292,7 @@ class Session:
 
     def bind_model(self, role: int, desc, weights: Sequence):
         torch = self.torch
-        ws = torch.zeros(specdec_workspace_bytes(self.ctx, desc), dtype=torch.uint8, device=self.device)
+        ws = torch.full((specdec_workspace_bytes(self.ctx, desc),), self.fill, dtype=torch.uint8, device=self.device)
         specdec_bind_model(self.ctx, role, desc, weights, ws)
         self._keep.append((weights, ws))
         self.desc[role] = desc

@@ -82,6 +82,7 @@ struct specdec_ctx {
   int B = 0;          // batch of the current begin()
   int max_new = 0;
   int last_T = 0;     // rows per sequence (k + 1) of the latest verify (0: none)
+  int last_k_draft = 0;   // k of the latest drafter pass (0: none)
   int S_cur = 0;      // S_max of the current memory
   int uncached_ub[2] = {0, 0};
   bool trusted[2] = {false, false};
@@ -89,9 +90,9 @@ struct specdec_ctx {
   int prof_kind = SPECDEC_KIND_NONE;
   std::vector<hipEvent_t> prof_ev;
   int prof_used = 0;
-  bool no_skinny = false;   // SPECDEC_NO_SKINNY=1: always take the general kernels
-  bool no_ln_fold = false;  // SPECDEC_NO_LN_FOLD=1: LayerNorm as a pass of its own between the GEMMs
-  bool resident = false;    // SPECDEC_RESIDENT=1: small batches run the decoder pass as one resident kernel
+  bool no_skinny = false;   // SPECDEC_OPT_SMALL_BATCH_KERNELS = 0: always take the general kernels
+  bool no_ln_fold = false;  // SPECDEC_OPT_LN_FOLD = 0: LayerNorm as a pass of its own between the GEMMs
+  bool resident = false;    // SPECDEC_OPT_RESIDENT = 1: small batches run the decoder pass as one resident kernel
   char err[512] = {0};
 };
 
@@ -425,9 +426,6 @@ int specdec_create(specdec_ctx** out, const specdec_limits* lim) {
   if (!c) return SPECDEC_ERR_TOO_LARGE;
   c->lim = *lim;
   c->Tmax = 2 * lim->k_max + 1;
-  if (const char* e = getenv("SPECDEC_NO_SKINNY")) c->no_skinny = (e[0] == '1');
-  if (const char* e = getenv("SPECDEC_NO_LN_FOLD")) c->no_ln_fold = (e[0] == '1');
-  if (const char* e = getenv("SPECDEC_RESIDENT")) c->resident = (e[0] == '1');
   c->Lcap = (lim->max_tgt + lim->k_max + 1 + 31) & ~31;   // rows of the KV arenas (32-key chunks)
   c->Scap = (lim->max_src + 31) & ~31;
   c->n_pos = c->Lcap > c->Scap ? c->Lcap : c->Scap;
@@ -442,6 +440,18 @@ void specdec_destroy(specdec_ctx* c) {
 }
 
 const char* specdec_last_error(const specdec_ctx* c) { return c ? c->err : "null context"; }
+
+int specdec_configure(specdec_ctx* c, int32_t option, int32_t value) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (value != 0 && value != 1) return fail(c, SPECDEC_ERR_INVALID_ARG, "option value %d (0 or 1)", value);
+  switch (option) {
+    case SPECDEC_OPT_SMALL_BATCH_KERNELS: c->no_skinny = (value == 0); break;
+    case SPECDEC_OPT_LN_FOLD: c->no_ln_fold = (value == 0); break;
+    case SPECDEC_OPT_RESIDENT: c->resident = (value == 1); break;
+    default: return fail(c, SPECDEC_ERR_INVALID_ARG, "unknown option %d", option);
+  }
+  return SPECDEC_OK;
+}
 
 int specdec_num_weights(const specdec_model_desc* d, int32_t* out) {
   if (!out || !desc_ok(d)) return SPECDEC_ERR_INVALID_ARG;
@@ -559,6 +569,7 @@ int specdec_begin(specdec_ctx* c, int32_t B, int32_t max_new, void* stream) {
   if (B < 1 || max_new < 0) return fail(c, SPECDEC_ERR_INVALID_ARG, "B = %d, max_new = %d", B, max_new);
   if (B > c->lim.max_batch) return fail(c, SPECDEC_ERR_TOO_LARGE, "B = %d exceeds max_batch = %d", B, c->lim.max_batch);
   const Model& any = c->m[0].bound ? c->m[0] : c->m[1];
+  if (max_new > c->lim.max_tgt) max_new = c->lim.max_tgt;   // no stream grows beyond the arena
   HIPCHK(c, sd::begin_state(S(stream), c->st, B, max_new, c->lim.max_tgt, any.d.bos_id));
   if (c->m[0].bound) {   // a new run clears the resident kernel's counters and error flag
     HIPCHK(c, sd::fill_i32(S(stream), reinterpret_cast<int*>(c->m[0].rs_bar), 0, sd::kRsBarWords));
@@ -567,6 +578,7 @@ int specdec_begin(specdec_ctx* c, int32_t B, int32_t max_new, void* stream) {
   c->B = B;
   c->max_new = max_new;
   c->last_T = 0;
+  c->last_k_draft = 0;
   c->uncached_ub[0] = 0;
   c->uncached_ub[1] = 1;
   c->trusted[0] = c->trusted[1] = false;
@@ -673,6 +685,17 @@ int specdec_load_cache(specdec_ctx* c, specdec_role role, const void* k_cache, c
   return SPECDEC_OK;
 }
 
+int specdec_set_prefix(specdec_ctx* c, specdec_role role, const int32_t* tokens, const int32_t* len, int32_t L_max,
+                       const void* k_cache, const void* v_cache, void* stream) {
+  int rc = check_ready(c, role, false);
+  if (rc) return rc;
+  if (!k_cache || !v_cache) return fail(c, SPECDEC_ERR_INVALID_ARG, "null cache");
+  rc = specdec_set_stream(c, tokens, len, L_max, stream);
+  if (rc) return rc;
+  // every position below j is cached (the drafter's own count of u_j is left to its next pass)
+  return specdec_load_cache(c, role, k_cache, v_cache, len, L_max, stream);
+}
+
 int specdec_prefill(specdec_ctx* c, specdec_role role, void* stream) {
   int rc = check_ready(c, role, true);
   if (rc) return rc;
@@ -692,7 +715,7 @@ int specdec_prefill(specdec_ctx* c, specdec_role role, void* stream) {
   return SPECDEC_OK;
 }
 
-int specdec_draft(specdec_ctx* c, int32_t k, int32_t* draft, void* stream) {
+int specdec_draft(specdec_ctx* c, int32_t k, int32_t* draft, float* logits, void* stream) {
   int rc = check_ready(c, SPECDEC_DRAFTER, true);
   if (rc) return rc;
   if (!draft) return fail(c, SPECDEC_ERR_INVALID_ARG, "null draft");
@@ -717,10 +740,12 @@ int specdec_draft(specdec_ctx* c, int32_t k, int32_t* draft, void* stream) {
   rc = decoder_layers(c, m, B, T, st, true, k, packed);
   if (rc) return rc;
   const int R = B * k, n_tiles = (m.d.vocab + 127) / 128;
-  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, m.d.d_model, nullptr, nullptr, m.part, nullptr));
-  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_drafts(st, m.part, n_tiles, m.row_stats, c->st, B, k, m.d.pad_id, m.new_rows, draft));
+  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, m.d.d_model, nullptr, nullptr, m.part, logits));
+  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_drafts(st, m.part, n_tiles, m.row_stats, c->st, B, k, m.d.pad_id, m.new_rows,
+                                      m.rm.seq_rows, draft));
   c->uncached_ub[1] = 0;
   c->trusted[1] = false;
+  c->last_k_draft = k;
   return SPECDEC_OK;
 }
 
@@ -782,7 +807,7 @@ int specdec_commit(specdec_ctx* c, const int32_t* accept_len, const int32_t* nex
   if (rc) return rc;
   if (!accept_len || !next_token) return fail(c, SPECDEC_ERR_INVALID_ARG, "null accept_len/next_token");
   if (c->last_T <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_commit without a preceding specdec_verify");
-  HIPCHK(c, sd::commit_rows(S(stream), c->st, accept_len, next_token, c->B, c->m[0].d.eos_id, n_active));
+  HIPCHK(c, sd::commit_rows(S(stream), c->st, accept_len, next_token, c->B, c->last_T - 1, c->m[0].d.eos_id, n_active));
   c->last_T = 0;
   c->uncached_ub[1] += c->lim.k_max + 1;
   return SPECDEC_OK;
@@ -859,6 +884,24 @@ int specdec_get_memory(specdec_ctx* c, specdec_role role, void* memory, void* st
   if (m.d.enc_layers == 0 || !m.exb) return fail(c, SPECDEC_ERR_BAD_STATE, "model has no encoder");
   const size_t n = (size_t)c->B * c->S_cur * m.d.d_model;
   HIPCHK(c, hipMemcpyAsync(memory, m.exb, n * sizeof(bf16), hipMemcpyDeviceToDevice, S(stream)));
+  return SPECDEC_OK;
+}
+
+int specdec_get_draft_stats(specdec_ctx* c, float* stats, void* stream) {
+  int rc = check_ready(c, SPECDEC_DRAFTER, false);
+  if (rc) return rc;
+  if (!stats) return fail(c, SPECDEC_ERR_INVALID_ARG, "null stats");
+  if (c->last_k_draft <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "no drafter pass to report");
+  const size_t n = (size_t)c->B * c->last_k_draft * SPECDEC_ROW_STATS;
+  HIPCHK(c, hipMemcpyAsync(stats, c->m[1].row_stats, n * sizeof(float), hipMemcpyDeviceToDevice, S(stream)));
+  return SPECDEC_OK;
+}
+
+int specdec_get_counters(specdec_ctx* c, int32_t* counters, void* stream) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (!c->state_bound || c->B <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "begin not called");
+  if (!counters) return fail(c, SPECDEC_ERR_INVALID_ARG, "null counters");
+  HIPCHK(c, hipMemcpyAsync(counters, c->st.scratch, SPECDEC_COUNTERS * sizeof(int32_t), hipMemcpyDeviceToDevice, S(stream)));
   return SPECDEC_OK;
 }
 

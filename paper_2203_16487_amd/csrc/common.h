@@ -18,7 +18,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWave = 64;
 constexpr int kHeadDim = 64;   // d_model = 64 * n_heads for every model in the paper's setups
-constexpr int kTopN = 8;       // depth of the per-row top lists (SPECDEC_BETA_MAX)
 constexpr float kNegInf = -__builtin_inff();
 
 // Value caches are stored in blocks of 8 keys: element (key, e) of one (sequence, head) lies at

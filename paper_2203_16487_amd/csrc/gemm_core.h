@@ -9,6 +9,7 @@
 // depth, not by occupancy.  Waves form a WAVES_M x WAVES_N arrangement (4 or 8 waves).
 #pragma once
 #include "common.h"
+#include <stdint.h>
 
 namespace sd {
 
@@ -55,98 +56,164 @@ struct GemmAcc {
   f32x16 c[Cfg::kTM][Cfg::kTN];
 };
 
-template <class Cfg>
-struct GemmFrag {
-  bf16x8 a[Cfg::kTM], b[Cfg::kTN];
-};
-
-template <class Cfg>
-__device__ __forceinline__ void load_frags(GemmFrag<Cfg>& f, const bf16* sA, const bf16* sW, int wm,
-                                           int wn, int lrow, int lhalf, int kk) {
-#pragma unroll
-  for (int i = 0; i < Cfg::kTM; ++i)
-    f.a[i] = *reinterpret_cast<const bf16x8*>(sA + lds_off<Cfg::GK>(wm + i * 32 + lrow, kk * 2 + lhalf));
-#pragma unroll
-  for (int j = 0; j < Cfg::kTN; ++j)
-    f.b[j] = *reinterpret_cast<const bf16x8*>(sW + lds_off<Cfg::GK>(wn + j * 32 + lrow, kk * 2 + lhalf));
+// Global -> LDS request of 64 lanes x 16 bytes, landing at lds_dst + lane * 16 (lds_dst is the same
+// for the whole wave).  An asm statement, so that the compiler does not order it against the LDS
+// reads in flight (it would wait for all of them before every request); the ring protocol of the
+// main loop guarantees that the slot being filled is not read between the two barriers around the
+// request.  The compiler's own vmcnt bookkeeping stays safe: loads complete in order, and a count it
+// computes without these requests can only make it wait longer.
+__device__ __forceinline__ void dma16(const bf16* g, bf16* lds_dst) {
+  const unsigned l = __builtin_amdgcn_readfirstlane((unsigned)(uintptr_t)SD_LDS_PTR(lds_dst));
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(l), "v"(g));
 }
 
-template <class Cfg>
-__device__ __forceinline__ void mma_frags(GemmAcc<Cfg>& acc, const GemmFrag<Cfg>& f) {
-#pragma unroll
-  for (int i = 0; i < Cfg::kTM; ++i)
-#pragma unroll
-    for (int j = 0; j < Cfg::kTN; ++j)
-      acc.c[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc.c[i][j], 0, 0, 0);
+// wait until at most allow * IPW of this wave's requests are outstanding (allow in [0, MAXA])
+template <int IPW, int MAXA>
+__device__ __forceinline__ void wait_vm_stages(int allow) {
+  if constexpr (MAXA <= 0) {
+    wait_vmcnt<0>();
+  } else {
+    if (allow >= MAXA) wait_vmcnt<IPW * MAXA>();
+    else wait_vm_stages<IPW, MAXA - 1>(allow);
+  }
 }
 
 // Whole K range [k_begin, k_begin + GK*KT) of the block tile at (m0, n0).  Rows beyond M / N
 // are clamped to the last valid row (their products land in outputs that are never stored).
 // Requirements: K % GK == 0, lda/ldw % 8 == 0, A and W 16-byte aligned, smem 1024-aligned.
+//
+// Stage j (GK columns of k) lives in ring slot j % S and is multiplied in GK/16 sub-steps of one
+// MFMA per 32x32 tile each.  What keeps the matrix pipe busy:
+//  * the fragments of sub-step s+1 are read from LDS into a second register set while the MFMAs
+//    of sub-step s issue, in a fixed order written out in the source (MFMA, LDS read, MFMA, ...);
+//  * the block's one barrier per stage sits before the LAST sub-step of stage kt and certifies
+//    that stage kt+1 has landed for every wave, so the fragments of (kt+1, 0) are read while the
+//    last MFMAs of stage kt run: no wave ever waits for LDS latency right after a barrier;
+//  * with S >= 3 the requests of stage kt+S-1 (slot of stage kt-1, free since the barrier inside
+//    stage kt-1) go out a few per sub-step during stage kt instead of in one burst; with S = 2
+//    the requests of stage kt+2 follow the barrier inside stage kt (the slot just vacated).
 template <class Cfg>
 __device__ __forceinline__ void gemm_mainloop(const bf16* __restrict__ A, int lda,
                                               const bf16* __restrict__ W, int ldw, int M, int N,
                                               int k_begin, int KT, int m0, int n0, bf16* smem,
                                               GemmAcc<Cfg>& acc) {
-  constexpr int IPW = Cfg::kIPW, STAGES = Cfg::kStages, GK = Cfg::GK, RPL = Cfg::kRowsPerLoad, CPR = GK / 8;
+  constexpr int IPW = Cfg::kIPW, S = Cfg::kStages, GK = Cfg::GK, RPL = Cfg::kRowsPerLoad, CPR = GK / 8;
+  constexpr int TM = Cfg::kTM, TN = Cfg::kTN, NS = GK / 16, TMIN = TM < TN ? TM : TN;
+  static_assert(S >= 2 && NS % 2 == 0, "ring depth / fragment buffer parity");
+  constexpr bool SPREAD = S >= 3;
+  constexpr int PRO = SPREAD ? S - 1 : S;      // stages requested before the loop
+  constexpr int AHEAD = PRO;                   // during stage kt the requests of stage kt + AHEAD go out
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = (wave / Cfg::kWavesN) * Cfg::kWM, wn = (wave % Cfg::kWavesN) * Cfg::kWN;
 #pragma unroll
-  for (int i = 0; i < Cfg::kTM; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < Cfg::kTN; ++j)
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc.c[i][j][r] = 0.f;
 
-  // One global_load_lds moves 64 lanes x 16 B = RPL tile rows; lane l lands at row l/CPR,
-  // physical chunk l%CPR, so it fetches the logical chunk that the swizzle maps there.
+  // One request moves 64 lanes x 16 B = RPL tile rows; lane l lands at row l/CPR, physical chunk
+  // l%CPR, so it fetches the logical chunk that the swizzle maps there.
   const bf16* gptr[IPW];
 #pragma unroll
   for (int i = 0; i < IPW; ++i) {
     const int row = (wave * IPW + i) * RPL + lane / CPR;
     const int chunk = GK == 64 ? ((lane & 7) ^ ((row >> 1) & 7)) : ((lane & 3) ^ ((row >> 2) & 3));
-    if (row < Cfg::kBM) {
-      gptr[i] = A + (size_t)min(m0 + row, M - 1) * lda + k_begin + chunk * 8;
-    } else {
-      gptr[i] = W + (size_t)min(n0 + row - Cfg::kBM, N - 1) * ldw + k_begin + chunk * 8;
-    }
+    if (row < Cfg::kBM) gptr[i] = A + (size_t)min(m0 + row, M - 1) * lda + k_begin + chunk * 8;
+    else gptr[i] = W + (size_t)min(n0 + row - Cfg::kBM, N - 1) * ldw + k_begin + chunk * 8;
   }
-  auto issue = [&](int kt, int slot) {
+  bf16* const wslot = smem + wave * IPW * 512;   // this wave's part of slot 0
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      bf16* dst = smem + slot * Cfg::kStageElems + (wave * IPW + i) * 512;
-      __builtin_amdgcn_global_load_lds(SD_GLB_PTR(gptr[i] + kt * GK), SD_LDS_PTR(dst), 16, 0, 0);
+  for (int s = 0; s < PRO; ++s)
+    if (s < KT) {
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) dma16(gptr[i] + s * GK, wslot + s * Cfg::kStageElems + i * 512);
     }
-  };
-#pragma unroll
-  for (int s = 0; s < STAGES - 1; ++s)
-    if (s < KT) issue(s, s);
-
   const int lrow = lane & 31, lhalf = lane >> 5;
-  for (int kt = 0; kt < KT; ++kt) {
-    // tile kt has landed once at most STAGES-2 younger tiles are still in flight
-    if (kt + STAGES - 2 < KT) wait_vmcnt<IPW * (STAGES - 2)>(); else wait_vmcnt<0>();
-    block_barrier();   // everyone's part of tile kt is in LDS; everyone is done with tile kt-1
-    if (kt + STAGES - 1 < KT) issue(kt + STAGES - 1, (kt + STAGES - 1) % STAGES);
-    const bf16* sA = smem + (kt % STAGES) * Cfg::kStageElems;
-    const bf16* sW = sA + Cfg::kBM * GK;
-    // fragments of step kk+1 are fetched from LDS while the MFMAs of step kk run
-    GemmFrag<Cfg> f0, f1;
-    load_frags<Cfg>(f0, sA, sW, wm, wn, lrow, lhalf, 0);
-    load_frags<Cfg>(f1, sA, sW, wm, wn, lrow, lhalf, 1);
-    mma_frags<Cfg>(acc, f0);
-    if (GK == 64) {
-      load_frags<Cfg>(f0, sA, sW, wm, wn, lrow, lhalf, 2);
-      mma_frags<Cfg>(acc, f1);
-      load_frags<Cfg>(f1, sA, sW, wm, wn, lrow, lhalf, 3);
-      mma_frags<Cfg>(acc, f0);
+  int offA[TM][NS], offB[TN][NS];   // fragment offsets inside a stage
+#pragma unroll
+  for (int ss = 0; ss < NS; ++ss) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) offA[i][ss] = lds_off<GK>(wm + i * 32 + lrow, ss * 2 + lhalf);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) offB[j][ss] = Cfg::kBM * GK + lds_off<GK>(wn + j * 32 + lrow, ss * 2 + lhalf);
+  }
+  bf16x8 fa[2][TM], fb[2][TN];
+  // fragment q of a sub-step in read order a0 b0 a1 b1 ..: the first product of the next sub-step
+  // gets its operands first
+  auto read_frag = [&](int buf, const bf16* st, int ss, int q) {
+    const bool isA = q < 2 * TMIN ? (q & 1) == 0 : TM > TN;
+    const int idx = q < 2 * TMIN ? q >> 1 : q - TMIN;
+    if (isA) fa[buf][idx] = *reinterpret_cast<const bf16x8*>(st + offA[idx][ss]);
+    else fb[buf][idx] = *reinterpret_cast<const bf16x8*>(st + offB[idx][ss]);
+  };
+  // One sub-step in issue order.  cur: fragment set multiplied now; READ: the fragments of
+  // (nst, nss) go to the other set; requests [d0, d1) of stage dkt go to slot dslot.
+  auto substep = [&](int cur, bool READ, const bf16* nst, int nss, int dkt, int dslot, int d0, int d1) {
+    int nread = 0, nd = d0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        acc.c[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc.c[i][j], 0, 0, 0);
+        if (READ && nread < TM + TN) read_frag(cur ^ 1, nst, nss, nread++);
+        if (((i * TN + j) & 1) && nd < d1) {
+          dma16(gptr[nd] + dkt * GK, wslot + dslot * Cfg::kStageElems + nd * 512);
+          ++nd;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    if (READ) {   // fewer products than fragments
+#pragma unroll
+      for (; nread < TM + TN; ++nread) read_frag(cur ^ 1, nst, nss, nread);
     }
-    mma_frags<Cfg>(acc, f1);
+#pragma unroll
+    for (; nd < d1; ++nd) dma16(gptr[nd] + dkt * GK, wslot + dslot * Cfg::kStageElems + nd * 512);
+  };
+  // stage 0 has landed for everyone
+  wait_vm_stages<IPW, PRO - 1>(min(PRO, KT) - 1);
+  block_barrier();
+#pragma unroll
+  for (int q = 0; q < TM + TN; ++q) read_frag(0, smem, 0, q);
+  constexpr int LASTBUF = (NS - 1) & 1;
+  int kt = 0;
+  // stages during which another stage is still to be requested
+  for (; kt + AHEAD < KT; ++kt) {
+    const bf16* st = smem + (kt % S) * Cfg::kStageElems;
+    const int nslot = (kt + AHEAD) % S;
+#pragma unroll
+    for (int ss = 0; ss + 1 < NS; ++ss)
+      substep(ss & 1, true, st, ss + 1, kt + AHEAD, nslot, SPREAD ? ss * IPW / NS : 0, SPREAD ? (ss + 1) * IPW / NS : 0);
+    // my reads of this stage are done (its slot may be refilled after the barrier), my part of
+    // stage kt+1 has landed (younger requests may still be in flight)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    wait_vmcnt<SPREAD ? IPW * (S - 3) + (NS - 1) * IPW / NS : IPW * (S - 2)>();
+    block_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    substep(LASTBUF, true, smem + ((kt + 1) % S) * Cfg::kStageElems, 0, kt + AHEAD, nslot,
+            SPREAD ? (NS - 1) * IPW / NS : 0, IPW);
+  }
+  // the last stages: nothing left to request
+  for (; kt + 1 < KT; ++kt) {
+    const bf16* st = smem + (kt % S) * Cfg::kStageElems;
+#pragma unroll
+    for (int ss = 0; ss + 1 < NS; ++ss) substep(ss & 1, true, st, ss + 1, 0, 0, 0, 0);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    wait_vm_stages<IPW, AHEAD - 2>(KT - kt - 2);
+    block_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    substep(LASTBUF, true, smem + ((kt + 1) % S) * Cfg::kStageElems, 0, 0, 0, 0, 0);
+  }
+  {
+    const bf16* st = smem + (kt % S) * Cfg::kStageElems;
+#pragma unroll
+    for (int ss = 0; ss + 1 < NS; ++ss) substep(ss & 1, true, st, ss + 1, 0, 0, 0, 0);
+    substep(LASTBUF, false, st, 0, 0, 0, 0, 0);
   }
 #pragma unroll
-  for (int i = 0; i < Cfg::kTM; ++i)
+  for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < Cfg::kTN; ++j) mfma_settle(acc.c[i][j]);
+    for (int j = 0; j < TN; ++j) mfma_settle(acc.c[i][j]);
   block_barrier();   // LDS may be reused by the caller's epilogue
 }
 

@@ -189,7 +189,7 @@ struct SeqState {       // device arrays of the bound state buffer, all [max_bat
   int* cached[2];       // per role: stream positions whose K/V are cached
   int* src_len;
   int* last_draft;      // [max_batch][k_max]
-  int* scratch;         // [8] counters
+  int* scratch;         // [8] counters since begin: commits, tokens appended, finished sequences, near-tau rows
   int tok_pitch, k_max;
 };
 // rows of a verification pass: [u_j, drafts]; also stores the drafts for commit
@@ -218,10 +218,12 @@ hipError_t merge_accept(hipStream_t st, const float* part, const float* zd_row, 
                         int* next_token, const unsigned* fail = nullptr);
 // the same merge for the B*k mask-slot rows of a drafter pass, draft[b][s] = their arg-max (pad
 // for finished sequences), and cached[drafter][b] += new_rows[b]
+// (seq_rows: rows of each sequence in the pass; a sequence without its k slots gets pad drafts)
 hipError_t merge_drafts(hipStream_t st, const float* part, int n_tiles, float* row_stats, const SeqState& s, int B,
-                        int k, int pad_id, const int* new_rows, int* draft);
+                        int k, int pad_id, const int* new_rows, const int* seq_rows, int* draft);
+// k: block size of the pass whose drafts are being committed (accept_len is clamped to it)
 hipError_t commit_rows(hipStream_t st, const SeqState& s, const int* accept_len,
-                       const int* next_token, int B, int eos_id, int* n_active);
+                       const int* next_token, int B, int k, int eos_id, int* n_active);
 hipError_t begin_state(hipStream_t st, const SeqState& s, int B, int max_new, int max_tgt,
                        int bos_id);
 hipError_t set_stream(hipStream_t st, const SeqState& s, const int* tokens, const int* len, int B,

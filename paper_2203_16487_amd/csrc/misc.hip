@@ -444,12 +444,20 @@ __global__ __launch_bounds__(64 * kMergeWaves) void merge_accept_kernel(const fl
   __syncthreads();
   if (threadIdx.x != 0) return;
   if (fail && *fail) { accept_len[b] = -1; next_token[b] = pad_id; return; }
+  // keys/values of u_0..u_{j-1} must be cached: a cache loaded short of the stream (and not
+  // completed by a prefill) would have let this pass attend to rows that were never written
+  if (s.cached[0][b] < s.len[b] && !s.finished[b]) { accept_len[b] = -1; next_token[b] = pad_id; return; }
   int a = 0;
   for (; a < k; ++a)
     if (!(scnt[a] < beta && sm[a] - szd[a] <= tau)) break;
   const bool fin = s.finished[b] != 0;
   accept_len[b] = fin ? 0 : a;
   next_token[b] = fin ? pad_id : sarg[a];
+  if (!fin) {   // rows whose tau test was decided by a margin of at most 1e-2 (up to the bifurcation row)
+    int near = 0;
+    for (int i = 0; i <= a && i < k; ++i) near += fabsf(tau - (sm[i] - szd[i])) <= 1e-2f ? 1 : 0;
+    if (near) atomicAdd(&s.scratch[3], near);
+  }
 }
 hipError_t merge_accept(hipStream_t st, const float* part, const float* zd_row, int n_tiles, float* row_stats,
                         const SeqState& s, int B, int k, int beta, float tau, int pad_id, int* accept_len,
@@ -467,19 +475,24 @@ hipError_t merge_accept(hipStream_t st, const float* part, const float* zd_row, 
 __global__ __launch_bounds__(64) void merge_drafts_kernel(const float* __restrict__ part, int n_tiles,
                                                           float* __restrict__ row_stats, SeqState s, int B, int k,
                                                           int pad_id, const int* __restrict__ new_rows,
+                                                          const int* __restrict__ seq_rows,
                                                           int* __restrict__ draft) {
   const int o = blockIdx.x, lane = threadIdx.x;
   const RowMerge res = merge_row(part + (size_t)o * n_tiles * kPartF, n_tiles, lane);
   if (lane != 0) return;
   store_row_stats(row_stats + (size_t)o * kRowStats, res, kNegInf);
-  draft[o] = s.finished[o / k] ? pad_id : res.arg;
+  // a sequence whose uncached stream did not fit into this pass got no mask slots (its rows of
+  // the pass were all stream rows): what sits at its slot rows belongs to another sequence
+  const int b = o / k;
+  const bool has_slots = seq_rows[b] - new_rows[b] == k;
+  draft[o] = (s.finished[b] || !has_slots) ? pad_id : res.arg;
   if (o < B) s.cached[1][o] += new_rows[o];
 }
 hipError_t merge_drafts(hipStream_t st, const float* part, int n_tiles, float* row_stats, const SeqState& s, int B,
-                        int k, int pad_id, const int* new_rows, int* draft) {
+                        int k, int pad_id, const int* new_rows, const int* seq_rows, int* draft) {
   if (B <= 0 || k <= 0) return hipSuccess;
   hipLaunchKernelGGL(merge_drafts_kernel, dim3(B * k), dim3(64), 0, st, part, n_tiles, row_stats, s, B, k, pad_id,
-                     new_rows, draft);
+                     new_rows, seq_rows, draft);
   return hipGetLastError();
 }
 
@@ -488,17 +501,17 @@ hipError_t merge_drafts(hipStream_t st, const float* part, int n_tiles, float* r
 // sequence stops after its first EOS or when it reaches its cap.  j advances by the number
 // of tokens appended: exactly that many of this pass's cache rows become valid.
 __global__ void commit_kernel(SeqState s, const int* __restrict__ accept_len, const int* __restrict__ next_token,
-                              int B, int eos_id, int* n_active) {
-  __shared__ int active;
-  if (threadIdx.x == 0) active = 0;
+                              int B, int k, int eos_id, int* n_active) {
+  __shared__ int active, tokens;
+  if (threadIdx.x == 0) { active = 0; tokens = 0; }
   __syncthreads();
-  int mine = 0;
+  int mine = 0, added = 0;
   for (int b = threadIdx.x; b < B; b += blockDim.x) {
     // two memory round trips per sequence: the scalars, then every token that may be appended
     const int fin0 = s.finished[b], a0 = accept_len[b], j0 = s.len[b], cap = s.cap[b], nt = next_token[b];
     if (fin0) continue;
     if (a0 < 0) { ++mine; continue; }   // verification reported a failure: nothing to commit
-    const int a = min(a0, s.k_max);
+    const int a = min(a0, k);   // k of the pass whose drafts are stored: entries beyond it are stale
     int t[32];                           // k_max <= 31
 #pragma unroll
     for (int i = 0; i < 31; ++i) t[i] = (i < a) ? s.last_draft[b * s.k_max + i] : 0;
@@ -518,24 +531,33 @@ __global__ void commit_kernel(SeqState s, const int* __restrict__ accept_len, co
         }
       }
     }
+    added += j - j0;
     s.len[b] = j;
     s.cached[0][b] = j;   // the verifier's rows of the kept tokens are now valid cache
     s.finished[b] = fin;
     if (!fin) ++mine;
   }
   if (mine) atomicAdd(&active, mine);
+  if (added) atomicAdd(&tokens, added);
   __syncthreads();
-  if (threadIdx.x == 0 && n_active) *n_active = active;
+  if (threadIdx.x == 0) {
+    if (n_active) *n_active = active;
+    s.scratch[0] += 1;          // commits
+    s.scratch[1] += tokens;     // tokens appended
+    s.scratch[2] = B - active;  // finished sequences
+  }
 }
 hipError_t commit_rows(hipStream_t st, const SeqState& s, const int* accept_len, const int* next_token, int B,
-                       int eos_id, int* n_active) {
-  hipLaunchKernelGGL(commit_kernel, dim3(1), dim3(256), 0, st, s, accept_len, next_token, B, eos_id, n_active);
+                       int k, int eos_id, int* n_active) {
+  hipLaunchKernelGGL(commit_kernel, dim3(1), dim3(256), 0, st, s, accept_len, next_token, B, min(k, s.k_max), eos_id,
+                     n_active);
   return hipGetLastError();
 }
 
 // ----------------------------------------------------------------------------- state
 __global__ void begin_kernel(SeqState s, int B, int max_new, int max_tgt, int bos_id) {
   int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < 8) s.scratch[b] = 0;   // counters: commits, tokens appended, finished, near-threshold rows
   if (b >= B) return;
   s.tokens[(size_t)b * s.tok_pitch] = bos_id;
   s.len[b] = 0;
@@ -560,8 +582,9 @@ __global__ void set_stream_kernel(SeqState s, const int* __restrict__ tokens, co
   if (threadIdx.x == 0) {
     s.len[b] = j;
     s.start[b] = j;
-    s.cap[b] = min(j + max_new, max_tgt);
-    s.finished[b] = (j >= min(j + max_new, max_tgt));
+    const int cap = j + min(max_new, max(max_tgt - j, 0));   // (max_new may be huge: no j + max_new)
+    s.cap[b] = cap;
+    s.finished[b] = (j >= cap);
     s.cached[0][b] = 0;
     s.cached[1][b] = 0;
   }

@@ -9,12 +9,17 @@ from paper_2203_16487_amd import synth
 import cases
 
 
-def open_verifier(case: cases.VerifyCase, k_max=None, max_tgt=None, max_batch=None, max_new=10 ** 6):
-    """Session with the verifier bound, memory set, streams set and the oracle's cache loaded."""
+def open_verifier(case: cases.VerifyCase, k_max=None, max_tgt=None, max_batch=None, max_new=10 ** 6, options=None,
+                  fill=0):
+    """Session with the verifier bound, memory set, streams set and the oracle's cache loaded.
+    options: {specdec_option: value} passed to specdec_configure; fill: byte the state and workspace
+    buffers hold before they are bound."""
     k_max = k_max or case.k
     max_tgt = max_tgt or (case.L_max + case.k + 8)
     S = case.memory.shape[1]
-    ses = sd.Session(max_batch or case.B, k_max, S, max_tgt)
+    ses = sd.Session(max_batch or case.B, k_max, S, max_tgt, fill=fill)
+    for opt, val in (options or {}).items():
+        sd.specdec_configure(ses.ctx, opt, val)
     w = ses.upload_weights(case.bits)
     ses.bind_model(sd.SPECDEC_VERIFIER, case.desc, w)
     sd.specdec_begin(ses.ctx, case.B, max_new)

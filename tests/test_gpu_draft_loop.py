@@ -23,8 +23,10 @@ def make_models(seed, V=1000, d=128, H=2, F=256, enc_v=2, enc_d=3, dec_v=2, dec_
     return (vd, vb, orc.Model(vd, synth.weights_f32(vb))), (dd, db, orc.Model(dd, synth.weights_f32(db)))
 
 
-def open_session(B, k_max, S_max, max_tgt, ver=None, dr=None):
+def open_session(B, k_max, S_max, max_tgt, ver=None, dr=None, options=None):
     ses = sd.Session(B, k_max, S_max, max_tgt)
+    for opt, val in (options or {}).items():
+        sd.specdec_configure(ses.ctx, opt, val)
     if ver is not None:
         ses.bind_model(sd.SPECDEC_VERIFIER, ver[0], ses.upload_weights(ver[1]))
     if dr is not None:
@@ -81,7 +83,7 @@ def test_encoder_and_drafter_pass_small():
     print(f"[drafter-small] drafts match, {ex} near-tie excused")
 
 
-def run_loop(seed, beta, tau, B=5, S_max=12, k=4, max_new=18):
+def run_loop(seed, beta, tau, B=5, S_max=12, k=4, max_new=18, options=None):
     """Draft-then-verify loop on the GPU with the oracle following in lock step: every
     iteration the oracle recomputes the drafts and the decision from the same state; the state
     of both sides then advances by the GPU's decision (so one excused near-threshold difference
@@ -94,7 +96,7 @@ def run_loop(seed, beta, tau, B=5, S_max=12, k=4, max_new=18):
         model.w["embed"][vd.eos_id] = synth.bf16_bits_to_f32(bits["embed"][vd.eos_id])
     src_len = synth.random_lengths(seed, "src_len", B, 2, S_max)
     src = synth.random_tokens(seed, "src", (B, S_max), vd)
-    ses = open_session(B, k, S_max, 64, ver=(vd, vb), dr=(dd, db))
+    ses = open_session(B, k, S_max, 64, ver=(vd, vb), dr=(dd, db), options=options)
     dev = ses.device
     sd.specdec_begin(ses.ctx, B, max_new)
     sd.specdec_encode(ses.ctx, ses.i32(src), ses.i32(src_len))
@@ -164,11 +166,10 @@ def test_loop_relaxed():
     assert any(s.stream[-1] == 2 for s in seqs) or True
 
 
-def test_loop_relaxed_separate_layernorm(monkeypatch):
-    """The same loop with LayerNorm run as a pass of its own (SPECDEC_NO_LN_FOLD=1): the drafter pass
-    then keeps T rows per sequence (padding rows between sequences) instead of packing them."""
-    monkeypatch.setenv("SPECDEC_NO_LN_FOLD", "1")
-    *_, seqs, stats = run_loop(seed=23, beta=3, tau=1.0, B=7, k=5)
+def test_loop_relaxed_separate_layernorm():
+    """The same loop with LayerNorm run as a pass of its own (SPECDEC_OPT_LN_FOLD = 0): the drafter
+    pass then keeps T rows per sequence (padding rows between sequences) instead of packing them."""
+    *_, seqs, stats = run_loop(seed=23, beta=3, tau=1.0, B=7, k=5, options={sd.SPECDEC_OPT_LN_FOLD: 0})
     print(f"[loop relaxed, separate LayerNorm] {stats}")
     assert stats["committed"] == sum(len(s.stream) - 1 for s in seqs)
 

@@ -8,6 +8,7 @@ import torch
 
 import cases
 import specdec_oracle as orc
+from paper_2203_16487_amd import binding as sd
 from paper_2203_16487_amd import synth
 
 pytestmark = pytest.mark.gpu
@@ -247,7 +248,7 @@ def test_argument_errors_on_device():
     assert np.abs(out["logits"] - case.logits).max() <= LOGIT_TOL
 
 
-def test_small_batch_paths_agree(monkeypatch):
+def test_small_batch_paths_agree():
     """The implementations of a pass of at most 32 rows -- general kernels with LayerNorm folded
     into the GEMMs around it (what larger batches run), general kernels with LayerNorm as a
     pass of its own, fused per-projection kernels (the default at this size) and the single
@@ -271,14 +272,10 @@ def test_small_batch_paths_agree(monkeypatch):
     cases.run_oracle(case4)
     for cs in (case, case2, case3, case4):
         outs = {}
-        for tag, env in (("general", {"SPECDEC_NO_SKINNY": "1"}),
-                         ("general, separate LayerNorm", {"SPECDEC_NO_SKINNY": "1", "SPECDEC_NO_LN_FOLD": "1"}),
-                         ("fused", {}), ("resident", {"SPECDEC_RESIDENT": "1"})):
-            for name in ("SPECDEC_NO_SKINNY", "SPECDEC_RESIDENT", "SPECDEC_NO_LN_FOLD"):
-                monkeypatch.delenv(name, raising=False)
-            for k_, v_ in env.items():
-                monkeypatch.setenv(k_, v_)
-            ses = gh.open_verifier(cs)
+        for tag, opts in (("general", {sd.SPECDEC_OPT_SMALL_BATCH_KERNELS: 0}),
+                          ("general, separate LayerNorm", {sd.SPECDEC_OPT_SMALL_BATCH_KERNELS: 0, sd.SPECDEC_OPT_LN_FOLD: 0}),
+                          ("fused", {}), ("resident", {sd.SPECDEC_OPT_RESIDENT: 1})):
+            ses = gh.open_verifier(cs, options=opts)
             outs[tag] = gh.gpu_verify(ses, cs)
             ses.close()
             err = np.abs(outs[tag]["logits"] - cs.logits).max()
