@@ -179,6 +179,18 @@ int specdec_draft(specdec_ctx* ctx, int32_t k, int32_t* draft, float* logits_or_
 int specdec_verify(specdec_ctx* ctx, const int32_t* draft, int32_t k, int32_t beta, float tau,
                    int32_t* accept_len, int32_t* next_token, float* logits_or_null, void* stream);
 
+/* specdec_verify for callers that cannot allocate device memory or hand over a workspace for the
+ * pass's scratch (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the vocabulary partial records, draft logits and row statistics of the pass live in
+ * a static device array inside the library (5.6 MiB per GPU, held until the process ends)
+ * instead of the bound workspace.  Same arguments, same results, no allocation of any kind.
+ * Limits: B * (k + 1) <= 1408 rows and rows x vocabulary tiles (128 columns; 64 for passes of at
+ * most 32 rows) <= 1408 x 256, else SPECDEC_ERR_TOO_LARGE.  Every call on a GPU shares that GPU's
+ * array: calls that overlap on one GPU (two streams, two contexts) race; specdec_get_row_stats
+ * after it reads the array, so it must precede the next such call. */
+int specdec_verify_static(specdec_ctx* ctx, const int32_t* draft, int32_t k, int32_t beta, float tau,
+                          int32_t* accept_len, int32_t* next_token, float* logits_or_null, void* stream);
+
 /* Commit (Eq. 3): append y~_{j+1..j+a} and next_token to each stream, stop a sequence after
  * its first EOS or at its cap; j advances by the number of tokens appended, which also is
  * the number of this pass's cache rows that become valid -- rejected rows are simply left

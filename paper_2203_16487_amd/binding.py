@@ -65,6 +65,8 @@ EXPORTS = {
     "specdec_get_counters": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "specdec_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p]),
+    "specdec_verify_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
+                                        C.c_void_p, C.c_void_p]),
     "specdec_commit": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "specdec_rewind": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "specdec_profile_select": (C.c_int, [C.c_void_p, C.c_int32]),
@@ -223,6 +225,11 @@ def specdec_get_counters(ctx, counters):
 def specdec_verify(ctx, draft, k: int, beta: int, tau: float, accept_len, next_token, logits=None):
     _check(ctx, lib().specdec_verify(ctx, _ptr(draft), k, beta, tau, _ptr(accept_len), _ptr(next_token),
                                      _ptr(logits), _stream()))
+
+
+def specdec_verify_static(ctx, draft, k: int, beta: int, tau: float, accept_len, next_token, logits=None):
+    _check(ctx, lib().specdec_verify_static(ctx, _ptr(draft), k, beta, tau, _ptr(accept_len), _ptr(next_token),
+                                            _ptr(logits), _stream()))
 
 
 def specdec_commit(ctx, accept_len, next_token, n_active=None):

@@ -83,6 +83,7 @@ struct specdec_ctx {
   int max_new = 0;
   int last_T = 0;     // rows per sequence (k + 1) of the latest verify (0: none)
   int last_k_draft = 0;   // k of the latest drafter pass (0: none)
+  const float* last_row_stats = nullptr;   // merged row statistics of the latest verify
   int S_cur = 0;      // S_max of the current memory
   int uncached_ub[2] = {0, 0};
   bool trusted[2] = {false, false};
@@ -749,8 +750,28 @@ int specdec_draft(specdec_ctx* c, int32_t k, int32_t* draft, float* logits, void
   return SPECDEC_OK;
 }
 
-int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, float tau, int32_t* accept_len,
-                   int32_t* next_token, float* logits, void* stream) {
+}  // extern "C"
+
+// Scratch of specdec_verify_static (callers that may not allocate or bring a workspace for it):
+// vocabulary partial records, draft logits and merged row statistics of one verification pass.
+// One array per GPU, held until the process ends and shared by every call on that GPU.  In host
+// code the name is only a handle for hipGetSymbolAddress; kernels get the device address.
+constexpr size_t kStaticRows = 1408;                                   // B * (k + 1) of the largest pass it serves
+constexpr size_t kStaticPartFloats = kStaticRows * 256 * sd::kPartF;   // rows x tiles x record (5.5 MiB)
+constexpr size_t kStaticFloats = kStaticPartFloats + kStaticRows + kStaticRows * sd::kRowStats;
+static __device__ __align__(256) float scratch[kStaticFloats];
+
+namespace {
+
+// Scratch of a verification pass; specdec_verify carves it from the caller's workspace.
+struct VerifyScratch {
+  float *part, *zd, *row_stats;
+};
+constexpr int kMaxDevices = 64;
+float* scratch_ptr[kMaxDevices] = {nullptr};                  // device address of `scratch` on each GPU
+
+int verify_impl(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, float tau, int32_t* accept_len,
+                int32_t* next_token, float* logits, void* stream, const VerifyScratch* ext) {
   int rc = check_ready(c, SPECDEC_VERIFIER, true);
   if (rc) return rc;
   if (!accept_len || !next_token || (!draft && k > 0)) return fail(c, SPECDEC_ERR_INVALID_ARG, "null draft/accept_len/next_token");
@@ -763,6 +784,14 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
   hipStream_t st = S(stream);
   const int B = c->B, T = k + 1, R = B * T;
   const bool small = skinny_ok(c, m, R, T);   // the small-batch kernels embed the rows themselves
+  VerifyScratch vs{m.part, m.zd, m.row_stats};
+  if (ext) {
+    const size_t tiles = small ? (m.d.vocab + 63) / 64 : (m.d.vocab + 127) / 128;
+    if ((size_t)R > kStaticRows || (size_t)R * tiles * sd::kPartF > kStaticPartFloats)
+      return fail(c, SPECDEC_ERR_TOO_LARGE, "pass of %d rows x %zu vocabulary tiles exceeds the static scratch "
+                  "(%zu rows, %zu floats of records)", R, tiles, kStaticRows, kStaticPartFloats);
+    vs = *ext;
+  }
   if (small)
     LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::assemble_verify(st, c->st, m.rm, draft, B, k, m.d.vocab));
   else
@@ -778,7 +807,7 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
     a.row_draft = m.rm.row_draft; a.seq_rows = m.rm.seq_rows; a.src_len = c->st.src_len;
     a.E = m.embed; a.pe = m.pe; a.xs0 = m.x; a.xs1 = m.x2; a.q = m.q; a.hid = m.hid;
     a.kc = m.kc; a.vc = m.vc; a.xk = m.xk; a.xv = m.xv; a.kv_layer = m.kv_layer; a.xkv_layer = m.xkv_layer;
-    a.zd = m.zd; a.part = m.part; a.logits = logits;
+    a.zd = vs.zd; a.part = vs.part; a.logits = logits;
     a.bar = m.rs_bar; a.parity = m.rs_parity;
     m.rs_seq = m.rs_seq >= 0x3fffffff ? 1 : m.rs_seq + 1;
     a.seq = m.rs_seq;
@@ -789,17 +818,44 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
     sd::SkSrc fin{};
     rc = decoder_layers_skinny(c, m, B, T, st, &fin);
     if (rc) return rc;
-    LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::skinny_vocab(st, fin, R, m.d.d_model, m.embed, m.d.vocab, m.rm.row_draft, m.zd, m.part, logits));
+    LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::skinny_vocab(st, fin, R, m.d.d_model, m.embed, m.d.vocab, m.rm.row_draft, vs.zd, vs.part, logits));
   } else {
     rc = decoder_layers(c, m, B, T, st, true);
     if (rc) return rc;
     n_tiles = (m.d.vocab + 127) / 128;
-    LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, m.zd, m.part, logits));
+    LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, vs.zd, vs.part, logits));
   }
-  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_accept(st, m.part, m.zd, n_tiles, m.row_stats, c->st, B, k, beta, tau, m.d.pad_id,
+  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_accept(st, vs.part, vs.zd, n_tiles, vs.row_stats, c->st, B, k, beta, tau, m.d.pad_id,
                                       accept_len, next_token, failed));
   c->last_T = k + 1;
+  c->last_row_stats = vs.row_stats;
   return SPECDEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, float tau, int32_t* accept_len,
+                   int32_t* next_token, float* logits, void* stream) {
+  return verify_impl(c, draft, k, beta, tau, accept_len, next_token, logits, stream, nullptr);
+}
+
+int specdec_verify_static(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, float tau, int32_t* accept_len,
+                          int32_t* next_token, float* logits, void* stream) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  int dev = -1;
+  HIPCHK(c, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(c, SPECDEC_ERR_HIP, "device ordinal %d out of range", dev);
+  if (!scratch_ptr[dev]) {   // once per GPU, with that GPU current: each GPU holds its own copy of the array
+    float* p = nullptr;
+    HIPCHK(c, hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)));
+    if (!p) return fail(c, SPECDEC_ERR_HIP, "hipGetSymbolAddress returned a null address");
+    scratch_ptr[dev] = p;
+  }
+  float* base = scratch_ptr[dev];
+  const VerifyScratch vs{base, base + kStaticPartFloats, base + kStaticPartFloats + kStaticRows};
+  return verify_impl(c, draft, k, beta, tau, accept_len, next_token, logits, stream, &vs);
 }
 
 int specdec_commit(specdec_ctx* c, const int32_t* accept_len, const int32_t* next_token, int32_t* n_active, void* stream) {
@@ -911,7 +967,7 @@ int specdec_get_row_stats(specdec_ctx* c, float* stats, void* stream) {
   if (!stats) return fail(c, SPECDEC_ERR_INVALID_ARG, "null stats");
   if (c->last_T <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "no verification pass to report");
   const size_t n = (size_t)c->B * c->last_T * SPECDEC_ROW_STATS;
-  HIPCHK(c, hipMemcpyAsync(stats, c->m[0].row_stats, n * sizeof(float), hipMemcpyDeviceToDevice, S(stream)));
+  HIPCHK(c, hipMemcpyAsync(stats, c->last_row_stats, n * sizeof(float), hipMemcpyDeviceToDevice, S(stream)));
   return SPECDEC_OK;
 }
 
