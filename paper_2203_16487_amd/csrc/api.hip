@@ -740,7 +740,7 @@ int specdec_draft(specdec_ctx* c, int32_t k, int32_t* draft, float* logits, void
                                       m.d.vocab, m.new_rows, m.embed, m.pe, m.x, m.xb, m.d.d_model, packed));
   rc = decoder_layers(c, m, B, T, st, true, k, packed);
   if (rc) return rc;
-  const int R = B * k, n_tiles = (m.d.vocab + 127) / 128;
+  const int R = B * k, tc = sd::vocab_tile_cols(R), n_tiles = (m.d.vocab + tc - 1) / tc;
   LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, m.d.d_model, nullptr, nullptr, m.part, logits));
   LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_drafts(st, m.part, n_tiles, m.row_stats, c->st, B, k, m.d.pad_id, m.new_rows,
                                       m.rm.seq_rows, draft));
@@ -786,7 +786,7 @@ int verify_impl(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, f
   const bool small = skinny_ok(c, m, R, T);   // the small-batch kernels embed the rows themselves
   VerifyScratch vs{m.part, m.zd, m.row_stats};
   if (ext) {
-    const size_t tiles = small ? (m.d.vocab + 63) / 64 : (m.d.vocab + 127) / 128;
+    const size_t tiles = small ? (m.d.vocab + 63) / 64 : (m.d.vocab + sd::vocab_tile_cols(R) - 1) / sd::vocab_tile_cols(R);
     if ((size_t)R > kStaticRows || (size_t)R * tiles * sd::kPartF > kStaticPartFloats)
       return fail(c, SPECDEC_ERR_TOO_LARGE, "pass of %d rows x %zu vocabulary tiles exceeds the static scratch "
                   "(%zu rows, %zu floats of records)", R, tiles, kStaticRows, kStaticPartFloats);
@@ -822,7 +822,7 @@ int verify_impl(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, f
   } else {
     rc = decoder_layers(c, m, B, T, st, true);
     if (rc) return rc;
-    n_tiles = (m.d.vocab + 127) / 128;
+    n_tiles = (m.d.vocab + sd::vocab_tile_cols(R) - 1) / sd::vocab_tile_cols(R);
     LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, vs.zd, vs.part, logits));
   }
   LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_accept(st, vs.part, vs.zd, n_tiles, vs.row_stats, c->st, B, k, beta, tau, m.d.pad_id,

@@ -220,13 +220,10 @@ typedef GemmCfg<256, 128, 3, 4, 2> CfgTall;   // 144 KB LDS, eight waves: one bl
 template <class Cfg, class Epi>
 static hipError_t launch_cfg(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
                              const Epi& epi, const int* m_real) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<Cfg, Epi>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kSmemBytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  // (initialisation of a function-local static is thread-safe)
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel<Cfg, Epi>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kSmemBytes);
+  if (attr != hipSuccess) return attr;
   const int MT = (M + Cfg::kBM - 1) / Cfg::kBM, NT = (N + Cfg::kBN - 1) / Cfg::kBN;
   hipLaunchKernelGGL((gemm_kernel<Cfg, Epi>), dim3(xcd_grid(MT, NT)), dim3(Cfg::kThreads), Cfg::kSmemBytes, st,
                      A, lda, W, K, M, N, K, MT, NT, epi, m_real);
@@ -519,13 +516,9 @@ template <class Cfg, class Epi>
 static hipError_t launch_ln_cfg(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
                                 const Epi& epi, const int* m_real) {
   constexpr int kBytes = ln_smem_bytes<Cfg, Epi::kVec>();
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ln_kernel<Cfg, Epi>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ln_kernel<Cfg, Epi>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
+  if (attr != hipSuccess) return attr;
   const int MT = (M + Cfg::kBM - 1) / Cfg::kBM, NT = (N + Cfg::kBN - 1) / Cfg::kBN;
   hipLaunchKernelGGL((gemm_ln_kernel<Cfg, Epi>), dim3(xcd_grid(MT, NT)), dim3(Cfg::kThreads), kBytes, st,
                      A, lda, W, K, M, N, K, MT, NT, epi, m_real);
@@ -536,10 +529,10 @@ static hipError_t launch_ln(hipStream_t st, const bf16* A, int lda, const bf16* 
                             const Epi& epi, const int* m_real) {
   if (M <= 0 || N <= 0) return hipSuccess;
   const long wide_tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
-  // the widest outputs (FFN1 of the big model) gain 3 % from 256x128 tiles on eight waves with a
-  // three-deep ring (measured; 3072 columns do not)
+  // the widest outputs (QKV and FFN1 of the big model) run on 256x128 tiles, eight waves, three-deep
+  // ring: 9-15 % faster than 128x128 on weights streamed from HBM, a few % inside the decoder pass
   if constexpr (Epi::kVec == 2) {
-    if (N >= 4096 && M >= 1024) return launch_ln_cfg<CfgTall>(st, A, lda, W, M, N, K, epi, m_real);
+    if (N >= 3072 && M >= 1024) return launch_ln_cfg<CfgTall>(st, A, lda, W, M, N, K, epi, m_real);
   }
   if (wide_tiles >= 200) return launch_ln_cfg<CfgWide>(st, A, lda, W, M, N, K, epi, m_real);
   return launch_ln_cfg<CfgSmall>(st, A, lda, W, M, N, K, epi, m_real);
@@ -747,24 +740,26 @@ __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* _
   }
 }
 
+int vocab_tile_cols(int) { return CfgVocab::kBN; }
+
 hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int V, int K,
                        const int* row_draft, float* zd_row, float* part, float* logits) {
   if (M <= 0) return hipSuccess;
-  static bool attr_done = false;
-  if (!attr_done) {
+  static const hipError_t attr128 = [] {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_kernel<false>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, CfgVocab::kSmemBytes);
     if (e == hipSuccess)
       e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_kernel<true>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, CfgVocab::kSmemBytes);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+    return e;
+  }();
+  if (attr128 != hipSuccess) return attr128;
   // without row_draft no row scores a draft (drafter pass): every count is taken against -inf, unused
   if (row_draft)
     hipLaunchKernelGGL(draft_logit_kernel, dim3((M + 31) / 32), dim3(64), 0, st, A, E, M, V, K, row_draft, zd_row);
+  const bool stats = row_draft || logits;
   const int MT = (M + 127) / 128, NT = (V + 127) / 128;
-  if (row_draft || logits)
+  if (stats)
     hipLaunchKernelGGL(vocab_kernel<false>, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
                        A, E, M, V, K, MT, NT, row_draft ? zd_row : nullptr, part, logits);
   else

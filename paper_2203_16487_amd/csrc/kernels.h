@@ -81,14 +81,16 @@ hipError_t gemm_ln_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int 
                               const int* row_pos, int H, int Lcap, const int* m_real = nullptr);
 
 // Vocabulary projection fused with per-row statistics.  zd_row [M] receives the logit of the
-// draft each row scores (-inf if none).  For every row and every 128-column vocabulary tile one
-// partial record of kPartF floats is written to part[M][n_tiles][kPartF]: {tile max, tile
+// draft each row scores (-inf if none).  For every row and every vocabulary tile of
+// vocab_tile_cols(M) columns one partial record of kPartF floats is written to
+// part[M][n_tiles][kPartF], n_tiles = ceil(V / vocab_tile_cols(M)): {tile max, tile
 // arg-max (int bits), sum exp(z - tile max), number of tile logits > zd_row (int bits)}.
 // logits (optional, fp32 [M, V]) receives the full rows.  row_draft may be null: no row scores a
 // draft (the pre-pass is skipped, zd_row is left untouched and may be null); if logits is null as
 // well only max / arg-max are formed (records carry sum 0 and count 0: merged LSE is -inf).
 constexpr int kPartF = 4;
 constexpr int kRowStats = 8;   // floats per row of merged statistics
+int vocab_tile_cols(int M);
 hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int V, int K,
                        const int* row_draft, float* zd_row, float* part, float* logits);
 
