@@ -71,7 +71,10 @@ enum { SPECDEC_COUNTERS = 8 };  /* int32 words reported by specdec_get_counters 
 typedef enum {
   SPECDEC_OPT_SMALL_BATCH_KERNELS = 0, /* default 1: passes of at most 32 rows use the fused small-batch kernels */
   SPECDEC_OPT_LN_FOLD = 1,             /* default 1: decoder LayerNorms folded into the projections around them  */
-  SPECDEC_OPT_RESIDENT = 2             /* default 0: passes of at most 32 rows run as ONE resident kernel        */
+  SPECDEC_OPT_RESIDENT = 2,            /* default 0: passes of at most 32 rows run as ONE resident kernel        */
+  SPECDEC_OPT_SLICED_SUBLAYERS = 3     /* default 0: the small-batch kernels own sub-layers by output column (six
+                                          kernels per layer); 1: by head / FFN slice (three per layer; measured
+                                          slower: 8-16 workgroups cannot pull a layer's weights fast enough)      */
 } specdec_option;
 
 /* ---- life cycle -------------------------------------------------------------------- */

@@ -30,6 +30,7 @@ SPECDEC_COUNTERS = 8
 SPECDEC_OPT_SMALL_BATCH_KERNELS = 0
 SPECDEC_OPT_LN_FOLD = 1
 SPECDEC_OPT_RESIDENT = 2
+SPECDEC_OPT_SLICED_SUBLAYERS = 3
 
 
 class specdec_model_desc(C.Structure):

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspecdec.so")
-SOURCES = ["api.hip", "gemm.hip", "attn.hip", "misc.hip", "skinny.hip", "resident.hip"]
+SOURCES = ["api.hip", "gemm.hip", "attn.hip", "misc.hip", "skinny.hip", "skinny2.hip", "resident.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", *os.environ.get("SD_EXTRA_FLAGS", "").split(), "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-parameter",
          # packed-fp32 instruction selection off (device pass only; the host pass

@@ -46,6 +46,7 @@ struct Model {
   bf16 *xk = nullptr, *xv = nullptr;   // [Ld][Bmax][H][Scap][64]
   float* x = nullptr;        // [Rmax][d] residual stream
   float* x2 = nullptr;       // [32][d] second residual buffer of the fused small-batch path
+  float* skp = nullptr;      // [2][kSk2MaxParts][32][d] partial results of the sliced small-batch kernels
   bool skinny_ready = false;
   sd::RsLayer* rs_layers = nullptr;   // device copy of the decoder layers' pointers (resident kernel)
   unsigned* rs_bar = nullptr;         // barrier counters + error flag of the resident kernel
@@ -94,6 +95,7 @@ struct specdec_ctx {
   bool no_skinny = false;   // SPECDEC_OPT_SMALL_BATCH_KERNELS = 0: always take the general kernels
   bool no_ln_fold = false;  // SPECDEC_OPT_LN_FOLD = 0: LayerNorm as a pass of its own between the GEMMs
   bool resident = false;    // SPECDEC_OPT_RESIDENT = 1: small batches run the decoder pass as one resident kernel
+  bool sliced = false;      // SPECDEC_OPT_SLICED_SUBLAYERS = 1: small-batch sub-layers owned by head / FFN slice
   char err[512] = {0};
 };
 
@@ -214,6 +216,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   t.xv = cv.take<bf16>(t.xkv_layer * d->dec_layers);
   t.x = cv.take<float>(Rmax * D);
   t.x2 = cv.take<float>(32 * D);
+  t.skp = cv.take<float>((size_t)2 * sd::kSk2MaxParts * 32 * D);
   t.xb = cv.take<bf16>(Rmax * D);
   t.lnp[0] = cv.take<float>(Rmax * (D / 64 + 1) * 2);
   t.lnp[1] = cv.take<float>(Rmax * (D / 64 + 1) * 2);
@@ -249,7 +252,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
     m->kv_layer = t.kv_layer; m->xkv_layer = t.xkv_layer;
     m->pe = t.pe; m->kc = t.kc; m->vc = t.vc; m->xk = t.xk; m->xv = t.xv;
     m->lnp[0] = t.lnp[0]; m->lnp[1] = t.lnp[1]; m->fold = t.fold;
-    m->x = t.x; m->x2 = t.x2; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
+    m->x = t.x; m->x2 = t.x2; m->skp = t.skp; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
     m->part = t.part; m->row_stats = t.row_stats; m->zd = t.zd; m->rm = t.rm;
     m->slots = t.slots; m->new_rows = t.new_rows; m->rs_layers = t.rs_layers; m->rs_bar = t.rs_bar;
     m->ex = t.ex; m->exb = t.exb; m->eqkv = t.eqkv; m->eatt = t.eatt; m->ehid = t.ehid;
@@ -391,6 +394,70 @@ int decoder_layers_skinny(specdec_ctx* c, Model& m, int B, int T, hipStream_t st
   return SPECDEC_OK;
 }
 
+
+// The same pass with three kernels per layer: sub-layers owned by head (attention) and by slice of
+// the FFN width; each kernel leaves partial results that the next one's prologue sums (fixed order),
+// adds bias and residual to, and normalises.  The last layer's FFN runs as two column-owned kernels,
+// so that the vocabulary tiles start from a stored sum.
+int decoder_layers_sliced(specdec_ctx* c, Model& m, int B, int T, hipStream_t st, sd::SkSrc* out) {
+  const int R = B * T, D = m.d.d_model, F = m.d.d_ffn, H = m.d.n_heads;
+  const int Lcap = c->Lcap, Scap = c->Scap;
+  if (!m.skinny_ready) {
+    HIPCHK(c, sd::skinny_init(D));
+    m.skinny_ready = true;
+  }
+  float* S[2] = {m.x, m.x2};
+  float* P[2] = {m.skp, m.skp + (size_t)sd::kSk2MaxParts * 32 * D};
+  const size_t pstride = (size_t)32 * D;
+  int si = 0, pi = 0;
+  // the state a kernel starts from once its pending sum (if any) has been stored by the kernel before
+  auto resolved = [](const sd::SkSrc& s) {
+    if (s.np == 0) return s;
+    sd::SkSrc r{2, s.xs_out, s.g2, s.b2, nullptr, nullptr, nullptr, nullptr};
+    return r;
+  };
+  auto with_sum = [&](sd::SkSrc base, const float* part, int np, const bf16* pbias, const bf16* g2, const bf16* b2,
+                      float* xs_out) {
+    base.part = part; base.np = np; base.part_stride = pstride; base.pbias = pbias; base.g2 = g2; base.b2 = b2;
+    base.xs_out = xs_out;
+    return base;
+  };
+  sd::SkSrc cur{0, nullptr, nullptr, nullptr, m.rm.row_tok, m.rm.row_pos, m.embed, m.pe};
+  for (int l = 0; l < m.d.dec_layers; ++l) {
+    const DecLayer& L = m.dec[l];
+    bf16* kc = m.kc + m.kv_layer * l;
+    bf16* vc = m.vc + m.kv_layer * l;
+    sd::AttnArgs a{};
+    a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
+    a.k = kc; a.k_b = (long)H * Lcap * 64; a.k_h = (long)Lcap * 64; a.k_row = 64;
+    a.v = vc; a.v_b = (long)H * Lcap * 64; a.v_h = (long)Lcap * 64; a.v_row = 64; a.v_blocked = 0;
+    a.o = nullptr; a.o_b = 0; a.o_row = 0;
+    a.q_count = m.rm.seq_rows; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
+    a.T = T; a.H = H; a.B = B; a.key_split = 0; a.cap = Lcap;
+    LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::skinny2_head(st, cur, R, D, a, true, L.wqkv, L.bqkv, m.q, kc, vc, m.rm.row_b,
+                                      m.rm.row_pos, Lcap, L.wo, P[pi]));
+    const sd::SkSrc bsrc = with_sum(resolved(cur), P[pi], H, L.bo, L.ln1g, L.ln1b, S[si]);
+    a.k = m.xk + m.xkv_layer * l; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64;
+    a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_blocked = 1;
+    a.lim_row = nullptr; a.lim_seq = c->st.src_len; a.cap = Scap;
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny2_head(st, bsrc, R, D, a, false, L.cwq, L.cbq, m.q, nullptr, nullptr, nullptr,
+                                      nullptr, Lcap, L.cwo, P[pi ^ 1]));
+    const sd::SkSrc csrc = with_sum(resolved(bsrc), P[pi ^ 1], H, L.cbo, L.ln2g, L.ln2b, S[si ^ 1]);
+    if (l + 1 < m.d.dec_layers) {
+      LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny2_ffn(st, csrc, R, D, L.w1, L.b1, F, L.w2, P[pi]));
+      cur = with_sum(resolved(csrc), P[pi], sd::sk2_ffn_slices(F), L.b2, L.ln3g, L.ln3b, S[si]);
+      si ^= 1;
+      pi ^= 1;
+    } else {
+      LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, csrc, R, D, L.w1, F, L.b1, m.hid, true));
+      LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_ffn2(st, resolved(csrc), R, D, m.hid, F, L.w2, L.b2, S[si]));
+      cur = sd::SkSrc{2, S[si], L.ln3g, L.ln3b, nullptr, nullptr, nullptr, nullptr};
+    }
+  }
+  *out = cur;
+  return SPECDEC_OK;
+}
+
 int cross_kv_from(specdec_ctx* c, Model& m, const bf16* memory, int B, int S_max, hipStream_t st) {
   const int D = m.d.d_model;
   for (int l = 0; l < m.d.dec_layers; ++l)
@@ -449,6 +516,7 @@ int specdec_configure(specdec_ctx* c, int32_t option, int32_t value) {
     case SPECDEC_OPT_SMALL_BATCH_KERNELS: c->no_skinny = (value == 0); break;
     case SPECDEC_OPT_LN_FOLD: c->no_ln_fold = (value == 0); break;
     case SPECDEC_OPT_RESIDENT: c->resident = (value == 1); break;
+    case SPECDEC_OPT_SLICED_SUBLAYERS: c->sliced = (value == 1); break;
     default: return fail(c, SPECDEC_ERR_INVALID_ARG, "unknown option %d", option);
   }
   return SPECDEC_OK;
@@ -816,7 +884,10 @@ int verify_impl(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, f
     failed = m.rs_bar + 16;
   } else if (small) {
     sd::SkSrc fin{};
-    rc = decoder_layers_skinny(c, m, B, T, st, &fin);
+    if (c->sliced && sd::sk2_supported(m.d.d_model, m.d.d_ffn) && m.d.n_heads <= sd::kSk2MaxParts)
+      rc = decoder_layers_sliced(c, m, B, T, st, &fin);
+    else
+      rc = decoder_layers_skinny(c, m, B, T, st, &fin);
     if (rc) return rc;
     LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::skinny_vocab(st, fin, R, m.d.d_model, m.embed, m.d.vocab, m.rm.row_draft, vs.zd, vs.part, logits));
   } else {

@@ -126,6 +126,16 @@ struct SkSrc {
   const int* pos;
   const bf16* E;
   const float* pe;
+  // np > 0: a sub-layer computed in np slices is still to be summed on top of the state above:
+  // hidden = LayerNorm_{g2,b2}(state + pbias + part[0] + .. + part[np-1]), part[p] fp32 [R][d] at
+  // part + p * part_stride; the sum itself is stored to xs_out (fp32 [R][d]) by block 0
+  const float* part = nullptr;
+  int np = 0;
+  size_t part_stride = 0;
+  const bf16* pbias = nullptr;
+  const bf16* g2 = nullptr;
+  const bf16* b2 = nullptr;
+  float* xs_out = nullptr;
 };
 bool skinny_supported(int d, int F);
 
@@ -165,6 +175,17 @@ hipError_t skinny_proj(hipStream_t st, const SkSrc& src, int R, int d, const bf1
                        bf16* out, bool relu);
 hipError_t skinny_ffn2(hipStream_t st, const SkSrc& resid, int R, int d, const bf16* hid, int F, const bf16* W,
                        const bf16* bias, float* xs_out);
+// ---- skinny2.hip: the same passes with sub-layers owned by head / by FFN slice (three kernels per layer) ----
+bool sk2_supported(int d, int F);
+int sk2_ffn_slices(int F);             // partial results the FFN kernel leaves (at most 16)
+constexpr int kSk2MaxParts = 16;       // heads / FFN slices: partial results [R <= 32][d] per kernel
+// head h = block h: [hidden from src] -> Q (| K | V, appended) -> attention -> part_out[h] = att_h Wo[:, 64h..64h+63]^T
+hipError_t skinny2_head(hipStream_t st, const SkSrc& src, int R, int d, const AttnArgs& a, bool self, const bf16* W,
+                        const bf16* bias, bf16* q, bf16* kc, bf16* vc, const int* row_b, const int* row_pos, int Lcap,
+                        const bf16* Wo, float* part_out);
+// slice s = block s: part_out[s] = ReLU(hidden W1[s]^T + b1[s]) W2[:, s]^T
+hipError_t skinny2_ffn(hipStream_t st, const SkSrc& src, int R, int d, const bf16* W1, const bf16* b1, int F,
+                       const bf16* W2, float* part_out);
 // draft logits + per-row partial records per 64-column vocabulary tile (n_tiles = ceil(V/64))
 hipError_t skinny_vocab(hipStream_t st, const SkSrc& src, int R, int d, const bf16* E, int V, const int* row_draft,
                         float* zd_row, float* part, float* logits);

@@ -151,7 +151,10 @@ struct SkHidden {
   // normalise the requested rows and write them out (rows >= R: nothing, see above)
   __device__ __forceinline__ void finish(const SkSrc& s, int R, int nrows, int base, bf16* hb, float* hown, int n0,
                                          bool want_hb, int n0b) {
-    const int lane = threadIdx.x & 63;
+    normalize(s, R, nrows, base);
+    write(R, nrows, base, hb, hown, n0, want_hb, n0b);
+  }
+  __device__ __forceinline__ void normalize(const SkSrc& s, int R, int nrows, int base) {
     const int rmax = min(R, nrows);
     if (s.mode == 2) {
       if (base + STRIDE * 2 < rmax) {
@@ -194,6 +197,11 @@ struct SkHidden {
         }
       }
     }
+  }
+  __device__ __forceinline__ void write(int R, int nrows, int base, bf16* hb, float* hown, int n0, bool want_hb,
+                                        int n0b) {
+    const int lane = threadIdx.x & 63;
+    const int rmax = min(R, nrows);
 #pragma unroll
     for (int u = 0; u < RU; ++u) {
       const int r = base + STRIDE * u;
@@ -221,9 +229,88 @@ struct SkHidden {
   }
 };
 
+// Hidden state with a pending sub-layer sum: the sub-layer before this kernel was computed in
+// slices (one per head, or per slice of the FFN width), each slice leaving a partial result
+// part[p] [R][d] (fp32).  What the kernel needs is
+//     y = base + pbias + part[0] + part[1] + ... + part[np-1]      (summed in this order, always)
+//     hidden = LayerNorm_{g2,b2}(y)
+// with base = the hidden state that SkSrc's first fields describe (the sub-layer's input: the
+// residual).  Every block recomputes it; block 0 also stores y to xs_out (the `xs` of the next
+// kernel's base).  A wave takes rows wave, wave + NW, ..., one at a time: the row's base data and
+// all its partial slices are requested before the first reduction.
+template <int PER, int NW, int PREG = 128>
+__device__ __forceinline__ void sk_hidden_sum(const SkSrc& s, int R, int nrows, bf16* hb, float* hown, int n0,
+                                              bool want_hb, int n0b) {
+  typedef SkHidden<PER, false, 1, NW> HS;
+  constexpr int d = 64 * PER, VEC = HS::VEC, NV = HS::NV;
+  constexpr int PB = (PREG / PER) < 1 ? 1 : (PREG / PER);   // partial slices held in registers at a time
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (wave >= NW) return;
+  HS hs;
+  hs.params(s);
+  float g2[PER], b2[PER], pb[PER];
+#pragma unroll
+  for (int j = 0; j < NV; ++j) {
+    HS::load_vec(s.g2 + HS::col(j * VEC, lane), g2 + j * VEC);
+    HS::load_vec(s.b2 + HS::col(j * VEC, lane), b2 + j * VEC);
+    HS::load_vec(s.pbias + HS::col(j * VEC, lane), pb + j * VEC);
+  }
+  const int rmax = min(R, nrows);
+  for (int r = wave; r < rmax; r += NW) {
+    hs.load(s, R, r);
+    float acc[PER];
+    bool first = true;
+    for (int p0 = 0; p0 < s.np; p0 += PB) {
+      float pv[PB][PER];
+#pragma unroll
+      for (int u = 0; u < PB; ++u) {
+        const int p = min(p0 + u, s.np - 1);
+        const float* src = s.part + (size_t)p * s.part_stride + (size_t)r * d;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) HS::load_vec(src + HS::col(j * VEC, lane), pv[u] + j * VEC);
+      }
+      if (first) {
+        hs.normalize(s, R, nrows, r);
+#pragma unroll
+        for (int i = 0; i < PER; ++i) acc[i] = hs.v[0][i] + pb[i];
+        first = false;
+      }
+#pragma unroll
+      for (int u = 0; u < PB; ++u)
+        if (p0 + u < s.np) {
+#pragma unroll
+          for (int i = 0; i < PER; ++i) acc[i] += pv[u][i];
+        }
+    }
+    if (blockIdx.x == 0 && s.xs_out) {
+#pragma unroll
+      for (int j = 0; j < NV; ++j) {
+        float* dst = s.xs_out + (size_t)r * d + HS::col(j * VEC, lane);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) dst[i] = acc[j * VEC + i];
+      }
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) sum += acc[i];
+    const float mean = wave_sum(sum) / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) { const float t = acc[i] - mean; q += t * t; }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+#pragma unroll
+    for (int i = 0; i < PER; ++i) hs.v[0][i] = (acc[i] - mean) * rstd * g2[i] + b2[i];
+    hs.write(R, nrows, r, hb, hown, n0, want_hb, n0b);
+  }
+}
+
 template <int PER, bool COH = false>
 __device__ __forceinline__ void sk_hidden(const SkSrc& s, int R, int nrows, bf16* hb, float* hown, int n0,
                                           bool want_hb, int n0b = -64) {
+  if (!COH && s.np > 0) {   // (same for the whole grid)
+    sk_hidden_sum<PER, 4>(s, R, nrows, hb, hown, n0, want_hb, n0b);
+    return;
+  }
   const int wave = (threadIdx.x >> 6) & 3;
   if (PER <= 8 && nrows > 16) {   // eight rows per wave at once: still one round trip for 32 rows
     SkHidden<PER, COH, 8> hs;
@@ -245,6 +332,16 @@ __device__ __forceinline__ void sk_hidden(const SkSrc& s, int R, int nrows, bf16
 // (LayerNorm, attention) runs; sk_mma consumes them:
 //   acc[t] += W[n0 + i][k] . B_t[j][k],  getB(t, k) = 8 bf16 of activation row t*16 + lane%16 at k.
 // Step counts and the second row tile are compile-time, so the MFMA sequence is straight-line.
+// four consecutive bf16 (8-byte aligned) stored so that other waves' coherent loads see them
+__device__ __forceinline__ void st_coh4(bf16* p, const float (&v)[4]) {
+  bf16x4 t;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) t[i] = (bf16)v[i];
+  unsigned long long u;
+  __builtin_memcpy(&u, &t, 8);
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 constexpr int kSkW = 16;   // most steps held in registers at a time
 template <int S>
 __device__ __forceinline__ void sk_wload(const bf16* __restrict__ W, int ldw, int n0, int N, int k0,

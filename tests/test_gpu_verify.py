@@ -251,9 +251,10 @@ def test_argument_errors_on_device():
 def test_small_batch_paths_agree():
     """The implementations of a pass of at most 32 rows -- general kernels with LayerNorm folded
     into the GEMMs around it (what larger batches run), general kernels with LayerNorm as a
-    pass of its own, fused per-projection kernels (the default at this size) and the single
-    resident kernel (opt-in) -- all match the oracle, and the two fused paths give the same
-    logits to the last bit; the cases cover d = 128, d = 512 with two 16-row tiles (B = 2,
+    pass of its own, fused per-projection kernels (the default at this size), kernels that own
+    sub-layers by head / FFN slice (opt-in) and the single resident kernel (opt-in) -- all match the oracle,
+    every one gives the same bits when run twice, and the per-projection and resident paths give
+    the same logits to the last bit; the cases cover d = 128, d = 512 with two 16-row tiles (B = 2,
     k = 10) and d = 1024 with one and two tiles."""
     import gpu_harness as gh
     case = cases.make_verify_case(small_desc(), seed=21, B=3, S=9, k=4, beta=3, tau=1.0, len_lo=0, len_hi=12,
@@ -274,9 +275,12 @@ def test_small_batch_paths_agree():
         outs = {}
         for tag, opts in (("general", {sd.SPECDEC_OPT_SMALL_BATCH_KERNELS: 0}),
                           ("general, separate LayerNorm", {sd.SPECDEC_OPT_SMALL_BATCH_KERNELS: 0, sd.SPECDEC_OPT_LN_FOLD: 0}),
-                          ("fused", {}), ("resident", {sd.SPECDEC_OPT_RESIDENT: 1})):
+                          ("fused", {}), ("sliced", {sd.SPECDEC_OPT_SLICED_SUBLAYERS: 1}),
+                          ("resident", {sd.SPECDEC_OPT_RESIDENT: 1})):
             ses = gh.open_verifier(cs, options=opts)
             outs[tag] = gh.gpu_verify(ses, cs)
+            again = gh.gpu_verify(ses, cs)          # every path gives the same bits when run twice
+            assert np.array_equal(outs[tag]["logits"], again["logits"]), tag
             ses.close()
             err = np.abs(outs[tag]["logits"] - cs.logits).max()
             print(f"[paths {tag}] logits max-abs err {err:.3e}")
