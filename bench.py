@@ -98,6 +98,44 @@ def _timed(torch, fn, steps, warmup):
     return (time.perf_counter() - t0) / steps
 
 
+class Evictor:
+    """A streaming pass over 1 GiB between replays: whatever the last-level cache (256 MiB) held of
+    weights and K/V is gone when the next replay starts (the LLC-cold figures)."""
+
+    def __init__(self, torch, dev):
+        self.a = torch.empty(128 << 20, dtype=torch.float32, device=dev)
+        self.b = torch.empty(128 << 20, dtype=torch.float32, device=dev)
+        self.a.fill_(1.0)
+
+    def __call__(self):
+        self.b.copy_(self.a)
+
+
+def latency_stats(torch, fn, reps=200, warmup=20, evict=None, prep=None):
+    """Per-replay durations from event pairs on the current stream (the one the library launches on):
+    median / p10 / p90 in microseconds.  prep, evict: called before every replay, outside the bracket."""
+    for _ in range(warmup):
+        if prep is not None:
+            prep()
+        fn()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for e0, e1 in ev:
+        if prep is not None:
+            prep()
+        if evict is not None:
+            evict()
+        e0.record()
+        fn()
+        e1.record()
+    torch.cuda.synchronize()
+    us = np.array([e0.elapsed_time(e1) * 1e3 for e0, e1 in ev])
+    return {"median_us": float(np.median(us)), "p10_us": float(np.percentile(us, 10)), "p90_us": float(np.percentile(us, 90))}
+
+
+def warm_and_cold(torch, fn, evictor, reps=200, prep=None):
+    return {"warm": latency_stats(torch, fn, reps, prep=prep), "llc_cold": latency_stats(torch, fn, reps, evict=evictor, prep=prep)}
+
+
 def dec_flops_per_row(desc):
     d, F = desc.d_model, desc.d_ffn
     return 2.0 * desc.dec_layers * (3 * d * d + 3 * d * d + 2 * d * F)
@@ -130,7 +168,8 @@ def kind_work(vdesc, ddesc, B, k, L, src_len, tokens_per_step):
 
 def batch1_latency(sd, synth, torch, steps=200):
     """Single verify step at batch 1 (base verifier, memory 32 x 512 ~N(0,1), 16 tokens decoded,
-    k=5 random drafts, beta=3, tau=1)."""
+    k=5 random drafts, beta=3, tau=1): mean of back-to-back replays as before, plus median / p10 /
+    p90 of event-bracketed replays, warm and LLC-cold."""
     desc = synth.base_verifier(max_src=32, max_tgt=64, enc_layers=0)
     B, k, L = 1, 5, 16
     ses = sd.Session(B, k, 32, 64)
@@ -142,7 +181,10 @@ def batch1_latency(sd, synth, torch, steps=200):
     dr = ses.i32(synth.random_tokens(SEED, "drafts", (B, k), desc, full_vocab=True))
     acc = torch.zeros(B, dtype=torch.int32, device=ses.device)
     nxt = torch.zeros_like(acc)
-    sec = _timed(torch, lambda: sd.specdec_verify(ses.ctx, dr, k, 3, 1.0, acc, nxt), steps, 20)
+    evictor = Evictor(torch, ses.device)
+    fn = lambda: sd.specdec_verify(ses.ctx, dr, k, 3, 1.0, acc, nxt)
+    sec = _timed(torch, fn, steps, 20)
+    stats = warm_and_cold(torch, fn, evictor, steps)
     # the paper's best block size (k = 25, Table 3): 26 rows still fit one pass of the same kernels
     ses25 = sd.Session(B, 25, 32, 96)
     ses25.bind_model(sd.SPECDEC_VERIFIER, desc, ses25.upload_weights(synth.make_weights(desc, SEED)))
@@ -159,9 +201,153 @@ def batch1_latency(sd, synth, torch, steps=200):
     kvbytes = 2 * 2 * desc.dec_layers * ((L + k + 1) + 32) * d
     ses.close()
     return {"workload": "single verify step: base verifier 6L d512, B=1, memory 32, 16 decoded, k=5",
-            "verify_us": sec * 1e6, "algorithmic_bytes": wbytes + kvbytes,
+            "verify_us": sec * 1e6, "verify_us_stats": stats, "algorithmic_bytes": wbytes + kvbytes,
             "hbm_frac": (wbytes + kvbytes) / sec / (PEAK_HBM_GBS * 1e9),
+            "hbm_frac_llc_cold": (wbytes + kvbytes) / (stats["llc_cold"]["median_us"] * 1e-6) / (PEAK_HBM_GBS * 1e9),
             "verify_us_k25": sec25 * 1e6, "ar_step_us_k0": sec_ar * 1e6}
+
+
+def other_configs(sd, synth, torch, reps=200):
+    """Verify-step / drafter-pass latencies of the remaining workload definitions (median / p10 / p90,
+    warm and LLC-cold): batched verify step on the base verifier (B=32, memory 64, decoded U[0,64],
+    k=10), the Spec-Drafter pass (B=64, source 128, 32 decoded, k=10), and the summarization-shaped
+    verify step (big verifier, B=32, source 1024, 224 decoded, k=10, beta=5, tau=3)."""
+    out = {}
+    # batched verify step, base verifier
+    desc = synth.base_verifier(max_src=64, max_tgt=128, enc_layers=0)
+    B, k, S = 32, 10, 64
+    ses = sd.Session(B, k, S, 128)
+    ses.bind_model(sd.SPECDEC_VERIFIER, desc, ses.upload_weights(synth.make_weights(desc, SEED)))
+    sd.specdec_begin(ses.ctx, B, 10 ** 6)
+    sd.specdec_set_memory(ses.ctx, sd.SPECDEC_VERIFIER, ses.bf16(synth.make_memory(SEED, B, S, desc.d_model)), ses.i32(np.full(B, S)))
+    lens = synth.random_lengths(SEED, "prefix_len", B, 0, 64)
+    toks = synth.random_tokens(SEED, "prefix", (B, 65), desc)
+    toks[:, 0] = desc.bos_id
+    sd.specdec_set_stream(ses.ctx, ses.i32(toks), ses.i32(lens))
+    sd.specdec_prefill(ses.ctx, sd.SPECDEC_VERIFIER)
+    dr = ses.i32(synth.random_tokens(SEED, "drafts", (B, k), desc, full_vocab=True))
+    acc = torch.zeros(B, dtype=torch.int32, device=ses.device)
+    nxt = torch.zeros_like(acc)
+    evictor = Evictor(torch, ses.device)
+    r = warm_and_cold(torch, lambda: sd.specdec_verify(ses.ctx, dr, k, 3, 1.0, acc, nxt), evictor, reps)
+    r["workload"] = "verify step: base verifier, B=32, memory 64, decoded U[0,64], k=10 (352 rows)"
+    out["batched_verify_base"] = r
+    ses.close()
+    # Spec-Drafter pass
+    dd = synth.spec_drafter(max_src=128, max_tgt=64, enc_layers=12)
+    B, k, S, L = 64, 10, 128, 32
+    ses = sd.Session(B, k, S, 64)
+    ses.bind_model(sd.SPECDEC_DRAFTER, dd, ses.upload_weights(synth.make_weights(dd, SEED, tag="drafter")))
+    sd.specdec_begin(ses.ctx, B, 10 ** 6)
+    sd.specdec_encode(ses.ctx, ses.i32(synth.random_tokens(SEED, "src", (B, S), dd)), ses.i32(np.full(B, S)))
+    toks = synth.random_tokens(SEED, "prefix", (B, L + 1), dd)
+    toks[:, 0] = dd.bos_id
+    len0 = ses.i32(np.full(B, L))
+    sd.specdec_set_stream(ses.ctx, ses.i32(toks), len0)
+    sd.specdec_prefill(ses.ctx, sd.SPECDEC_DRAFTER)
+    out_dr = torch.zeros((B, k), dtype=torch.int32, device=ses.device)
+    Kc = torch.zeros((dd.dec_layers, B, L, dd.d_model), dtype=torch.bfloat16, device=ses.device)
+    Vc = torch.zeros_like(Kc)
+    sd.specdec_get_cache(ses.ctx, sd.SPECDEC_DRAFTER, Kc, Vc)
+    # before every replay (outside the bracket) the drafter's cache is set back to the 32 decoded
+    # tokens, so that every pass ingests the pending token and drafts k slots: 1 + k rows per sequence
+    r = warm_and_cold(torch, lambda: sd.specdec_draft(ses.ctx, k, out_dr), evictor, reps,
+                      prep=lambda: sd.specdec_load_cache(ses.ctx, sd.SPECDEC_DRAFTER, Kc, Vc, len0))
+    r["workload"] = "Spec-Drafter pass: 12+2 d512, B=64, source 128, 32 decoded + pending token, k=10 mask slots (704 rows)"
+    out["drafter_pass"] = r
+    ses.close()
+    # summarization-shaped verify step
+    desc = synth.big_verifier(max_src=1024, max_tgt=256, enc_layers=0)
+    B, k, S, L = 32, 10, 1024, 224
+    ses = sd.Session(B, k, S, 256)
+    ses.bind_model(sd.SPECDEC_VERIFIER, desc, ses.upload_weights(synth.make_weights(desc, SEED, tag="verifier")))
+    sd.specdec_begin(ses.ctx, B, 10 ** 6)
+    sd.specdec_set_memory(ses.ctx, sd.SPECDEC_VERIFIER, ses.bf16(synth.make_memory(SEED, B, S, desc.d_model)), ses.i32(np.full(B, S)))
+    toks = synth.random_tokens(SEED, "prefix", (B, L + 1), desc)
+    toks[:, 0] = desc.bos_id
+    sd.specdec_set_stream(ses.ctx, ses.i32(toks), ses.i32(np.full(B, L)))
+    sd.specdec_prefill(ses.ctx, sd.SPECDEC_VERIFIER)
+    dr = ses.i32(synth.random_tokens(SEED, "drafts", (B, k), desc, full_vocab=True))
+    acc = torch.zeros(B, dtype=torch.int32, device=ses.device)
+    nxt = torch.zeros_like(acc)
+    r = warm_and_cold(torch, lambda: sd.specdec_verify(ses.ctx, dr, k, 5, 3.0, acc, nxt), evictor, reps)
+    d, F, V, H = desc.d_model, desc.d_ffn, desc.vocab, desc.n_heads
+    bytes_alg = 2.0 * (desc.dec_layers * (8 * d * d + 2 * d * F) + V * d) + 2.0 * 2 * desc.dec_layers * B * (S + L + k + 1) * d
+    r["workload"] = "verify step: big verifier, B=32, source 1024, 224 decoded, k=10 (352 rows), beta=5 tau=3"
+    r["algorithmic_bytes"] = bytes_alg
+    r["hbm_frac_warm"] = bytes_alg / (r["warm"]["median_us"] * 1e-6) / (PEAK_HBM_GBS * 1e9)
+    out["summarization_verify"] = r
+    ses.close()
+    return out
+
+
+def full_loop(sd, synth, torch, ses, vdesc, B, k, beta, tau, d_src, d_len, max_new):
+    """The whole translation-shaped job, run to the length cap (Sec. 3.1.1 Eq. 4: time = iterations x
+    (t_d + t_v)): encode once, then draft -> verify -> commit until every sequence has max_new tokens
+    (or an EOS).  First plain autoregressive decoding (k = 0) to the cap, which also yields the
+    verifier's greedy output; then the draft-then-verify loop with the drafter running at full cost
+    and its tokens replaced by that greedy output with 20 % of the positions corrupted (the drafts of a
+    sequence are gathered on the device from its current length: no host round trip per iteration)."""
+    dev = ses.device
+    acc = torch.zeros(B, dtype=torch.int32, device=dev)
+    nxt = torch.zeros(B, dtype=torch.int32, device=dev)
+    nact = torch.ones(1, dtype=torch.int32, device=dev)
+    zero = torch.zeros(B, dtype=torch.int32, device=dev)
+    toks = torch.zeros((B, max_new), dtype=torch.int32, device=dev)
+    olen = torch.zeros(B, dtype=torch.int32, device=dev)
+    cnt = torch.zeros(sd.SPECDEC_COUNTERS, dtype=torch.int32, device=dev)
+
+    def start():
+        sd.specdec_begin(ses.ctx, B, max_new)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        sd.specdec_encode(ses.ctx, d_src, d_len)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    enc_s = start()
+    t0 = time.perf_counter()
+    for _ in range(max_new):
+        sd.specdec_verify(ses.ctx, None, 0, 1, 0.0, acc, nxt)
+        sd.specdec_commit(ses.ctx, zero, nxt, nact)
+    sd.specdec_get_output(ses.ctx, toks, olen)
+    sd.specdec_get_counters(ses.ctx, cnt)
+    torch.cuda.synchronize()
+    ar_s = time.perf_counter() - t0
+    ar_tokens = int(cnt[1].item())
+    greedy = toks.cpu().numpy()
+    script = np.concatenate([greedy, np.full((B, k + 1), vdesc.pad_id, np.int32)], axis=1)
+    script = torch.as_tensor(synth.corrupt(SEED, "corrupt_loop", script, 0.2, vdesc), device=dev).long()
+    col = torch.arange(k, device=dev).long()[None, :]
+    scratch = torch.zeros((B, k), dtype=torch.int32, device=dev)
+
+    enc2_s = start()
+    t0 = time.perf_counter()
+    iters = 0
+    while iters < max_new + 2:
+        sd.specdec_draft(ses.ctx, k, scratch)                              # drafter at full cost, output unused
+        sd.specdec_get_output(ses.ctx, toks, olen)
+        drafts = torch.gather(script, 1, olen.long()[:, None] + col).to(torch.int32).contiguous()
+        sd.specdec_verify(ses.ctx, drafts, k, beta, tau, acc, nxt)
+        sd.specdec_commit(ses.ctx, acc, nxt, nact)
+        iters += 1
+        if iters % 4 == 0 and int(nact.item()) == 0:
+            break
+    sd.specdec_get_counters(ses.ctx, cnt)
+    torch.cuda.synchronize()
+    loop_s = time.perf_counter() - t0
+    c = cnt.cpu().numpy()
+    tokens = int(c[1])
+    return {"workload": f"B={B}, up to {max_new} tokens per sequence, k={k}, beta={beta}, tau={tau}; greedy output of the "
+                        "verifier with 20% corrupted positions as drafts, drafter run at full cost",
+            "encode_ms": enc2_s * 1e3, "iterations": int(c[0]), "committed_tokens": tokens,
+            "tok_per_iteration": tokens / max(1, int(c[0])) / B, "loop_ms": loop_s * 1e3,
+            "tokens_per_s_excl_encode": tokens / loop_s, "tokens_per_s_incl_encode": tokens / (loop_s + enc2_s),
+            "autoregressive": {"committed_tokens": ar_tokens, "loop_ms": ar_s * 1e3, "tokens_per_s_excl_encode": ar_tokens / ar_s,
+                               "tokens_per_s_incl_encode": ar_tokens / (ar_s + enc_s)},
+            "speedup_vs_autoregressive": (tokens / (loop_s + enc2_s)) / (ar_tokens / (ar_s + enc_s)),
+            "note": "host polls the number of unfinished sequences every 4 iterations; the loop counts iterations in which every "
+                    "sequence is already finished until that poll"}
 
 
 def cpu_baseline(vdesc, ddesc, B_sample, k, L, src, src_len, beta, tau, budget_s=24.0):
@@ -222,7 +408,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-batch1", action="store_true")
+    ap.add_argument("--no-batch1", action="store_true", help="skip the single-sequence step and the other workload configs")
+    ap.add_argument("--no-full-loop", action="store_true", help="skip the loop run to the length cap")
     ap.add_argument("--batch1-only", action="store_true",
                     help="run only the single-sequence verify step (the `batch1` object of the usual line) and "
                          "print it: the command behind profiles/verify_step_batch1.kernel_stats.md")
@@ -358,9 +545,39 @@ def main():
     out["ar_baseline"] = {"step_us": asec * 1e6, "tokens_per_s": B / asec,
                           "specdec_speedup": (tokens_per_step / sec) / (B / asec),
                           "note": "same library, k = 0 (one token per sequence per step), same state"}
+    evictor = Evictor(torch, dev)
+    out["batch128"]["verify_us_stats"] = warm_and_cold(
+        torch, lambda: sd.specdec_verify(ses.ctx, drafts, k, beta, tau, acc, nxt), evictor, 200)
+    out["batch128"]["kernel_ms_per_step_note"] = ("each kind bracketed by HIP events in a pass of its own: the brackets include the "
+                                                  "dispatch gaps, so the kinds do not add up to ms_per_step")
+
+    # the same iteration at the three operating points of an untrained model pair
+    def op_point(vdrafts, b_, t_):
+        def st():
+            sd.specdec_verify(ses.ctx, vdrafts, k, b_, t_, acc, nxt)
+            sd.specdec_commit(ses.ctx, acc, nxt)
+            sd.specdec_draft(ses.ctx, k, scratch)
+            sd.specdec_rewind(ses.ctx, len0)
+        st()
+        torch.cuda.synchronize()
+        tps = int((acc + 1).sum().item())
+        t = _timed(torch, st, max(20, args.steps // 4), 5)
+        return {"tokens_per_step": tps, "tok_per_iteration": tps / B, "iteration_us": t * 1e6, "tokens_per_s": tps / t}
+
+    sd.specdec_draft(ses.ctx, k, scratch)
+    natural = scratch.clone()
+    out["operating_points"] = {
+        "natural": dict(op_point(natural, beta, tau), note="verify is fed the drafter's own output (untrained pair: nothing is accepted)"),
+        "scripted": {"tokens_per_step": tokens_per_step, "tok_per_iteration": tokens_per_step / B, "iteration_us": sec * 1e6,
+                     "tokens_per_s": tokens_per_step / sec, "note": "the headline value: greedy continuation with 20% corruption"},
+        "accept_all": dict(op_point(drafts, vdesc.vocab, 3.0e38), note="beta = V, tau = 3e38: every draft passes (upper bound, k + 1 tokens)"),
+    }
+    if not args.no_full_loop:
+        out["full_loop"] = full_loop(sd, synth, torch, ses, vdesc, B, k, beta, tau, d_src, d_len, 128)
     ses.close()
     if not args.no_batch1:
         out["batch1"] = batch1_latency(sd, synth, torch)
+        out["other_configs"] = other_configs(sd, synth, torch)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(vdesc, ddesc, 4, k, L, src, src_len, beta, tau)
     print(json.dumps(out))
