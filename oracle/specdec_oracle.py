@@ -16,6 +16,7 @@ What follows the paper, and where:
   * strict acceptance / bifurcation position c                 (Sec. 2, Eq. 1, 3)
   * relaxed top-beta / tau acceptance                          (Sec. 3.2, Eq. 8-10)
   * Spec-Drafter inference: prefix + k [MASK] slots, argmax    (Sec. 3.1.3, Eq. 7)
+  * head-based drafting (the Blockwise Decoding comparison)    (Sec. 2 "Draft", Table 2)
   * loop: draft, verify, commit until EOS or the length cap    (Sec. 2)
   * Tok. = accepted tokens per iteration                       (Sec. 3.1.1, Eq. 4)
 
@@ -220,11 +221,12 @@ def verify_sequential(model: Model, st: DecState, pending: int, drafts) -> np.nd
     return np.stack(rows)
 
 
-def verify_onepass(model: Model, st: DecState, pending: int, drafts) -> np.ndarray:
-    """The same k+1 rows of logits from ONE causal pass over [pending, drafts]."""
+def verify_onepass(model: Model, st: DecState, pending: int, drafts, return_hidden: bool = False):
+    """The same k+1 rows of logits from ONE causal pass over [pending, drafts]
+    (return_hidden: also the final hidden states [k+1, d] the logits were taken from)."""
     T = len(drafts) + 1
     h = decoder_rows(model, st, [pending] + list(drafts), np.tril(np.ones((T, T), dtype=bool)))
-    return vocab_logits(model, h)
+    return (vocab_logits(model, h), h) if return_hidden else vocab_logits(model, h)
 
 
 def accept(logits, drafts, beta: int, tau: float) -> Tuple[int, int]:
@@ -293,6 +295,21 @@ def draft(model: Model, dst: DecState, stream: Sequence[int], k: int, return_log
     h = decoder_rows(model, dst, new + [model.desc.mask_id] * k, vis)
     dst.len += n
     z = vocab_logits(model, h[n:])
+    toks = [int(t) for t in np.argmax(z, axis=-1)]
+    return (toks, z) if return_logits else toks
+
+
+def head_draft(model: Model, heads: Sequence[Dict[str, np.ndarray]], h: np.ndarray, return_logits: bool = False):
+    """Head-based drafting (the drafter of Blockwise Decoding that Sec. 2 'Draft' and Table 2
+    compare against): FFN heads on top of the target model's final hidden state h [d] of the
+    last position, one per drafted token, all sharing the model's attention and its output
+    embedding.  The paper gives no more than that; the reading taken: head i is a residual
+    feed-forward block, h_i = h + W2_i relu(W1_i h + b1_i) + b2_i, its token is the arg-max of
+    the tied output projection of h_i.  The model's own head (no block) predicts the next token;
+    head i predicts the token i positions after it.
+    heads: dicts with w1 [F,d], b1 [F], w2 [d,F], b2 [d].  Returns len(heads) tokens."""
+    rows = [h + linear(np.maximum(linear(h, hd["w1"], hd["b1"]), 0), hd["w2"], hd["b2"]) for hd in heads]
+    z = vocab_logits(model, np.stack(rows))
     toks = [int(t) for t in np.argmax(z, axis=-1)]
     return (toks, z) if return_logits else toks
 

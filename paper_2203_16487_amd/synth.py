@@ -129,6 +129,20 @@ def make_weights(desc: ModelDesc, seed: int, tag: str = "model", std: float = 0.
     return out
 
 
+def make_head_weights(desc: ModelDesc, n_heads: int, seed: int, std: float = 0.02) -> List[Dict[str, np.ndarray]]:
+    """Drafting heads on top of a model (residual FFN blocks of the model's widths): per head
+    w1 [F,d], b1 [F], w2 [d,F], b2 [d] as bf16 bit patterns."""
+    d, f = desc.d_model, desc.d_ffn
+    out = []
+    for i in range(n_heads):
+        hd = {}
+        for name, shape in (("w1", (f, d)), ("b1", (f,)), ("w2", (d, f)), ("b2", (d,))):
+            g = stream(seed, f"head{i}/{name}")
+            hd[name] = f32_to_bf16_bits(g.standard_normal(shape, dtype=np.float32) * np.float32(std))
+        out.append(hd)
+    return out
+
+
 def weights_f32(bits: Dict[str, np.ndarray]) -> Dict[str, np.ndarray]:
     return {k: bf16_bits_to_f32(v) for k, v in bits.items()}
 

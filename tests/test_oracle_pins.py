@@ -437,3 +437,35 @@ def test_fp32_oracle_close_to_fp64():
     a = orc.verify_onepass(m32, prefilled_state(m32, mem, toks[:-1], 32), toks[-1], [9, 10, 11])
     b = orc.verify_onepass(m64, prefilled_state(m64, mem.astype(np.float64), toks[:-1], 32), toks[-1], [9, 10, 11])
     assert np.abs(a - b).max() < 1e-4
+
+
+# ----------------------------------------------------------------------------- head-based drafter
+def test_head_draft_reduces_to_the_models_own_prediction_and_matches_torch():
+    """Pins of orc.head_draft (Sec. 2 'Draft': FFN heads on the target model's last hidden state).
+    (i) A head whose second layer is zero leaves h unchanged, so its token is the model's own
+    next-token arg-max (shared output embedding, residual path).  (ii) The block itself against
+    torch.nn.functional on the same weights.  (iii) A head that adds the embedding of token t,
+    scaled up, to h drafts t (the residual sum feeds the tied projection)."""
+    import torch
+    import torch.nn.functional as TF
+    model = tiny_model(seed=3)
+    mem = tiny_memory(model, seed=3)
+    st = prefilled_state(model, mem, [0, 7, 9], 12)
+    z, h = orc.verify_onepass(model, st, 11, [5, 6], return_hidden=True)
+    d, F = model.desc.d_model, model.desc.d_ffn
+    rng = np.random.default_rng(5)
+    zero = dict(w1=rng.standard_normal((F, d)).astype(np.float32), b1=rng.standard_normal(F).astype(np.float32),
+                w2=np.zeros((d, F), np.float32), b2=np.zeros(d, np.float32))
+    assert orc.head_draft(model, [zero, zero], h[2]) == [int(np.argmax(z[2]))] * 2
+    hd = dict(w1=rng.standard_normal((F, d)).astype(np.float32) * 0.3, b1=rng.standard_normal(F).astype(np.float32) * 0.3,
+              w2=rng.standard_normal((d, F)).astype(np.float32) * 0.3, b2=rng.standard_normal(d).astype(np.float32) * 0.3)
+    toks, zl = orc.head_draft(model, [hd], h[1], return_logits=True)
+    ht = torch.from_numpy(h[1].astype(np.float32))
+    ref = ht + TF.linear(TF.relu(TF.linear(ht, torch.from_numpy(hd["w1"]), torch.from_numpy(hd["b1"]))),
+                         torch.from_numpy(hd["w2"]), torch.from_numpy(hd["b2"]))
+    zr = (ref @ torch.from_numpy(model.w["embed"].astype(np.float32)).T).numpy()
+    assert np.abs(zl[0] - zr).max() <= 1e-4 and toks[0] == int(np.argmax(zr))
+    t = 17
+    push = dict(w1=np.zeros((F, d), np.float32), b1=np.zeros(F, np.float32), w2=np.zeros((d, F), np.float32),
+                b2=(model.w["embed"][t] * 100.0).astype(np.float32))
+    assert orc.head_draft(model, [push], h[0]) == [t]
