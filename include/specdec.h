@@ -159,6 +159,23 @@ int specdec_prefill(specdec_ctx* ctx, specdec_role role, void* stream);
  * logits_or_null: optional device fp32 [B, k, V] receiving the slots' logits (parity mode; slow). */
 int specdec_draft(specdec_ctx* ctx, int32_t k, int32_t* draft, float* logits_or_null, void* stream);
 
+/* Head-based drafting, the cheap drafter the paper compares the Spec-Drafter with (Sec. 2 "Draft",
+ * Table 2 first row: k - 1 feed-forward heads on top of the target model, sharing its attention).
+ * specdec_bind_draft_heads: n_heads residual feed-forward blocks of the verifier's widths, stacked
+ * (device bf16): w1 [n_heads * F, d], b1 [n_heads * F], w2 [n_heads, d, F], b2 [n_heads * d];
+ * used in place.  specdec_draft_heads, called after specdec_verify (before or after
+ * specdec_commit of the same pass): with h_b the verifier's final hidden state on the bifurcation
+ * row accept_len[b] of that pass (the row whose arg-max is next_token),
+ *   draft[b][i] = arg-max of  E (h_b + W2_i relu(W1_i h_b + b1_i) + b2_i),   i = 0 .. k-1,
+ * the drafts of the positions after next_token: the input of the next specdec_verify once this
+ * pass is committed.  pad_id for finished sequences.  k <= n_heads.  The projection is the
+ * verifier's tied output matrix.  Overwrites the row statistics of the verification pass.
+ * logits_or_null: optional device fp32 [B, k, V] (parity mode). */
+int specdec_bind_draft_heads(specdec_ctx* ctx, int32_t n_heads, const void* w1, const void* b1, const void* w2,
+                             const void* b2);
+int specdec_draft_heads(specdec_ctx* ctx, const int32_t* accept_len, int32_t k, int32_t* draft,
+                        float* logits_or_null, void* stream);
+
 /* Verification (Sec. 2 Eq. 1-3; Sec. 3.2 Eq. 8-10): one KV-cached pass of the verifier's
  * decoder over rows [u_j, y~_{j+1}, .., y~_{j+k}] (causal; keys/values of the rows are
  * appended after the cached ones), vocabulary projection and log-softmax statistics fused

@@ -60,6 +60,8 @@ EXPORTS = {
     "specdec_load_cache": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]),
     "specdec_prefill": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p]),
     "specdec_draft": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "specdec_bind_draft_heads": (C.c_int, [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "specdec_draft_heads": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "specdec_configure": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "specdec_set_prefix": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "specdec_get_draft_stats": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
@@ -204,6 +206,14 @@ def specdec_prefill(ctx, role: int):
 
 def specdec_draft(ctx, k: int, draft, logits=None):
     _check(ctx, lib().specdec_draft(ctx, k, _ptr(draft), _ptr(logits), _stream()))
+
+
+def specdec_bind_draft_heads(ctx, n_heads: int, w1, b1, w2, b2):
+    _check(ctx, lib().specdec_bind_draft_heads(ctx, n_heads, _ptr(w1), _ptr(b1), _ptr(w2), _ptr(b2)))
+
+
+def specdec_draft_heads(ctx, accept_len, k: int, draft, logits=None):
+    _check(ctx, lib().specdec_draft_heads(ctx, _ptr(accept_len), k, _ptr(draft), _ptr(logits), _stream()))
 
 
 def specdec_configure(ctx, option: int, value: int):

@@ -47,6 +47,7 @@ struct Model {
   float* x = nullptr;        // [Rmax][d] residual stream
   float* x2 = nullptr;       // [32][d] second residual buffer of the fused small-batch path
   float* skp = nullptr;      // [2][kSk2MaxParts][32][d] partial results of the sliced small-batch kernels
+  float* hx = nullptr;       // [Bmax*k_max][d] head-based drafting: the hidden state each head adds to, then its output
   bool skinny_ready = false;
   sd::RsLayer* rs_layers = nullptr;   // device copy of the decoder layers' pointers (resident kernel)
   unsigned* rs_bar = nullptr;         // barrier counters + error flag of the resident kernel
@@ -85,6 +86,13 @@ struct specdec_ctx {
   int last_T = 0;     // rows per sequence (k + 1) of the latest verify (0: none)
   int last_k_draft = 0;   // k of the latest drafter pass (0: none)
   const float* last_row_stats = nullptr;   // merged row statistics of the latest verify
+  // final hidden states of the latest verify: rows [B*T][d], normalised, or still to be normalised with (fin_g, fin_b)
+  const float* fin_x = nullptr;
+  const bf16 *fin_g = nullptr, *fin_b = nullptr;
+  // drafting heads on top of the verifier (stacked): w1 [n*F,d], b1 [n*F], w2 [n][d,F], b2 [n*d]
+  int n_draft_heads = 0;
+  const bf16 *hw1 = nullptr, *hb1 = nullptr, *hw2 = nullptr, *hb2 = nullptr;
+  bool last_draft_by_heads = false;
   int S_cur = 0;      // S_max of the current memory
   int uncached_ub[2] = {0, 0};
   bool trusted[2] = {false, false};
@@ -217,6 +225,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   t.x = cv.take<float>(Rmax * D);
   t.x2 = cv.take<float>(32 * D);
   t.skp = cv.take<float>((size_t)2 * sd::kSk2MaxParts * 32 * D);
+  t.hx = cv.take<float>(Bm * (size_t)c->lim.k_max * D);
   t.xb = cv.take<bf16>(Rmax * D);
   t.lnp[0] = cv.take<float>(Rmax * (D / 64 + 1) * 2);
   t.lnp[1] = cv.take<float>(Rmax * (D / 64 + 1) * 2);
@@ -252,7 +261,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
     m->kv_layer = t.kv_layer; m->xkv_layer = t.xkv_layer;
     m->pe = t.pe; m->kc = t.kc; m->vc = t.vc; m->xk = t.xk; m->xv = t.xv;
     m->lnp[0] = t.lnp[0]; m->lnp[1] = t.lnp[1]; m->fold = t.fold;
-    m->x = t.x; m->x2 = t.x2; m->skp = t.skp; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
+    m->x = t.x; m->x2 = t.x2; m->skp = t.skp; m->hx = t.hx; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
     m->part = t.part; m->row_stats = t.row_stats; m->zd = t.zd; m->rm = t.rm;
     m->slots = t.slots; m->new_rows = t.new_rows; m->rs_layers = t.rs_layers; m->rs_bar = t.rs_bar;
     m->ex = t.ex; m->exb = t.exb; m->eqkv = t.eqkv; m->eatt = t.eatt; m->ehid = t.ehid;
@@ -882,6 +891,7 @@ int verify_impl(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, f
     m.rs_parity ^= 1;
     LAUNCH(c, SPECDEC_KIND_RESIDENT, st, sd::resident_verify(st, a, m.d.d_model, m.d.d_ffn));
     failed = m.rs_bar + 16;
+    c->fin_x = nullptr;   // (the resident kernel keeps its last sum to itself)
   } else if (small) {
     sd::SkSrc fin{};
     if (c->sliced && sd::sk2_supported(m.d.d_model, m.d.d_ffn) && m.d.n_heads <= sd::kSk2MaxParts)
@@ -890,9 +900,11 @@ int verify_impl(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, f
       rc = decoder_layers_skinny(c, m, B, T, st, &fin);
     if (rc) return rc;
     LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::skinny_vocab(st, fin, R, m.d.d_model, m.embed, m.d.vocab, m.rm.row_draft, vs.zd, vs.part, logits));
+    c->fin_x = fin.xs; c->fin_g = fin.g; c->fin_b = fin.b;
   } else {
     rc = decoder_layers(c, m, B, T, st, true);
     if (rc) return rc;
+    c->fin_x = m.x; c->fin_g = nullptr; c->fin_b = nullptr;   // normalised in place by the last LayerNorm
     n_tiles = (m.d.vocab + sd::vocab_tile_cols(R) - 1) / sd::vocab_tile_cols(R);
     LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, vs.zd, vs.part, logits));
   }
@@ -927,6 +939,51 @@ int specdec_verify_static(specdec_ctx* c, const int32_t* draft, int32_t k, int32
   float* base = scratch_ptr[dev];
   const VerifyScratch vs{base, base + kStaticPartFloats, base + kStaticPartFloats + kStaticRows};
   return verify_impl(c, draft, k, beta, tau, accept_len, next_token, logits, stream, &vs);
+}
+
+int specdec_bind_draft_heads(specdec_ctx* c, int32_t n_heads, const void* w1, const void* b1, const void* w2,
+                             const void* b2) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (!c->m[0].bound) return fail(c, SPECDEC_ERR_BAD_STATE, "bind the verifier first: the heads sit on top of it");
+  if (n_heads < 1) return fail(c, SPECDEC_ERR_INVALID_ARG, "n_heads = %d", n_heads);
+  if (n_heads > c->lim.k_max) return fail(c, SPECDEC_ERR_TOO_LARGE, "n_heads = %d exceeds k_max = %d", n_heads, c->lim.k_max);
+  if (!w1 || !b1 || !w2 || !b2) return fail(c, SPECDEC_ERR_INVALID_ARG, "null head weights");
+  if ((reinterpret_cast<uintptr_t>(w1) | reinterpret_cast<uintptr_t>(b1) | reinterpret_cast<uintptr_t>(w2) |
+       reinterpret_cast<uintptr_t>(b2)) & 15)
+    return fail(c, SPECDEC_ERR_INVALID_ARG, "head weights not 16-byte aligned");
+  c->n_draft_heads = n_heads;
+  c->hw1 = static_cast<const bf16*>(w1); c->hb1 = static_cast<const bf16*>(b1);
+  c->hw2 = static_cast<const bf16*>(w2); c->hb2 = static_cast<const bf16*>(b2);
+  return SPECDEC_OK;
+}
+
+int specdec_draft_heads(specdec_ctx* c, const int32_t* accept_len, int32_t k, int32_t* draft, float* logits, void* stream) {
+  int rc = check_ready(c, SPECDEC_VERIFIER, false);
+  if (rc) return rc;
+  if (!accept_len || !draft) return fail(c, SPECDEC_ERR_INVALID_ARG, "null accept_len/draft");
+  if (c->n_draft_heads < 1) return fail(c, SPECDEC_ERR_BAD_STATE, "no drafting heads bound");
+  if (k < 1) return fail(c, SPECDEC_ERR_INVALID_ARG, "k = %d", k);
+  if (k > c->n_draft_heads) return fail(c, SPECDEC_ERR_TOO_LARGE, "k = %d exceeds the %d heads bound", k, c->n_draft_heads);
+  if (c->last_T <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "specdec_draft_heads needs the hidden states of a specdec_verify "
+                                  "(call it after specdec_verify, before specdec_commit)");
+  if (!c->fin_x) return fail(c, SPECDEC_ERR_BAD_STATE, "the latest verification pass (resident kernel) kept no hidden states");
+  Model& m = c->m[SPECDEC_VERIFIER];
+  hipStream_t st = S(stream);
+  const int B = c->B, D = m.d.d_model, F = m.d.d_ffn, nh = c->n_draft_heads, R = B * k;
+  // the verifier's final hidden state at each sequence's bifurcation row -> bf16 [B][d], fp32 x k
+  LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::head_rows(st, c->fin_x, c->fin_g, c->fin_b, accept_len, B, c->last_T, k, D, m.att, m.hx));
+  // first layer of the k heads in one product: hid [B][k*F] = ReLU(h W1_all^T + b1_all)
+  LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.att, D, c->hw1, B, k * F, D, c->hb1, m.hid, k * F, true));
+  // second layer, head by head (block diagonal): row b*k + i of hx += hid[b][i*F .. ] W2_i^T + b2_i
+  for (int i = 0; i < k; ++i)
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.hid + (size_t)i * F, k * F, c->hw2 + (size_t)i * D * F, B, D, F,
+                                     c->hb2 + (size_t)i * D, m.hx + (size_t)i * D, m.hx + (size_t)i * D, k * D));
+  HIPCHK(c, sd::f32_to_bf16(st, m.hx, m.slots, (long)R * D));
+  const int tc = sd::vocab_tile_cols(R), n_tiles = (m.d.vocab + tc - 1) / tc;
+  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, D, nullptr, nullptr, m.part, logits));
+  LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_head_drafts(st, m.part, n_tiles, m.row_stats, c->st, accept_len, B, k, m.d.pad_id, draft));
+  (void)nh;
+  return SPECDEC_OK;
 }
 
 int specdec_commit(specdec_ctx* c, const int32_t* accept_len, const int32_t* next_token, int32_t* n_active, void* stream) {

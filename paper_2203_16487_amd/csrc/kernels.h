@@ -245,6 +245,12 @@ hipError_t merge_accept(hipStream_t st, const float* part, const float* zd_row, 
 hipError_t merge_drafts(hipStream_t st, const float* part, int n_tiles, float* row_stats, const SeqState& s, int B,
                         int k, int pad_id, const int* new_rows, const int* seq_rows, int* draft);
 // k: block size of the pass whose drafts are being committed (accept_len is clamped to it)
+// head-based drafting: input rows of the heads (see misc.hip), fp32 -> bf16 rows, arg-max per head row
+hipError_t head_rows(hipStream_t st, const float* x, const bf16* g, const bf16* beta, const int* accept_len, int B, int T,
+                     int k, int d, bf16* rows, float* rep);
+hipError_t f32_to_bf16(hipStream_t st, const float* src, bf16* dst, long n);
+hipError_t merge_head_drafts(hipStream_t st, const float* part, int n_tiles, float* row_stats, const SeqState& s,
+                             const int* accept_len, int B, int k, int pad_id, int* draft);
 hipError_t commit_rows(hipStream_t st, const SeqState& s, const int* accept_len,
                        const int* next_token, int B, int k, int eos_id, int* n_active);
 hipError_t begin_state(hipStream_t st, const SeqState& s, int B, int max_new, int max_tgt,

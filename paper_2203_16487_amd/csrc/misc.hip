@@ -496,6 +496,103 @@ hipError_t merge_drafts(hipStream_t st, const float* part, int n_tiles, float* r
   return hipGetLastError();
 }
 
+// ----------------------------------------------------------------------------- head-based drafting
+// Input rows of the drafting heads (Sec. 2 "Draft": FFN heads on the target model's last hidden
+// state): for sequence b the verifier's final hidden state at the bifurcation row a_b of the
+// latest pass (the row whose arg-max is next_token).  x holds the pass's rows [B*T][d], already
+// normalised (g == null) or as the last residual sum still to be normalised with (g, beta).
+// Written as bf16 [B][d] (GEMM operand) and, replicated k times, as fp32 [B*k][d] (the residual
+// each head adds to).  One wave per sequence.
+template <int PER>
+__global__ __launch_bounds__(256) void head_rows_kernel(const float* __restrict__ x, const bf16* __restrict__ g,
+                                                        const bf16* __restrict__ beta,
+                                                        const int* __restrict__ accept_len, int B, int T, int k,
+                                                        bf16* __restrict__ rows, float* __restrict__ rep) {
+  constexpr int d = 64 * PER;
+  const int lane = threadIdx.x & 63;
+  const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (b >= B) return;
+  const int a = min(max(accept_len[b], 0), T - 1);
+  const float* xr = x + ((size_t)b * T + a) * d;
+  float v[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) v[i] = xr[i * 64 + lane];
+  if (g) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) s += v[i];
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) { float t = v[i] - mean; q += t * t; }
+    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+#pragma unroll
+    for (int i = 0; i < PER; ++i) v[i] = (v[i] - mean) * rstd * (float)g[i * 64 + lane] + (float)beta[i * 64 + lane];
+  }
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int c = i * 64 + lane;
+    rows[(size_t)b * d + c] = (bf16)v[i];
+    for (int h = 0; h < k; ++h) rep[((size_t)b * k + h) * d + c] = v[i];
+  }
+}
+template <int PER>
+static hipError_t head_rows_launch(hipStream_t st, const float* x, const bf16* g, const bf16* beta, const int* accept_len,
+                                   int B, int T, int k, bf16* rows, float* rep) {
+  hipLaunchKernelGGL(head_rows_kernel<PER>, dim3((B + 3) / 4), dim3(256), 0, st, x, g, beta, accept_len, B, T, k, rows, rep);
+  return hipGetLastError();
+}
+hipError_t head_rows(hipStream_t st, const float* x, const bf16* g, const bf16* beta, const int* accept_len, int B, int T,
+                     int k, int d, bf16* rows, float* rep) {
+  if (B <= 0 || k <= 0) return hipSuccess;
+  switch (d / 64) {
+#define SD_LN_CASE(P) case P: return head_rows_launch<P>(st, x, g, beta, accept_len, B, T, k, rows, rep);
+    SD_LN_CASE(1) SD_LN_CASE(2) SD_LN_CASE(3) SD_LN_CASE(4) SD_LN_CASE(5) SD_LN_CASE(6) SD_LN_CASE(7) SD_LN_CASE(8)
+    SD_LN_CASE(9) SD_LN_CASE(10) SD_LN_CASE(11) SD_LN_CASE(12) SD_LN_CASE(13) SD_LN_CASE(14) SD_LN_CASE(15)
+    SD_LN_CASE(16) SD_LN_CASE(17) SD_LN_CASE(18) SD_LN_CASE(19) SD_LN_CASE(20) SD_LN_CASE(21) SD_LN_CASE(22)
+    SD_LN_CASE(23) SD_LN_CASE(24) SD_LN_CASE(25) SD_LN_CASE(26) SD_LN_CASE(27) SD_LN_CASE(28) SD_LN_CASE(29)
+    SD_LN_CASE(30) SD_LN_CASE(31) SD_LN_CASE(32)
+#undef SD_LN_CASE
+    default: return hipErrorInvalidValue;
+  }
+}
+
+__global__ void f32_to_bf16_kernel(const float* __restrict__ src, bf16* __restrict__ dst, long n) {
+  const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (i >= n) return;   // n % 4 == 0
+  const f32x4 v = *reinterpret_cast<const f32x4*>(src + i);
+  bf16x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+  *reinterpret_cast<bf16x4*>(dst + i) = o;
+}
+hipError_t f32_to_bf16(hipStream_t st, const float* src, bf16* dst, long n) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(f32_to_bf16_kernel, blocks_for(n / 4, 256), dim3(256), 0, st, src, dst, n);
+  return hipGetLastError();
+}
+
+// draft[b][i] = arg-max of head row b*k + i (pad for finished sequences and for sequences whose
+// verification reported a failure)
+__global__ __launch_bounds__(64) void merge_head_drafts_kernel(const float* __restrict__ part, int n_tiles,
+                                                               float* __restrict__ row_stats, SeqState s,
+                                                               const int* __restrict__ accept_len, int k, int pad_id,
+                                                               int* __restrict__ draft) {
+  const int o = blockIdx.x, lane = threadIdx.x;
+  const RowMerge res = merge_row(part + (size_t)o * n_tiles * kPartF, n_tiles, lane);
+  if (lane != 0) return;
+  store_row_stats(row_stats + (size_t)o * kRowStats, res, kNegInf);
+  const int b = o / k;
+  draft[o] = (s.finished[b] || accept_len[b] < 0) ? pad_id : res.arg;
+}
+hipError_t merge_head_drafts(hipStream_t st, const float* part, int n_tiles, float* row_stats, const SeqState& s,
+                             const int* accept_len, int B, int k, int pad_id, int* draft) {
+  if (B <= 0 || k <= 0) return hipSuccess;
+  hipLaunchKernelGGL(merge_head_drafts_kernel, dim3(B * k), dim3(64), 0, st, part, n_tiles, row_stats, s, accept_len, k,
+                     pad_id, draft);
+  return hipGetLastError();
+}
+
 // ----------------------------------------------------------------------------- commit
 // Eq. 3: the iteration's output is the accepted drafts followed by the verifier's token; a
 // sequence stops after its first EOS or when it reaches its cap.  j advances by the number
