@@ -194,7 +194,7 @@ def decoder_rows(model: Model, st: DecState, tokens, block_visible) -> np.ndarra
 
 
 def vocab_logits(model: Model, h):
-    return h @ model.w["embed"].T
+    return h @ model.w.get("embed_out", model.w["embed"]).T
 
 
 def log_softmax(z):
@@ -312,6 +312,70 @@ def head_draft(model: Model, heads: Sequence[Dict[str, np.ndarray]], h: np.ndarr
     z = vocab_logits(model, np.stack(rows))
     toks = [int(t) for t in np.argmax(z, axis=-1)]
     return (toks, z) if return_logits else toks
+
+
+# ----------------------------------------------------------------------------- reduced-precision weights
+# Weight streaming in 8 bits (a precision / bandwidth variant of the verification pass, not part of
+# the paper's method): a matrix is stored as OCP FP8 E4M3 codes (1 sign, 4 exponent bits with bias
+# 7, 3 mantissa bits; no infinities; largest finite value 448) with one fp32 scale per output row,
+# and multiplied as the up-cast values.  The oracle's side of it is the definition: what values
+# the codes stand for, and which code a weight gets.
+E4M3_MAX = 448.0
+
+
+def e4m3_decode(codes: np.ndarray) -> np.ndarray:
+    """Value of every E4M3 code: (-1)^s 2^(e-7) (1 + m/8) for e > 0, (-1)^s 2^-6 (m/8) for e = 0."""
+    c = codes.astype(np.int64)
+    s, e, m = (c >> 7) & 1, (c >> 3) & 15, c & 7
+    mag = np.where(e > 0, np.ldexp(1.0 + m / 8.0, e - 7), np.ldexp(m / 8.0, -6))
+    return np.where(s == 1, -mag, mag).astype(np.float32)
+
+
+def e4m3_encode(x: np.ndarray) -> np.ndarray:
+    """Nearest E4M3 code of fp32 values, ties to the even mantissa, magnitudes beyond 448 saturate
+    to +-448 (code 0x7e / 0xfe: the all-ones mantissa at e = 15 is NaN and never produced)."""
+    x = np.asarray(x, np.float32)
+    sign = (np.signbit(x)).astype(np.uint8) << 7
+    a = np.abs(x).astype(np.float32)
+    bits = a.view(np.uint32).astype(np.int64)
+    E = (bits >> 23) - 127
+    mant = bits & 0x7FFFFF
+    m = mant >> 20
+    rem = mant & 0xFFFFF
+    up = (rem > 0x80000) | ((rem == 0x80000) & ((m & 1) == 1))
+    m = m + up
+    carry = m == 8
+    m = np.where(carry, 0, m)
+    E = E + carry
+    normal = ((E + 7) << 3) | m
+    q = np.rint(a.astype(np.float64) * 512.0).astype(np.int64)       # subnormal grid: multiples of 2^-9 (rint: ties to even)
+    sub = np.where(q >= 8, 0x08, q)
+    code = np.where(a < np.float32(2.0 ** -6), sub, normal)
+    code = np.where(a >= np.float32(E4M3_MAX), 0x7E, np.minimum(code, 0x7E))
+    return (code.astype(np.uint8) | sign).astype(np.uint8)
+
+
+def quantize_rows_e4m3(w: np.ndarray):
+    """Per-output-row scaling: row n of w [N, K] is stored as codes of w[n] / s_n with
+    s_n = max|w[n]| / 448 (1 for an all-zero row), all in fp32.  Returns (codes uint8 [N,K],
+    scales fp32 [N], the values the codes stand for: decode(codes) * s_n, fp32 [N,K])."""
+    w = np.asarray(w, np.float32)
+    amax = np.abs(w).max(axis=1)
+    s = np.where(amax > 0, amax / np.float32(E4M3_MAX), np.float32(1.0)).astype(np.float32)
+    codes = e4m3_encode((w / s[:, None]).astype(np.float32))
+    return codes, s, (e4m3_decode(codes) * s[:, None]).astype(np.float32)
+
+
+def with_fp8_weights(model: Model) -> Model:
+    """The model whose decoder projection matrices and (tied) output projection are the E4M3-stored
+    values; biases, LayerNorm parameters, the cross K/V projection and the INPUT embedding rows
+    stay as given.  Returns a model with an extra entry 'embed_out' used by vocab_logits."""
+    w = dict(model.w)
+    for name in list(w):
+        if name.startswith("dec.") and name.split(".")[-1] in ("wqkv", "wo", "wq", "w1", "w2") and w[name].ndim == 2:
+            w[name] = quantize_rows_e4m3(w[name])[2].astype(model.dtype)
+    w["embed_out"] = quantize_rows_e4m3(w["embed"])[2].astype(model.dtype)
+    return Model(model.desc, w)
 
 
 # ----------------------------------------------------------------------------- decoding loops

@@ -469,3 +469,35 @@ def test_head_draft_reduces_to_the_models_own_prediction_and_matches_torch():
     push = dict(w1=np.zeros((F, d), np.float32), b1=np.zeros(F, np.float32), w2=np.zeros((d, F), np.float32),
                 b2=(model.w["embed"][t] * 100.0).astype(np.float32))
     assert orc.head_draft(model, [push], h[0]) == [t]
+
+
+# ----------------------------------------------------------------------------- FP8 E4M3 storage
+def test_e4m3_table_rounding_and_saturation():
+    """Pins of the oracle's 8-bit weight format against the format's closed form: the table of all
+    finite codes (spot values from the definition: 0x38 = 1, 0x01 = 2^-9, 0x08 = 2^-6, 0x7e = 448),
+    strict monotonicity, encode(decode(c)) == c, nearest-value rounding by brute force against the
+    table, ties to the even mantissa, saturation, and the per-row scaling reaching code 0x7e."""
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], np.uint8)
+    vals = orc.e4m3_decode(codes)
+    lut = dict(zip(codes.tolist(), vals.tolist()))
+    assert lut[0x38] == 1.0 and lut[0x01] == 2.0 ** -9 and lut[0x08] == 2.0 ** -6 and lut[0x7E] == 448.0
+    assert lut[0x3C] == 1.5 and lut[0xB8] == -1.0 and lut[0x07] == 7 * 2.0 ** -9 and lut[0x00] == 0.0
+    pos = vals[codes < 0x80]
+    assert (np.diff(pos) > 0).all()
+    assert np.array_equal(orc.e4m3_encode(vals)[codes != 0x80], codes[codes != 0x80])   # (-0 encodes as 0x80 too)
+    rng = np.random.default_rng(0)
+    x = np.concatenate([rng.standard_normal(20000).astype(np.float32) * s for s in (1e-3, 0.05, 1.0, 40.0, 300.0)])
+    got = orc.e4m3_decode(orc.e4m3_encode(x))
+    grid = np.sort(vals.astype(np.float64))
+    xc = np.clip(x.astype(np.float64), -448.0, 448.0)
+    best = np.abs(xc[:, None] - grid[None, :]).min(axis=1)
+    assert np.allclose(np.abs(got.astype(np.float64) - xc), best, rtol=0, atol=0)
+    # ties: midway between 1.0 (m = 0) and 1.125 (m = 1) -> 1.0; between 1.125 and 1.25 (m = 2) -> 1.25
+    assert orc.e4m3_decode(orc.e4m3_encode(np.array([1.0625, 1.1875, 2.0 ** -10, 3 * 2.0 ** -10], np.float32))).tolist() == \
+        [1.0, 1.25, 0.0, 2.0 ** -8]
+    assert orc.e4m3_decode(orc.e4m3_encode(np.array([1e9, -500.0, 465.0], np.float32))).tolist() == [448.0, -448.0, 448.0]
+    w = rng.standard_normal((5, 64)).astype(np.float32) * 0.02
+    w[3] = 0.0
+    c, s, deq = orc.quantize_rows_e4m3(w)
+    assert ((c & 0x7F).max(axis=1)[[0, 1, 2, 4]] == 0x7E).all() and (c[3] == 0).all() and s[3] == 1.0
+    assert np.abs(deq - w).max() <= np.abs(w).max() / 16.0 + 1e-12          # half a step of the top binade
