@@ -72,9 +72,23 @@ typedef enum {
   SPECDEC_OPT_SMALL_BATCH_KERNELS = 0, /* default 1: passes of at most 32 rows use the fused small-batch kernels */
   SPECDEC_OPT_LN_FOLD = 1,             /* default 1: decoder LayerNorms folded into the projections around them  */
   SPECDEC_OPT_RESIDENT = 2,            /* default 0: passes of at most 32 rows run as ONE resident kernel        */
-  SPECDEC_OPT_SLICED_SUBLAYERS = 3     /* default 0: the small-batch kernels own sub-layers by output column (six
+  SPECDEC_OPT_SLICED_SUBLAYERS = 3,    /* default 0: the small-batch kernels own sub-layers by output column (six
                                           kernels per layer); 1: by head / FFN slice (three per layer; measured
                                           slower: 8-16 workgroups cannot pull a layer's weights fast enough)      */
+  SPECDEC_OPT_FP8_WEIGHTS = 4          /* default 0.  1, set BEFORE specdec_workspace_bytes and specdec_bind_model:
+                                          the model keeps a second copy of its decoder projection matrices (self
+                                          QKV, self O, cross Q, cross O, FFN W1, W2) and of the tied output matrix
+                                          as FP8 E4M3 codes (OCP 8-bit format: 1-4-3, bias 7, largest value 448, no
+                                          infinities) with one fp32 scale per output row, s_n = max_k |w_nk| / 448,
+                                          code = nearest-even E4M3 of w_nk / s_n, written by a kernel at bind time.
+                                          Passes of at most 32 rows (where weight bytes bound the verification pass
+                                          of Sec. 2) then stream the codes -- half the bytes -- turn them into bf16
+                                          operands in registers and apply s_n to the fp32 sum:
+                                          y_n = s_n * sum_k q_nk h_k + b_n.  This changes the model: its results are
+                                          those of the model whose matrices are s_n * q_nk, not of the bf16 one.
+                                          Larger passes, the drafter's pass, the encoder, the cross K/V projection
+                                          and the input embedding rows keep the bf16 matrices; the RESIDENT and
+                                          SLICED_SUBLAYERS paths refuse such a model.                               */
 } specdec_option;
 
 /* ---- life cycle -------------------------------------------------------------------- */
@@ -82,7 +96,9 @@ int specdec_create(specdec_ctx** out, const specdec_limits* limits); /* host onl
 void specdec_destroy(specdec_ctx* ctx);
 const char* specdec_last_error(const specdec_ctx* ctx); /* (host) valid until the next call */
 /* Chooses between kernel paths that compute the same pass (all are parity-tested against each other);
- * takes effect from the next specdec_verify / specdec_draft / specdec_prefill.  Host only. */
+ * takes effect from the next specdec_verify / specdec_draft / specdec_prefill.  SPECDEC_OPT_FP8_WEIGHTS
+ * is the exception on both counts: it selects a weight format, and is read by specdec_workspace_bytes
+ * and specdec_bind_model.  Host only. */
 int specdec_configure(specdec_ctx* ctx, int32_t option, int32_t value);
 
 /* Number of weight tensors of a model and the shape of tensor idx (cols = 1 for vectors). */
@@ -251,6 +267,14 @@ int specdec_get_draft_stats(specdec_ctx* ctx, float* stats, void* stream);
  * |tau - (log P(top-1) - log P(draft))| <= 1e-2, 0, 0, 0, 0}.  Mean tokens per iteration (the paper's
  * Tok., Sec. 3.1.1 Eq. 4) = tokens appended / (commits x B). */
 int specdec_get_counters(specdec_ctx* ctx, int32_t* counters, void* stream);
+
+/* The bind-time FP8 conversion of SPECDEC_OPT_FP8_WEIGHTS as a call of its own (so that the stored
+ * codes can be inspected): w device bf16 [N, K] row-major, K % 8 == 0 -> codes device uint8 [N, K]
+ * (8-byte aligned), scale device fp32 [N]; scale[n] = max_k |w[n][k]| / 448 (1 for an all-zero row),
+ * codes[n][k] = nearest E4M3 code (ties to the even mantissa, saturating at 448) of w[n][k] / scale[n],
+ * every operation in correctly rounded fp32.  Stateless; ctx only receives the error text. */
+int specdec_quantize_rows(specdec_ctx* ctx, const void* w, int64_t N, int64_t K, void* codes, float* scale,
+                               void* stream);
 
 /* ---- timing of one kernel kind ----------------------------------------------------------- */
 /* While a kind is selected every launch of that kernel is bracketed by a pair of HIP events

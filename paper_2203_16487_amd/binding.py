@@ -31,6 +31,7 @@ SPECDEC_OPT_SMALL_BATCH_KERNELS = 0
 SPECDEC_OPT_LN_FOLD = 1
 SPECDEC_OPT_RESIDENT = 2
 SPECDEC_OPT_SLICED_SUBLAYERS = 3
+SPECDEC_OPT_FP8_WEIGHTS = 4
 
 
 class specdec_model_desc(C.Structure):
@@ -66,6 +67,8 @@ EXPORTS = {
     "specdec_set_prefix": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
     "specdec_get_draft_stats": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "specdec_get_counters": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "specdec_quantize_rows": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                             C.c_void_p]),
     "specdec_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p]),
     "specdec_verify_static": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p,
@@ -231,6 +234,11 @@ def specdec_get_draft_stats(ctx, stats):
 
 def specdec_get_counters(ctx, counters):
     _check(ctx, lib().specdec_get_counters(ctx, _ptr(counters), _stream()))
+
+
+def specdec_quantize_rows(ctx, w, codes, scale):
+    N, K = w.shape
+    _check(ctx, lib().specdec_quantize_rows(ctx, _ptr(w), N, K, _ptr(codes), _ptr(scale), _stream()))
 
 
 def specdec_verify(ctx, draft, k: int, beta: int, tau: float, accept_len, next_token, logits=None):

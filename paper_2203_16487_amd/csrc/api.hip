@@ -33,6 +33,11 @@ struct LnFolds {
   const float *vo, *vco, *v2;   // column vectors of the three residual sums (wo, cwo, w2), [3][d] each
 };
 
+// FP8 copies of the matrices the small-batch kernels stream (codes + per-row scales)
+struct Fp8Layer {
+  sd::SkWeight wqkv, wo, cwq, cwo, w1, w2;
+};
+
 struct Model {
   bool bound = false;
   bool has_memory = false;
@@ -47,6 +52,11 @@ struct Model {
   float* x = nullptr;        // [Rmax][d] residual stream
   float* x2 = nullptr;       // [32][d] second residual buffer of the fused small-batch path
   float* skp = nullptr;      // [2][kSk2MaxParts][32][d] partial results of the sliced small-batch kernels
+  unsigned char* w8 = nullptr;   // E4M3 codes of every decoder layer's six matrices, then the embedding (or null)
+  float* w8s = nullptr;          // their row scales, same order
+  bool fp8 = false;              // bound with SPECDEC_OPT_FP8_WEIGHTS: passes of at most 32 rows stream w8
+  std::vector<Fp8Layer> dec8;
+  sd::SkWeight embed8;
   float* hx = nullptr;       // [Bmax*k_max][d] head-based drafting: the hidden state each head adds to, then its output
   bool skinny_ready = false;
   sd::RsLayer* rs_layers = nullptr;   // device copy of the decoder layers' pointers (resident kernel)
@@ -104,6 +114,7 @@ struct specdec_ctx {
   bool no_ln_fold = false;  // SPECDEC_OPT_LN_FOLD = 0: LayerNorm as a pass of its own between the GEMMs
   bool resident = false;    // SPECDEC_OPT_RESIDENT = 1: small batches run the decoder pass as one resident kernel
   bool sliced = false;      // SPECDEC_OPT_SLICED_SUBLAYERS = 1: small-batch sub-layers owned by head / FFN slice
+  bool fp8 = false;         // SPECDEC_OPT_FP8_WEIGHTS = 1: models bound from now on keep E4M3 copies for small batches
   char err[512] = {0};
 };
 
@@ -226,6 +237,10 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   t.x2 = cv.take<float>(32 * D);
   t.skp = cv.take<float>((size_t)2 * sd::kSk2MaxParts * 32 * D);
   t.hx = cv.take<float>(Bm * (size_t)c->lim.k_max * D);
+  if (c->fp8) {
+    t.w8 = cv.take<unsigned char>((size_t)d->dec_layers * (6 * D * D + 2 * D * F) + (size_t)d->vocab * D);
+    t.w8s = cv.take<float>((size_t)d->dec_layers * (7 * D + F) + (size_t)d->vocab);
+  }
   t.xb = cv.take<bf16>(Rmax * D);
   t.lnp[0] = cv.take<float>(Rmax * (D / 64 + 1) * 2);
   t.lnp[1] = cv.take<float>(Rmax * (D / 64 + 1) * 2);
@@ -261,7 +276,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
     m->kv_layer = t.kv_layer; m->xkv_layer = t.xkv_layer;
     m->pe = t.pe; m->kc = t.kc; m->vc = t.vc; m->xk = t.xk; m->xv = t.xv;
     m->lnp[0] = t.lnp[0]; m->lnp[1] = t.lnp[1]; m->fold = t.fold;
-    m->x = t.x; m->x2 = t.x2; m->skp = t.skp; m->hx = t.hx; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
+    m->x = t.x; m->x2 = t.x2; m->skp = t.skp; m->hx = t.hx; m->w8 = t.w8; m->w8s = t.w8s; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
     m->part = t.part; m->row_stats = t.row_stats; m->zd = t.zd; m->rm = t.rm;
     m->slots = t.slots; m->new_rows = t.new_rows; m->rs_layers = t.rs_layers; m->rs_bar = t.rs_bar;
     m->ex = t.ex; m->exb = t.exb; m->eqkv = t.eqkv; m->eatt = t.eatt; m->ehid = t.ehid;
@@ -377,9 +392,12 @@ int decoder_layers_skinny(specdec_ctx* c, Model& m, int B, int T, hipStream_t st
   };
   for (int l = 0; l < m.d.dec_layers; ++l) {
     const DecLayer& L = m.dec[l];
+    Fp8Layer W;   // the matrices streamed: bf16 as bound, or their E4M3 copies
+    if (m.fp8) W = m.dec8[l];
+    else { W.wqkv = L.wqkv; W.wo = L.wo; W.cwq = L.cwq; W.cwo = L.cwo; W.w1 = L.w1; W.w2 = L.w2; }
     bf16* kc = m.kc + m.kv_layer * l;
     bf16* vc = m.vc + m.kv_layer * l;
-    LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::skinny_qkv(st, cur, R, D, L.wqkv, L.bqkv, m.q, kc, vc, m.rm.row_b, m.rm.row_pos, H, Lcap));
+    LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::skinny_qkv(st, cur, R, D, W.wqkv, L.bqkv, m.q, kc, vc, m.rm.row_b, m.rm.row_pos, H, Lcap));
     sd::AttnArgs a{};
     a.q = m.q; a.q_b = (long)T * D; a.q_row = D;
     a.k = kc; a.k_b = (long)H * Lcap * 64; a.k_h = (long)Lcap * 64; a.k_row = 64;
@@ -387,16 +405,16 @@ int decoder_layers_skinny(specdec_ctx* c, Model& m, int B, int T, hipStream_t st
     a.o = nullptr; a.o_b = 0; a.o_row = 0;
     a.q_count = m.rm.seq_rows; a.lim_row = m.rm.row_lim; a.lim_seq = nullptr;
     a.T = T; a.H = H; a.B = B; a.key_split = 0; a.cap = Lcap;
-    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_attn_o(st, cur, R, D, a, L.wo, L.bo, freeb));
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_attn_o(st, cur, R, D, a, W.wo, L.bo, freeb));
     produced(L.ln1g, L.ln1b);
-    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, cur, R, D, L.cwq, D, L.cbq, m.q, false));
+    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, cur, R, D, W.cwq, D, L.cbq, m.q, false));
     a.k = m.xk + m.xkv_layer * l; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64;
     a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_blocked = 1;
     a.lim_row = nullptr; a.lim_seq = c->st.src_len; a.cap = Scap;
-    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_attn_o(st, cur, R, D, a, L.cwo, L.cbo, freeb));
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_attn_o(st, cur, R, D, a, W.cwo, L.cbo, freeb));
     produced(L.ln2g, L.ln2b);
-    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, cur, R, D, L.w1, F, L.b1, m.hid, true));
-    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_ffn2(st, cur, R, D, m.hid, F, L.w2, L.b2, freeb));
+    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, cur, R, D, W.w1, F, L.b1, m.hid, true));
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_ffn2(st, cur, R, D, m.hid, F, W.w2, L.b2, freeb));
     produced(L.ln3g, L.ln3b);
   }
   *out = cur;
@@ -526,6 +544,7 @@ int specdec_configure(specdec_ctx* c, int32_t option, int32_t value) {
     case SPECDEC_OPT_LN_FOLD: c->no_ln_fold = (value == 0); break;
     case SPECDEC_OPT_RESIDENT: c->resident = (value == 1); break;
     case SPECDEC_OPT_SLICED_SUBLAYERS: c->sliced = (value == 1); break;
+    case SPECDEC_OPT_FP8_WEIGHTS: c->fp8 = (value == 1); break;
     default: return fail(c, SPECDEC_ERR_INVALID_ARG, "unknown option %d", option);
   }
   return SPECDEC_OK;
@@ -624,6 +643,30 @@ int specdec_bind_model(specdec_ctx* c, specdec_role role, const specdec_model_de
       HIPCHK(c, sd::ln_fold(S(stream), L.cwq, L.ln1g, L.ln1b, L.cbq, D, D, o.cq));
       HIPCHK(c, sd::ln_fold(S(stream), L.w1, L.ln2g, L.ln2b, L.b1, F, D, o.w1));
     }
+  }
+  m.fp8 = c->fp8;
+  if (m.fp8) {
+    const int D = d->d_model, F = d->d_ffn;
+    unsigned char* q = m.w8;
+    float* sc = m.w8s;
+    int rcq = SPECDEC_OK;
+    auto quant = [&](const bf16* w, int N, int K) {
+      sd::SkWeight o(q, sc);
+      if (rcq == SPECDEC_OK && sd::quantize_rows_e4m3(S(stream), w, N, K, q, sc) != hipSuccess) rcq = SPECDEC_ERR_HIP;
+      q += (size_t)N * K;
+      sc += N;
+      return o;
+    };
+    m.dec8.resize(d->dec_layers);
+    for (int l = 0; l < d->dec_layers; ++l) {
+      const DecLayer& L = m.dec[l];
+      Fp8Layer& o = m.dec8[l];
+      o.wqkv = quant(L.wqkv, 3 * D, D); o.wo = quant(L.wo, D, D);
+      o.cwq = quant(L.cwq, D, D); o.cwo = quant(L.cwo, D, D);
+      o.w1 = quant(L.w1, F, D); o.w2 = quant(L.w2, D, F);
+    }
+    m.embed8 = quant(m.embed, d->vocab, D);
+    if (rcq != SPECDEC_OK) return fail(c, rcq, "FP8 weight quantisation failed: %s", hipGetErrorString(hipGetLastError()));
   }
   {
     std::vector<sd::RsLayer> rl(d->dec_layers);
@@ -876,6 +919,8 @@ int verify_impl(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, f
                                         m.d.d_model));
   const unsigned* failed = nullptr;
   int n_tiles = (m.d.vocab + 63) / 64;   // per-row partial records of the vocabulary kernel that ran
+  if (small && m.fp8 && (c->resident || c->sliced))
+    return fail(c, SPECDEC_ERR_BAD_STATE, "a model bound with FP8 weights runs small passes on the default kernels only");
   if (small && c->resident) {
     sd::RsArgs a{};
     a.R = R; a.T = T; a.B = B; a.H = m.d.n_heads; a.V = m.d.vocab; a.Lcap = c->Lcap; a.Scap = c->Scap;
@@ -899,7 +944,7 @@ int verify_impl(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, f
     else
       rc = decoder_layers_skinny(c, m, B, T, st, &fin);
     if (rc) return rc;
-    LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::skinny_vocab(st, fin, R, m.d.d_model, m.embed, m.d.vocab, m.rm.row_draft, vs.zd, vs.part, logits));
+    LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::skinny_vocab(st, fin, R, m.d.d_model, m.fp8 ? m.embed8 : sd::SkWeight(m.embed), m.d.vocab, m.rm.row_draft, vs.zd, vs.part, logits));
     c->fin_x = fin.xs; c->fin_g = fin.g; c->fin_b = fin.b;
   } else {
     rc = decoder_layers(c, m, B, T, st, true);
@@ -1086,6 +1131,19 @@ int specdec_get_counters(specdec_ctx* c, int32_t* counters, void* stream) {
   if (!c->state_bound || c->B <= 0) return fail(c, SPECDEC_ERR_BAD_STATE, "begin not called");
   if (!counters) return fail(c, SPECDEC_ERR_INVALID_ARG, "null counters");
   HIPCHK(c, hipMemcpyAsync(counters, c->st.scratch, SPECDEC_COUNTERS * sizeof(int32_t), hipMemcpyDeviceToDevice, S(stream)));
+  return SPECDEC_OK;
+}
+
+int specdec_quantize_rows(specdec_ctx* c, const void* w, int64_t N, int64_t K, void* codes, float* scale,
+                               void* stream) {
+  if (!c) return SPECDEC_ERR_INVALID_ARG;
+  if (!w || !codes || !scale) return fail(c, SPECDEC_ERR_INVALID_ARG, "null w/codes/scale");
+  if (N < 0 || K <= 0 || K % 8 != 0 || N > INT32_MAX || K > INT32_MAX)
+    return fail(c, SPECDEC_ERR_INVALID_ARG, "N = %lld, K = %lld (K must be a positive multiple of 8)", (long long)N, (long long)K);
+  if ((reinterpret_cast<uintptr_t>(w) & 15) || (reinterpret_cast<uintptr_t>(codes) & 7))
+    return fail(c, SPECDEC_ERR_INVALID_ARG, "w must be 16-byte aligned, codes 8-byte aligned");
+  HIPCHK(c, sd::quantize_rows_e4m3(S(stream), static_cast<const bf16*>(w), (int)N, (int)K,
+                                   static_cast<unsigned char*>(codes), scale));
   return SPECDEC_OK;
 }
 

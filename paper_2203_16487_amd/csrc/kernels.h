@@ -138,6 +138,18 @@ struct SkSrc {
   float* xs_out = nullptr;
 };
 bool skinny_supported(int d, int F);
+// A weight matrix [N][K] row-major: bf16 values (scale == nullptr), or FP8 E4M3 codes (one byte each)
+// with one fp32 scale per row, value = scale[n] * decode(code[n][k]).
+struct SkWeight {
+  const void* p = nullptr;
+  const float* scale = nullptr;
+  SkWeight() {}
+  SkWeight(const bf16* w) : p(w) {}
+  SkWeight(const unsigned char* codes, const float* s) : p(codes), scale(s) {}
+};
+// codes, scale <- per-row E4M3 quantisation of w [N][K]: scale = max|row| / 448 (1 for a zero row),
+// code = nearest-even E4M3 of w / scale.  K % 8 == 0.
+hipError_t quantize_rows_e4m3(hipStream_t st, const bf16* w, int N, int K, unsigned char* codes, float* scale);
 
 // ---- resident.hip: the whole verification pass of at most 32 rows as one resident kernel ----
 struct RsLayer {
@@ -166,14 +178,14 @@ constexpr int kRsWorkers = 32;        // workgroups of the resident kernel that 
 constexpr int kRsBarWords = 64 * 226;
 hipError_t resident_verify(hipStream_t st, const RsArgs& a, int d, int F);
 hipError_t skinny_init(int d);
-hipError_t skinny_qkv(hipStream_t st, const SkSrc& src, int R, int d, const bf16* W, const bf16* bias, bf16* q,
+hipError_t skinny_qkv(hipStream_t st, const SkSrc& src, int R, int d, SkWeight W, const bf16* bias, bf16* q,
                       bf16* kc, bf16* vc, const int* row_b, const int* row_pos, int H, int Lcap);
 // xs_out = hidden(resid) + attention(a) W^T + bias   (every block recomputes the attention)
-hipError_t skinny_attn_o(hipStream_t st, const SkSrc& resid, int R, int d, const AttnArgs& a, const bf16* W,
+hipError_t skinny_attn_o(hipStream_t st, const SkSrc& resid, int R, int d, const AttnArgs& a, SkWeight W,
                          const bf16* bias, float* xs_out);
-hipError_t skinny_proj(hipStream_t st, const SkSrc& src, int R, int d, const bf16* W, int N, const bf16* bias,
+hipError_t skinny_proj(hipStream_t st, const SkSrc& src, int R, int d, SkWeight W, int N, const bf16* bias,
                        bf16* out, bool relu);
-hipError_t skinny_ffn2(hipStream_t st, const SkSrc& resid, int R, int d, const bf16* hid, int F, const bf16* W,
+hipError_t skinny_ffn2(hipStream_t st, const SkSrc& resid, int R, int d, const bf16* hid, int F, SkWeight W,
                        const bf16* bias, float* xs_out);
 // ---- skinny2.hip: the same passes with sub-layers owned by head / by FFN slice (three kernels per layer) ----
 bool sk2_supported(int d, int F);
@@ -187,7 +199,7 @@ hipError_t skinny2_head(hipStream_t st, const SkSrc& src, int R, int d, const At
 hipError_t skinny2_ffn(hipStream_t st, const SkSrc& src, int R, int d, const bf16* W1, const bf16* b1, int F,
                        const bf16* W2, float* part_out);
 // draft logits + per-row partial records per 64-column vocabulary tile (n_tiles = ceil(V/64))
-hipError_t skinny_vocab(hipStream_t st, const SkSrc& src, int R, int d, const bf16* E, int V, const int* row_draft,
+hipError_t skinny_vocab(hipStream_t st, const SkSrc& src, int R, int d, SkWeight E, int V, const int* row_draft,
                         float* zd_row, float* part, float* logits);
 
 // ---- misc.hip ------------------------------------------------------------------------

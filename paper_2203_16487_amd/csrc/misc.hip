@@ -793,4 +793,61 @@ hipError_t cache_to_flat(hipStream_t st, const bf16* cache, bf16* flat, int B, i
   return cache_flat(st, const_cast<bf16*>(cache), flat, B, H, Lcap, L, tr, 1);
 }
 
+// ---- FP8 E4M3 weight storage (1-4-3, bias 7, largest value 448, no infinities) ----------------
+// Nearest code of |x|, ties to the even mantissa, saturating at 448 (0x7e).
+__device__ __forceinline__ unsigned e4m3_code(float x) {
+  const unsigned sign = (__float_as_uint(x) >> 24) & 0x80u;
+  const float a = fabsf(x);
+  unsigned code;
+  if (a >= 448.f) {
+    code = 0x7eu;
+  } else if (a < 0x1p-6f) {
+    const unsigned q = (unsigned)rintf(a * 512.f);   // subnormal grid: multiples of 2^-9
+    code = q >= 8u ? 0x08u : q;
+  } else {
+    const unsigned bits = __float_as_uint(a);
+    int E = (int)(bits >> 23) - 127;
+    unsigned m = (bits >> 20) & 7u;
+    const unsigned rem = bits & 0xfffffu;
+    if (rem > 0x80000u || (rem == 0x80000u && (m & 1u))) ++m;
+    if (m == 8u) { m = 0u; ++E; }
+    code = min(((unsigned)(E + 7) << 3) | m, 0x7eu);
+  }
+  return code | sign;
+}
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const bf16* __restrict__ w, int K,
+                                                            unsigned char* __restrict__ codes,
+                                                            float* __restrict__ scale) {
+  __shared__ float red[4];
+  const bf16* row = w + (size_t)blockIdx.x * K;
+  float amax = 0.f;
+  for (int k = threadIdx.x * 8; k < K; k += 256 * 8) {
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(row + k);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf((float)v[i]));
+  }
+  amax = wave_max(amax);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = amax;
+  __syncthreads();
+  amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  const float s = amax > 0.f ? __fdiv_rn(amax, 448.f) : 1.f;
+  if (threadIdx.x == 0) scale[blockIdx.x] = s;
+  for (int k = threadIdx.x * 8; k < K; k += 256 * 8) {
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(row + k);
+    unsigned lo = 0, hi = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      lo |= e4m3_code(__fdiv_rn((float)v[i], s)) << (8 * i);
+      hi |= e4m3_code(__fdiv_rn((float)v[4 + i], s)) << (8 * i);
+    }
+    *reinterpret_cast<uint2*>(codes + (size_t)blockIdx.x * K + k) = make_uint2(lo, hi);
+  }
+}
+hipError_t quantize_rows_e4m3(hipStream_t st, const bf16* w, int N, int K, unsigned char* codes, float* scale) {
+  if (N <= 0) return hipSuccess;
+  if (K <= 0 || K % 8 != 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(quantize_rows_kernel, dim3(N), dim3(256), 0, st, w, K, codes, scale);
+  return hipGetLastError();
+}
+
 }  // namespace sd

@@ -15,14 +15,19 @@
 // before the first MFMA (one memory round trip per kernel), and the 4 partial tiles are summed
 // through LDS in a fixed order.  MFMA 16x16x32: A = 16 weight rows, B = up to 2 x 16 activation
 // rows, so D[n][m]: lane holds row m = lane%16, columns n = 4*(lane/16) + r.
+//
+// Every kernel exists for two weight types WT: bf16, and FP8 E4M3 codes with one fp32 scale per
+// output row (wscale; half the streamed bytes).  The codes become bf16 operands in registers,
+// the scale multiplies the finished fp32 sum before the bias: y = s_n * (sum_k q_nk h_k) + b_n.
 #include "skinny_core.h"
 
 namespace sd {
 
 
 // ------------------------------------------------------------------------------------ qkv
-template <int PER, bool TWO>
-__global__ __launch_bounds__(kSkThreads) void sk_qkv_kernel(SkSrc src, int R, const bf16* __restrict__ W,
+template <int PER, bool TWO, class WT>
+__global__ __launch_bounds__(kSkThreads) void sk_qkv_kernel(SkSrc src, int R, const WT* __restrict__ W,
+                                                            const float* __restrict__ wscale,
                                                             const bf16* __restrict__ bias, bf16* __restrict__ q,
                                                             bf16* __restrict__ kc, bf16* __restrict__ vc,
                                                             const int* __restrict__ row_b,
@@ -33,11 +38,12 @@ __global__ __launch_bounds__(kSkThreads) void sk_qkv_kernel(SkSrc src, int R, co
   const int n0 = blockIdx.x * 16, wave = threadIdx.x >> 6, lq = threadIdx.x & 15;
   constexpr int steps = d / 128;
   const int k0 = wave * (d / 4);
-  bf16x8 wf[steps];
+  typename SkFrag<WT>::type wf[steps];
   sk_wload<steps>(W, d, n0, 3 * d, k0, wf);
   // what the epilogue reads from memory for this thread's outputs (sk_reduce: column
   // threadIdx % 16, rows threadIdx / 16 and + 16) is requested now, not after the product
   const bf16 bias_n = bias[n0 + (threadIdx.x & 15)];
+  const float ws_n = sk_wscale<WT>(wscale, n0 + (threadIdx.x & 15));
   int rb[2], rp[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
@@ -53,7 +59,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_qkv_kernel(SkSrc src, int R, co
          [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); }, acc);
   sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
     const int n = n0 + nl;
-    v += (float)bias_n;
+    v = v * ws_n + (float)bias_n;
     const int part = n / d, c = n - part * d;
     if (part == 0) { q[(size_t)m * d + c] = (bf16)v; return; }
     const int b = rb[m >> 4];
@@ -65,9 +71,10 @@ __global__ __launch_bounds__(kSkThreads) void sk_qkv_kernel(SkSrc src, int R, co
 
 // ------------------------------------------------------------------------------------ attention + O
 // resid: hidden state the sublayer started from (its own 16 columns are added back).
-template <int PER, bool VBLK, bool TWO>
+template <int PER, bool VBLK, bool TWO, class WT>
 __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resid, int R, AttnArgs a,
-                                                                      const bf16* __restrict__ W,
+                                                                      const WT* __restrict__ W,
+                                                                      const float* __restrict__ wscale,
                                                                       const bf16* __restrict__ bias,
                                                                       float* __restrict__ xs_out) {
   extern __shared__ __attribute__((aligned(16))) char sk_smem[];
@@ -76,7 +83,7 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
   const int n0 = blockIdx.x * 16, lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
   const bool kwave = wave < 4;                 // the four waves that split K of the O-projection
   const int k0 = (wave & 3) * (d / 4);
-  bf16x8 wf[steps];
+  typename SkFrag<WT>::type wf[steps];
   // hb receives the attention output of every (sequence, head) pair.  Its rows beyond R are
   // left as they are: an activation row only feeds its own output row, and those are dropped.
   // the block's 16 columns of the sublayer's input (for the residual add) are requested now
@@ -85,6 +92,7 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
   SkHidden<PER, false, TWO ? 4 : 2, kSkAttnWaves> hs;
   if (kwave) sk_wload<steps>(W, d, n0, d, k0, wf);
   const bf16 bias_n = bias[n0 + (threadIdx.x & 15)];   // for the epilogue (sk_reduce: column threadIdx % 16)
+  const float ws_n = sk_wscale<WT>(wscale, n0 + (threadIdx.x & 15));
   hs.params(resid);
   hs.load(resid, R, wave);
   // One pair per wave: eight pairs are in flight at once.
@@ -118,14 +126,15 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
            [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); }, acc);
   const float* hown = L.hown;
   sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
-    xs_out[(size_t)m * d + n0 + nl] = v + (float)bias_n + hown[m * 16 + nl];
+    xs_out[(size_t)m * d + n0 + nl] = v * ws_n + (float)bias_n + hown[m * 16 + nl];
   });
 }
 
 // ------------------------------------------------------------------------------------ plain projection
 // out = act(hidden W^T + bias) as bf16 [R][N] (cross-attention Q, FFN1)
-template <int PER, bool TWO>
-__global__ __launch_bounds__(kSkThreads) void sk_proj_kernel(SkSrc src, int R, const bf16* __restrict__ W, int N,
+template <int PER, bool TWO, class WT>
+__global__ __launch_bounds__(kSkThreads) void sk_proj_kernel(SkSrc src, int R, const WT* __restrict__ W,
+                                                             const float* __restrict__ wscale, int N,
                                                              const bf16* __restrict__ bias, bf16* __restrict__ out,
                                                              int relu) {
   extern __shared__ __attribute__((aligned(16))) char sk_smem[];
@@ -134,9 +143,10 @@ __global__ __launch_bounds__(kSkThreads) void sk_proj_kernel(SkSrc src, int R, c
   const int n0 = blockIdx.x * 16, wave = threadIdx.x >> 6, lq = threadIdx.x & 15;
   constexpr int steps = d / 128;
   const int k0 = wave * (d / 4);
-  bf16x8 wf[steps];
+  typename SkFrag<WT>::type wf[steps];
   sk_wload<steps>(W, d, n0, N, k0, wf);
   const bf16 bias_n = bias[min(n0 + (int)(threadIdx.x & 15), N - 1)];   // for the epilogue (column threadIdx % 16)
+  const float ws_n = sk_wscale<WT>(wscale, min(n0 + (int)(threadIdx.x & 15), N - 1));
   sk_hidden<PER>(src, R, TWO ? 32 : 16, L.hb, L.hown, -64, true);
   __syncthreads();
   f32x4 acc[2];
@@ -146,7 +156,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_proj_kernel(SkSrc src, int R, c
          [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); }, acc);
   sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
     if (n0 + nl < N) {
-      v += (float)bias_n;
+      v = v * ws_n + (float)bias_n;
       if (relu) v = fmaxf(v, 0.f);
       out[(size_t)m * N + n0 + nl] = (bf16)v;
     }
@@ -173,9 +183,10 @@ constexpr size_t sk_ffn2_lds_bytes() {
   return SkFfn2Lds<FS, TWO>::kStaged ? SkFfn2Lds<FS, TWO>::kBytes : SkLds<PER>::kBytes;
 }
 
-template <int PER, int FS, bool TWO>   // FS = F / 128 = k steps per wave
+template <int PER, int FS, bool TWO, class WT>   // FS = F / 128 = k steps per wave
 __global__ __launch_bounds__(kSkThreads) void sk_ffn2_kernel(SkSrc resid, int R, const bf16* __restrict__ hid,
-                                                             const bf16* __restrict__ W,
+                                                             const WT* __restrict__ W,
+                                                             const float* __restrict__ wscale,
                                                              const bf16* __restrict__ bias,
                                                              float* __restrict__ xs_out) {
   extern __shared__ __attribute__((aligned(16))) char sk_smem[];
@@ -184,13 +195,14 @@ __global__ __launch_bounds__(kSkThreads) void sk_ffn2_kernel(SkSrc resid, int R,
   const int n0 = blockIdx.x * 16, wave = threadIdx.x >> 6, lq = threadIdx.x & 15, g = (threadIdx.x & 63) >> 4;
   const int k0 = wave * (F / 4);
   const bf16 bias_n = bias[n0 + (threadIdx.x & 15)];   // for the epilogue (sk_reduce: column threadIdx % 16)
+  const float ws_n = sk_wscale<WT>(wscale, n0 + (threadIdx.x & 15));
   f32x4 acc[2];
   sk_zero(acc);
   if constexpr (FL::kStaged) {
     bf16* hidl = reinterpret_cast<bf16*>(sk_smem);
     float* hown = reinterpret_cast<float*>(sk_smem + FL::kHid);
     float* red = reinterpret_cast<float*>(sk_smem + FL::kHid + FL::kOwn);
-    bf16x8 wf[S1];
+    typename SkFrag<WT>::type wf[S1];
     sk_wload<S1>(W, F, n0, d, k0, wf);
     // one request = 64 lanes x 16 B = 512 columns of a row; wave w takes columns 512 w, 512 (w + 4), ...
     for (int r = 0; r < R; ++r)
@@ -207,11 +219,12 @@ __global__ __launch_bounds__(kSkThreads) void sk_ffn2_kernel(SkSrc resid, int R,
     mfma_settle(acc[0], acc[1]);
     __syncthreads();
     sk_reduce(acc, red, R, [&](int m, int nl, float v) {
-      xs_out[(size_t)m * d + n0 + nl] = v + (float)bias_n + hown[m * 16 + nl];
+      xs_out[(size_t)m * d + n0 + nl] = v * ws_n + (float)bias_n + hown[m * 16 + nl];
     });
   } else {
     SkLds<PER> L(sk_smem);
-    bf16x8 wf[S1], hf[S1];
+    typename SkFrag<WT>::type wf[S1];
+    bf16x8 hf[S1];
     sk_wload<S1>(W, F, n0, d, k0, wf);
     // first-tile activations of the same k range, straight from memory (same operand layout)
     {
@@ -225,15 +238,16 @@ __global__ __launch_bounds__(kSkThreads) void sk_ffn2_kernel(SkSrc resid, int R,
     };
 #pragma unroll
     for (int u = 0; u < S1; ++u) {
-      acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], hf[u], acc[0], 0, 0, 0);
-      if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], getB(1, k0 + u * 32 + 8 * g), acc[1], 0, 0, 0);
+      const bf16x8 w = sk_frag(wf[u]);
+      acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, hf[u], acc[0], 0, 0, 0);
+      if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, getB(1, k0 + u * 32 + 8 * g), acc[1], 0, 0, 0);
     }
     sk_mma_tail<FS, TWO>(W, F, n0, d, k0, getB, acc);
     mfma_settle(acc[0], acc[1]);
     __syncthreads();
     const float* hown = L.hown;
     sk_reduce(acc, L.red, R, [&](int m, int nl, float v) {
-      xs_out[(size_t)m * d + n0 + nl] = v + (float)bias_n + hown[m * 16 + nl];
+      xs_out[(size_t)m * d + n0 + nl] = v * ws_n + (float)bias_n + hown[m * 16 + nl];
     });
   }
 }
@@ -242,8 +256,9 @@ __global__ __launch_bounds__(kSkThreads) void sk_ffn2_kernel(SkSrc resid, int R,
 // Every block first forms the draft logits itself (waves 0 and 1, the sk_draft_logit sequence on
 // its own copy of the hidden rows: the same bits in every block, and the bits its own tile would
 // hold for that column), so the rank counts need no launch of their own before this one.
-template <int PER, bool TWO>
-__global__ __launch_bounds__(kSkThreads) void sk_vocab_kernel(SkSrc src, int R, const bf16* __restrict__ E, int V,
+template <int PER, bool TWO, class WT>
+__global__ __launch_bounds__(kSkThreads) void sk_vocab_kernel(SkSrc src, int R, const WT* __restrict__ E,
+                                                              const float* __restrict__ wscale, int V,
                                                               const int* __restrict__ row_draft,
                                                               float* __restrict__ zd_out,
                                                               float* __restrict__ part, int n_tiles,
@@ -254,14 +269,17 @@ __global__ __launch_bounds__(kSkThreads) void sk_vocab_kernel(SkSrc src, int R, 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15;
   const int n0 = blockIdx.x * 64 + wave * 16;
   constexpr int steps = d / 32, S1 = steps < kSkW ? steps : kSkW;
-  bf16x8 wf[S1];
+  typename SkFrag<WT>::type wf[S1];
   sk_wload<S1>(E, d, n0, V, 0, wf);
-  SkDraft<PER> dr;
-  sk_draft_fetch<PER>(dr, R, E, V, row_draft);
+  SkDraft<PER, WT> dr;
+  sk_draft_fetch<PER, WT>(dr, R, E, V, row_draft, wscale);
+  float ws[4];   // this lane's columns n0 + 4 (lane / 16) + r
+#pragma unroll
+  for (int r = 0; r < 4; ++r) ws[r] = sk_wscale<WT>(wscale, min(n0 + 4 * (lane >> 4) + r, V - 1));
   sk_hidden<PER>(src, R, TWO ? 32 : 16, L.hb, L.hown, -64, true);
   __syncthreads();
   float* zds = L.hown;   // [32] (the residual slices are not used by this kernel)
-  sk_draft_logit<PER>(dr, L.hb, R, [&](int row, float v) {
+  sk_draft_logit<PER, WT>(dr, L.hb, R, [&](int row, float v) {
     zds[row] = v;
     if (blockIdx.x == 0) zd_out[row] = v;
   });
@@ -271,6 +289,12 @@ __global__ __launch_bounds__(kSkThreads) void sk_vocab_kernel(SkSrc src, int R, 
   auto getB = [&](int t, int k) { return *reinterpret_cast<const bf16x8*>(hb + (t * 16 + lq) * pitch + k); };
   sk_mma<S1, TWO>(wf, 0, getB, acc);
   sk_mma_tail<steps, TWO>(E, d, n0, V, 0, getB, acc);
+  if constexpr (!std::is_same<WT, bf16>::value) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[t][r] *= ws[r];
+  }
   __syncthreads();
   float zd[2];
 #pragma unroll
@@ -307,69 +331,80 @@ bool skinny_supported(int d, int F) {
     default: return hipErrorInvalidValue;             \
   }
 
-template <int PER, bool TWO>
+template <int PER, bool TWO, class WT>
 static hipError_t sk_init_rows() {
   hipError_t e;
-  if ((e = sk_attr<PER>(sk_qkv_kernel<PER, TWO>)) != hipSuccess) return e;
-  if ((e = sk_attr<PER>(sk_attn_o_kernel<PER, false, TWO>)) != hipSuccess) return e;
-  if ((e = sk_attr<PER>(sk_attn_o_kernel<PER, true, TWO>)) != hipSuccess) return e;
-  if ((e = sk_attr<PER>(sk_proj_kernel<PER, TWO>)) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(sk_ffn2_kernel<PER, 2, TWO>),
+  if ((e = sk_attr<PER>(sk_qkv_kernel<PER, TWO, WT>)) != hipSuccess) return e;
+  if ((e = sk_attr<PER>(sk_attn_o_kernel<PER, false, TWO, WT>)) != hipSuccess) return e;
+  if ((e = sk_attr<PER>(sk_attn_o_kernel<PER, true, TWO, WT>)) != hipSuccess) return e;
+  if ((e = sk_attr<PER>(sk_proj_kernel<PER, TWO, WT>)) != hipSuccess) return e;
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(sk_ffn2_kernel<PER, 2, TWO, WT>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sk_ffn2_lds_bytes<PER, 2, TWO>())) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(sk_ffn2_kernel<PER, 16, TWO>),
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(sk_ffn2_kernel<PER, 16, TWO, WT>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sk_ffn2_lds_bytes<PER, 16, TWO>())) != hipSuccess) return e;
-  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(sk_ffn2_kernel<PER, 32, TWO>),
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(sk_ffn2_kernel<PER, 32, TWO, WT>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sk_ffn2_lds_bytes<PER, 32, TWO>())) != hipSuccess) return e;
-  if ((e = sk_attr<PER>(sk_vocab_kernel<PER, TWO>)) != hipSuccess) return e;
+  if ((e = sk_attr<PER>(sk_vocab_kernel<PER, TWO, WT>)) != hipSuccess) return e;
   return hipSuccess;
 }
 
 hipError_t skinny_init(int d) {
   hipError_t e = hipSuccess;
   SK_DISPATCH(d, {
-    if ((e = sk_init_rows<PER, false>()) != hipSuccess) return e;
-    if ((e = sk_init_rows<PER, true>()) != hipSuccess) return e;
+    if ((e = sk_init_rows<PER, false, bf16>()) != hipSuccess) return e;
+    if ((e = sk_init_rows<PER, true, bf16>()) != hipSuccess) return e;
+    if ((e = sk_init_rows<PER, false, fp8>()) != hipSuccess) return e;
+    if ((e = sk_init_rows<PER, true, fp8>()) != hipSuccess) return e;
   });
   return e;
 }
 
-hipError_t skinny_qkv(hipStream_t st, const SkSrc& src, int R, int d, const bf16* W, const bf16* bias, bf16* q,
+// A weight argument is a SkWeight: bf16 values, or (scale != nullptr) E4M3 codes + row scales.
+#define SK_WT(w, CALL)                                                                     \
+  if ((w).scale) { typedef fp8 WT; const fp8* Wp = static_cast<const fp8*>((w).p); CALL; } \
+  else { typedef bf16 WT; const bf16* Wp = static_cast<const bf16*>((w).p); CALL; }
+
+hipError_t skinny_qkv(hipStream_t st, const SkSrc& src, int R, int d, SkWeight W, const bf16* bias, bf16* q,
                       bf16* kc, bf16* vc, const int* row_b, const int* row_pos, int H, int Lcap) {
-  SK_DISPATCH(d, SK_ROWS(R, hipLaunchKernelGGL((sk_qkv_kernel<PER, TWO>), dim3(3 * d / 16), dim3(kSkThreads),
-                                               SkLds<PER>::kBytesNoAttn, st, src, R, W, bias, q, kc, vc, row_b, row_pos,
-                                               H, Lcap)));
+  SK_DISPATCH(d, SK_ROWS(R, SK_WT(W, hipLaunchKernelGGL((sk_qkv_kernel<PER, TWO, WT>), dim3(3 * d / 16),
+                                                        dim3(kSkThreads), SkLds<PER>::kBytesNoAttn, st, src, R, Wp,
+                                                        W.scale, bias, q, kc, vc, row_b, row_pos, H, Lcap))));
   return hipGetLastError();
 }
-hipError_t skinny_attn_o(hipStream_t st, const SkSrc& resid, int R, int d, const AttnArgs& a, const bf16* W,
+hipError_t skinny_attn_o(hipStream_t st, const SkSrc& resid, int R, int d, const AttnArgs& a, SkWeight W,
                          const bf16* bias, float* xs_out) {
   if (a.v_blocked) {
-    SK_DISPATCH(d, SK_ROWS(R, hipLaunchKernelGGL((sk_attn_o_kernel<PER, true, TWO>), dim3(d / 16),
-                                                 dim3(64 * kSkAttnWaves), SkLds<PER>::kBytes, st, resid, R, a, W, bias, xs_out)));
+    SK_DISPATCH(d, SK_ROWS(R, SK_WT(W, hipLaunchKernelGGL((sk_attn_o_kernel<PER, true, TWO, WT>), dim3(d / 16),
+                                                          dim3(64 * kSkAttnWaves), SkLds<PER>::kBytes, st, resid, R, a,
+                                                          Wp, W.scale, bias, xs_out))));
   } else {
-    SK_DISPATCH(d, SK_ROWS(R, hipLaunchKernelGGL((sk_attn_o_kernel<PER, false, TWO>), dim3(d / 16),
-                                                 dim3(64 * kSkAttnWaves), SkLds<PER>::kBytes, st, resid, R, a, W, bias, xs_out)));
+    SK_DISPATCH(d, SK_ROWS(R, SK_WT(W, hipLaunchKernelGGL((sk_attn_o_kernel<PER, false, TWO, WT>), dim3(d / 16),
+                                                          dim3(64 * kSkAttnWaves), SkLds<PER>::kBytes, st, resid, R, a,
+                                                          Wp, W.scale, bias, xs_out))));
   }
   return hipGetLastError();
 }
-hipError_t skinny_proj(hipStream_t st, const SkSrc& src, int R, int d, const bf16* W, int N, const bf16* bias,
+hipError_t skinny_proj(hipStream_t st, const SkSrc& src, int R, int d, SkWeight W, int N, const bf16* bias,
                        bf16* out, bool relu) {
-  SK_DISPATCH(d, SK_ROWS(R, hipLaunchKernelGGL((sk_proj_kernel<PER, TWO>), dim3((N + 15) / 16), dim3(kSkThreads),
-                                               SkLds<PER>::kBytesNoAttn, st, src, R, W, N, bias, out, relu ? 1 : 0)));
+  SK_DISPATCH(d, SK_ROWS(R, SK_WT(W, hipLaunchKernelGGL((sk_proj_kernel<PER, TWO, WT>), dim3((N + 15) / 16),
+                                                        dim3(kSkThreads), SkLds<PER>::kBytesNoAttn, st, src, R, Wp,
+                                                        W.scale, N, bias, out, relu ? 1 : 0))));
   return hipGetLastError();
 }
-hipError_t skinny_ffn2(hipStream_t st, const SkSrc& resid, int R, int d, const bf16* hid, int F, const bf16* W,
+hipError_t skinny_ffn2(hipStream_t st, const SkSrc& resid, int R, int d, const bf16* hid, int F, SkWeight W,
                        const bf16* bias, float* xs_out) {
-  SK_DISPATCH(d, SK_FFN(F, SK_ROWS(R, hipLaunchKernelGGL((sk_ffn2_kernel<PER, FS, TWO>), dim3(d / 16),
-                                                         dim3(kSkThreads), (sk_ffn2_lds_bytes<PER, FS, TWO>()), st, resid,
-                                                         R, hid, W, bias, xs_out))));
+  SK_DISPATCH(d, SK_FFN(F, SK_ROWS(R, SK_WT(W, hipLaunchKernelGGL((sk_ffn2_kernel<PER, FS, TWO, WT>), dim3(d / 16),
+                                                                  dim3(kSkThreads), (sk_ffn2_lds_bytes<PER, FS, TWO>()),
+                                                                  st, resid, R, hid, Wp, W.scale, bias, xs_out)))));
   return hipGetLastError();
 }
-hipError_t skinny_vocab(hipStream_t st, const SkSrc& src, int R, int d, const bf16* E, int V, const int* row_draft,
+hipError_t skinny_vocab(hipStream_t st, const SkSrc& src, int R, int d, SkWeight E, int V, const int* row_draft,
                         float* zd_row, float* part, float* logits) {
   const int n_tiles = (V + 63) / 64;
   SK_DISPATCH(d, {
-    SK_ROWS(R, hipLaunchKernelGGL((sk_vocab_kernel<PER, TWO>), dim3(n_tiles), dim3(kSkThreads), SkLds<PER>::kBytesNoAttn,
-                                  st, src, R, E, V, row_draft, zd_row, part, n_tiles, logits));
+    SK_ROWS(R, SK_WT(E, hipLaunchKernelGGL((sk_vocab_kernel<PER, TWO, WT>), dim3(n_tiles), dim3(kSkThreads),
+                                           SkLds<PER>::kBytesNoAttn, st, src, R, Wp, E.scale, V, row_draft, zd_row,
+                                           part, n_tiles, logits)));
   });
   return hipGetLastError();
 }

@@ -2,6 +2,7 @@
 // hidden-state prologue, K-split weight-streaming products on MFMA 16x16x32 and their
 // reduction.  Used by the per-projection kernels and by the single resident kernel.
 #pragma once
+#include <type_traits>
 #include "attn_core.h"
 
 namespace sd {
@@ -351,26 +352,64 @@ __device__ __forceinline__ void sk_wload(const bf16* __restrict__ W, int ldw, in
 #pragma unroll
   for (int u = 0; u < S; ++u) wf[u] = *reinterpret_cast<const bf16x8*>(wp + u * 32);
 }
-template <int S, bool TWO, class GetB>
-__device__ __forceinline__ void sk_mma(const bf16x8 (&wf)[S], int k0, GetB&& getB, f32x4 (&acc)[2]) {
+// Weights stored as FP8 E4M3 codes (1-4-3, bias 7, no infinities) with one fp32 scale per output
+// row: the same operand positions, half the bytes per request; a fragment is up-cast to bf16
+// (exact: 3 mantissa bits) right before its MFMA and the row scale multiplies the finished sum.
+typedef unsigned char fp8;
+typedef unsigned int fp8x8 __attribute__((ext_vector_type(2)));   // 8 codes
+template <class WT> struct SkFrag { typedef bf16x8 type; };
+template <class WT>
+__device__ __forceinline__ float sk_wscale(const float* __restrict__ wscale, int n) {
+  if constexpr (std::is_same<WT, bf16>::value) return 1.f;
+  else return wscale[n];
+}
+template <> struct SkFrag<fp8> { typedef fp8x8 type; };
+__device__ __forceinline__ bf16x8 sk_frag(const bf16x8& f) { return f; }
+__device__ __forceinline__ bf16x8 sk_frag(const fp8x8& f) {
+  // the hardware's E4M3 -> fp32 conversion, one code (byte select 0..3) per instruction; an E4M3
+  // value has 3 mantissa bits, so the upper half of its fp32 pattern IS its bf16 pattern: v_perm
+  // packs two upper halves
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 o;
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    const unsigned c0 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 0));
+    const unsigned c1 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 1));
+    const unsigned c2 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 2));
+    const unsigned c3 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 3));
+    o[2 * w] = __builtin_amdgcn_perm(c1, c0, 0x07060302u);
+    o[2 * w + 1] = __builtin_amdgcn_perm(c3, c2, 0x07060302u);
+  }
+  return __builtin_bit_cast(bf16x8, o);
+}
+template <int S>
+__device__ __forceinline__ void sk_wload(const fp8* __restrict__ W, int ldw, int n0, int N, int k0, fp8x8 (&wf)[S]) {
+  const int lane = threadIdx.x & 63, lq = lane & 15, g = lane >> 4;
+  const fp8* wp = W + (size_t)min(n0 + lq, N - 1) * ldw + k0 + 8 * g;
+#pragma unroll
+  for (int u = 0; u < S; ++u) wf[u] = *reinterpret_cast<const fp8x8*>(wp + u * 32);
+}
+template <int S, bool TWO, class FR, class GetB>
+__device__ __forceinline__ void sk_mma(const FR (&wf)[S], int k0, GetB&& getB, f32x4 (&acc)[2]) {
   const int g = (threadIdx.x & 63) >> 4;
 #pragma unroll
   for (int u = 0; u < S; ++u) {
     const int k = k0 + u * 32 + 8 * g;
-    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], getB(0, k), acc[0], 0, 0, 0);
-    if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[u], getB(1, k), acc[1], 0, 0, 0);
+    const bf16x8 w = sk_frag(wf[u]);
+    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, getB(0, k), acc[0], 0, 0, 0);
+    if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w, getB(1, k), acc[1], 0, 0, 0);
   }
   mfma_settle(acc[0], acc[1]);
 }
 // steps kSkW .. STEPS - 1 of a long k range, kSkW at a time
-template <int STEPS, bool TWO, class GetB>
-__device__ __forceinline__ void sk_mma_tail(const bf16* __restrict__ W, int ldw, int n0, int N, int k0,
+template <int STEPS, bool TWO, class WT, class GetB>
+__device__ __forceinline__ void sk_mma_tail(const WT* __restrict__ W, int ldw, int n0, int N, int k0,
                                             GetB&& getB, f32x4 (&acc)[2]) {
   if constexpr (STEPS > kSkW) {
     static_assert(STEPS % kSkW == 0, "long k ranges come in whole batches");
 #pragma unroll 1
     for (int s0 = kSkW; s0 < STEPS; s0 += kSkW) {
-      bf16x8 wf[kSkW];
+      typename SkFrag<WT>::type wf[kSkW];
       sk_wload<kSkW>(W, ldw, n0, N, k0 + s0 * 32, wf);
       sk_mma<kSkW, TWO>(wf, k0 + s0 * 32, getB, acc);
     }
@@ -412,15 +451,16 @@ __device__ __forceinline__ void sk_reduce(const f32x4 (&acc)[2], float* red, int
 // Two parts: sk_draft_fetch requests the embedding rows of the drafts (first the draft ids,
 // then the rows: two round trips that run while the caller's prologue does), sk_draft_logit
 // multiplies once the hidden rows are in LDS.
-template <int PER>
+template <int PER, class WT = bf16>
 struct SkDraft {
   static constexpr int kSteps = 2 * PER;   // d / 32
-  bf16x8 wf[kSteps];
+  typename SkFrag<WT>::type wf[kSteps];
+  float scale;                             // row scale of the draft's embedding row (1 for bf16 weights)
   bool has;
 };
-template <int PER>
-__device__ __forceinline__ void sk_draft_fetch(SkDraft<PER>& dr, int R, const bf16* __restrict__ E, int V,
-                                               const int* __restrict__ row_draft) {
+template <int PER, class WT>
+__device__ __forceinline__ void sk_draft_fetch(SkDraft<PER, WT>& dr, int R, const WT* __restrict__ E, int V,
+                                               const int* __restrict__ row_draft, const float* __restrict__ wscale) {
   constexpr int d = 64 * PER;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
   dr.has = false;
@@ -428,21 +468,23 @@ __device__ __forceinline__ void sk_draft_fetch(SkDraft<PER>& dr, int R, const bf
   const int row = wave * 16 + lq;
   const int tok = row_draft[min(row, R - 1)];
   dr.has = row < R && tok >= 0 && tok < V;
-  const bf16* wp = E + (size_t)(dr.has ? tok : 0) * d + 8 * g;
+  dr.scale = wscale ? wscale[dr.has ? tok : 0] : 1.f;
+  const WT* wp = E + (size_t)(dr.has ? tok : 0) * d + 8 * g;
 #pragma unroll
-  for (int s = 0; s < SkDraft<PER>::kSteps; ++s) dr.wf[s] = *reinterpret_cast<const bf16x8*>(wp + s * 32);
+  for (int s = 0; s < SkDraft<PER, WT>::kSteps; ++s)
+    dr.wf[s] = *reinterpret_cast<const typename SkFrag<WT>::type*>(wp + s * 32);
 }
-template <int PER, class Out>
-__device__ __forceinline__ void sk_draft_logit(const SkDraft<PER>& dr, const bf16* hb, int R, Out&& out) {
+template <int PER, class WT, class Out>
+__device__ __forceinline__ void sk_draft_logit(const SkDraft<PER, WT>& dr, const bf16* hb, int R, Out&& out) {
   constexpr int d = 64 * PER, pitch = d + kSkPad;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
   if (wave >= 2) return;
   const int row = wave * 16 + lq;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-  for (int s = 0; s < SkDraft<PER>::kSteps; ++s) {
+  for (int s = 0; s < SkDraft<PER, WT>::kSteps; ++s) {
     bf16x8 hf = *reinterpret_cast<const bf16x8*>(hb + row * pitch + s * 32 + 8 * g);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dr.wf[s], hf, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sk_frag(dr.wf[s]), hf, acc, 0, 0, 0);
   }
   mfma_settle(acc);
   // D[i][j]: this lane holds j = lq, i = 4g + r; diagonal i = j  <=>  g == lq/4, r = lq%4
@@ -450,7 +492,8 @@ __device__ __forceinline__ void sk_draft_logit(const SkDraft<PER>& dr, const bf1
     float v = 0.f;
 #pragma unroll
     for (int r = 0; r < 4; ++r) if (r == (lq & 3)) v = acc[r];
-    out(row, dr.has ? v : kNegInf);
+    // (the row scale multiplies the sum exactly as the projection does for that column)
+    out(row, dr.has ? v * dr.scale : kNegInf);
   }
 }
 

@@ -48,9 +48,14 @@ def oracle_prefill(model: orc.Model, st: orc.DecState, tokens) -> None:
 
 def make_verify_case(desc: synth.ModelDesc, seed: int, B: int, S: int, k: int, beta: int, tau: float,
                      len_lo: int, len_hi: int, drafts: str = "random", ragged_src: bool = False,
-                     std: float = 0.02, corrupt_p: float = 0.2, cap_extra: int = 0) -> VerifyCase:
+                     std: float = 0.02, corrupt_p: float = 0.2, cap_extra: int = 0, fp8: bool = False) -> VerifyCase:
+    """fp8: the expected values (prefix cache, greedy drafts, logits) come from the model whose decoder
+    projection matrices and output matrix are stored as E4M3 codes with per-row scales; `bits` stay
+    the bf16 weights the library is given."""
     bits = synth.make_weights(desc, seed, std=std)
     model = orc.Model(desc, synth.weights_f32(bits))
+    if fp8:
+        model = orc.with_fp8_weights(model)
     memory = synth.make_memory(seed, B, S, desc.d_model)
     src_len = synth.random_lengths(seed, "src_len", B, 1, S) if ragged_src else np.full((B,), S, np.int32)
     lens = synth.random_lengths(seed, "prefix_len", B, len_lo, len_hi)
