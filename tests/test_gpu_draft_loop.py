@@ -151,19 +151,33 @@ def run_loop(seed, beta, tau, B=5, S_max=12, k=4, max_new=18, options=None):
 
 
 def test_loop_strict_equals_greedy():
-    vm, dm, src, src_len, seqs, stats = run_loop(seed=21, beta=1, tau=0.0)
-    print(f"[loop strict] {stats}")
-    if stats["excused_accept"] == 0:
-        for b, s in enumerate(seqs):
-            ref = orc.greedy_decode(vm, orc.encode(vm, list(src[b, :src_len[b]])), 18)
-            assert s.stream[1:] == ref
-    assert stats["committed"] == sum(len(s.stream) - 1 for s in seqs)
+    """beta = 1, tau = 0 reproduces greedy decoding whatever the drafter proposes (Sec. 2).  A run in
+    which a near-tie was excused may legitimately part from the oracle's greedy stream, so several
+    seeds are run and at least one must go through with no excuse at all."""
+    compared = 0
+    for seed in (21, 24, 25):
+        vm, dm, src, src_len, seqs, stats = run_loop(seed=seed, beta=1, tau=0.0)
+        print(f"[loop strict, seed {seed}] {stats}")
+        assert stats["committed"] == sum(len(s.stream) - 1 for s in seqs)
+        if stats["excused_accept"] == 0:
+            compared += 1
+            for b, s in enumerate(seqs):
+                ref = orc.greedy_decode(vm, orc.encode(vm, list(src[b, :src_len[b]])), 18)
+                assert s.stream[1:] == ref
+    assert compared > 0, "every seed needed a near-tie excuse: the strict rule was never compared with greedy decoding"
 
 
 def test_loop_relaxed():
+    """Relaxed rule: the loop ends for every sequence, by EOS or by the cap, the committed tokens are
+    the accepted drafts + 1 of every iteration minus what the cap / EOS cut off (Sec. 3.1.1 Eq. 4:
+    each iteration commits at least one token), and the library's output equals the oracle's streams
+    (checked inside run_loop)."""
     *_, seqs, stats = run_loop(seed=22, beta=3, tau=1.0)
     print(f"[loop relaxed] {stats}")
-    assert any(s.stream[-1] == 2 for s in seqs) or True
+    assert stats["committed"] == sum(len(s.stream) - 1 for s in seqs)
+    assert stats["committed"] >= stats["iters"]
+    for s in seqs:
+        assert s.stream[-1] == 2 or len(s.stream) - 1 == 18, s.stream
 
 
 def test_loop_relaxed_separate_layernorm():
@@ -215,6 +229,7 @@ def test_autoregressive_baseline_k0():
     baseline SpecDec is measured against).  The oracle follows in lock step with dec_step; the
     whole output must equal the oracle's greedy decoding unless a near-tie was excused.  B = 40
     takes the general kernels, B = 5 the fused small-batch ones."""
+    compared = 0
     for B in (5, 40):
         (vd, vb, vm), _ = make_models(seed=31)
         row = synth.bf16_bits_to_f32(vb["embed"][vd.eos_id]) * 2.0          # make EOS reachable
@@ -257,7 +272,9 @@ def test_autoregressive_baseline_k0():
                 break
         assert all(done)
         if excused == 0:
+            compared += 1
             for b in range(B):
                 assert streams[b][1:] == orc.greedy_decode(vm, mems[b], max_new)
         print(f"[ar baseline B={B}] greedy decoding reproduced ({excused} near-ties excused)")
         ses.close()
+    assert compared > 0, "every batch size needed a near-tie excuse: k = 0 was never compared with greedy decoding"

@@ -95,16 +95,20 @@ def run_full_size(label, B, k, beta, tau, S_max, src_lo, max_tgt, len_lo, len_hi
         excused += dl.check_drafts(g_dr[b:b + 1], [t_o], [z_o], f"{label} draft {b}")
     print(f"[{label}] {len(sample)} sampled sequences match ({excused} near-threshold excused)")
 
-    # every sequence: reported decision == the rule on the reported logits (rank counted on the
-    # same logits, so no tolerance), checked in slices to bound host memory
+    # every sequence: reported decision == the rule on the reported logits.  The rank count is taken
+    # on the same logits and is exact; the tau test compares log-probabilities whose log-sum-exp the
+    # kernel accumulates in another order than NumPy, so a decision may differ where -- and only
+    # where -- the row at which the two part sits within the near-threshold margin
     bad = []
     for b in range(B):
         zg = logits[b].cpu().numpy()
         a, n = orc.accept(zg, [int(t) for t in drafts[b]], beta, tau)
         if (a, n) != (int(g_acc[b]), int(g_nxt[b])):
+            # excused only if the row where the two decisions part is itself within the near-threshold margin
             na, ng = cases.near_threshold_rows(zg, [int(t) for t in drafts[b]], beta, tau)
-            if not (na.any() or ng.any()):
-                bad.append((b, a, n, int(g_acc[b]), int(g_nxt[b])))
+            ga, row = int(g_acc[b]), min(a, int(g_acc[b]))
+            if not ((a != ga and row < k and na[row]) or (a == ga and ng[a])):
+                bad.append((b, a, n, ga, int(g_nxt[b])))
     assert not bad, bad
     assert (g_dr >= 0).all() and (g_dr < V).all()
     hist = np.bincount(g_acc, minlength=k + 1).tolist()
