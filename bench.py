@@ -42,10 +42,10 @@ SEED = 0
 # HBM-side bytes per launch of each kernel kind on this workload, from two rocprofv3 --pmc runs of
 # this script (FETCH_SIZE, then WRITE_SIZE; averages over the kind's launches), each scaled by
 # what the same counter reads for a plain 256 MiB device copy (`--copy-calibration`): FETCH_SIZE
-# reads 0.5 per KiB copied, WRITE_SIZE 1.0.  Summary and commands:
-# profiles/loop_iteration_batch128.hbm_traffic.md.  Offline measurements, not taken in this run.
+# reads 0.5 per KiB copied, WRITE_SIZE 1.0.  Summary and commands: profiles/hbm_traffic.md.
+# Offline measurements, not taken in this run.
 MEASURED_TRAFFIC_BYTES = {
-    "gemm_f32": {"fetch": 2.0 * 21338.4 * 1024, "write": 1.0 * 6580.2 * 1024},
+    "gemm_f32": {"fetch": 1.9998 * 26694.0 * 1024, "write": 1.0 * 8465.9 * 1024},
 }
 
 
@@ -166,7 +166,7 @@ def kind_work(vdesc, ddesc, B, k, L, src_len, tokens_per_step):
     return out
 
 
-def batch1_latency(sd, synth, torch, steps=200):
+def batch1_latency(sd, synth, torch, steps=200, plain=False):
     """Single verify step at batch 1 (base verifier, memory 32 x 512 ~N(0,1), 16 tokens decoded,
     k=5 random drafts, beta=3, tau=1): mean of back-to-back replays as before, plus median / p10 /
     p90 of event-bracketed replays, warm and LLC-cold."""
@@ -184,6 +184,10 @@ def batch1_latency(sd, synth, torch, steps=200):
     evictor = Evictor(torch, ses.device)
     fn = lambda: sd.specdec_verify(ses.ctx, dr, k, 3, 1.0, acc, nxt)
     sec = _timed(torch, fn, steps, 20)
+    if plain:
+        ses.close()
+        return {"workload": "single verify step: base verifier 6L d512, B=1, memory 32, 16 decoded, k=5",
+                "verify_us": sec * 1e6, "steps": steps}
     stats = warm_and_cold(torch, fn, evictor, steps)
     # the paper's best block size (k = 25, Table 3): 26 rows still fit one pass of the same kernels
     def open_k25(options):
@@ -434,6 +438,12 @@ def main():
     ap.add_argument("--batch1-only", action="store_true",
                     help="run only the single-sequence verify step (the `batch1` object of the usual line) and "
                          "print it: the command behind profiles/verify_step_batch1.kernel_stats.md")
+    ap.add_argument("--batch1-plain", action="store_true",
+                    help="with --batch1-only: time only the k = 5 bf16 pass (no k = 25 / k = 0 / FP8 variants), so that "
+                         "a profile of the command holds that pass alone")
+    ap.add_argument("--loop-only", action="store_true",
+                    help="set the batch-128 loop up, run --warmup + --steps iterations and print their time: no "
+                         "per-kind passes, baselines or other configs (the command behind the loop's profiles)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device-to-device copy of 256 MiB, five times (reference for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters), and exit")
@@ -451,7 +461,7 @@ def main():
         sys.exit(1)
     sd.lib()   # fails loudly if the HIP library is missing
     if args.batch1_only:
-        print(json.dumps({"batch1": batch1_latency(sd, synth, torch, steps=args.steps)}))
+        print(json.dumps({"batch1": batch1_latency(sd, synth, torch, steps=args.steps, plain=args.batch1_plain)}))
         return
     if args.copy_calibration:
         src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device="cuda")
@@ -499,6 +509,13 @@ def main():
     step()
     torch.cuda.synchronize()
     tokens_per_step = int((acc + 1).sum().item())
+
+    if args.loop_only:
+        sec = _timed(torch, step, args.steps, args.warmup)
+        print(json.dumps({"loop_only": True, "steps": args.steps, "ms_per_step": sec * 1e3,
+                          "tokens_per_step": tokens_per_step, "value": tokens_per_step / sec}))
+        ses.close()
+        return
 
     # rank the kernel kinds by time (one short pass per kind), then time the dominant one with
     # events inside a timed region of its own
