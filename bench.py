@@ -444,6 +444,10 @@ def main():
     ap.add_argument("--loop-only", action="store_true",
                     help="set the batch-128 loop up, run --warmup + --steps iterations and print their time: no "
                          "per-kind passes, baselines or other configs (the command behind the loop's profiles)")
+    ap.add_argument("--vendor-gemm-calibration", action="store_true",
+                    help="time torch.matmul (the vendor GEMM library, bf16) on the projection shapes of the batch-128 "
+                         "verify pass and exit: a yardstick for what a launch of that shape costs on this box, not "
+                         "part of the product path")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device-to-device copy of 256 MiB, five times (reference for scaling "
                          "rocprofv3's FETCH_SIZE / WRITE_SIZE counters), and exit")
@@ -462,6 +466,17 @@ def main():
     sd.lib()   # fails loudly if the HIP library is missing
     if args.batch1_only:
         print(json.dumps({"batch1": batch1_latency(sd, synth, torch, steps=args.steps, plain=args.batch1_plain)}))
+        return
+    if args.vendor_gemm_calibration:
+        res = []
+        for name, M, N, K in (("QKV", 1408, 3072, 1024), ("O / cross-O / cross-Q", 1408, 1024, 1024), ("FFN1", 1408, 4096, 1024),
+                              ("FFN2", 1408, 1024, 4096), ("vocabulary", 1408, 32768, 1024), ("square", 8192, 8192, 8192)):
+            a_ = torch.randn((M, K), device="cuda", dtype=torch.bfloat16)
+            w_ = torch.randn((N, K), device="cuda", dtype=torch.bfloat16)
+            fn = lambda: torch.matmul(a_, w_.t())
+            sec = _timed(torch, fn, 200 if M < 8192 else 30, 10)
+            res.append({"shape": name, "M": M, "N": N, "K": K, "us": sec * 1e6, "tflops": 2.0 * M * N * K / sec / 1e12})
+        print(json.dumps({"vendor_gemm_bf16": res}))
         return
     if args.copy_calibration:
         src = torch.full((64 << 20,), 1.0, dtype=torch.float32, device="cuda")
