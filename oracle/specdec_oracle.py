@@ -378,6 +378,21 @@ def with_fp8_weights(model: Model) -> Model:
     return Model(model.desc, w)
 
 
+def with_fp8_cross_kv(model: Model, st: DecState) -> DecState:
+    """The state whose cross-attention keys and values (computed once per input, read by every
+    verification pass: the bulk of the bytes when the source is long) are the E4M3-stored values:
+    each key's and each value's 64-wide per-head vector is one row of quantize_rows_e4m3 (its own
+    fp32 scale).  The self-attention cache is untouched (shared, not copied)."""
+    H, d = model.desc.n_heads, model.desc.d_model
+    dh = d // H
+
+    def q(a):
+        S = a.shape[0]
+        return quantize_rows_e4m3(np.asarray(a, np.float32).reshape(S * H, dh))[2].reshape(S, d).astype(model.dtype)
+
+    return DecState(st.K, st.V, [q(a) for a in st.Kx], [q(a) for a in st.Vx], st.len)
+
+
 # ----------------------------------------------------------------------------- decoding loops
 def greedy_decode(model: Model, memory, max_tgt: int, prefix: Optional[Sequence[int]] = None) -> List[int]:
     """Plain autoregressive greedy decoding from BOS (or a given input prefix)."""

@@ -501,3 +501,29 @@ def test_e4m3_table_rounding_and_saturation():
     c, s, deq = orc.quantize_rows_e4m3(w)
     assert ((c & 0x7F).max(axis=1)[[0, 1, 2, 4]] == 0x7E).all() and (c[3] == 0).all() and s[3] == 1.0
     assert np.abs(deq - w).max() <= np.abs(w).max() / 16.0 + 1e-12          # half a step of the top binade
+
+
+def test_fp8_cross_kv_is_per_key_per_head_and_bounded():
+    """with_fp8_cross_kv against what the format fixes: every (key, head) 64-vector is scaled on its
+    own (its largest entry is stored exactly: code 0x7e times amax / 448), the error of an entry is
+    at most half an E4M3 step of its vector's top binade, the self-attention cache is shared, and the
+    cross-attention output moves by no more than the value error allows (a convex combination of
+    value rows: |change| <= max value error + what the perturbed scores shift, checked loosely)."""
+    model = tiny_model(seed=3)
+    mem = tiny_memory(model, seed=4, S=9)
+    st = prefilled_state(model, mem, [0, 5, 7], cap=8)
+    q = orc.with_fp8_cross_kv(model, st)
+    H, d = model.desc.n_heads, model.desc.d_model
+    assert q.K is st.K and q.V is st.V and q.len == st.len
+    for a, b in zip(st.Kx + st.Vx, q.Kx + q.Vx):
+        av = np.asarray(a, np.float64).reshape(-1, H, d // H)
+        bv = np.asarray(b, np.float64).reshape(-1, H, d // H)
+        amax = np.abs(av).max(axis=-1, keepdims=True)
+        assert np.abs(bv - av).max() <= (amax / 16.0).max() + 1e-12
+        assert (np.abs(bv - av) <= amax / 16.0 + 1e-12).all()
+        top = np.take_along_axis(bv, np.abs(av).argmax(axis=-1)[..., None], axis=-1)
+        assert np.allclose(np.abs(top), np.float32(amax / np.float32(448.0)) * np.float32(448.0), rtol=1e-6)
+    # one decoding step with either state: same shape, finite, close (values ~0.1, error <= 1/16 of a vector's max)
+    z0 = orc.dec_step(model, st.clone(), 11)
+    z1 = orc.dec_step(model, orc.with_fp8_cross_kv(model, st.clone()), 11)
+    assert np.isfinite(z1).all() and 0 < np.abs(z1 - z0).max() < 0.5 * np.abs(z0).std()
