@@ -281,28 +281,39 @@ def other_configs(sd, synth, torch, reps=200):
     r["workload"] = "Spec-Drafter pass: 12+2 d512, B=64, source 128, 32 decoded + pending token, k=10 mask slots (704 rows)"
     out["drafter_pass"] = r
     ses.close()
-    # summarization-shaped verify step
+    # summarization-shaped verify step, with the cross keys / values in bf16 and in FP8 E4M3
     desc = synth.big_verifier(max_src=1024, max_tgt=256, enc_layers=0)
     B, k, S, L = 32, 10, 1024, 224
-    ses = sd.Session(B, k, S, 256)
-    ses.bind_model(sd.SPECDEC_VERIFIER, desc, ses.upload_weights(synth.make_weights(desc, SEED, tag="verifier")))
-    sd.specdec_begin(ses.ctx, B, 10 ** 6)
-    sd.specdec_set_memory(ses.ctx, sd.SPECDEC_VERIFIER, ses.bf16(synth.make_memory(SEED, B, S, desc.d_model)), ses.i32(np.full(B, S)))
-    toks = synth.random_tokens(SEED, "prefix", (B, L + 1), desc)
-    toks[:, 0] = desc.bos_id
-    sd.specdec_set_stream(ses.ctx, ses.i32(toks), ses.i32(np.full(B, L)))
-    sd.specdec_prefill(ses.ctx, sd.SPECDEC_VERIFIER)
-    dr = ses.i32(synth.random_tokens(SEED, "drafts", (B, k), desc, full_vocab=True))
-    acc = torch.zeros(B, dtype=torch.int32, device=ses.device)
-    nxt = torch.zeros_like(acc)
-    r = warm_and_cold(torch, lambda: sd.specdec_verify(ses.ctx, dr, k, 5, 3.0, acc, nxt), evictor, reps)
     d, F, V, H = desc.d_model, desc.d_ffn, desc.vocab, desc.n_heads
-    bytes_alg = 2.0 * (desc.dec_layers * (8 * d * d + 2 * d * F) + V * d) + 2.0 * 2 * desc.dec_layers * B * (S + L + k + 1) * d
+
+    def summarization(fp8_kv):
+        ses = sd.Session(B, k, S, 256)
+        if fp8_kv:
+            sd.specdec_configure(ses.ctx, sd.SPECDEC_OPT_FP8_CROSS_KV, 1)
+        ses.bind_model(sd.SPECDEC_VERIFIER, desc, ses.upload_weights(synth.make_weights(desc, SEED, tag="verifier")))
+        sd.specdec_begin(ses.ctx, B, 10 ** 6)
+        sd.specdec_set_memory(ses.ctx, sd.SPECDEC_VERIFIER, ses.bf16(synth.make_memory(SEED, B, S, desc.d_model)), ses.i32(np.full(B, S)))
+        toks = synth.random_tokens(SEED, "prefix", (B, L + 1), desc)
+        toks[:, 0] = desc.bos_id
+        sd.specdec_set_stream(ses.ctx, ses.i32(toks), ses.i32(np.full(B, L)))
+        sd.specdec_prefill(ses.ctx, sd.SPECDEC_VERIFIER)
+        dr = ses.i32(synth.random_tokens(SEED, "drafts", (B, k), desc, full_vocab=True))
+        acc = torch.zeros(B, dtype=torch.int32, device=ses.device)
+        nxt = torch.zeros_like(acc)
+        r = warm_and_cold(torch, lambda: sd.specdec_verify(ses.ctx, dr, k, 5, 3.0, acc, nxt), evictor, reps)
+        cross = desc.dec_layers * B * S * d * 2            # keys + values, elements
+        bytes_alg = (2.0 * (desc.dec_layers * (8 * d * d + 2 * d * F) + V * d) + 2.0 * 2 * desc.dec_layers * B * (L + k + 1) * d +
+                     (cross * 1.0 + cross / 64 * 4.0 if fp8_kv else cross * 2.0))
+        r["algorithmic_bytes"] = bytes_alg
+        r["hbm_frac_warm"] = bytes_alg / (r["warm"]["median_us"] * 1e-6) / (PEAK_HBM_GBS * 1e9)
+        ses.close()
+        return r
+
+    r = summarization(False)
     r["workload"] = "verify step: big verifier, B=32, source 1024, 224 decoded, k=10 (352 rows), beta=5 tau=3"
-    r["algorithmic_bytes"] = bytes_alg
-    r["hbm_frac_warm"] = bytes_alg / (r["warm"]["median_us"] * 1e-6) / (PEAK_HBM_GBS * 1e9)
+    r["fp8_cross_kv"] = dict(summarization(True), note="same step with the cross-attention keys / values stored as E4M3 codes + "
+                             "one scale per (key, head): a different (quantised) model, reported beside the bf16 one")
     out["summarization_verify"] = r
-    ses.close()
     return out
 
 

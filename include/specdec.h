@@ -75,7 +75,7 @@ typedef enum {
   SPECDEC_OPT_SLICED_SUBLAYERS = 3,    /* default 0: the small-batch kernels own sub-layers by output column (six
                                           kernels per layer); 1: by head / FFN slice (three per layer; measured
                                           slower: 8-16 workgroups cannot pull a layer's weights fast enough)      */
-  SPECDEC_OPT_FP8_WEIGHTS = 4          /* default 0.  1, set BEFORE specdec_workspace_bytes and specdec_bind_model:
+  SPECDEC_OPT_FP8_WEIGHTS = 4,         /* default 0.  1, set BEFORE specdec_workspace_bytes and specdec_bind_model:
                                           the model keeps a second copy of its decoder projection matrices (self
                                           QKV, self O, cross Q, cross O, FFN W1, W2) and of the tied output matrix
                                           as FP8 E4M3 codes (OCP 8-bit format: 1-4-3, bias 7, largest value 448, no
@@ -89,6 +89,16 @@ typedef enum {
                                           Larger passes, the drafter's pass, the encoder, the cross K/V projection
                                           and the input embedding rows keep the bf16 matrices; the RESIDENT and
                                           SLICED_SUBLAYERS paths refuse such a model.                               */
+  SPECDEC_OPT_FP8_CROSS_KV = 5         /* default 0.  1, set BEFORE specdec_workspace_bytes and specdec_bind_model:
+                                          the cross-attention keys and values of the model (computed once per input
+                                          by specdec_encode / specdec_set_memory, read by every pass of Sec. 2: most
+                                          of the bytes of a pass when the source is long) are also stored as E4M3
+                                          codes, every key's and every value's 64-wide per-head vector with its own
+                                          fp32 scale (max |x| / 448), converted from the bf16 arenas right after they
+                                          are written.  Every decoder pass of that model (verification, prefill,
+                                          drafting) then reads the codes: score = k_scale * (codes . q),
+                                          out += (p * v_scale) * codes.  Changes the model like FP8_WEIGHTS does;
+                                          the two options are independent.  Refused by RESIDENT / SLICED_SUBLAYERS. */
 } specdec_option;
 
 /* ---- life cycle -------------------------------------------------------------------- */
@@ -96,9 +106,9 @@ int specdec_create(specdec_ctx** out, const specdec_limits* limits); /* host onl
 void specdec_destroy(specdec_ctx* ctx);
 const char* specdec_last_error(const specdec_ctx* ctx); /* (host) valid until the next call */
 /* Chooses between kernel paths that compute the same pass (all are parity-tested against each other);
- * takes effect from the next specdec_verify / specdec_draft / specdec_prefill.  SPECDEC_OPT_FP8_WEIGHTS
- * is the exception on both counts: it selects a weight format, and is read by specdec_workspace_bytes
- * and specdec_bind_model.  Host only. */
+ * takes effect from the next specdec_verify / specdec_draft / specdec_prefill.  SPECDEC_OPT_FP8_WEIGHTS and
+ * SPECDEC_OPT_FP8_CROSS_KV are the exception on both counts: they select a storage format, and are read by
+ * specdec_workspace_bytes and specdec_bind_model.  Host only. */
 int specdec_configure(specdec_ctx* ctx, int32_t option, int32_t value);
 
 /* Number of weight tensors of a model and the shape of tensor idx (cols = 1 for vectors). */

@@ -378,17 +378,27 @@ def with_fp8_weights(model: Model) -> Model:
     return Model(model.desc, w)
 
 
+def bf16_round(x: np.ndarray) -> np.ndarray:
+    """fp32 values rounded to the nearest bf16 (8 significand bits, ties to even), returned as fp32."""
+    u = np.ascontiguousarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32)
+
+
 def with_fp8_cross_kv(model: Model, st: DecState) -> DecState:
     """The state whose cross-attention keys and values (computed once per input, read by every
     verification pass: the bulk of the bytes when the source is long) are the E4M3-stored values:
     each key's and each value's 64-wide per-head vector is one row of quantize_rows_e4m3 (its own
-    fp32 scale).  The self-attention cache is untouched (shared, not copied)."""
+    fp32 scale).  Reading taken: the 8-bit store is a re-encoding of the 16-bit one, i.e. the codes
+    are those of the keys / values as a bf16 tensor holds them (rounded to bf16 first), not of the
+    unrounded projections.  The self-attention cache is untouched (shared, not copied)."""
     H, d = model.desc.n_heads, model.desc.d_model
     dh = d // H
 
     def q(a):
         S = a.shape[0]
-        return quantize_rows_e4m3(np.asarray(a, np.float32).reshape(S * H, dh))[2].reshape(S, d).astype(model.dtype)
+        a16 = bf16_round(np.asarray(a, np.float32))
+        return quantize_rows_e4m3(a16.reshape(S * H, dh))[2].reshape(S, d).astype(model.dtype)
 
     return DecState(st.K, st.V, [q(a) for a in st.Kx], [q(a) for a in st.Vx], st.len)
 

@@ -32,6 +32,7 @@ SPECDEC_OPT_LN_FOLD = 1
 SPECDEC_OPT_RESIDENT = 2
 SPECDEC_OPT_SLICED_SUBLAYERS = 3
 SPECDEC_OPT_FP8_WEIGHTS = 4
+SPECDEC_OPT_FP8_CROSS_KV = 5
 
 
 class specdec_model_desc(C.Structure):

@@ -55,6 +55,9 @@ struct Model {
   unsigned char* w8 = nullptr;   // E4M3 codes of every decoder layer's six matrices, then the embedding (or null)
   float* w8s = nullptr;          // their row scales, same order
   bool fp8 = false;              // bound with SPECDEC_OPT_FP8_WEIGHTS: passes of at most 32 rows stream w8
+  bool kv8 = false;              // bound with SPECDEC_OPT_FP8_CROSS_KV: cross-attention reads xk8 / xv8
+  unsigned char *xk8 = nullptr, *xv8 = nullptr;   // E4M3 codes of xk / xv, same layouts
+  float *xks = nullptr, *xvs = nullptr;           // one scale per (layer, sequence, head, key)
   std::vector<Fp8Layer> dec8;
   sd::SkWeight embed8;
   float* hx = nullptr;       // [Bmax*k_max][d] head-based drafting: the hidden state each head adds to, then its output
@@ -115,6 +118,7 @@ struct specdec_ctx {
   bool resident = false;    // SPECDEC_OPT_RESIDENT = 1: small batches run the decoder pass as one resident kernel
   bool sliced = false;      // SPECDEC_OPT_SLICED_SUBLAYERS = 1: small-batch sub-layers owned by head / FFN slice
   bool fp8 = false;         // SPECDEC_OPT_FP8_WEIGHTS = 1: models bound from now on keep E4M3 copies for small batches
+  bool fp8_kv = false;      // SPECDEC_OPT_FP8_CROSS_KV = 1: models bound from now on keep E4M3 cross keys / values
   char err[512] = {0};
 };
 
@@ -237,6 +241,12 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
   t.x2 = cv.take<float>(32 * D);
   t.skp = cv.take<float>((size_t)2 * sd::kSk2MaxParts * 32 * D);
   t.hx = cv.take<float>(Bm * (size_t)c->lim.k_max * D);
+  if (c->fp8_kv) {
+    t.xk8 = cv.take<unsigned char>(t.xkv_layer * d->dec_layers);
+    t.xv8 = cv.take<unsigned char>(t.xkv_layer * d->dec_layers);
+    t.xks = cv.take<float>(t.xkv_layer / 64 * d->dec_layers);
+    t.xvs = cv.take<float>(t.xkv_layer / 64 * d->dec_layers);
+  }
   if (c->fp8) {
     t.w8 = cv.take<unsigned char>((size_t)d->dec_layers * (6 * D * D + 2 * D * F) + (size_t)d->vocab * D);
     t.w8s = cv.take<float>((size_t)d->dec_layers * (7 * D + F) + (size_t)d->vocab);
@@ -276,7 +286,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
     m->kv_layer = t.kv_layer; m->xkv_layer = t.xkv_layer;
     m->pe = t.pe; m->kc = t.kc; m->vc = t.vc; m->xk = t.xk; m->xv = t.xv;
     m->lnp[0] = t.lnp[0]; m->lnp[1] = t.lnp[1]; m->fold = t.fold;
-    m->x = t.x; m->x2 = t.x2; m->skp = t.skp; m->hx = t.hx; m->w8 = t.w8; m->w8s = t.w8s; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
+    m->x = t.x; m->x2 = t.x2; m->skp = t.skp; m->hx = t.hx; m->w8 = t.w8; m->w8s = t.w8s; m->xk8 = t.xk8; m->xv8 = t.xv8; m->xks = t.xks; m->xvs = t.xvs; m->xb = t.xb; m->q = t.q; m->att = t.att; m->hid = t.hid;
     m->part = t.part; m->row_stats = t.row_stats; m->zd = t.zd; m->rm = t.rm;
     m->slots = t.slots; m->new_rows = t.new_rows; m->rs_layers = t.rs_layers; m->rs_bar = t.rs_bar;
     m->ex = t.ex; m->exb = t.exb; m->eqkv = t.eqkv; m->eatt = t.eatt; m->ehid = t.ehid;
@@ -286,6 +296,14 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
 }
 
 inline hipStream_t S(void* s) { return static_cast<hipStream_t>(s); }
+
+// Point a cross-attention launch of layer l at the E4M3 copies of the keys / values (same strides).
+inline void cross_fp8(const Model& m, int l, sd::AttnArgs& a) {
+  a.k = reinterpret_cast<const bf16*>(m.xk8 + m.xkv_layer * l);
+  a.v = reinterpret_cast<const bf16*>(m.xv8 + m.xkv_layer * l);
+  a.k_scale = m.xks + m.xkv_layer / 64 * l;
+  a.v_scale = m.xvs + m.xkv_layer / 64 * l;
+}
 
 // Embedding (unless the caller's row assembly has already written it to m.x / m.xb) + every
 // decoder layer over the R = B*T rows described by m.rm.  Leaves the final hidden states in
@@ -346,6 +364,7 @@ int decoder_layers(specdec_ctx* c, Model& m, int B, int T, hipStream_t st, bool 
     a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_blocked = 1;
     a.lim_row = nullptr; a.lim_seq = c->st.src_len;
     a.key_split = c->S_cur > 256; a.cap = Scap;
+    if (m.kv8) cross_fp8(m, l, a);
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
     if (fold) {
       LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sum(m.att, D, L.cwo, m.folds[l].vco));
@@ -411,6 +430,7 @@ int decoder_layers_skinny(specdec_ctx* c, Model& m, int B, int T, hipStream_t st
     a.k = m.xk + m.xkv_layer * l; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64;
     a.v = m.xv + m.xkv_layer * l; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_blocked = 1;
     a.lim_row = nullptr; a.lim_seq = c->st.src_len; a.cap = Scap;
+    if (m.kv8) cross_fp8(m, l, a);
     LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::skinny_attn_o(st, cur, R, D, a, W.cwo, L.cbo, freeb));
     produced(L.ln2g, L.ln2b);
     LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::skinny_proj(st, cur, R, D, W.w1, F, L.b1, m.hid, true));
@@ -491,6 +511,8 @@ int cross_kv_from(specdec_ctx* c, Model& m, const bf16* memory, int B, int S_max
     HIPCHK(c, sd::gemm_cross_kv(st, memory, m.dec[l].cwkv, B * S_max, D, D, m.dec[l].cbkv,
                                 m.xk + m.xkv_layer * l, m.xv + m.xkv_layer * l, S_max, m.d.n_heads,
                                 c->Scap));
+  if (m.kv8)   // whole arenas: every (layer, sequence of the batch limit, head, key row)
+    HIPCHK(c, sd::quantize_cross_kv(st, m.xk, m.xv, (long)(m.xkv_layer / 64) * m.d.dec_layers, m.xk8, m.xv8, m.xks, m.xvs));
   m.has_memory = true;
   return SPECDEC_OK;
 }
@@ -545,6 +567,7 @@ int specdec_configure(specdec_ctx* c, int32_t option, int32_t value) {
     case SPECDEC_OPT_RESIDENT: c->resident = (value == 1); break;
     case SPECDEC_OPT_SLICED_SUBLAYERS: c->sliced = (value == 1); break;
     case SPECDEC_OPT_FP8_WEIGHTS: c->fp8 = (value == 1); break;
+    case SPECDEC_OPT_FP8_CROSS_KV: c->fp8_kv = (value == 1); break;
     default: return fail(c, SPECDEC_ERR_INVALID_ARG, "unknown option %d", option);
   }
   return SPECDEC_OK;
@@ -644,6 +667,7 @@ int specdec_bind_model(specdec_ctx* c, specdec_role role, const specdec_model_de
       HIPCHK(c, sd::ln_fold(S(stream), L.w1, L.ln2g, L.ln2b, L.b1, F, D, o.w1));
     }
   }
+  m.kv8 = c->fp8_kv;
   m.fp8 = c->fp8;
   if (m.fp8) {
     const int D = d->d_model, F = d->d_ffn;
@@ -919,8 +943,8 @@ int verify_impl(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, f
                                         m.d.d_model));
   const unsigned* failed = nullptr;
   int n_tiles = (m.d.vocab + 63) / 64;   // per-row partial records of the vocabulary kernel that ran
-  if (small && m.fp8 && (c->resident || c->sliced))
-    return fail(c, SPECDEC_ERR_BAD_STATE, "a model bound with FP8 weights runs small passes on the default kernels only");
+  if (small && (m.fp8 || m.kv8) && (c->resident || c->sliced))
+    return fail(c, SPECDEC_ERR_BAD_STATE, "a model bound with FP8 weights or FP8 cross keys/values runs small passes on the default kernels only");
   if (small && c->resident) {
     sd::RsArgs a{};
     a.R = R; a.T = T; a.B = B; a.H = m.d.n_heads; a.V = m.d.vocab; a.Lcap = c->Lcap; a.Scap = c->Scap;

@@ -25,7 +25,7 @@ namespace sd {
 
 constexpr int kAttnThreads = 256;
 
-template <int NQT, bool VBLK>
+template <int NQT, bool VBLK, bool KV8>
 __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   __shared__ float Om[4][NQT * 16][kHeadDim + 1];
   __shared__ float Ms[4][NQT * 16], Ls[4][NQT * 16];
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
 
   float mrun[NQT], lrun[NQT];
   f32x4 oacc[NQT][4];
-  attn_wave<NQT, VBLK>(a, b, h, q0, nq, kw, kstep, Vs[VBLK ? 0 : wave], mrun, lrun, oacc);
+  attn_wave<NQT, VBLK, false, false, KV8>(a, b, h, q0, nq, kw, kstep, Vs[VBLK ? 0 : wave], mrun, lrun, oacc);
   bf16* obase = a.q_off ? a.o + (long)(active_pair ? a.q_off[b] : 0) * a.o_row : a.o + b * a.o_b;
 
   // oacc[qt][et][r] = O^T[e = et*16 + 4g + r][q = qt*16 + lq]
@@ -101,22 +101,26 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   }
 }
 
-template <bool VBLK>
+template <bool VBLK, bool KV8>
 static hipError_t attention_launch(hipStream_t st, const AttnArgs& a) {
   const int nqt = a.T <= 16 ? 1 : (a.T <= 32 ? 2 : 4);
   const int qgroups = (a.T + nqt * 16 - 1) / (nqt * 16);
   const long units = (long)a.B * a.H * qgroups;
   const unsigned blocks = (unsigned)(a.key_split ? units : (units + 3) / 4);
-  if (nqt == 1) hipLaunchKernelGGL((attn_kernel<1, VBLK>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
-  else if (nqt == 2) hipLaunchKernelGGL((attn_kernel<2, VBLK>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
-  else hipLaunchKernelGGL((attn_kernel<4, VBLK>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
+  if (nqt == 1) hipLaunchKernelGGL((attn_kernel<1, VBLK, KV8>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
+  else if (nqt == 2) hipLaunchKernelGGL((attn_kernel<2, VBLK, KV8>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
+  else hipLaunchKernelGGL((attn_kernel<4, VBLK, KV8>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
   return hipGetLastError();
 }
 
 hipError_t attention(hipStream_t st, const AttnArgs& a) {
   if (a.B <= 0 || a.T <= 0) return hipSuccess;
   if (a.cap < 32 || a.cap % 32 != 0) return hipErrorInvalidValue;   // whole chunks are read
-  return a.v_blocked ? attention_launch<true>(st, a) : attention_launch<false>(st, a);
+  if (a.k_scale || a.v_scale) {   // FP8 keys and values
+    if (!a.k_scale || !a.v_scale || !a.v_blocked) return hipErrorInvalidValue;
+    return attention_launch<true, true>(st, a);
+  }
+  return a.v_blocked ? attention_launch<true, false>(st, a) : attention_launch<false, false>(st, a);
 }
 
 }  // namespace sd

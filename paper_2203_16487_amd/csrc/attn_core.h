@@ -1,5 +1,6 @@
 // Wave-level attention core shared by the attention kernel and the fused small-batch kernels.
 #pragma once
+#include <type_traits>
 #include "common.h"
 #include "kernels.h"
 
@@ -22,27 +23,57 @@ constexpr int kVtPitch = 68;   // bf16 per staged value row: 34 banks, so the tr
 // + r][q = qt*16 + lane%16].  Vs: wave-private LDS tile [32][kVtPitch] (row-layout values only).
 // COHQ / COHKV: queries / keys and row-layout values may have been written by other workgroups
 // of the running kernel (coherent loads, see ld16).
-template <int NQT, bool VBLK, bool COHQ = false, bool COHKV = false>
+// KV8 (key-blocked values only): keys and values are E4M3 codes with one fp32 scale per key and head;
+// fragments are half as wide, become bf16 operands in registers, and the scales go where they
+// factor out: score[key] = k_scale[key] * (codes . q), O += (p[key] * v_scale[key]) * codes.
+template <bool KV8> struct AttnFrag { typedef bf16x8 type; };
+template <> struct AttnFrag<true> { typedef fp8x8 type; };
+__device__ __forceinline__ bf16x8 attn_operand(const bf16x8& f) { return f; }
+__device__ __forceinline__ bf16x8 attn_operand(const fp8x8& f) { return e4m3x8_to_bf16(f); }
+
+template <int NQT, bool VBLK, bool COHQ = false, bool COHKV = false, bool KV8 = false>
 __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q0, int nq, int kw, int kstep,
                                           bf16 (*Vs)[kVtPitch], float (&mrun)[NQT], float (&lrun)[NQT],
                                           f32x4 (&oacc)[NQT][4]) {
   const int lane = threadIdx.x & 63;
   const int lq = lane & 15, g = lane >> 4;
-  const bf16* kbase = a.k + b * a.k_b + h * a.k_h;
-  const bf16* vbase = a.v + b * a.v_b + h * a.v_h;
+  static_assert(!KV8 || (VBLK && !COHKV), "FP8 keys / values: cross-attention arenas only");
+  typedef typename AttnFrag<KV8>::type Frag;
+  typedef typename std::conditional<KV8, fp8, bf16>::type Elem;
+  const Elem* kbase = reinterpret_cast<const Elem*>(a.k) + b * a.k_b + h * a.k_h;
+  const Elem* vbase = reinterpret_cast<const Elem*>(a.v) + b * a.v_b + h * a.v_h;
+  const float* ksc = KV8 ? a.k_scale + (b * a.k_b + h * a.k_h) / kHeadDim : nullptr;
+  const float* vsc = KV8 ? a.v_scale + (b * a.v_b + h * a.v_h) / kHeadDim : nullptr;
+  typedef float f32x4s __attribute__((ext_vector_type(4)));
+  struct Scales { f32x4s k[2], v[2]; };   // of keys c0 + 8*(lane/16) .. + 7 (this lane's eight scores)
 
   // operands of one 32-key chunk (8 x 16 B per lane), key rows clamped to `last`; the next
   // chunk is fetched while the current one is multiplied
-  auto load_chunk = [&](int c0, int last, bf16x8 (&kf)[2][2], bf16x8 (&vf)[4]) {
+  auto load_chunk = [&](int c0, int last, Frag (&kf)[2][2], Frag (&vf)[4], Scales& sc) {
     // K operands: tile t, row lq  <->  key c0 + 8*(lq/4) + 4*t + lq%4
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int key = min(c0 + 8 * (lq >> 2) + 4 * t + (lq & 3), last);
-      const bf16* kp = kbase + (long)key * a.k_row + g * 8;
-      kf[t][0] = ld16<COHKV>(kp);
-      kf[t][1] = ld16<COHKV>(kp + 32);
+      const Elem* kp = kbase + (long)key * a.k_row + g * 8;
+      if constexpr (KV8) {
+        kf[t][0] = *reinterpret_cast<const fp8x8*>(kp);
+        kf[t][1] = *reinterpret_cast<const fp8x8*>(kp + 32);
+      } else {
+        kf[t][0] = ld16<COHKV>(kp);
+        kf[t][1] = ld16<COHKV>(kp + 32);
+      }
     }
-    if (VBLK) {
+    if constexpr (KV8) {
+      const int kb = min(c0 + 8 * g, a.cap - 8);
+#pragma unroll
+      for (int et = 0; et < 4; ++et)
+        vf[et] = *reinterpret_cast<const fp8x8*>(vbase + vt_off(kb, et * 16 + lq));
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        sc.k[i] = *reinterpret_cast<const f32x4s*>(ksc + kb + 4 * i);
+        sc.v[i] = *reinterpret_cast<const f32x4s*>(vsc + kb + 4 * i);
+      }
+    } else if constexpr (VBLK) {
       // V operands: dim e = et*16 + lq, keys kb .. kb+7 = one block of the key-blocked layout
       const int kb = min(c0 + 8 * g, a.cap - 8);
 #pragma unroll
@@ -54,7 +85,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int key = min(c0 + 8 * i + (lane >> 3), last);
-        vf[i] = ld16<COHKV>(vbase + (long)key * a.v_row + (lane & 7) * 8);
+        if constexpr (!KV8) vf[i] = ld16<COHKV>(vbase + (long)key * a.v_row + (lane & 7) * 8);
       }
     }
   };
@@ -62,9 +93,10 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
   // loaded value: rows are clamped to the arena, whose every row may be read; keys past a
   // query's limit are masked by selection and their values zeroed), so limits, queries, keys
   // and values of a short context arrive in one memory round trip.
-  bf16x8 kf[2][2], vf[4], kn[2][2], vn[4];
+  Frag kf[2][2], vf[4], kn[2][2], vn[4];
+  Scales sc, scn;
   const int cfirst = kw * 32, cstep = kstep * 32;
-  load_chunk(cfirst, a.cap - 1, kf, vf);
+  load_chunk(cfirst, a.cap - 1, kf, vf, sc);
 
   // this lane's queries: q0 + qt*16 + lq; limits and Q operands (pre-scaled by 1/sqrt(64))
   int lim[NQT];
@@ -100,8 +132,9 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
 
   for (int c0 = cfirst; c0 < kmax; c0 += cstep) {
     const bool more = c0 + cstep < kmax;
-    if (more) load_chunk(c0 + cstep, kclamp, kn, vn);
-    if (!VBLK) {
+    if (more) load_chunk(c0 + cstep, kclamp, kn, vn, scn);
+    bf16x8 vo[4];   // value operands of this chunk
+    if constexpr (!VBLK) {
       // wave-private transposition: rows -> LDS -> (dim, 8 consecutive keys) operands
       // (LDS operations of one wave execute in order, so no barrier is needed; memcpy keeps
       // the 16-byte store and the 2-byte loads in one alias class for the compiler)
@@ -111,20 +144,29 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
 #pragma unroll
       for (int et = 0; et < 4; ++et)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) vf[et][i] = Vs[8 * g + i][et * 16 + lq];
+        for (int i = 0; i < 8; ++i) vo[et][i] = Vs[8 * g + i][et * 16 + lq];
+    } else {
+#pragma unroll
+      for (int et = 0; et < 4; ++et) vo[et] = attn_operand(vf[et]);
     }
     if (c0 + 32 > kmax) {
       const int nvalid = kmax - (c0 + 8 * g);
 #pragma unroll
-      for (int et = 0; et < 4; ++et) vf[et] = zero_tail(vf[et], nvalid);
+      for (int et = 0; et < 4; ++et) vo[et] = zero_tail(vo[et], nvalid);
     }
+    const bf16x8 ko00 = attn_operand(kf[0][0]), ko01 = attn_operand(kf[0][1]);
+    const bf16x8 ko10 = attn_operand(kf[1][0]), ko11 = attn_operand(kf[1][1]);
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
       f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][0], qf[qt][0], s0, 0, 0, 0);
-      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[0][1], qf[qt][1], s0, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][0], qf[qt][0], s1, 0, 0, 0);
-      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[1][1], qf[qt][1], s1, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ko00, qf[qt][0], s0, 0, 0, 0);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ko01, qf[qt][1], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ko10, qf[qt][0], s1, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ko11, qf[qt][1], s1, 0, 0, 0);
+      if constexpr (KV8) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { s0[r] *= sc.k[0][r]; s1[r] *= sc.k[1][r]; }
+      }
       // this lane: query lq of tile qt, keys kb .. kb+7 = {s0[0..3], s1[0..3]}
       const int kb = c0 + 8 * g;
       float s[8];
@@ -145,9 +187,12 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
       bf16x8 pf;
 #pragma unroll
       for (int r = 0; r < 8; ++r) {
-        float p = (any && s[r] > kNegInf) ? __expf(s[r] - mnew) : 0.f;
+        const bool on = any && s[r] > kNegInf;
+        float p = on ? __expf(s[r] - mnew) : 0.f;
         ps += p;
-        pf[r] = (bf16)p;
+        // (a masked key's scale may be anything, NaN included: it must not meet the 0)
+        if constexpr (KV8) pf[r] = (bf16)(on ? p * sc.v[r >> 2][r & 3] : 0.f);
+        else pf[r] = (bf16)p;
       }
       ps += __shfl_xor(ps, 16, 64);
       ps += __shfl_xor(ps, 32, 64);
@@ -157,7 +202,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
       for (int et = 0; et < 4; ++et) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) oacc[qt][et][r] *= alpha;
-        oacc[qt][et] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[et], pf, oacc[qt][et], 0, 0, 0);
+        oacc[qt][et] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vo[et], pf, oacc[qt][et], 0, 0, 0);
       }
     }
     if (more) {
@@ -165,6 +210,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
       for (int t = 0; t < 2; ++t) { kf[t][0] = kn[t][0]; kf[t][1] = kn[t][1]; }
 #pragma unroll
       for (int et = 0; et < 4; ++et) vf[et] = vn[et];
+      sc = scn;
     }
   }
 #pragma unroll

@@ -115,6 +115,28 @@ __device__ __forceinline__ void st_coh(bf16* p, bf16 v) {
   __builtin_memcpy(&bits, &v, 2);
   __hip_atomic_store(reinterpret_cast<unsigned short*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// FP8 E4M3 codes (OCP 8-bit float: 1-4-3, bias 7, largest value 448, no infinities) as stored
+// weights / keys / values: eight codes are one operand fragment's worth.
+typedef unsigned char fp8;
+typedef unsigned int fp8x8 __attribute__((ext_vector_type(2)));
+// Eight codes -> the bf16 operand of an MFMA: the hardware's E4M3 -> fp32 conversion, one code (byte
+// select 0..3) per instruction; an E4M3 value has 3 mantissa bits, so the upper half of its fp32
+// pattern IS its bf16 pattern, and v_perm packs two upper halves.
+__device__ __forceinline__ bf16x8 e4m3x8_to_bf16(const fp8x8& f) {
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  u32x4 o;
+#pragma unroll
+  for (int w = 0; w < 2; ++w) {
+    const unsigned c0 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 0));
+    const unsigned c1 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 1));
+    const unsigned c2 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 2));
+    const unsigned c3 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 3));
+    o[2 * w] = __builtin_amdgcn_perm(c1, c0, 0x07060302u);
+    o[2 * w + 1] = __builtin_amdgcn_perm(c3, c2, 0x07060302u);
+  }
+  return __builtin_bit_cast(bf16x8, o);
+}
+
 template <bool COH>
 __device__ __forceinline__ bf16x8 ld16(const bf16* p) {
   if (COH) return ld_coh16(p);

@@ -111,6 +111,11 @@ struct AttnArgs {
   int H, B;
   int cap;                                    // key rows of one (b, h) arena (multiple of 32); any row below it may be read
   int key_split;                              // 1: the 4 waves of a block split one pair's keys
+  // FP8 keys / values (key-blocked values only): k and v then point at E4M3 codes, one byte per element at the
+  // same element offsets, and every key's 64-wide vector has its own fp32 scale at index (element offset of the
+  // key's row) / 64 of k_scale (keys) / v_scale (values): [b][h][cap] with the arena strides above
+  const float* k_scale = nullptr;
+  const float* v_scale = nullptr;
 };
 hipError_t attention(hipStream_t st, const AttnArgs& a);
 
@@ -150,6 +155,11 @@ struct SkWeight {
 // codes, scale <- per-row E4M3 quantisation of w [N][K]: scale = max|row| / 448 (1 for a zero row),
 // code = nearest-even E4M3 of w / scale.  K % 8 == 0.
 hipError_t quantize_rows_e4m3(hipStream_t st, const bf16* w, int N, int K, unsigned char* codes, float* scale);
+// The same per-row conversion for cross-attention arenas, a row being one key's 64-wide vector of one head:
+// xk [rows][64] -> k8 [rows][64], ksc [rows]; xv key-blocked [rows/8][64][8] -> v8 (same layout), vsc [rows].
+// rows % 8 == 0.
+hipError_t quantize_cross_kv(hipStream_t st, const bf16* xk, const bf16* xv, long rows, unsigned char* k8,
+                             unsigned char* v8, float* ksc, float* vsc);
 
 // ---- resident.hip: the whole verification pass of at most 32 rows as one resident kernel ----
 struct RsLayer {

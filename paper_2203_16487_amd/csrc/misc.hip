@@ -843,6 +843,58 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const bf16* __restri
     *reinterpret_cast<uint2*>(codes + (size_t)blockIdx.x * K + k) = make_uint2(lo, hi);
   }
 }
+// One wave per block of 8 keys.  Keys: lane = (row lane/8, dims 8*(lane%8) .. +7).  Values (key-blocked:
+// element (key r, dim e) of the block at e*8 + r): lane = dim e, its 8 elements are the 8 keys.
+__global__ __launch_bounds__(256) void quantize_cross_kv_kernel(const bf16* __restrict__ xk, const bf16* __restrict__ xv,
+                                                                long n_blocks, unsigned char* __restrict__ k8,
+                                                                unsigned char* __restrict__ v8, float* __restrict__ ksc,
+                                                                float* __restrict__ vsc) {
+  const long blk = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (blk >= n_blocks) return;
+  const int lane = threadIdx.x & 63;
+  const long off = blk * 512 + lane * 8;
+  {
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(xk + off);
+    float amax = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf((float)v[i]));
+    amax = fmaxf(amax, __shfl_xor(amax, 1, 64));
+    amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
+    amax = fmaxf(amax, __shfl_xor(amax, 4, 64));
+    const float s = amax > 0.f ? __fdiv_rn(amax, 448.f) : 1.f;
+    unsigned lo = 0, hi = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      lo |= e4m3_code(__fdiv_rn((float)v[i], s)) << (8 * i);
+      hi |= e4m3_code(__fdiv_rn((float)v[4 + i], s)) << (8 * i);
+    }
+    *reinterpret_cast<uint2*>(k8 + off) = make_uint2(lo, hi);
+    if ((lane & 7) == 0) ksc[blk * 8 + (lane >> 3)] = s;
+  }
+  {
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(xv + off);
+    unsigned lo = 0, hi = 0;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const float amax = wave_max(fabsf((float)v[r]));
+      const float s = amax > 0.f ? __fdiv_rn(amax, 448.f) : 1.f;
+      const unsigned code = e4m3_code(__fdiv_rn((float)v[r], s));
+      if (r < 4) lo |= code << (8 * r); else hi |= code << (8 * (r - 4));
+      if (lane == r) vsc[blk * 8 + r] = s;
+    }
+    *reinterpret_cast<uint2*>(v8 + off) = make_uint2(lo, hi);
+  }
+}
+hipError_t quantize_cross_kv(hipStream_t st, const bf16* xk, const bf16* xv, long rows, unsigned char* k8,
+                             unsigned char* v8, float* ksc, float* vsc) {
+  if (rows <= 0) return hipSuccess;
+  if (rows % 8 != 0 || rows / 8 > 0x7fffffffL * 4) return hipErrorInvalidValue;
+  const long n_blocks = rows / 8;
+  hipLaunchKernelGGL(quantize_cross_kv_kernel, dim3((unsigned)((n_blocks + 3) / 4)), dim3(256), 0, st, xk, xv, n_blocks, k8,
+                     v8, ksc, vsc);
+  return hipGetLastError();
+}
+
 hipError_t quantize_rows_e4m3(hipStream_t st, const bf16* w, int N, int K, unsigned char* codes, float* scale) {
   if (N <= 0) return hipSuccess;
   if (K <= 0 || K % 8 != 0) return hipErrorInvalidValue;

@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kSkThreads) void sk_qkv_kernel(SkSrc src, int R, co
 
 // ------------------------------------------------------------------------------------ attention + O
 // resid: hidden state the sublayer started from (its own 16 columns are added back).
-template <int PER, bool VBLK, bool TWO, class WT>
+template <int PER, bool VBLK, bool TWO, class WT, bool KV8 = false>
 __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resid, int R, AttnArgs a,
                                                                       const WT* __restrict__ W,
                                                                       const float* __restrict__ wscale,
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
     const int nq = min(a.q_count ? a.q_count[b] : a.T, 16 * NQT);
     float mrun[NQT], lrun[NQT];
     f32x4 oacc[NQT][4];
-    attn_wave<NQT, VBLK>(a, b, h, 0, nq, 0, 1, L.vs[wave], mrun, lrun, oacc);
+    attn_wave<NQT, VBLK, false, false, KV8>(a, b, h, 0, nq, 0, 1, L.vs[wave], mrun, lrun, oacc);
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
       const int qi = qt * 16 + lq;
@@ -337,6 +337,7 @@ static hipError_t sk_init_rows() {
   if ((e = sk_attr<PER>(sk_qkv_kernel<PER, TWO, WT>)) != hipSuccess) return e;
   if ((e = sk_attr<PER>(sk_attn_o_kernel<PER, false, TWO, WT>)) != hipSuccess) return e;
   if ((e = sk_attr<PER>(sk_attn_o_kernel<PER, true, TWO, WT>)) != hipSuccess) return e;
+  if ((e = sk_attr<PER>(sk_attn_o_kernel<PER, true, TWO, WT, true>)) != hipSuccess) return e;
   if ((e = sk_attr<PER>(sk_proj_kernel<PER, TWO, WT>)) != hipSuccess) return e;
   if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(sk_ffn2_kernel<PER, 2, TWO, WT>),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)sk_ffn2_lds_bytes<PER, 2, TWO>())) != hipSuccess) return e;
@@ -373,7 +374,12 @@ hipError_t skinny_qkv(hipStream_t st, const SkSrc& src, int R, int d, SkWeight W
 }
 hipError_t skinny_attn_o(hipStream_t st, const SkSrc& resid, int R, int d, const AttnArgs& a, SkWeight W,
                          const bf16* bias, float* xs_out) {
-  if (a.v_blocked) {
+  if (a.k_scale || a.v_scale) {   // FP8 cross-attention keys and values
+    if (!a.k_scale || !a.v_scale || !a.v_blocked) return hipErrorInvalidValue;
+    SK_DISPATCH(d, SK_ROWS(R, SK_WT(W, hipLaunchKernelGGL((sk_attn_o_kernel<PER, true, TWO, WT, true>), dim3(d / 16),
+                                                          dim3(64 * kSkAttnWaves), SkLds<PER>::kBytes, st, resid, R, a,
+                                                          Wp, W.scale, bias, xs_out))));
+  } else if (a.v_blocked) {
     SK_DISPATCH(d, SK_ROWS(R, SK_WT(W, hipLaunchKernelGGL((sk_attn_o_kernel<PER, true, TWO, WT>), dim3(d / 16),
                                                           dim3(64 * kSkAttnWaves), SkLds<PER>::kBytes, st, resid, R, a,
                                                           Wp, W.scale, bias, xs_out))));

@@ -355,8 +355,6 @@ __device__ __forceinline__ void sk_wload(const bf16* __restrict__ W, int ldw, in
 // Weights stored as FP8 E4M3 codes (1-4-3, bias 7, no infinities) with one fp32 scale per output
 // row: the same operand positions, half the bytes per request; a fragment is up-cast to bf16
 // (exact: 3 mantissa bits) right before its MFMA and the row scale multiplies the finished sum.
-typedef unsigned char fp8;
-typedef unsigned int fp8x8 __attribute__((ext_vector_type(2)));   // 8 codes
 template <class WT> struct SkFrag { typedef bf16x8 type; };
 template <class WT>
 __device__ __forceinline__ float sk_wscale(const float* __restrict__ wscale, int n) {
@@ -365,23 +363,7 @@ __device__ __forceinline__ float sk_wscale(const float* __restrict__ wscale, int
 }
 template <> struct SkFrag<fp8> { typedef fp8x8 type; };
 __device__ __forceinline__ bf16x8 sk_frag(const bf16x8& f) { return f; }
-__device__ __forceinline__ bf16x8 sk_frag(const fp8x8& f) {
-  // the hardware's E4M3 -> fp32 conversion, one code (byte select 0..3) per instruction; an E4M3
-  // value has 3 mantissa bits, so the upper half of its fp32 pattern IS its bf16 pattern: v_perm
-  // packs two upper halves
-  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-  u32x4 o;
-#pragma unroll
-  for (int w = 0; w < 2; ++w) {
-    const unsigned c0 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 0));
-    const unsigned c1 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 1));
-    const unsigned c2 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 2));
-    const unsigned c3 = __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_f32_fp8((int)f[w], 3));
-    o[2 * w] = __builtin_amdgcn_perm(c1, c0, 0x07060302u);
-    o[2 * w + 1] = __builtin_amdgcn_perm(c3, c2, 0x07060302u);
-  }
-  return __builtin_bit_cast(bf16x8, o);
-}
+__device__ __forceinline__ bf16x8 sk_frag(const fp8x8& f) { return e4m3x8_to_bf16(f); }
 template <int S>
 __device__ __forceinline__ void sk_wload(const fp8* __restrict__ W, int ldw, int n0, int N, int k0, fp8x8 (&wf)[S]) {
   const int lane = threadIdx.x & 63, lq = lane & 15, g = lane >> 4;

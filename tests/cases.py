@@ -48,10 +48,12 @@ def oracle_prefill(model: orc.Model, st: orc.DecState, tokens) -> None:
 
 def make_verify_case(desc: synth.ModelDesc, seed: int, B: int, S: int, k: int, beta: int, tau: float,
                      len_lo: int, len_hi: int, drafts: str = "random", ragged_src: bool = False,
-                     std: float = 0.02, corrupt_p: float = 0.2, cap_extra: int = 0, fp8: bool = False) -> VerifyCase:
+                     std: float = 0.02, corrupt_p: float = 0.2, cap_extra: int = 0, fp8: bool = False,
+                     fp8_kv: bool = False) -> VerifyCase:
     """fp8: the expected values (prefix cache, greedy drafts, logits) come from the model whose decoder
     projection matrices and output matrix are stored as E4M3 codes with per-row scales; `bits` stay
-    the bf16 weights the library is given."""
+    the bf16 weights the library is given.  fp8_kv: likewise with the cross-attention keys / values stored
+    as E4M3 codes with one scale per (key, head) vector."""
     bits = synth.make_weights(desc, seed, std=std)
     model = orc.Model(desc, synth.weights_f32(bits))
     if fp8:
@@ -69,6 +71,8 @@ def make_verify_case(desc: synth.ModelDesc, seed: int, B: int, S: int, k: int, b
         if j == 0:
             tokens[b, 0] = desc.bos_id
         st = orc.new_state(model, memory[b, :src_len[b]], j + k + 1 + cap_extra)
+        if fp8_kv:
+            st = orc.with_fp8_cross_kv(model, st)
         oracle_prefill(model, st, tokens[b, :j])
         states.append(st)
     if drafts == "random":

@@ -126,3 +126,64 @@ def test_fp8_format_error_is_reported():
     print(f"[fp8 format] max-abs logit change {diff:.3e} ({diff / zstd:.1%} of the logit std {zstd:.3f}), "
           f"same arg-max on {same_top:.0%} of rows")
     assert diff <= 0.5 * zstd     # E4M3's 2^-4 relative step per weight, averaged over d = 512 terms and six layers
+
+
+# ----------------------------------------------------------------------------- FP8 cross-attention keys / values
+KV8 = {sd.SPECDEC_OPT_FP8_CROSS_KV: 1}
+
+
+@pytest.mark.parametrize("shape", ["toy_small", "toy_general", "toy_long_source", "base_b3", "both_formats", "garbage_fill"])
+def test_fp8_cross_kv_matches_the_quantised_oracle(shape):
+    """Cross keys / values stored as E4M3 with one scale per (key, head) vector, against the oracle whose
+    state holds the same stored values.  The library converts from its bf16 arenas, the oracle from
+    unrounded values: a code may differ by one step where bf16 rounding crosses an E4M3 boundary, which
+    stays far inside the logit tolerance.  Cases: the fused small-batch kernels, the general kernels
+    (40 rows), a source longer than 256 (4-way key split), the base verifier, both FP8 options at once,
+    and buffers filled with 0xFF (dead keys then carry NaN codes AND NaN scales)."""
+    toy = synth.ModelDesc(0, 2, 128, 2, 256, 1000, 16, 64).resolved()
+    opts, fill, fp8w = dict(KV8), 0, False
+    if shape == "toy_small":
+        desc, args = toy, dict(seed=91, B=5, S=9, k=4, len_lo=0, len_hi=14, std=0.08)
+    elif shape == "toy_general":
+        desc, args = toy, dict(seed=92, B=8, S=40, k=4, len_lo=0, len_hi=14, std=0.08)
+    elif shape == "toy_long_source":
+        desc = synth.ModelDesc(0, 2, 128, 2, 256, 1000, 320, 64).resolved()
+        args = dict(seed=93, B=3, S=300, k=4, len_lo=2, len_hi=9, std=0.08)
+    elif shape == "base_b3":
+        desc = synth.base_verifier(max_src=32, max_tgt=64, enc_layers=0)
+        args = dict(seed=94, B=3, S=24, k=9, len_lo=0, len_hi=20, std=0.02)
+    elif shape == "both_formats":
+        desc = synth.base_verifier(max_src=32, max_tgt=64, enc_layers=0)
+        args = dict(seed=95, B=1, S=32, k=5, len_lo=16, len_hi=16, std=0.02)
+        opts.update(FP8)
+        fp8w = True
+    else:
+        desc, args, fill = toy, dict(seed=96, B=5, S=9, k=4, len_lo=0, len_hi=14, std=0.08), 0xFF
+    case = cases.make_verify_case(desc, beta=3, tau=1.0, drafts="greedy", ragged_src=True, fp8=fp8w, fp8_kv=True, **args)
+    cases.run_oracle(case)
+    ses = gh.open_verifier(case, options=opts, fill=fill)
+    out = gh.gpu_verify(ses, case)
+    ses.close()
+    assert np.isfinite(out["logits"]).all()
+    err = float(np.abs(out["logits"] - case.logits).max())
+    zstd = float(case.logits.std())
+    print(f"[fp8 cross-kv {shape}] logit std {zstd:.3f}, max-abs err vs the quantised oracle {err:.3e}")
+    assert err <= max(LOGIT_TOL, REL_TOL * zstd)
+    assert not cases.compare_decisions(case, out["accept"], out["next"])[2]
+
+
+def test_fp8_cross_kv_format_error_is_reported():
+    """Both passes on the GPU, same inputs: how far E4M3 keys / values move the logits of the bf16 model."""
+    desc = synth.base_verifier(max_src=64, max_tgt=64, enc_layers=0)
+    case = cases.make_verify_case(desc, seed=97, B=2, S=64, k=9, beta=3, tau=1.0, len_lo=9, len_hi=12, drafts="greedy",
+                                  std=0.02)
+    cases.run_oracle(case)
+    outs = {}
+    for name, opt in (("bf16", None), ("fp8", KV8)):
+        ses = gh.open_verifier(case, options=opt)
+        outs[name] = gh.gpu_verify(ses, case)
+        ses.close()
+    diff = float(np.abs(outs["fp8"]["logits"] - outs["bf16"]["logits"]).max())
+    zstd = float(case.logits.std())
+    print(f"[fp8 cross-kv format] max-abs logit change {diff:.3e} ({diff / zstd:.1%} of the logit std {zstd:.3f})")
+    assert 0 < diff <= 0.25 * zstd

@@ -509,6 +509,12 @@ def test_fp8_cross_kv_is_per_key_per_head_and_bounded():
     at most half an E4M3 step of its vector's top binade, the self-attention cache is shared, and the
     cross-attention output moves by no more than the value error allows (a convex combination of
     value rows: |change| <= max value error + what the perturbed scores shift, checked loosely)."""
+    # bf16 rounding: exact on bf16 values, nearest with ties to even otherwise (1 + 2^-8 is midway
+    # between 1 and 1 + 2^-7 -> 1; 1 + 3 * 2^-8 is midway between 1 + 2^-7 and 1 + 2^-6 -> the latter)
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, -3.140625, 0.0], np.float32)
+    assert orc.bf16_round(x).tolist() == [1.0, 1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7, -3.140625, 0.0]
+    r = np.random.default_rng(1).standard_normal(4096).astype(np.float32)
+    assert np.array_equal(orc.bf16_round(r), torch.from_numpy(r).to(torch.bfloat16).float().numpy())
     model = tiny_model(seed=3)
     mem = tiny_memory(model, seed=4, S=9)
     st = prefilled_state(model, mem, [0, 5, 7], cap=8)
@@ -516,7 +522,7 @@ def test_fp8_cross_kv_is_per_key_per_head_and_bounded():
     H, d = model.desc.n_heads, model.desc.d_model
     assert q.K is st.K and q.V is st.V and q.len == st.len
     for a, b in zip(st.Kx + st.Vx, q.Kx + q.Vx):
-        av = np.asarray(a, np.float64).reshape(-1, H, d // H)
+        av = orc.bf16_round(np.asarray(a, np.float32)).astype(np.float64).reshape(-1, H, d // H)   # the 16-bit store
         bv = np.asarray(b, np.float64).reshape(-1, H, d // H)
         amax = np.abs(av).max(axis=-1, keepdims=True)
         assert np.abs(bv - av).max() <= (amax / 16.0).max() + 1e-12
