@@ -996,6 +996,8 @@ int specdec_verify(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta
 int specdec_verify_static(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, float tau, int32_t* accept_len,
                           int32_t* next_token, float* logits, void* stream) {
   if (!c) return SPECDEC_ERR_INVALID_ARG;
+  const int ready = check_ready(c, SPECDEC_VERIFIER, true);   // call-order errors before the device is touched
+  if (ready) return ready;
   int dev = -1;
   HIPCHK(c, hipGetDevice(&dev));
   if (dev < 0 || dev >= kMaxDevices) return fail(c, SPECDEC_ERR_HIP, "device ordinal %d out of range", dev);

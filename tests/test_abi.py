@@ -97,3 +97,42 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "ONE GPU" in r.stderr
+
+
+def test_options_and_new_entry_points_validate_their_arguments():
+    """specdec_configure, the FP8 workspace sizing, specdec_quantize_rows, specdec_bind_draft_heads and
+    specdec_verify_static: argument checks that need no GPU."""
+    ctx = sd.specdec_create(4, 10, 64, 64)
+    try:
+        L = sd.lib()
+        assert L.specdec_configure(ctx, 99, 1) == sd.SPECDEC_ERR_INVALID_ARG
+        assert L.specdec_configure(ctx, sd.SPECDEC_OPT_RESIDENT, 2) == sd.SPECDEC_ERR_INVALID_ARG
+        assert L.specdec_configure(None, sd.SPECDEC_OPT_RESIDENT, 1) == sd.SPECDEC_ERR_INVALID_ARG
+        desc = synth.base_verifier(enc_layers=0)
+        d, F, V, Ld = desc.d_model, desc.d_ffn, desc.vocab, desc.dec_layers
+        w0 = sd.specdec_workspace_bytes(ctx, desc)
+        sd.specdec_configure(ctx, sd.SPECDEC_OPT_FP8_WEIGHTS, 1)
+        w1 = sd.specdec_workspace_bytes(ctx, desc)
+        # one byte per weight of the six decoder matrices and of the output matrix, one fp32 scale per row
+        extra = Ld * (6 * d * d + 2 * d * F) + V * d + 4 * (Ld * (7 * d + F) + V)
+        assert extra <= w1 - w0 <= extra + 4096
+        sd.specdec_configure(ctx, sd.SPECDEC_OPT_FP8_CROSS_KV, 1)
+        w2 = sd.specdec_workspace_bytes(ctx, desc)
+        # codes for keys and values + their scales: (1 + 1 + 2 * 4 / 64) bytes per element of one bf16 arena
+        arena = Ld * 4 * desc.n_heads * 64 * 64          # layers x max_batch x heads x Scap(64) x 64
+        assert 2 * arena + 2 * arena // 16 <= w2 - w1 <= 2 * arena + 2 * arena // 16 + 4096
+        sd.specdec_configure(ctx, sd.SPECDEC_OPT_FP8_WEIGHTS, 0)
+        sd.specdec_configure(ctx, sd.SPECDEC_OPT_FP8_CROSS_KV, 0)
+        assert sd.specdec_workspace_bytes(ctx, desc) == w0
+        one = C.c_void_p(16)
+        assert L.specdec_quantize_rows(ctx, None, 4, 64, one, one, None) == sd.SPECDEC_ERR_INVALID_ARG
+        assert L.specdec_quantize_rows(ctx, one, 4, 60, one, one, None) == sd.SPECDEC_ERR_INVALID_ARG     # K % 8
+        assert L.specdec_quantize_rows(ctx, one, -1, 64, one, one, None) == sd.SPECDEC_ERR_INVALID_ARG
+        assert L.specdec_quantize_rows(ctx, C.c_void_p(8), 4, 64, one, one, None) == sd.SPECDEC_ERR_INVALID_ARG  # alignment
+        assert b"aligned" in L.specdec_last_error(ctx)
+        # nothing bound yet: the hot-path variants refuse, and say why
+        assert L.specdec_verify_static(ctx, None, 5, 3, 1.0, None, None, None, None) == sd.SPECDEC_ERR_BAD_STATE
+        assert L.specdec_draft_heads(ctx, None, 3, None, None, None) == sd.SPECDEC_ERR_BAD_STATE
+        assert L.specdec_bind_draft_heads(ctx, 3, None, None, None, None) != sd.SPECDEC_OK
+    finally:
+        sd.specdec_destroy(ctx)
