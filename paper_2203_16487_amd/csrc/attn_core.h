@@ -133,7 +133,12 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
   for (int c0 = cfirst; c0 < kmax; c0 += cstep) {
     const bool more = c0 + cstep < kmax;
     if (more) load_chunk(c0 + cstep, kclamp, kn, vn, scn);
-    bf16x8 vo[4];   // value operands of this chunk
+    // value operands of this chunk: the fetched registers themselves unless they hold codes
+    bf16x8 vo8[KV8 ? 4 : 1];
+    bf16x8(&vo)[4] = [&]() -> bf16x8(&)[4] {
+      if constexpr (KV8) return vo8;
+      else return vf;
+    }();
     if constexpr (!VBLK) {
       // wave-private transposition: rows -> LDS -> (dim, 8 consecutive keys) operands
       // (LDS operations of one wave execute in order, so no barrier is needed; memcpy keeps
@@ -145,7 +150,7 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
       for (int et = 0; et < 4; ++et)
 #pragma unroll
         for (int i = 0; i < 8; ++i) vo[et][i] = Vs[8 * g + i][et * 16 + lq];
-    } else {
+    } else if constexpr (KV8) {
 #pragma unroll
       for (int et = 0; et < 4; ++et) vo[et] = attn_operand(vf[et]);
     }
