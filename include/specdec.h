@@ -260,8 +260,9 @@ int specdec_get_output(specdec_ctx* ctx, int32_t* tokens, int32_t out_cap, int32
  * cached length hold whatever the last pass wrote there. */
 int specdec_get_cache(specdec_ctx* ctx, specdec_role role, void* k_cache, void* v_cache, int32_t L,
                       void* stream);
-/* Encoder memory of one model after specdec_encode: device bf16 [B, S_max, d] (rows beyond a
- * sequence's source length hold padding results). */
+/* Encoder memory of one model after specdec_encode: device bf16 [B, S_max, d], zeros in the rows beyond a
+ * sequence's source length (the encoder itself runs on the sources' tokens only, without padding rows).
+ * SPECDEC_ERR_BAD_STATE if the memory in use came from specdec_set_memory. */
 int specdec_get_memory(specdec_ctx* ctx, specdec_role role, void* memory, void* stream);
 /* Per-row statistics of the latest specdec_verify, device fp32 [B, k+1, SPECDEC_ROW_STATS]:
  * {max logit, arg-max (as float), log-sum-exp, logit z_d of the draft scored on this row (-inf

@@ -41,6 +41,7 @@ struct Fp8Layer {
 struct Model {
   bool bound = false;
   bool has_memory = false;
+  bool enc_packed = false;   // exb holds the memory of the latest specdec_encode as packed rows
   specdec_model_desc d{};
   const bf16* embed = nullptr;
   std::vector<EncLayer> enc;
@@ -82,6 +83,7 @@ struct Model {
   float* ex = nullptr;
   bf16 *exb = nullptr, *eqkv = nullptr, *eatt = nullptr, *ehid = nullptr;
   int *etok = nullptr, *epos = nullptr;
+  int *erow_b = nullptr, *erow_start = nullptr, *en_rows = nullptr;   // packed encoder rows: owner, first row per sequence, count
   sd::RowMap rm{};
   size_t kv_layer = 0, xkv_layer = 0;  // elements per layer of the arenas
 };
@@ -281,6 +283,9 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
     t.ehid = cv.take<bf16>(Re * F);
     t.etok = cv.take<int>(Re);
     t.epos = cv.take<int>(Re);
+    t.erow_b = cv.take<int>(Re);
+    t.erow_start = cv.take<int>(Bm + 1);
+    t.en_rows = cv.take<int>(1);
   }
   if (m) {
     m->kv_layer = t.kv_layer; m->xkv_layer = t.xkv_layer;
@@ -290,7 +295,7 @@ size_t carve_model(const specdec_ctx* c, const specdec_model_desc* d, void* base
     m->part = t.part; m->row_stats = t.row_stats; m->zd = t.zd; m->rm = t.rm;
     m->slots = t.slots; m->new_rows = t.new_rows; m->rs_layers = t.rs_layers; m->rs_bar = t.rs_bar;
     m->ex = t.ex; m->exb = t.exb; m->eqkv = t.eqkv; m->eatt = t.eatt; m->ehid = t.ehid;
-    m->etok = t.etok; m->epos = t.epos;
+    m->etok = t.etok; m->epos = t.epos; m->erow_b = t.erow_b; m->erow_start = t.erow_start; m->en_rows = t.en_rows;
   }
   return (cv.off + 255) & ~size_t(255);
 }
@@ -505,12 +510,14 @@ int decoder_layers_sliced(specdec_ctx* c, Model& m, int B, int T, hipStream_t st
   return SPECDEC_OK;
 }
 
-int cross_kv_from(specdec_ctx* c, Model& m, const bf16* memory, int B, int S_max, hipStream_t st) {
+// memory: [B][S_max][d] padded, or (packed) the model's own packed encoder rows (erow_b / epos / en_rows)
+int cross_kv_from(specdec_ctx* c, Model& m, const bf16* memory, int B, int S_max, hipStream_t st, bool packed) {
   const int D = m.d.d_model;
   for (int l = 0; l < m.d.dec_layers; ++l)
     HIPCHK(c, sd::gemm_cross_kv(st, memory, m.dec[l].cwkv, B * S_max, D, D, m.dec[l].cbkv,
                                 m.xk + m.xkv_layer * l, m.xv + m.xkv_layer * l, S_max, m.d.n_heads,
-                                c->Scap));
+                                c->Scap, packed ? m.erow_b : nullptr, packed ? m.epos : nullptr,
+                                packed ? m.en_rows : nullptr));
   if (m.kv8)   // whole arenas: every (layer, sequence of the batch limit, head, key row)
     HIPCHK(c, sd::quantize_cross_kv(st, m.xk, m.xv, (long)(m.xkv_layer / 64) * m.d.dec_layers, m.xk8, m.xv8, m.xks, m.xvs));
   m.has_memory = true;
@@ -740,36 +747,43 @@ int specdec_set_memory(specdec_ctx* c, specdec_role role, const void* memory, co
   if (S_max > c->lim.max_src) return fail(c, SPECDEC_ERR_TOO_LARGE, "S_max = %d exceeds max_src = %d", S_max, c->lim.max_src);
   HIPCHK(c, sd::set_src_len(S(stream), c->st, src_len, c->B, S_max));
   c->S_cur = S_max;
-  return cross_kv_from(c, c->m[role], static_cast<const bf16*>(memory), c->B, S_max, S(stream));
+  c->m[role].enc_packed = false;
+  return cross_kv_from(c, c->m[role], static_cast<const bf16*>(memory), c->B, S_max, S(stream), false);
 }
 
-// Encoder of one model over B*S_max padded rows; leaves the memory (bf16) in m.exb.
+// Encoder of one model over the sources' rows without padding (sequence b owns rows erow_start[b] ..
+// + src_len[b] - 1; grids are sized for B*S_max rows, row tiles beyond the real count return at once);
+// leaves the memory (bf16, packed) in m.exb.
 static int encoder_pass(specdec_ctx* c, Model& m, const int32_t* src, int B, int S_max, hipStream_t st) {
   const int R = B * S_max, D = m.d.d_model, F = m.d.d_ffn, H = m.d.n_heads, Scap = c->Scap;
   const size_t Re = (size_t)c->lim.max_batch * Scap;
   bf16* eq = m.eqkv;                 // [R][d]
   bf16* ek = m.eqkv + Re * D;        // [B][H][Scap][64]
   bf16* ev = m.eqkv + 2 * Re * D;    // [B][H][Scap/8][64][8]
-  HIPCHK(c, sd::encoder_rows(st, src, m.etok, m.epos, B, S_max, m.d.vocab));
+  const int* nr = m.en_rows;
+  HIPCHK(c, sd::encoder_rows_packed(st, src, c->st.src_len, m.etok, m.epos, m.erow_b, m.erow_start, m.en_rows, B, S_max,
+                                    m.d.vocab));
   LAUNCH(c, SPECDEC_KIND_OTHER, st, sd::embed_rows(st, m.etok, m.epos, m.embed, m.pe, m.ex, m.exb, R, D));
   for (int l = 0; l < m.d.enc_layers; ++l) {
     const EncLayer& L = m.enc[l];
-    LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::gemm_enc_qkv(st, m.exb, L.wqkv, R, D, D, L.bqkv, eq, ek, ev, S_max, H, Scap));
+    LAUNCH(c, SPECDEC_KIND_GEMM_QKV, st, sd::gemm_enc_qkv(st, m.exb, L.wqkv, R, D, D, L.bqkv, eq, ek, ev, S_max, H, Scap,
+                                                          m.erow_b, m.epos, nr));
     sd::AttnArgs a{};
     a.q = eq; a.q_b = (long)S_max * D; a.q_row = D;
     a.k = ek; a.k_b = (long)H * Scap * 64; a.k_h = (long)Scap * 64; a.k_row = 64;
     a.v = ev; a.v_b = (long)H * Scap * 64; a.v_h = (long)Scap * 64; a.v_row = 64; a.v_blocked = 1;
     a.o = m.eatt; a.o_b = (long)S_max * D; a.o_row = D;
-    a.q_count = c->st.src_len; a.lim_row = nullptr; a.lim_seq = c->st.src_len;
+    a.q_count = c->st.src_len; a.q_off = m.erow_start; a.lim_row = nullptr; a.lim_seq = c->st.src_len;
     a.T = S_max; a.H = H; a.B = B;
     a.key_split = S_max > 256; a.cap = Scap;
     LAUNCH(c, SPECDEC_KIND_ATTN, st, sd::attention(st, a));
-    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.eatt, D, L.wo, R, D, D, L.bo, m.ex, m.ex, D));
-    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.ex, L.ln1g, L.ln1b, m.exb, R, D));
-    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.exb, D, L.w1, R, F, D, L.b1, m.ehid, F, true));
-    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.ehid, F, L.w2, R, D, F, L.b2, m.ex, m.ex, D));
-    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.ex, L.ln2g, L.ln2b, m.exb, R, D));
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.eatt, D, L.wo, R, D, D, L.bo, m.ex, m.ex, D, nr));
+    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.ex, L.ln1g, L.ln1b, m.exb, R, D, nr));
+    LAUNCH(c, SPECDEC_KIND_GEMM_BF16, st, sd::gemm_bf16(st, m.exb, D, L.w1, R, F, D, L.b1, m.ehid, F, true, nr));
+    LAUNCH(c, SPECDEC_KIND_GEMM_F32, st, sd::gemm_f32(st, m.ehid, F, L.w2, R, D, F, L.b2, m.ex, m.ex, D, nr));
+    LAUNCH(c, SPECDEC_KIND_LN, st, sd::layer_norm(st, m.ex, L.ln2g, L.ln2b, m.exb, R, D, nr));
   }
+  m.enc_packed = true;
   return SPECDEC_OK;
 }
 
@@ -790,7 +804,7 @@ int specdec_encode(specdec_ctx* c, const int32_t* src, const int32_t* src_len, i
     if (!m.bound || m.d.enc_layers == 0) continue;
     int rc = encoder_pass(c, m, src, c->B, S_max, st);
     if (rc) return rc;
-    rc = cross_kv_from(c, m, m.exb, c->B, S_max, st);
+    rc = cross_kv_from(c, m, m.exb, c->B, S_max, st, true);
     if (rc) return rc;
   }
   return SPECDEC_OK;
@@ -1137,8 +1151,9 @@ int specdec_get_memory(specdec_ctx* c, specdec_role role, void* memory, void* st
   if (!memory) return fail(c, SPECDEC_ERR_INVALID_ARG, "null memory");
   Model& m = c->m[role];
   if (m.d.enc_layers == 0 || !m.exb) return fail(c, SPECDEC_ERR_BAD_STATE, "model has no encoder");
-  const size_t n = (size_t)c->B * c->S_cur * m.d.d_model;
-  HIPCHK(c, hipMemcpyAsync(memory, m.exb, n * sizeof(bf16), hipMemcpyDeviceToDevice, S(stream)));
+  if (!m.enc_packed) return fail(c, SPECDEC_ERR_BAD_STATE, "the memory in use was supplied by specdec_set_memory, not computed by specdec_encode");
+  HIPCHK(c, sd::unpack_rows(S(stream), m.exb, m.erow_start, c->st.src_len, static_cast<bf16*>(memory), c->B, c->S_cur,
+                            m.d.d_model));
   return SPECDEC_OK;
 }
 

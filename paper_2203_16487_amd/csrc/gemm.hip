@@ -114,19 +114,35 @@ struct EpiQkvAppend {
 
 // Cross-attention keys/values of the encoder memory: row m = b*S + s.
 //   xk [B][H][Scap][64]     xv [B][H][Scap/8][64][8] (blocked like the value cache)
+// Row m of the source side belongs to sequence b at source position s: m = b * S + s for padded
+// rows, or (row_b[m], row_s[m]) for packed rows (row_b < 0: a row no sequence owns).
+struct SrcRows {
+  const int* __restrict__ row_b;   // null: padded rows
+  const int* __restrict__ row_s;
+  int S;
+  struct At { int b, s; };
+  __device__ __forceinline__ At at(int m) const {
+    if (row_b) return At{row_b[m], row_s[m]};
+    const int b = m / S;
+    return At{b, m - b * S};
+  }
+};
+
 struct EpiCrossKv {
   const bf16* __restrict__ bias;
   bf16* __restrict__ xk;
   bf16* __restrict__ xv;
-  int d, H, S, Scap;
-  struct Pre { bf16x8 b; };
+  int d, H, Scap;
+  SrcRows rows;
+  struct Pre { bf16x8 b; SrcRows::At at; };
   __device__ __forceinline__ Pre fetch(int m, int n) const {
-    return Pre{*reinterpret_cast<const bf16x8*>(bias + n)};
+    return Pre{*reinterpret_cast<const bf16x8*>(bias + n), rows.at(m)};
   }
   __device__ __forceinline__ void store(int m, int n, const float (&v)[8], const Pre& p) const {
     const bf16x8 o = pack_bias(v, p.b, false);
     const int part = n / d, c = n - part * d;
-    const int b = m / S, s = m - b * S;
+    const int b = p.at.b, s = p.at.s;
+    if (b < 0) return;
     const int h = c >> 6, e = c & 63;
     if (part == 0) {
       *reinterpret_cast<bf16x8*>(xk + (((size_t)b * H + h) * Scap + s) * kHeadDim + e) = o;
@@ -145,10 +161,11 @@ struct EpiEncQkv {
   bf16* __restrict__ q;
   bf16* __restrict__ xk;
   bf16* __restrict__ xv;
-  int d, H, S, Scap;
-  struct Pre { bf16x8 b; };
+  int d, H, Scap;
+  SrcRows rows;
+  struct Pre { bf16x8 b; SrcRows::At at; };
   __device__ __forceinline__ Pre fetch(int m, int n) const {
-    return Pre{*reinterpret_cast<const bf16x8*>(bias + n)};
+    return Pre{*reinterpret_cast<const bf16x8*>(bias + n), rows.at(m)};
   }
   __device__ __forceinline__ void store(int m, int n, const float (&v)[8], const Pre& p) const {
     const bf16x8 o = pack_bias(v, p.b, false);
@@ -157,7 +174,8 @@ struct EpiEncQkv {
       *reinterpret_cast<bf16x8*>(q + (size_t)m * d + c) = o;
       return;
     }
-    const int b = m / S, s = m - b * S;
+    const int b = p.at.b, s = p.at.s;
+    if (b < 0) return;
     const int h = c >> 6, e = c & 63;
     if (part == 1) {
       *reinterpret_cast<bf16x8*>(xk + (((size_t)b * H + h) * Scap + s) * kHeadDim + e) = o;
@@ -241,12 +259,12 @@ static hipError_t launch(hipStream_t st, const bf16* A, int lda, const bf16* W, 
 }
 
 hipError_t gemm_f32(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
-                    const bf16* bias, const float* resid, float* out, int ldo) {
-  return launch(st, A, lda, W, M, N, K, EpiF32{bias, resid, out, ldo});
+                    const bf16* bias, const float* resid, float* out, int ldo, const int* m_real) {
+  return launch(st, A, lda, W, M, N, K, EpiF32{bias, resid, out, ldo}, m_real);
 }
 hipError_t gemm_bf16(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
-                     const bf16* bias, bf16* out, int ldo, bool relu) {
-  return launch(st, A, lda, W, M, N, K, EpiBf16{bias, out, ldo, relu ? 1 : 0});
+                     const bf16* bias, bf16* out, int ldo, bool relu, const int* m_real) {
+  return launch(st, A, lda, W, M, N, K, EpiBf16{bias, out, ldo, relu ? 1 : 0}, m_real);
 }
 hipError_t gemm_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
                            const bf16* bias, bf16* q_out, bf16* kc, bf16* vc, const int* row_b,
@@ -254,13 +272,15 @@ hipError_t gemm_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, 
   return launch(st, A, K, W, M, 3 * d, K, EpiQkvAppend{bias, q_out, kc, vc, row_b, row_pos, d, H, Lcap}, m_real);
 }
 hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
-                         const bf16* bias, bf16* xk, bf16* xv, int S, int H, int Scap) {
-  return launch(st, A, K, W, M, 2 * d, K, EpiCrossKv{bias, xk, xv, d, H, S, Scap});
+                         const bf16* bias, bf16* xk, bf16* xv, int S, int H, int Scap, const int* row_b,
+                         const int* row_s, const int* m_real) {
+  return launch(st, A, K, W, M, 2 * d, K, EpiCrossKv{bias, xk, xv, d, H, Scap, SrcRows{row_b, row_s, S}}, m_real);
 }
 
 hipError_t gemm_enc_qkv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
-                        const bf16* bias, bf16* q_out, bf16* ek, bf16* ev, int S, int H, int Scap) {
-  return launch(st, A, K, W, M, 3 * d, K, EpiEncQkv{bias, q_out, ek, ev, d, H, S, Scap});
+                        const bf16* bias, bf16* q_out, bf16* ek, bf16* ev, int S, int H, int Scap, const int* row_b,
+                        const int* row_s, const int* m_real) {
+  return launch(st, A, K, W, M, 3 * d, K, EpiEncQkv{bias, q_out, ek, ev, d, H, Scap, SrcRows{row_b, row_s, S}}, m_real);
 }
 
 // ----------------------------------------------------------------------------- LayerNorm folded into the GEMMs

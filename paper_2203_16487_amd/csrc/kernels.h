@@ -26,26 +26,31 @@ struct RowMap {
 };
 
 // ---- gemm.hip: C = A W^T (+bias) with different epilogues; A [M,K] bf16, W [N,K] bf16 ----
+// m_real (device, nullable, here and below): number of leading rows that hold data; row tiles at or beyond it
+// are skipped, rows beyond it neither read nor stored (M stays the upper bound the grid is sized for).
 // out fp32 [M,ldo] = A W^T + bias + resid (resid may alias out, may be null)
 hipError_t gemm_f32(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
-                    const bf16* bias, const float* resid, float* out, int ldo);
+                    const bf16* bias, const float* resid, float* out, int ldo, const int* m_real = nullptr);
 // out bf16 [M,ldo] = act(A W^T + bias)
 hipError_t gemm_bf16(hipStream_t st, const bf16* A, int lda, const bf16* W, int M, int N, int K,
-                     const bf16* bias, bf16* out, int ldo, bool relu);
+                     const bf16* bias, bf16* out, int ldo, bool relu, const int* m_real = nullptr);
 // Self-attention projection of decoder rows, N = 3d: q -> q_out [M,d]; k, v of row r ->
 // caches [B][H][Lcap][64] at sequence row_b[r], position row_pos[r] (the KV append).
 hipError_t gemm_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
                            const bf16* bias, bf16* q_out, bf16* kc, bf16* vc, const int* row_b,
                            const int* row_pos, int H, int Lcap, const int* m_real = nullptr);
-// Cross-attention keys/values of the encoder memory, N = 2d: memory rows m = b*S + s ->
-// xk [B][H][Scap][64], xv key-blocked [B][H][Scap/8][64][8].
+// Cross-attention keys/values of the encoder memory, N = 2d: memory row m -> sequence b, source position s ->
+// xk [B][H][Scap][64], xv key-blocked [B][H][Scap/8][64][8].  Padded rows (row_b null): m = b*S + s; packed
+// rows: b = row_b[m] (negative: a row no sequence owns, dropped), s = row_s[m].
 hipError_t gemm_cross_kv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
-                         const bf16* bias, bf16* xk, bf16* xv, int S, int H, int Scap);
+                         const bf16* bias, bf16* xk, bf16* xv, int S, int H, int Scap, const int* row_b = nullptr,
+                         const int* row_s = nullptr, const int* m_real = nullptr);
 
-// Encoder self-attention projection, N = 3d, rows m = b*S + s: q -> q_out [M,d], keys ->
+// Encoder self-attention projection, N = 3d, rows as above: q -> q_out [M,d] (row m), keys ->
 // ek [B][H][Scap][64], values -> ev key-blocked [B][H][Scap/8][64][8].
 hipError_t gemm_enc_qkv(hipStream_t st, const bf16* A, const bf16* W, int M, int d, int K,
-                        const bf16* bias, bf16* q_out, bf16* ek, bf16* ev, int S, int H, int Scap);
+                        const bf16* bias, bf16* q_out, bf16* ek, bf16* ev, int S, int H, int Scap,
+                        const int* row_b = nullptr, const int* row_s = nullptr, const int* m_real = nullptr);
 
 // ---- LayerNorm folded into the GEMM around it (post-LN blocks) ----
 // y = residual sum of a sub-layer, LN(y) = (y - mean) * rstd * g + beta.  The GEMM that forms y
@@ -218,7 +223,7 @@ hipError_t embed_rows(hipStream_t st, const int* tok, const int* pos, const bf16
                       const float* pe, float* x, bf16* xb, int R, int d);
 // x <- LayerNorm(x) * g + b in place (fp32), xb <- bf16(x)
 hipError_t layer_norm(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R,
-                      int d);
+                      int d, const int* m_real = nullptr);
 // dst [B*k][d] bf16 <- LayerNorm of the mask-slot rows first(b) + new_rows[b] + s of x (x unchanged),
 // first(b) = row_start[b], or b*T when row_start is null
 hipError_t layer_norm_slots(hipStream_t st, const float* x, const bf16* g, const bf16* b, bf16* dst,
@@ -253,6 +258,14 @@ hipError_t advance_cached(hipStream_t st, const SeqState& s, int role, const int
 hipError_t gather_slots(hipStream_t st, const bf16* xb, bf16* dst, const int* new_rows, const int* row_start, int B,
                         int T, int k, int d);
 hipError_t encoder_rows(hipStream_t st, const int* src, int* tok, int* pos, int B, int S, int V);
+// Encoder rows without padding: sequence b owns rows row_start[b] .. + src_len[b] - 1 (running sum, batch
+// order; row_start [B+1]), n_rows[0] = their number; tok / pos / row_b [B*S]: rows beyond n_rows get token 0,
+// position 0, sequence -1.
+hipError_t encoder_rows_packed(hipStream_t st, const int* src, const int* src_len, int* tok, int* pos, int* row_b,
+                               int* row_start, int* n_rows, int B, int S, int V);
+// dst [B][S][d] <- packed rows (zeros beyond a sequence's length)
+hipError_t unpack_rows(hipStream_t st, const bf16* src, const int* row_start, const int* src_len, bf16* dst, int B,
+                       int S, int d);
 // Merges the vocabulary partials of each of the B*(k+1) rows of a verification pass into
 // row_stats [R][kRowStats] = {max, arg-max, log-sum-exp, draft logit, number of logits above the
 // draft's, 0, 0, 0}, then applies the top-beta / tau rule and the leading-accept scan per

@@ -68,11 +68,11 @@ hipError_t embed_rows(hipStream_t st, const int* tok, const int* pos, const bf16
 template <int PER>   // d = 64 * PER
 __global__ __launch_bounds__(256) void ln_kernel(float* __restrict__ x, const bf16* __restrict__ g,
                                                  const bf16* __restrict__ bta, bf16* __restrict__ xb,
-                                                 int R) {
+                                                 int R, const int* __restrict__ m_real) {
   constexpr int d = 64 * PER;
   const int lane = threadIdx.x & 63;
   const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (r >= R) return;
+  if (r >= R || (m_real && r >= *m_real)) return;
   float* xr = x + (size_t)r * d;
   float v[PER], gg[PER], bb[PER];
 #pragma unroll
@@ -149,14 +149,14 @@ hipError_t layer_norm_slots(hipStream_t st, const float* x, const bf16* g, const
 }
 
 template <int PER>
-static hipError_t ln_launch(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R) {
-  hipLaunchKernelGGL(ln_kernel<PER>, dim3((R + 3) / 4), dim3(256), 0, st, x, g, b, xb, R);
+static hipError_t ln_launch(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R, const int* m_real) {
+  hipLaunchKernelGGL(ln_kernel<PER>, dim3((R + 3) / 4), dim3(256), 0, st, x, g, b, xb, R, m_real);
   return hipGetLastError();
 }
-hipError_t layer_norm(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R, int d) {
+hipError_t layer_norm(hipStream_t st, float* x, const bf16* g, const bf16* b, bf16* xb, int R, int d, const int* m_real) {
   if (R <= 0) return hipSuccess;
   switch (d / 64) {   // d = 64 * heads, heads <= 32
-#define SD_LN_CASE(P) case P: return ln_launch<P>(st, x, g, b, xb, R);
+#define SD_LN_CASE(P) case P: return ln_launch<P>(st, x, g, b, xb, R, m_real);
     SD_LN_CASE(1) SD_LN_CASE(2) SD_LN_CASE(3) SD_LN_CASE(4) SD_LN_CASE(5) SD_LN_CASE(6) SD_LN_CASE(7) SD_LN_CASE(8)
     SD_LN_CASE(9) SD_LN_CASE(10) SD_LN_CASE(11) SD_LN_CASE(12) SD_LN_CASE(13) SD_LN_CASE(14) SD_LN_CASE(15)
     SD_LN_CASE(16) SD_LN_CASE(17) SD_LN_CASE(18) SD_LN_CASE(19) SD_LN_CASE(20) SD_LN_CASE(21) SD_LN_CASE(22)
@@ -346,6 +346,75 @@ __global__ void encoder_rows_kernel(const int* __restrict__ src, int* __restrict
 hipError_t encoder_rows(hipStream_t st, const int* src, int* tok, int* pos, int B, int S, int V) {
   const long n = (long)B * S;
   hipLaunchKernelGGL(encoder_rows_kernel, blocks_for(n, 256), dim3(256), 0, st, src, tok, pos, n, S, V);
+  return hipGetLastError();
+}
+
+// The same without the padding: sequence b owns rows row_start[b] .. row_start[b] + src_len[b] - 1 (a
+// running sum, sources in batch order), n_rows[0] = their number.  Rows beyond it (up to B * S) get a
+// valid token, position 0 and sequence -1: whatever is computed on them is never stored anywhere else.
+__global__ __launch_bounds__(1024) void encoder_pack_scan_kernel(const int* __restrict__ src_len, int B, int S,
+                                                                 int* __restrict__ row_start, int* __restrict__ n_rows) {
+  __shared__ int part[1024];
+  const int per = (B + 1023) / 1024, b0 = threadIdx.x * per;
+  int sum = 0;
+  for (int i = 0; i < per; ++i)
+    if (b0 + i < B) sum += min(max(src_len[b0 + i], 0), S);
+  part[threadIdx.x] = sum;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int t = 0; t < 1024; ++t) { const int v = part[t]; part[t] = run; run += v; }
+    row_start[B] = run;
+    n_rows[0] = run;
+  }
+  __syncthreads();
+  int run = part[threadIdx.x];
+  for (int i = 0; i < per; ++i)
+    if (b0 + i < B) { row_start[b0 + i] = run; run += min(max(src_len[b0 + i], 0), S); }
+}
+__global__ void encoder_pack_rows_kernel(const int* __restrict__ src, const int* __restrict__ src_len,
+                                         const int* __restrict__ row_start, int* __restrict__ tok,
+                                         int* __restrict__ pos, int* __restrict__ row_b, long n, int B, int S, int V) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const int b = (int)(i / S), s = (int)(i - (long)b * S);
+  if (s < min(max(src_len[b], 0), S)) {
+    const int r = row_start[b] + s;
+    tok[r] = min(max(src[i], 0), V - 1);
+    pos[r] = s;
+    row_b[r] = b;
+  }
+  if (i >= row_start[B]) { tok[i] = 0; pos[i] = 0; row_b[i] = -1; }   // (the rows no sequence owns)
+}
+hipError_t encoder_rows_packed(hipStream_t st, const int* src, const int* src_len, int* tok, int* pos, int* row_b,
+                               int* row_start, int* n_rows, int B, int S, int V) {
+  const long n = (long)B * S;
+  hipLaunchKernelGGL(encoder_pack_scan_kernel, dim3(1), dim3(1024), 0, st, src_len, B, S, row_start, n_rows);
+  hipLaunchKernelGGL(encoder_pack_rows_kernel, blocks_for(n, 256), dim3(256), 0, st, src, src_len, row_start, tok, pos,
+                     row_b, n, B, S, V);
+  return hipGetLastError();
+}
+
+// dst [B][S][d] <- the packed rows of every sequence, zeros beyond its length
+__global__ void unpack_rows_kernel(const bf16* __restrict__ src, const int* __restrict__ row_start,
+                                   const int* __restrict__ src_len, bf16* __restrict__ dst, long n8, int S, int d) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;   // one 16-byte piece
+  if (i >= n8) return;
+  const int per = d / 8;
+  const long row = i / per;
+  const int c = (int)(i - row * per) * 8;
+  const int b = (int)(row / S), s = (int)(row - (long)b * S);
+  bf16x8 v;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = (bf16)0.f;
+  if (s < min(max(src_len[b], 0), S)) v = *reinterpret_cast<const bf16x8*>(src + (size_t)(row_start[b] + s) * d + c);
+  *reinterpret_cast<bf16x8*>(dst + (size_t)row * d + c) = v;
+}
+hipError_t unpack_rows(hipStream_t st, const bf16* src, const int* row_start, const int* src_len, bf16* dst, int B,
+                       int S, int d) {
+  const long n8 = (long)B * S * (d / 8);
+  if (n8 <= 0) return hipSuccess;
+  hipLaunchKernelGGL(unpack_rows_kernel, blocks_for(n8, 256), dim3(256), 0, st, src, row_start, src_len, dst, n8, S, d);
   return hipGetLastError();
 }
 
