@@ -21,7 +21,7 @@ pytestmark = pytest.mark.gpu
 LOGIT_TOL = 2e-2
 
 
-def run_full_size(label, B, k, beta, tau, S_max, src_lo, max_tgt, len_lo, len_hi, sample, seed=0):
+def run_full_size(label, B, k, beta, tau, S_max, src_lo, max_tgt, len_lo, len_hi, sample, seed=0, loop_iters=0):
     vdesc = synth.big_verifier(max_src=S_max, max_tgt=max_tgt, enc_layers=6)
     ddesc = synth.spec_drafter(max_src=S_max, max_tgt=max_tgt, enc_layers=12)
     vbits = synth.make_weights(vdesc, seed, tag="verifier")
@@ -43,7 +43,7 @@ def run_full_size(label, B, k, beta, tau, S_max, src_lo, max_tgt, len_lo, len_hi
         s_b = list(src[b, :src_len[b]])
         stream = [int(t) for t in toks[b, :lens[b] + 1]]
         n = len(stream) - 1
-        vst = orc.new_state(vm, orc.encode(vm, s_b), n + k + 2)
+        vst = orc.new_state(vm, orc.encode(vm, s_b), n + k + 2 + loop_iters * (k + 1))
         if n:
             orc.decoder_rows(vm, vst, stream[:-1], np.tril(np.ones((n, n), dtype=bool)))
             vst.len += n
@@ -113,6 +113,52 @@ def run_full_size(label, B, k, beta, tau, S_max, src_lo, max_tgt, len_lo, len_hi
     assert (g_dr >= 0).all() and (g_dr < V).all()
     hist = np.bincount(g_acc, minlength=k + 1).tolist()
     print(f"[{label}] all {B} decisions consistent with the library's logits; accept histogram {hist}")
+
+    # the loop goes on at full size: commit, draft, verify, with the oracle following the sampled
+    # sequences in lock step (its state advances by the library's decision, so one excused
+    # near-threshold difference does not cascade).  Drafts: the drafter's own output for the batch,
+    # replaced on the sampled sequences by the oracle's greedy continuation with 20 % corruption so
+    # that accept lengths above zero occur.
+    dmem = {b: orc.encode(dm, o[b]["src"]) for b in sample} if loop_iters else {}
+    seqs = {b: orc.SeqState(list(o[b]["stream"])) for b in sample}
+    cur = drafts
+    for it in range(loop_iters):
+        sd.specdec_commit(ses.ctx, acc, nxt)
+        for b in sample:
+            orc.commit(seqs[b], o[b]["vst"], [int(t) for t in cur[b]], int(g_acc[b]), int(g_nxt[b]), vdesc.eos_id, 10 ** 6)
+        sd.specdec_draft(ses.ctx, k, dr)
+        torch.cuda.synchronize()
+        g_dr = dr.cpu().numpy()
+        cur = g_dr.copy()
+        for b in sample:
+            stream = seqs[b].stream
+            dst = orc.new_state(dm, dmem[b], len(stream) + k + 2)
+            t_o, z_o = orc.draft(dm, dst, stream, k, return_logits=True)
+            excused += dl.check_drafts(g_dr[b:b + 1], [t_o], [z_o], f"{label} iteration {it + 1} draft {b}")
+            g, t, s2 = [], stream[-1], o[b]["vst"].clone()
+            for _ in range(k):
+                t = int(np.argmax(orc.dec_step(vm, s2, t)))
+                g.append(t)
+            cur[b] = synth.corrupt(seed + 100 * (it + 1) + b, "corrupt", np.array([g], np.int32), 0.2, vdesc)[0]
+        sd.specdec_verify(ses.ctx, ses.i32(cur), k, beta, tau, acc, nxt, logits)
+        torch.cuda.synchronize()
+        g_acc, g_nxt = acc.cpu().numpy(), nxt.cpu().numpy()
+        for b in sample:
+            d = [int(t) for t in cur[b]]
+            z = orc.verify_onepass(vm, o[b]["vst"], seqs[b].stream[-1], d)
+            zg = logits[b].cpu().numpy()
+            err = float(np.abs(zg - z).max())
+            a, n = orc.accept(z, d, beta, tau)
+            print(f"[{label}] iteration {it + 1}, sequence {b} (decoded {len(seqs[b].stream) - 1}): logits max-abs err {err:.3e}; "
+                  f"oracle accepts {a}, library {int(g_acc[b])}", flush=True)
+            assert np.isfinite(zg).all() and err <= LOGIT_TOL
+            if (a, n) != (int(g_acc[b]), int(g_nxt[b])):
+                na, ng = cases.near_threshold_rows(z, d, beta, tau)
+                row = min(a, int(g_acc[b]))
+                assert (a != g_acc[b] and row < k and na[row]) or (a == g_acc[b] and ng[a]), (it, b, a, n, g_acc[b], g_nxt[b])
+                excused += 1
+    if loop_iters:
+        print(f"[{label}] {loop_iters} more loop iterations at full size: sampled sequences in lock step ({excused} excused in all)")
     ses.close()
 
 
@@ -121,6 +167,13 @@ def test_config4_translation_loop_full_size():
     (decoded length U[48,64]); 3 sequences recomputed by the oracle."""
     run_full_size("config4", B=128, k=10, beta=3, tau=1.0, S_max=128, src_lo=16, max_tgt=128,
                   len_lo=48, len_hi=64, sample=[0, 77, 127])
+
+
+def test_config4_loop_iterations_full_size():
+    """The same workload carried on for three more iterations (commit -> draft -> verify) at full
+    size, two sequences followed by the oracle in lock step."""
+    run_full_size("config4 loop", B=128, k=10, beta=3, tau=1.0, S_max=128, src_lo=16, max_tgt=128,
+                  len_lo=48, len_hi=64, sample=[5, 90], seed=3, loop_iters=3)
 
 
 def test_config5_summarization_loop_full_size():
