@@ -101,12 +101,13 @@ hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int 
 
 // ---- attn.hip ------------------------------------------------------------------------
 struct AttnArgs {
-  const bf16* q;  long q_b, q_row;            // q + b*q_b + i*q_row + h*64
-  const bf16* k;  long k_b, k_h, k_row;       // keys   [key][64]:  k + b*k_b + h*k_h + key*k_row
-  const bf16* v;  long v_b, v_h, v_row;       // values: v + b*v_b + h*v_h + ...
+  const bf16* q;  long q_b;                   // q + b*q_b + i*q_row + h*64
+  const bf16* k;  long k_b, k_h;              // keys   [key][64]:  k + b*k_b + h*k_h + key*k_row
+  const bf16* v;  long v_b, v_h;              // values: v + b*v_b + h*v_h + ...
+  bf16* o;        long o_b;                   // o + b*o_b + i*o_row + h*64
+  int q_row, k_row, v_row, o_row;             // row strides in elements (the kernel arguments stay small)
   int v_blocked;                              //   1: key-blocked, + vt_off(key, e); whole 32-key chunks are
                                               //      read, capacity % 32 == 0      0: rows, + key*v_row + e
-  bf16* o;        long o_b, o_row;            // o + b*o_b + i*o_row + h*64
   const int* q_count;                         // [B] queries of sequence b (null: T)
   const int* q_off;                           // [B] first query / output / lim_row row of sequence b (null: b*T,
                                               //     addressed through q_b / o_b); rows are q_row / o_row apart
