@@ -374,3 +374,33 @@ def test_large_drafter_shape_24_plus_6():
     wz, wkv, ex = drafter_pass_case(dd, db, dm, B=3, S_max=40, k=10, lens=np.array([7, 12, 3], np.int32), seed=5,
                                     prefill=False)
     print(f"[drafter 24+6] logits max-abs err {wz:.3e}, K/V {wkv:.3e}, {ex} near-ties excused")
+
+
+def test_random_small_shapes_against_oracle_and_across_paths():
+    """Sixteen seeded random small cases (batch 1-8, block size 1-15, prefixes 0-40, ragged sources, a
+    pass of at most 32 rows): the fused small-batch kernels and the general kernels both against the
+    oracle, and against each other (same tolerance: different kernels, same arithmetic up to
+    rounding order)."""
+    desc = synth.ModelDesc(0, 2, 128, 2, 256, 1000, 24, 64).resolved()
+    rng = np.random.default_rng(2024)
+    worst = 0.0
+    for case_no in range(16):
+        B = int(rng.integers(1, 9))
+        k = int(rng.integers(1, min(15, 32 // B - 1) + 1))
+        hi = int(rng.integers(0, 41))
+        S = int(rng.integers(1, 25))
+        case = small_case(seed=500 + case_no, B=B, k=k, S=S, len_lo=0, len_hi=hi, beta=int(rng.integers(1, 6)),
+                          tau=float(rng.choice([0.0, 0.5, 1.0, 3.0])))
+        cases.run_oracle(case)
+        tol = max(LOGIT_TOL, REL_TOL * float(case.logits.std()))
+        outs = {}
+        for name, opt in (("fused", None), ("general", {sd.SPECDEC_OPT_SMALL_BATCH_KERNELS: 0})):
+            ses = gh.open_verifier(case, options=opt)
+            outs[name] = gh.gpu_verify(ses, case)
+            ses.close()
+            err = float(np.abs(outs[name]["logits"] - case.logits).max())
+            worst = max(worst, err)
+            assert err <= tol, (case_no, name, B, k, hi, S, err)
+            assert not cases.compare_decisions(case, outs[name]["accept"], outs[name]["next"])[2], (case_no, name, B, k)
+        assert np.abs(outs["fused"]["logits"] - outs["general"]["logits"]).max() <= tol, (case_no, B, k)
+    print(f"[random shapes] 16 cases x 2 paths, worst max-abs logit err {worst:.3e}")
