@@ -4,7 +4,8 @@
  *
  * C ABI.  Every pointer marked (device) is device memory owned by the caller; every
  * pointer marked (host) is ordinary host memory.  The library allocates no device memory:
- * weights, workspaces, inputs and outputs are the caller's.  `stream` is a hipStream_t
+ * weights, workspaces, inputs and outputs are the caller's (the one fixed array that
+ * specdec_verify_static uses is part of the loaded code object, not an allocation).  `stream` is a hipStream_t
  * passed as void* (NULL = the null stream).  Calls validate their arguments on the host,
  * enqueue work on `stream` and return without synchronising (except where stated).
  * Return value: SPECDEC_OK or a negative specdec_status; specdec_last_error() gives text.
