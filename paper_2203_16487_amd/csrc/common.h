@@ -30,7 +30,10 @@ __host__ __device__ __forceinline__ long vt_off(int key, int e) {
 
 // Wave-wide reductions; every lane receives the result.  The four steps inside a row of 16 lanes
 // are DPP moves (swap neighbours, swap pairs, mirror halves of 8, mirror the row), which cost an
-// ordinary vector instruction each; only the two steps across rows go through ds_bpermute.
+// ordinary vector instruction each and leave the row's result in all its lanes; the four row
+// results are then read as scalars (v_readlane of lanes 0, 16, 32, 48) and combined in a fixed
+// order, r0 + r1 + r2 + r3 from the left.  No step goes through LDS (ds_bpermute costs a round
+// trip of its own, and a LayerNorm is two dependent reductions).
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
@@ -41,32 +44,30 @@ __device__ __forceinline__ int dpp_i(int v) {
 }
 constexpr int kDppSwap1 = 0xB1, kDppSwap2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
 
+__device__ __forceinline__ float row_lane_f(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
 __device__ __forceinline__ float wave_sum(float v) {
   v += dpp_f<kDppSwap1>(v);
   v += dpp_f<kDppSwap2>(v);
   v += dpp_f<kDppHalfMirror>(v);
   v += dpp_f<kDppMirror>(v);
-  v += __shfl_xor(v, 16, 64);
-  v += __shfl_xor(v, 32, 64);
-  return v;
+  return ((row_lane_f(v, 0) + row_lane_f(v, 16)) + row_lane_f(v, 32)) + row_lane_f(v, 48);
 }
 __device__ __forceinline__ float wave_max(float v) {
   v = fmaxf(v, dpp_f<kDppSwap1>(v));
   v = fmaxf(v, dpp_f<kDppSwap2>(v));
   v = fmaxf(v, dpp_f<kDppHalfMirror>(v));
   v = fmaxf(v, dpp_f<kDppMirror>(v));
-  v = fmaxf(v, __shfl_xor(v, 16, 64));
-  v = fmaxf(v, __shfl_xor(v, 32, 64));
-  return v;
+  return fmaxf(fmaxf(row_lane_f(v, 0), row_lane_f(v, 16)), fmaxf(row_lane_f(v, 32), row_lane_f(v, 48)));
 }
 __device__ __forceinline__ int wave_max_i(int v) {
   v = max(v, dpp_i<kDppSwap1>(v));
   v = max(v, dpp_i<kDppSwap2>(v));
   v = max(v, dpp_i<kDppHalfMirror>(v));
   v = max(v, dpp_i<kDppMirror>(v));
-  v = max(v, __shfl_xor(v, 16, 64));
-  v = max(v, __shfl_xor(v, 32, 64));
-  return v;
+  return max(max(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+             max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
 // Workgroup barrier that orders LDS traffic only: __syncthreads() also waits for every global
