@@ -70,6 +70,14 @@ __device__ __forceinline__ int wave_max_i(int v) {
              max(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
+// 1 / sqrt(x) for a LayerNorm on a kernel's critical path: the hardware's reciprocal square root
+// (1 ulp) with one Newton step, instead of the correctly rounded square root and division (several
+// dozen instructions).
+__device__ __forceinline__ float fast_rsqrt(float x) {
+  const float r = __builtin_amdgcn_rsqf(x);
+  return r * __builtin_fmaf(-0.5f * x * r, r, 1.5f);
+}
+
 // Workgroup barrier that orders LDS traffic only: __syncthreads() also waits for every global
 // load in flight (vmcnt(0)), which serialises requests a kernel issued early on purpose.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }

@@ -353,7 +353,7 @@ struct LnRows {
     }
     q = group_sum<TPR>(q);
     if (j == 0) {
-      const float rstd = identity ? 1.f : 1.0f / sqrtf(q * inv_d + 1e-5f);
+      const float rstd = identity ? 1.f : fast_rsqrt(q * inv_d + 1e-5f);
       rowstat[2 * r] = rstd;
       rowstat[2 * r + 1] = identity ? 0.f : -mean * rstd;
     }

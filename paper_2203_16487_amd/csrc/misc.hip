@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) void ln_kernel(float* __restrict__ x, const bf
   float q = 0.f;
 #pragma unroll
   for (int i = 0; i < PER; ++i) { float t = v[i] - mean; q += t * t; }
-  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+  const float rstd = fast_rsqrt(wave_sum(q) / (float)d + 1e-5f);
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
     const int c = i * 64 + lane;
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void ln_slots_kernel(const float* __restrict__
   float q = 0.f;
 #pragma unroll
   for (int i = 0; i < PER; ++i) { float t = v[i] - mean; q += t * t; }
-  const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+  const float rstd = fast_rsqrt(wave_sum(q) / (float)d + 1e-5f);
 #pragma unroll
   for (int i = 0; i < PER; ++i)
     dst[(size_t)o * d + i * 64 + lane] = (bf16)((v[i] - mean) * rstd * gg[i] + bb[i]);
@@ -594,7 +594,7 @@ __global__ __launch_bounds__(256) void head_rows_kernel(const float* __restrict_
     float q = 0.f;
 #pragma unroll
     for (int i = 0; i < PER; ++i) { float t = v[i] - mean; q += t * t; }
-    const float rstd = 1.0f / sqrtf(wave_sum(q) / (float)d + 1e-5f);
+    const float rstd = fast_rsqrt(wave_sum(q) / (float)d + 1e-5f);
 #pragma unroll
     for (int i = 0; i < PER; ++i) v[i] = (v[i] - mean) * rstd * (float)g[i * 64 + lane] + (float)beta[i * 64 + lane];
   }

@@ -44,14 +44,6 @@ struct SkLds {
 // A lane holds VEC consecutive columns per 64*VEC-column group (VEC = 4 when d % 256 == 0), so a
 // row is fetched with 16-byte loads: the prologue's cost is the number of load instructions
 // the CU has to issue, not their bytes.
-// 1 / sqrt(x) for the LayerNorm of a prologue: the hardware's reciprocal square root (1 ulp) with one
-// Newton step, instead of the correctly rounded square root and division (several dozen
-// instructions on the critical path of every kernel of the chain).
-__device__ __forceinline__ float sk_rsqrt(float x) {
-  const float r = __builtin_amdgcn_rsqf(x);
-  return r * __builtin_fmaf(-0.5f * x * r, r, 1.5f);
-}
-
 template <int PER, bool COH = false, int RU = 4, int STRIDE = 4>
 struct SkHidden {
   static constexpr int d = 64 * PER, pitch = d + kSkPad;
@@ -183,7 +175,7 @@ struct SkHidden {
           float q = 0.f;
 #pragma unroll
           for (int i = 0; i < PER; ++i) { float t = v[u][i] - mean[u]; q += t * t; }
-          rstd[u] = sk_rsqrt(wave_sum(q) / (float)d + 1e-5f);
+          rstd[u] = fast_rsqrt(wave_sum(q) / (float)d + 1e-5f);
         }
 #pragma unroll
         for (int u = 0; u < RU; ++u)
@@ -200,7 +192,7 @@ struct SkHidden {
           float q = 0.f;
 #pragma unroll
           for (int i = 0; i < PER; ++i) { float t = v[u][i] - mean; q += t * t; }
-          const float rstd = sk_rsqrt(wave_sum(q) / (float)d + 1e-5f);
+          const float rstd = fast_rsqrt(wave_sum(q) / (float)d + 1e-5f);
 #pragma unroll
           for (int i = 0; i < PER; ++i) v[u][i] = (v[u][i] - mean) * rstd * raw_at(gg, i) + raw_at(bb, i);
         }
@@ -306,7 +298,7 @@ __device__ __forceinline__ void sk_hidden_sum(const SkSrc& s, int R, int nrows, 
     float q = 0.f;
 #pragma unroll
     for (int i = 0; i < PER; ++i) { const float t = acc[i] - mean; q += t * t; }
-    const float rstd = sk_rsqrt(wave_sum(q) / (float)d + 1e-5f);
+    const float rstd = fast_rsqrt(wave_sum(q) / (float)d + 1e-5f);
 #pragma unroll
     for (int i = 0; i < PER; ++i) hs.v[0][i] = (acc[i] - mean) * rstd * g2[i] + b2[i];
     hs.write(R, nrows, r, hb, hown, n0, want_hb, n0b);
