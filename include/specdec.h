@@ -90,7 +90,7 @@ typedef enum {
                                           Larger passes, the drafter's pass, the encoder, the cross K/V projection
                                           and the input embedding rows keep the bf16 matrices; the RESIDENT and
                                           SLICED_SUBLAYERS paths refuse such a model.                               */
-  SPECDEC_OPT_FP8_CROSS_KV = 5         /* default 0.  1, set BEFORE specdec_workspace_bytes and specdec_bind_model:
+  SPECDEC_OPT_FP8_CROSS_KV = 5,        /* default 0.  1, set BEFORE specdec_workspace_bytes and specdec_bind_model:
                                           the cross-attention keys and values of the model (computed once per input
                                           by specdec_encode / specdec_set_memory, read by every pass of Sec. 2: most
                                           of the bytes of a pass when the source is long) are also stored as E4M3
@@ -100,6 +100,10 @@ typedef enum {
                                           drafting) then reads the codes: score = k_scale * (codes . q),
                                           out += (p * v_scale) * codes.  Changes the model like FP8_WEIGHTS does;
                                           the two options are independent.  Refused by RESIDENT / SLICED_SUBLAYERS. */
+  SPECDEC_OPT_WIDE_VOCAB_TILES = 6     /* default 0: the vocabulary projection of a pass of more than 32 rows takes
+                                          its 256 x 256 tiles only where they give every compute unit two or more
+                                          (the batched passes), else 128 x 128 tiles.  1: 256 x 256 tiles in every
+                                          such pass (so that the wide kernel can be checked on small shapes).     */
 } specdec_option;
 
 /* ---- life cycle -------------------------------------------------------------------- */

@@ -33,6 +33,7 @@ SPECDEC_OPT_RESIDENT = 2
 SPECDEC_OPT_SLICED_SUBLAYERS = 3
 SPECDEC_OPT_FP8_WEIGHTS = 4
 SPECDEC_OPT_FP8_CROSS_KV = 5
+SPECDEC_OPT_WIDE_VOCAB_TILES = 6
 
 
 class specdec_model_desc(C.Structure):

@@ -121,6 +121,7 @@ struct specdec_ctx {
   bool sliced = false;      // SPECDEC_OPT_SLICED_SUBLAYERS = 1: small-batch sub-layers owned by head / FFN slice
   bool fp8 = false;         // SPECDEC_OPT_FP8_WEIGHTS = 1: models bound from now on keep E4M3 copies for small batches
   bool fp8_kv = false;      // SPECDEC_OPT_FP8_CROSS_KV = 1: models bound from now on keep E4M3 cross keys / values
+  bool wide_vocab = false;  // SPECDEC_OPT_WIDE_VOCAB_TILES = 1: 256 x 256 vocabulary tiles in every pass of more than 32 rows
   char err[512] = {0};
 };
 
@@ -575,6 +576,7 @@ int specdec_configure(specdec_ctx* c, int32_t option, int32_t value) {
     case SPECDEC_OPT_SLICED_SUBLAYERS: c->sliced = (value == 1); break;
     case SPECDEC_OPT_FP8_WEIGHTS: c->fp8 = (value == 1); break;
     case SPECDEC_OPT_FP8_CROSS_KV: c->fp8_kv = (value == 1); break;
+    case SPECDEC_OPT_WIDE_VOCAB_TILES: c->wide_vocab = (value == 1); break;
     default: return fail(c, SPECDEC_ERR_INVALID_ARG, "unknown option %d", option);
   }
   return SPECDEC_OK;
@@ -899,7 +901,7 @@ int specdec_draft(specdec_ctx* c, int32_t k, int32_t* draft, float* logits, void
   rc = decoder_layers(c, m, B, T, st, true, k, packed);
   if (rc) return rc;
   const int R = B * k, tc = sd::vocab_tile_cols(R), n_tiles = (m.d.vocab + tc - 1) / tc;
-  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, m.d.d_model, nullptr, nullptr, m.part, logits));
+  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, m.d.d_model, nullptr, nullptr, m.part, logits, c->wide_vocab));
   LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_drafts(st, m.part, n_tiles, m.row_stats, c->st, B, k, m.d.pad_id, m.new_rows,
                                       m.rm.seq_rows, draft));
   c->uncached_ub[1] = 0;
@@ -989,7 +991,7 @@ int verify_impl(specdec_ctx* c, const int32_t* draft, int32_t k, int32_t beta, f
     if (rc) return rc;
     c->fin_x = m.x; c->fin_g = nullptr; c->fin_b = nullptr;   // normalised in place by the last LayerNorm
     n_tiles = (m.d.vocab + sd::vocab_tile_cols(R) - 1) / sd::vocab_tile_cols(R);
-    LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, vs.zd, vs.part, logits));
+    LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.xb, m.embed, R, m.d.vocab, m.d.d_model, m.rm.row_draft, vs.zd, vs.part, logits, c->wide_vocab));
   }
   LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_accept(st, vs.part, vs.zd, n_tiles, vs.row_stats, c->st, B, k, beta, tau, m.d.pad_id,
                                       accept_len, next_token, failed));
@@ -1065,7 +1067,7 @@ int specdec_draft_heads(specdec_ctx* c, const int32_t* accept_len, int32_t k, in
                                      c->hb2 + (size_t)i * D, m.hx + (size_t)i * D, m.hx + (size_t)i * D, k * D));
   HIPCHK(c, sd::f32_to_bf16(st, m.hx, m.slots, (long)R * D));
   const int tc = sd::vocab_tile_cols(R), n_tiles = (m.d.vocab + tc - 1) / tc;
-  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, D, nullptr, nullptr, m.part, logits));
+  LAUNCH(c, SPECDEC_KIND_VOCAB, st, sd::vocab_stats(st, m.slots, m.embed, R, m.d.vocab, D, nullptr, nullptr, m.part, logits, c->wide_vocab));
   LAUNCH(c, SPECDEC_KIND_ACCEPT, st, sd::merge_head_drafts(st, m.part, n_tiles, m.row_stats, c->st, accept_len, B, k, m.d.pad_id, draft));
   (void)nh;
   return SPECDEC_OK;

@@ -1,6 +1,7 @@
 // MFMA GEMM kernels of the decoder / encoder blocks and the fused vocabulary kernel.
 #include "gemm_core.h"
 #include "kernels.h"
+#include <type_traits>
 
 namespace sd {
 
@@ -626,6 +627,7 @@ hipError_t ln_sum_vecs(hipStream_t st, const bf16* bias, const bf16* g_prev, con
 // count is exactly the count over the row the main kernel sees.
 //
 // One wave = 32 rows: D[i][j] = x_i . E[draft_j]; the diagonal is kept.
+template <bool SWAP>
 __global__ __launch_bounds__(64) void draft_logit_kernel(const bf16* __restrict__ A, const bf16* __restrict__ E,
                                                          int M, int V, int K, const int* __restrict__ row_draft,
                                                          float* __restrict__ zd_out) {
@@ -653,13 +655,16 @@ __global__ __launch_bounds__(64) void draft_logit_kernel(const bf16* __restrict_
     }
     if (kb0 + U <= nkb) {
 #pragma unroll
-      for (int u = 0; u < U; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[u], acc, 0, 0, 0);
+      for (int u = 0; u < U; ++u)
+        acc = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[u], a[u], acc, 0, 0, 0)
+                   : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[u], acc, 0, 0, 0);
     } else {
       for (int u = 0; u < nkb - kb0; ++u) {
         bf16x8 au = a[0], bu = b[0];
 #pragma unroll
         for (int v = 1; v < U; ++v) if (v == u) { au = a[v]; bu = b[v]; }
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(au, bu, acc, 0, 0, 0);
+        acc = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bu, au, acc, 0, 0, 0)
+                   : __builtin_amdgcn_mfma_f32_32x32x16_bf16(au, bu, acc, 0, 0, 0);
       }
     }
   }
@@ -760,10 +765,118 @@ __global__ __launch_bounds__(CfgVocab::kThreads) void vocab_kernel(const bf16* _
   }
 }
 
+// Many rows (the batched verify and draft passes): one block = 256 rows x 256 vocabulary columns,
+// 8 waves (2 along rows x 4 along the vocabulary), which halves what the operand tiles pull through
+// L2 per output.  The product is formed transposed (gemm_mainloop<.., SWAP>): a lane then owns 32
+// columns of each of its 4 rows, so a row's statistics are a serial scan of the lane's own
+// accumulators -- no staging of the fp32 tile through LDS -- followed by one exchange between the lane
+// halves and a merge of the two waves that share a 128-column tile through 16 KB of LDS.  The
+// partial records keep the 128-column granularity of the kernel above.
+typedef GemmCfg<256, 256, 2, 2, 4> CfgVocab256;
+
+template <bool ARGMAX>
+__global__ __launch_bounds__(CfgVocab256::kThreads) void vocab256_kernel(const bf16* __restrict__ A,
+                                                                         const bf16* __restrict__ E, int M, int V,
+                                                                         int K, int MT, int NT256, int NT,
+                                                                         const float* __restrict__ zd_row,
+                                                                         float* __restrict__ part,
+                                                                         float* __restrict__ logits) {
+  extern __shared__ __attribute__((aligned(1024))) bf16 smem[];
+  int mt, nt;
+  if (!xcd_tile(MT, NT256, mt, nt)) return;
+  const int m0 = mt * 256, n0 = nt * 256;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wy = wave >> 2, wx = wave & 3, lcol = lane & 31, lhalf = lane >> 5;
+  float zd[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + wy * 128 + i * 32 + lcol;
+    zd[i] = (zd_row && m < M) ? zd_row[m] : kNegInf;   // -inf on rows that score no draft: count unused
+  }
+  GemmAcc<CfgVocab256> acc;
+  gemm_mainloop<CfgVocab256, true>(A, K, E, K, M, V, 0, K / CfgVocab256::GK, m0, n0, smem, acc);
+  f32x4* rec = reinterpret_cast<f32x4*>(smem);   // [4 wave columns][256 rows]; the ring is free after the main loop
+  const int nw = n0 + wx * 64 + 4 * lhalf;        // first column of this lane
+  // column of accumulator (j, r) relative to nw: ascending in (j, r), so ">" keeps the lowest index of a tie
+  auto col = [](int j, int r) { return j * 32 + 8 * (r >> 2) + (r & 3); };
+  constexpr float kLog2e = 1.44269504088896341f;
+  auto scan = [&](auto full_tag) {
+    constexpr bool FULL = decltype(full_tag)::value;
+    const int nvalid = V - nw;   // columns of this lane inside the matrix (FULL: all of them)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float best = kNegInf;
+      int bestc = 0x3fffffff, cnt = 0;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float v = acc.c[i][j][r];
+          if (FULL || col(j, r) < nvalid) {
+            if (v > best) { best = v; bestc = col(j, r); }
+            if (!ARGMAX) cnt += (v > zd[i]) ? 1 : 0;
+          }
+        }
+      float se = 0.f;
+      if (!ARGMAX) {
+        const float nb2 = -best * kLog2e;   // exp(v - best) = 2^(v log2e - best log2e)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (FULL || col(j, r) < nvalid) se += __builtin_amdgcn_exp2f(__builtin_fmaf(acc.c[i][j][r], kLog2e, nb2));
+        if (!(best > kNegInf)) se = 0.f;    // no valid column (or all -inf): nothing to sum
+      }
+      const int besti = nw + bestc;
+      // the other lane half holds the interleaved groups of 4 columns of the same row
+      const float obest = __shfl_xor(best, 32, 64);
+      const int obesti = __shfl_xor(besti, 32, 64);
+      const float ose = __shfl_xor(se, 32, 64);
+      const int ocnt = __shfl_xor(cnt, 32, 64);
+      const float nb = fmaxf(best, obest);
+      float tot = 0.f;
+      if (best > kNegInf) tot += se * __expf(best - nb);
+      if (obest > kNegInf) tot += ose * __expf(obest - nb);
+      const int nbi = (obest > best || (obest == best && obesti < besti)) ? obesti : besti;
+      if (lhalf == 0)
+        rec[wx * 256 + wy * 128 + i * 32 + lcol] = f32x4{nb, __int_as_float(nbi), tot, __int_as_float(cnt + ocnt)};
+    }
+  };
+  if (n0 + 256 <= V) scan(std::true_type{});
+  else scan(std::false_type{});
+  if (logits) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int m = m0 + wy * 128 + i * 32 + lcol;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int n = nw + j * 32 + 8 * (r >> 2) + (r & 3);
+          if (m < M && n < V) logits[(size_t)m * V + n] = acc.c[i][j][r];
+        }
+    }
+  }
+  __syncthreads();
+  // thread (row, 128-column tile): waves 2t and 2t+1 of the row, lower columns first
+  const int row = tid & 255, ct = tid >> 8;
+  const int m = m0 + row, nt128 = nt * 2 + ct;
+  if (m < M && nt128 < NT) {
+    const f32x4 a = rec[(2 * ct) * 256 + row], b = rec[(2 * ct + 1) * 256 + row];
+    const float nb = fmaxf(a[0], b[0]);
+    float tot = 0.f;
+    if (a[0] > kNegInf) tot += a[2] * __expf(a[0] - nb);
+    if (b[0] > kNegInf) tot += b[2] * __expf(b[0] - nb);
+    const bool tb = b[0] > a[0];   // equal maxima: the lower columns (a) win
+    f32x4 out = {nb, tb ? b[1] : a[1], tot, __int_as_float(__float_as_int(a[3]) + __float_as_int(b[3]))};
+    *reinterpret_cast<f32x4*>(part + ((size_t)m * NT + nt128) * kPartF) = out;
+  }
+}
+
 int vocab_tile_cols(int) { return CfgVocab::kBN; }
 
 hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int V, int K,
-                       const int* row_draft, float* zd_row, float* part, float* logits) {
+                       const int* row_draft, float* zd_row, float* part, float* logits, bool force_wide) {
   if (M <= 0) return hipSuccess;
   static const hipError_t attr128 = [] {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab_kernel<false>),
@@ -774,11 +887,34 @@ hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int 
     return e;
   }();
   if (attr128 != hipSuccess) return attr128;
-  // without row_draft no row scores a draft (drafter pass): every count is taken against -inf, unused
-  if (row_draft)
-    hipLaunchKernelGGL(draft_logit_kernel, dim3((M + 31) / 32), dim3(64), 0, st, A, E, M, V, K, row_draft, zd_row);
   const bool stats = row_draft || logits;
   const int MT = (M + 127) / 128, NT = (V + 127) / 128;
+  // 256 x 256 tiles once they give every CU two or more (the batched passes); their product is formed with
+  // the operand roles swapped, and the draft logits follow suit
+  const int MT256 = (M + 255) / 256, NT256 = (V + 255) / 256;
+  const bool big = force_wide || (long)MT256 * NT256 >= 512;
+  // without row_draft no row scores a draft (drafter pass): every count is taken against -inf, unused
+  if (row_draft) {
+    if (big) hipLaunchKernelGGL(draft_logit_kernel<true>, dim3((M + 31) / 32), dim3(64), 0, st, A, E, M, V, K, row_draft, zd_row);
+    else hipLaunchKernelGGL(draft_logit_kernel<false>, dim3((M + 31) / 32), dim3(64), 0, st, A, E, M, V, K, row_draft, zd_row);
+  }
+  if (big) {
+    constexpr int kSmem256 = CfgVocab256::kSmemBytes;
+    static const hipError_t attr256 = [] {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab256_kernel<false>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kSmem256);
+      if (e == hipSuccess)
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(vocab256_kernel<true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmem256);
+      return e;
+    }();
+    if (attr256 != hipSuccess) return attr256;
+    if (stats)
+      hipLaunchKernelGGL(vocab256_kernel<false>, dim3(xcd_grid(MT256, NT256)), dim3(CfgVocab256::kThreads), kSmem256, st, A, E, M, V, K, MT256, NT256, NT, row_draft ? zd_row : nullptr, part, logits);
+    else
+      hipLaunchKernelGGL(vocab256_kernel<true>, dim3(xcd_grid(MT256, NT256)), dim3(CfgVocab256::kThreads), kSmem256, st, A, E, M, V, K, MT256, NT256, NT, nullptr, part, logits);
+    return hipGetLastError();
+  }
   if (stats)
     hipLaunchKernelGGL(vocab_kernel<false>, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
                        A, E, M, V, K, MT, NT, row_draft ? zd_row : nullptr, part, logits);

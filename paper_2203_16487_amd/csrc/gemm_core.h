@@ -92,7 +92,10 @@ __device__ __forceinline__ void wait_vm_stages(int allow) {
 //  * with S >= 3 the requests of stage kt+S-1 (slot of stage kt-1, free since the barrier inside
 //    stage kt-1) go out a few per sub-step during stage kt instead of in one burst; with S = 2
 //    the requests of stage kt+2 follow the barrier inside stage kt (the slot just vacated).
-template <class Cfg>
+// SWAP: W rows take the MFMA's row operand and A rows its column operand: register r of lane l of
+// tile (i, j) then holds row m = 32 i + l%32, column n = 32 j + 8*(r/4) + 4*(l/32) + r%4 (relative to
+// the wave tile), i.e. a lane owns 16 columns of ONE row per tile instead of 16 rows of one column.
+template <class Cfg, bool SWAP = false>
 __device__ __forceinline__ void gemm_mainloop(const bf16* __restrict__ A, int lda,
                                               const bf16* __restrict__ W, int ldw, int M, int N,
                                               int k_begin, int KT, int m0, int n0, bf16* smem,
@@ -155,7 +158,8 @@ __device__ __forceinline__ void gemm_mainloop(const bf16* __restrict__ A, int ld
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        acc.c[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc.c[i][j], 0, 0, 0);
+        acc.c[i][j] = SWAP ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[cur][j], fa[cur][i], acc.c[i][j], 0, 0, 0)
+                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][i], fb[cur][j], acc.c[i][j], 0, 0, 0);
         if (READ && nread < TM + TN) read_frag(cur ^ 1, nst, nss, nread++);
         if (((i * TN + j) & 1) && nd < d1) {
           dma16(gptr[nd] + dkt * GK, wslot + dslot * Cfg::kStageElems + nd * 512);

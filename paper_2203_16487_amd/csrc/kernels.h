@@ -93,11 +93,13 @@ hipError_t gemm_ln_qkv_append(hipStream_t st, const bf16* A, const bf16* W, int 
 // logits (optional, fp32 [M, V]) receives the full rows.  row_draft may be null: no row scores a
 // draft (the pre-pass is skipped, zd_row is left untouched and may be null); if logits is null as
 // well only max / arg-max are formed (records carry sum 0 and count 0: merged LSE is -inf).
+// The product runs on 256 x 256 tiles where those give every CU two or more, or when force_wide is
+// set, else on 128 x 128 tiles; the records are per 128 columns either way.
 constexpr int kPartF = 4;
 constexpr int kRowStats = 8;   // floats per row of merged statistics
 int vocab_tile_cols(int M);
 hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int V, int K,
-                       const int* row_draft, float* zd_row, float* part, float* logits);
+                       const int* row_draft, float* zd_row, float* part, float* logits, bool force_wide = false);
 
 // ---- attn.hip ------------------------------------------------------------------------
 struct AttnArgs {

@@ -108,6 +108,9 @@ def test_options_and_new_entry_points_validate_their_arguments():
         assert L.specdec_configure(ctx, 99, 1) == sd.SPECDEC_ERR_INVALID_ARG
         assert L.specdec_configure(ctx, sd.SPECDEC_OPT_RESIDENT, 2) == sd.SPECDEC_ERR_INVALID_ARG
         assert L.specdec_configure(None, sd.SPECDEC_OPT_RESIDENT, 1) == sd.SPECDEC_ERR_INVALID_ARG
+        assert L.specdec_configure(ctx, sd.SPECDEC_OPT_WIDE_VOCAB_TILES, 2) == sd.SPECDEC_ERR_INVALID_ARG
+        assert L.specdec_configure(ctx, sd.SPECDEC_OPT_WIDE_VOCAB_TILES, 1) == sd.SPECDEC_OK
+        assert L.specdec_configure(ctx, sd.SPECDEC_OPT_WIDE_VOCAB_TILES, 0) == sd.SPECDEC_OK
         desc = synth.base_verifier(enc_layers=0)
         d, F, V, Ld = desc.d_model, desc.d_ffn, desc.vocab, desc.dec_layers
         w0 = sd.specdec_workspace_bytes(ctx, desc)

@@ -25,7 +25,8 @@ KV_TOL = 3e-2
 REL_TOL = 0.04          # of the oracle's logit standard deviation
 
 
-def drafter_pass_case(dd, db, dm, B, S_max, k, lens, seed, prefill, sample=None, max_tgt=64, fixed_src=False):
+def drafter_pass_case(dd, db, dm, B, S_max, k, lens, seed, prefill, sample=None, max_tgt=64, fixed_src=False,
+                      options=None):
     """One Spec-Drafter pass of the whole batch on the GPU; the oracle recomputes `sample` (all
     by default).  Returns the worst logit / key-value errors seen."""
     src_len = np.full(B, S_max, np.int32) if fixed_src else synth.random_lengths(seed, "src_len", B, 2, S_max)
@@ -33,7 +34,7 @@ def drafter_pass_case(dd, db, dm, B, S_max, k, lens, seed, prefill, sample=None,
     L_max = int(lens.max())
     toks = synth.random_tokens(seed, "stream", (B, L_max + 1), dd)
     toks[:, 0] = dd.bos_id
-    ses = dl.open_session(B, k, S_max, max_tgt, dr=(dd, db))
+    ses = dl.open_session(B, k, S_max, max_tgt, dr=(dd, db), options=options)
     dev = ses.device
     sd.specdec_begin(ses.ctx, B, 100)
     sd.specdec_encode(ses.ctx, ses.i32(src), ses.i32(src_len))
@@ -404,3 +405,48 @@ def test_random_small_shapes_against_oracle_and_across_paths():
             assert not cases.compare_decisions(case, outs[name]["accept"], outs[name]["next"])[2], (case_no, name, B, k)
         assert np.abs(outs["fused"]["logits"] - outs["general"]["logits"]).max() <= tol, (case_no, B, k)
     print(f"[random shapes] 16 cases x 2 paths, worst max-abs logit err {worst:.3e}")
+
+
+def test_wide_vocabulary_tiles_on_small_shapes():
+    """The 256 x 256 vocabulary tiles (by default taken in the batched passes only) forced on shapes the
+    oracle covers in full: rows that end inside a row tile or span two of them, vocabularies that end
+    inside a 128-column record and inside a 256-column tile.  Logits against the oracle; decisions and
+    every row statistic that does not depend on a summation order bit for bit against the 128 x 128
+    tiles; the drafter's pass (arg-max only) likewise."""
+    worst = 0.0
+    for B, k, V in ((9, 4, 1000), (50, 5, 1000), (44, 6, 777), (37, 7, 300)):   # 45, 300, 308, 296 rows
+        desc = synth.ModelDesc(0, 2, 128, 2, 256, V, 16, 64).resolved()
+        case = cases.make_verify_case(desc, seed=900 + B, B=B, k=k, S=9, beta=3, tau=1.0, len_lo=0, len_hi=12,
+                                      drafts="greedy", ragged_src=True, std=0.08)
+        cases.run_oracle(case)
+        tol = max(LOGIT_TOL, REL_TOL * float(case.logits.std()))
+        outs = {}
+        for name, opt in (("narrow", None), ("wide", {sd.SPECDEC_OPT_WIDE_VOCAB_TILES: 1})):
+            ses = gh.open_verifier(case, options=opt)
+            outs[name] = gh.gpu_verify(ses, case)
+            ses.close()
+            err = float(np.abs(outs[name]["logits"] - case.logits).max())
+            worst = max(worst, err)
+            assert err <= tol, (name, B, k, V, err)
+            assert not cases.compare_decisions(case, outs[name]["accept"], outs[name]["next"])[2], (name, B, k, V)
+        n, w = outs["narrow"], outs["wide"]
+        assert np.array_equal(n["logits"], w["logits"]), (B, k, V)          # same MFMA chain per element
+        assert np.array_equal(n["accept"], w["accept"]) and np.array_equal(n["next"], w["next"])
+        for col in (0, 1, 3, 4):                                            # max, arg-max, z_d, count
+            assert np.array_equal(n["stats"][..., col], w["stats"][..., col]), (B, k, V, col)
+        assert np.abs(n["stats"][..., 2] - w["stats"][..., 2]).max() <= 1e-5, (B, k, V)   # log-sum-exp
+        # the draft's logit is the logit of its column, bit for bit, in the wide kernel as well
+        d = case.drafts
+        zd = np.take_along_axis(w["logits"][:, :k, :], d[:, :, None].astype(np.int64), axis=2)[..., 0]
+        assert np.array_equal(zd, w["stats"][:, :k, 3]), (B, k, V)
+    print(f"[wide vocabulary tiles] worst max-abs logit err {worst:.3e}")
+
+
+def test_wide_vocabulary_tiles_in_the_drafter_pass():
+    """The drafter's pass on 256 x 256 tiles (records with max / arg-max only when no logits are asked
+    for): slot logits, statistics, drafts and appended K/V against the oracle, 280 slot rows."""
+    _, (dd, db, dm) = dl.make_models(seed=12)
+    lens = synth.random_lengths(13, "len", 40, 0, 20)
+    wz, wkv, ex = drafter_pass_case(dd, db, dm, B=40, S_max=13, k=7, lens=lens, seed=13, prefill=True, max_tgt=48,
+                                    sample=(0, 7, 19, 39), options={sd.SPECDEC_OPT_WIDE_VOCAB_TILES: 1})
+    print(f"[drafter, wide vocabulary tiles] logits max-abs err {wz:.3e}, K/V {wkv:.3e}, {ex} near-ties excused")
