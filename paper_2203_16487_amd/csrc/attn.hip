@@ -31,7 +31,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   __shared__ float Ms[4][NQT * 16], Ls[4][NQT * 16];
   __shared__ __attribute__((aligned(16))) bf16 Vs[VBLK ? 1 : 4][VBLK ? 1 : 32][kVtPitch];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 15, g = lane >> 4;
   const int qgroups = (a.T + NQT * 16 - 1) / (NQT * 16);
   int pair, q0, kw, kstep;
@@ -43,12 +43,12 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   }
   const bool active_pair = pair < a.B * a.H;
   const int b = active_pair ? pair / a.H : 0, h = active_pair ? pair % a.H : 0;
-  const int nq_seq = a.q_count ? a.q_count[b] : a.T;
-  const int nq = active_pair ? min(nq_seq - q0, NQT * 16) : 0;
-
   float mrun[NQT], lrun[NQT];
   f32x4 oacc[NQT][4];
-  attn_wave<NQT, VBLK, false, false, KV8>(a, b, h, q0, nq, kw, kstep, Vs[VBLK ? 0 : wave], mrun, lrun, oacc);
+  attn_wave<NQT, VBLK, false, false, KV8>(a, b, h, q0, active_pair ? -1 : 0, kw, kstep, Vs[VBLK ? 0 : wave], mrun, lrun,
+                                          oacc);
+  const int nq_seq = a.q_count ? a.q_count[b] : a.T;
+  const int nq = active_pair ? min(nq_seq - q0, NQT * 16) : 0;
   bf16* obase = a.q_off ? a.o + (long)(active_pair ? a.q_off[b] : 0) * a.o_row : a.o + b * a.o_b;
 
   // oacc[qt][et][r] = O^T[e = et*16 + 4g + r][q = qt*16 + lq]

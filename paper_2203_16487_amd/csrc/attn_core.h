@@ -17,7 +17,8 @@ __device__ __forceinline__ bf16x8 zero_tail(bf16x8 v, int nvalid) {
 constexpr int kVtPitch = 68;   // bf16 per staged value row: 34 banks, so the transposed 2-byte
                                // reads of the four lane groups (8 rows apart) hit disjoint banks
 
-// One wave, one (sequence b, head h) pair, queries q0 .. q0 + nq - 1 (nq <= 16*NQT) against the
+// One wave, one (sequence b, head h) pair, queries q0 .. q0 + nq - 1 (nq <= 16*NQT; nq < 0: what
+// a.q_count leaves of the group, read here so that no request waits for it) against the
 // key chunks kw, kw + kstep, ... of 32 keys.  Results: running max / sum per query (lane%16
 // of tile qt) and the unnormalised O^T accumulators oacc[qt][et][r] = O^T[e = et*16 + 4*(lane/16)
 // + r][q = qt*16 + lane%16].  Vs: wave-private LDS tile [32][kVtPitch] (row-layout values only).
@@ -37,6 +38,11 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
                                           f32x4 (&oacc)[NQT][4]) {
   const int lane = threadIdx.x & 63;
   const int lq = lane & 15, g = lane >> 4;
+  // the pair and its query group are the same for the whole wave: say so, and per-sequence values are
+  // read with scalar loads (no vector-memory wait stands between them and the requests that follow)
+  b = __builtin_amdgcn_readfirstlane(b);
+  h = __builtin_amdgcn_readfirstlane(h);
+  q0 = __builtin_amdgcn_readfirstlane(q0);
   static_assert(!KV8 || (VBLK && !COHKV), "FP8 keys / values: cross-attention arenas only");
   typedef typename AttnFrag<KV8>::type Frag;
   typedef typename std::conditional<KV8, fp8, bf16>::type Elem;
@@ -98,26 +104,51 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
   const int cfirst = kw * 32, cstep = kstep * 32;
   load_chunk(cfirst, a.cap - 1, kf, vf, sc);
 
-  // this lane's queries: q0 + qt*16 + lq; limits and Q operands (pre-scaled by 1/sqrt(64))
+  // this lane's queries: q0 + qt*16 + lq; limits and Q operands (pre-scaled by 1/sqrt(64)).
+  // Nothing here waits for a loaded value before the last request is out: what is per sequence (first
+  // row, source length) is read with scalar loads, and a lane without a query reads the row and the limit
+  // of the clamped index min(q0 + qi, T - 1) -- rows below T exist for every sequence -- and discards
+  // them, so that addresses never depend on the query count.  (Coherent queries keep the older form:
+  // their row is the first one when the lane has no query.)
   int lim[NQT];
   bf16x8 qf[NQT][2];
   int kmax = 0;
-  const bf16* qbase = a.q_off ? a.q + (long)a.q_off[b] * a.q_row : a.q + b * a.q_b;
-  const int lbase = a.q_off ? a.q_off[b] : b * a.T;
+  // the three per-sequence values first (scalar loads, one round trip together), then their uses
+  const int qcount = (nq < 0 && a.q_count) ? a.q_count[b] : a.T;
+  const int qo = a.q_off ? a.q_off[b] : 0;
+  const int lseq = a.lim_row ? 0 : a.lim_seq[b];
+  if (nq < 0) nq = min(qcount - q0, NQT * 16);
+  nq = __builtin_amdgcn_readfirstlane(nq);
+  const bf16* qbase = a.q_off ? a.q + (long)qo * a.q_row : a.q + b * a.q_b;
+  const int lbase = a.q_off ? qo : b * a.T;
 #pragma unroll
   for (int qt = 0; qt < NQT; ++qt) {
     const int qi = qt * 16 + lq;
     const bool ok = qi < nq;
-    lim[qt] = ok ? (a.lim_row ? a.lim_row[lbase + q0 + qi] : a.lim_seq[b]) : 0;
-    kmax = max(kmax, lim[qt]);
-    const bf16* qp = qbase + (long)(q0 + (ok ? qi : 0)) * a.q_row + h * kHeadDim + g * 8;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 v = ld16<COHQ>(qp + ks * 32);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = (bf16)((float)v[e] * 0.125f);   // exact: power of two
-      qf[qt][ks] = v;
+    int row;
+    if constexpr (COHQ) {
+      row = q0 + (ok ? qi : 0);
+      lim[qt] = ok ? (a.lim_row ? a.lim_row[lbase + q0 + qi] : lseq) : 0;
+    } else {
+      row = min(q0 + qi, a.T - 1);
+      lim[qt] = a.lim_row ? a.lim_row[lbase + row] : lseq;
     }
+    const bf16* qp = qbase + (long)row * a.q_row + h * kHeadDim + g * 8;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) qf[qt][ks] = ld16<COHQ>(qp + ks * 32);
+  }
+  // The queries are needed where the limits are (same round trip): this use keeps their requests here,
+  // ahead of the first wait, instead of letting them sink behind the branch around the key loop.
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) asm volatile("" : : "v"(qf[qt][0]), "v"(qf[qt][1]), "v"(lim[qt]));
+#pragma unroll
+  for (int qt = 0; qt < NQT; ++qt) {
+    if constexpr (!COHQ) lim[qt] = (qt * 16 + lq < nq) ? lim[qt] : 0;
+    kmax = max(kmax, lim[qt]);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) qf[qt][ks][e] = (bf16)((float)qf[qt][ks][e] * 0.125f);   // exact: power of two
   }
   kmax = wave_max_i(kmax);
 
