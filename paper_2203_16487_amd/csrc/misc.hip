@@ -671,17 +671,21 @@ __global__ void commit_kernel(SeqState s, const int* __restrict__ accept_len, co
   __shared__ int active, tokens;
   if (threadIdx.x == 0) { active = 0; tokens = 0; }
   __syncthreads();
+  // the counters are read now and written at the end: their round trip runs under the sequences'
+  int c_commits = 0, c_tokens = 0;
+  if (threadIdx.x == 0) { c_commits = s.scratch[0]; c_tokens = s.scratch[1]; }
   int mine = 0, added = 0;
   for (int b = threadIdx.x; b < B; b += blockDim.x) {
-    // two memory round trips per sequence: the scalars, then every token that may be appended
+    // one memory round trip per sequence: the scalars and, whatever they turn out to be, every token
+    // that may be appended (k_max <= 31 drafts are stored per sequence)
     const int fin0 = s.finished[b], a0 = accept_len[b], j0 = s.len[b], cap = s.cap[b], nt = next_token[b];
+    int t[32];
+#pragma unroll
+    for (int i = 0; i < 31; ++i) t[i] = (i < k) ? s.last_draft[b * s.k_max + i] : 0;
+    t[31] = 0;
     if (fin0) continue;
     if (a0 < 0) { ++mine; continue; }   // verification reported a failure: nothing to commit
     const int a = min(a0, k);   // k of the pass whose drafts are stored: entries beyond it are stale
-    int t[32];                           // k_max <= 31
-#pragma unroll
-    for (int i = 0; i < 31; ++i) t[i] = (i < a) ? s.last_draft[b * s.k_max + i] : 0;
-    t[31] = 0;
     int j = j0;
     int* u = s.tokens + (size_t)b * s.tok_pitch;
     int fin = 0;
@@ -708,8 +712,8 @@ __global__ void commit_kernel(SeqState s, const int* __restrict__ accept_len, co
   __syncthreads();
   if (threadIdx.x == 0) {
     if (n_active) *n_active = active;
-    s.scratch[0] += 1;          // commits
-    s.scratch[1] += tokens;     // tokens appended
+    s.scratch[0] = c_commits + 1;        // commits
+    s.scratch[1] = c_tokens + tokens;    // tokens appended
     s.scratch[2] = B - active;  // finished sequences
   }
 }
