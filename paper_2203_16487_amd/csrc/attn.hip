@@ -45,10 +45,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(AttnArgs a) {
   const int b = active_pair ? pair / a.H : 0, h = active_pair ? pair % a.H : 0;
   float mrun[NQT], lrun[NQT];
   f32x4 oacc[NQT][4];
-  attn_wave<NQT, VBLK, false, false, KV8>(a, b, h, q0, active_pair ? -1 : 0, kw, kstep, Vs[VBLK ? 0 : wave], mrun, lrun,
-                                          oacc);
-  const int nq_seq = a.q_count ? a.q_count[b] : a.T;
-  const int nq = active_pair ? min(nq_seq - q0, NQT * 16) : 0;
+  int nq = active_pair ? -1 : 0;   // -1: the pair's query count is read inside, after the first requests
+  attn_wave<NQT, VBLK, false, false, KV8>(a, b, h, q0, nq, kw, kstep, Vs[VBLK ? 0 : wave], mrun, lrun, oacc);
   bf16* obase = a.q_off ? a.o + (long)(active_pair ? a.q_off[b] : 0) * a.o_row : a.o + b * a.o_b;
 
   // oacc[qt][et][r] = O^T[e = et*16 + 4g + r][q = qt*16 + lq]

@@ -17,13 +17,14 @@ __device__ __forceinline__ bf16x8 zero_tail(bf16x8 v, int nvalid) {
 constexpr int kVtPitch = 68;   // bf16 per staged value row: 34 banks, so the transposed 2-byte
                                // reads of the four lane groups (8 rows apart) hit disjoint banks
 
-// One wave, one (sequence b, head h) pair, queries q0 .. q0 + nq - 1 (nq <= 16*NQT; nq < 0: what
-// a.q_count leaves of the group, read here so that no request waits for it) against the
+// One wave, one (sequence b, head h) pair, queries q0 .. q0 + nq - 1 (nq <= 16*NQT; nq < 0 on entry: what
+// a.q_count leaves of the group, read here so that no request waits for it, and returned) against the
 // key chunks kw, kw + kstep, ... of 32 keys.  Results: running max / sum per query (lane%16
 // of tile qt) and the unnormalised O^T accumulators oacc[qt][et][r] = O^T[e = et*16 + 4*(lane/16)
 // + r][q = qt*16 + lane%16].  Vs: wave-private LDS tile [32][kVtPitch] (row-layout values only).
 // COHQ / COHKV: queries / keys and row-layout values may have been written by other workgroups
 // of the running kernel (coherent loads, see ld16).
+// QOFF = false: the caller never sets a.q_off (rows b*T .. of sequence b): no request depends on a loaded value.
 // KV8 (key-blocked values only): keys and values are E4M3 codes with one fp32 scale per key and head;
 // fragments are half as wide, become bf16 operands in registers, and the scales go where they
 // factor out: score[key] = k_scale[key] * (codes . q), O += (p[key] * v_scale[key]) * codes.
@@ -32,8 +33,8 @@ template <> struct AttnFrag<true> { typedef fp8x8 type; };
 __device__ __forceinline__ bf16x8 attn_operand(const bf16x8& f) { return f; }
 __device__ __forceinline__ bf16x8 attn_operand(const fp8x8& f) { return e4m3x8_to_bf16(f); }
 
-template <int NQT, bool VBLK, bool COHQ = false, bool COHKV = false, bool KV8 = false>
-__device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q0, int nq, int kw, int kstep,
+template <int NQT, bool VBLK, bool COHQ = false, bool COHKV = false, bool KV8 = false, bool QOFF = true>
+__device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q0, int& nq, int kw, int kstep,
                                           bf16 (*Vs)[kVtPitch], float (&mrun)[NQT], float (&lrun)[NQT],
                                           f32x4 (&oacc)[NQT][4]) {
   const int lane = threadIdx.x & 63;
@@ -113,29 +114,39 @@ __device__ __forceinline__ void attn_wave(const AttnArgs& a, int b, int h, int q
   int lim[NQT];
   bf16x8 qf[NQT][2];
   int kmax = 0;
-  // the three per-sequence values first (scalar loads, one round trip together), then their uses
+  // the three per-sequence values first (one round trip together), then their uses; the query count is not
+  // needed before every request is out (it only decides which lanes' results count)
   const int qcount = (nq < 0 && a.q_count) ? a.q_count[b] : a.T;
-  const int qo = a.q_off ? a.q_off[b] : 0;
+  const int qo = (QOFF && a.q_off) ? a.q_off[b] : 0;
   const int lseq = a.lim_row ? 0 : a.lim_seq[b];
-  if (nq < 0) nq = min(qcount - q0, NQT * 16);
-  nq = __builtin_amdgcn_readfirstlane(nq);
-  const bf16* qbase = a.q_off ? a.q + (long)qo * a.q_row : a.q + b * a.q_b;
-  const int lbase = a.q_off ? qo : b * a.T;
+  if constexpr (COHQ) {
+    if (nq < 0) nq = min(qcount - q0, NQT * 16);
+    nq = __builtin_amdgcn_readfirstlane(nq);
+  }
+  auto request = [&](const bf16* qbase, int lbase) {
 #pragma unroll
-  for (int qt = 0; qt < NQT; ++qt) {
-    const int qi = qt * 16 + lq;
-    const bool ok = qi < nq;
-    int row;
-    if constexpr (COHQ) {
-      row = q0 + (ok ? qi : 0);
-      lim[qt] = ok ? (a.lim_row ? a.lim_row[lbase + q0 + qi] : lseq) : 0;
-    } else {
-      row = min(q0 + qi, a.T - 1);
-      lim[qt] = a.lim_row ? a.lim_row[lbase + row] : lseq;
+    for (int qt = 0; qt < NQT; ++qt) {
+      const int qi = qt * 16 + lq;
+      int row;
+      if constexpr (COHQ) {
+        const bool ok = qi < nq;
+        row = q0 + (ok ? qi : 0);
+        lim[qt] = ok ? (a.lim_row ? a.lim_row[lbase + q0 + qi] : lseq) : 0;
+      } else {
+        row = min(q0 + qi, a.T - 1);
+        lim[qt] = a.lim_row ? a.lim_row[lbase + row] : lseq;
+      }
+      const bf16* qp = qbase + (long)row * a.q_row + h * kHeadDim + g * 8;
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) qf[qt][ks] = ld16<COHQ>(qp + ks * 32);
     }
-    const bf16* qp = qbase + (long)row * a.q_row + h * kHeadDim + g * 8;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) qf[qt][ks] = ld16<COHQ>(qp + ks * 32);
+  };
+  // two copies of the requests, so that only the packed one (rows found through q_off) waits for a loaded value
+  if (QOFF && a.q_off) request(a.q + (long)qo * a.q_row, qo);
+  else request(a.q + b * a.q_b, b * a.T);
+  if constexpr (!COHQ) {
+    if (nq < 0) nq = min(qcount - q0, NQT * 16);
+    nq = __builtin_amdgcn_readfirstlane(nq);
   }
   // The queries are needed where the limits are (same round trip): this use keeps their requests here,
   // ahead of the first wait, instead of letting them sink behind the branch around the key loop.

@@ -183,7 +183,7 @@ __device__ __forceinline__ void rs_attn_o(const SkLds<PER>& L, const SkSrc& resi
   for (int p = wave; p < a.B * a.H; p += 4) {
     const int b = p / a.H, h = p - b * a.H;
     constexpr int NQT = TWO ? 2 : 1;
-    const int nq = min(a.q_count ? a.q_count[b] : a.T, 16 * NQT);
+    int nq = min(a.q_count ? a.q_count[b] : a.T, 16 * NQT);
     float mrun[NQT], lrun[NQT];
     f32x4 oacc[NQT][4];
     attn_wave<NQT, VBLK, true, !VBLK>(a, b, h, 0, nq, 0, 1, L.vs[wave], mrun, lrun, oacc);

@@ -99,10 +99,10 @@ __global__ __launch_bounds__(64 * kSkAttnWaves) void sk_attn_o_kernel(SkSrc resi
   for (int p = wave; p < a.B * a.H; p += kSkAttnWaves) {
     const int b = p / a.H, h = p - b * a.H;
     constexpr int NQT = TWO ? 2 : 1;   // at most 16 rows in all: one query tile
-    const int nq = min(a.q_count ? a.q_count[b] : a.T, 16 * NQT);
+    int nq = -1;   // min(query count of b, 16 * NQT): read inside, after the first key / value requests
     float mrun[NQT], lrun[NQT];
     f32x4 oacc[NQT][4];
-    attn_wave<NQT, VBLK, false, false, KV8>(a, b, h, 0, nq, 0, 1, L.vs[wave], mrun, lrun, oacc);
+    attn_wave<NQT, VBLK, false, false, KV8, false>(a, b, h, 0, nq, 0, 1, L.vs[wave], mrun, lrun, oacc);
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
       const int qi = qt * 16 + lq;

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(64 * kHeadWaves) void sk2_head_kernel(SkSrc src, in
   // one (sequence, head) pair per wave
   for (int b = wave; b < a.B; b += kHeadWaves) {
     constexpr int NQT = TWO ? 2 : 1;
-    const int nq = min(a.q_count ? a.q_count[b] : a.T, 16 * NQT);
+    int nq = min(a.q_count ? a.q_count[b] : a.T, 16 * NQT);
     float mrun[NQT], lrun[NQT];
     f32x4 oacc[NQT][4];
     attn_wave<NQT, !SELF, true, SELF>(a, b, h, 0, nq, 0, 1, vs[wave], mrun, lrun, oacc);
