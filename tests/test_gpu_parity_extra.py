@@ -450,3 +450,34 @@ def test_wide_vocabulary_tiles_in_the_drafter_pass():
     wz, wkv, ex = drafter_pass_case(dd, db, dm, B=40, S_max=13, k=7, lens=lens, seed=13, prefill=True, max_tgt=48,
                                     sample=(0, 7, 19, 39), options={sd.SPECDEC_OPT_WIDE_VOCAB_TILES: 1})
     print(f"[drafter, wide vocabulary tiles] logits max-abs err {wz:.3e}, K/V {wkv:.3e}, {ex} near-ties excused")
+
+
+def test_random_medium_shapes_general_kernels():
+    """Eight seeded random cases of 40-450 rows (batch 12-90, block size 1-15, prefixes 0-45, ragged
+    sources of up to 40 tokens): the general kernels (64 x 64 and 128 x 128 GEMM tiles, one or two query
+    tiles per attention wave, both vocabulary kernels, LayerNorm folded or as a pass of its own) against
+    the oracle on every sequence."""
+    desc = synth.ModelDesc(0, 2, 128, 2, 256, 1000, 40, 64).resolved()
+    rng = np.random.default_rng(77)
+    worst = 0.0
+    for case_no in range(8):
+        B = int(rng.integers(12, 91))
+        k = int(rng.integers(max(1, 33 // B), 16))
+        while B * (k + 1) <= 32:
+            k += 1
+        hi = int(rng.integers(0, 46))
+        S = int(rng.integers(1, 41))
+        case = cases.make_verify_case(desc, seed=700 + case_no, B=B, k=k, S=S, beta=int(rng.integers(1, 6)),
+                                      tau=float(rng.choice([0.0, 0.5, 1.0, 3.0])), len_lo=0, len_hi=hi,
+                                      drafts="greedy", ragged_src=True, std=0.08)
+        cases.run_oracle(case)
+        tol = max(LOGIT_TOL, REL_TOL * float(case.logits.std()))
+        opt = {sd.SPECDEC_OPT_WIDE_VOCAB_TILES: case_no & 1, sd.SPECDEC_OPT_LN_FOLD: (case_no >> 1) & 1}
+        ses = gh.open_verifier(case, options=opt)
+        out = gh.gpu_verify(ses, case)
+        ses.close()
+        err = float(np.abs(out["logits"] - case.logits).max())
+        worst = max(worst, err)
+        assert err <= tol, (case_no, B, k, hi, S, opt, err)
+        assert not cases.compare_decisions(case, out["accept"], out["next"])[2], (case_no, B, k, opt)
+    print(f"[random medium shapes] 8 cases, worst max-abs logit err {worst:.3e}")
