@@ -612,8 +612,8 @@ def main():
     evictor = Evictor(torch, dev)
     out["batch128"]["verify_us_stats"] = warm_and_cold(
         torch, lambda: sd.specdec_verify(ses.ctx, drafts, k, beta, tau, acc, nxt), evictor, 200)
-    out["batch128"]["kernel_ms_per_step_note"] = ("each kind bracketed by HIP events in a pass of its own: the brackets include the "
-                                                  "dispatch gaps, so the kinds do not add up to ms_per_step")
+    out["batch128"]["kernel_ms_per_step_note"] = ("each kind timed in a pass of its own (HIP events holding the main kernel's own begin and "
+                                                  "end): the passes are perturbed by the event records, so the kinds do not add up to ms_per_step")
 
     # the same iteration at the three operating points of an untrained model pair
     def op_point(vdrafts, b_, t_):

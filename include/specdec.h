@@ -293,8 +293,11 @@ int specdec_quantize_rows(specdec_ctx* ctx, const void* w, int64_t N, int64_t K,
                                void* stream);
 
 /* ---- timing of one kernel kind ----------------------------------------------------------- */
-/* While a kind is selected every launch of that kernel is bracketed by a pair of HIP events
- * on the launch stream (up to 4096 launches between two reads; later ones are not recorded).
+/* While a kind is selected every launch of that kernel is timed by a pair of HIP events on the launch
+ * stream (up to 4096 launches between two reads; later ones are not recorded): for the GEMM, attention and
+ * vocabulary kernels of passes of more than 32 rows the pair holds the kernel's own begin and end, for the
+ * other kernels the moments the stream reaches a marker before and after the launch (the hand-over from the
+ * launch before is then inside).
  * specdec_profile_read waits for the recorded events (it synchronises on them), returns their
  * summed duration in milliseconds and their number, and clears the record. */
 typedef enum {

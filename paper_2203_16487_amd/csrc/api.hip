@@ -144,20 +144,32 @@ int fail(const specdec_ctx* c, int code, const char* fmt, ...) {
   } while (0)
 
 constexpr int kProfPairs = 4096;
-inline bool prof_begin(specdec_ctx* c, int kind, hipStream_t st) {
+// One launch of the selected kind between two events.  Where the launcher times its main kernel itself
+// (sd::KernelTimer) the pair holds that kernel's own begin and end; else the pair brackets the call on the
+// stream (and then also holds the hand-over from the launch before).
+inline bool prof_begin(specdec_ctx* c, int kind, hipStream_t st, sd::KernelTimer& t) {
   if (c->prof_kind != kind || c->prof_used + 2 > (int)c->prof_ev.size()) return false;
-  return hipEventRecord(c->prof_ev[c->prof_used], st) == hipSuccess;
+  if (hipEventRecord(c->prof_ev[c->prof_used], st) != hipSuccess) return false;
+  t.start = c->prof_ev[c->prof_used];
+  t.stop = c->prof_ev[c->prof_used + 1];
+  t.used = false;
+  sd::set_kernel_timer(&t);
+  return true;
 }
-inline void prof_end(specdec_ctx* c, hipStream_t st) {
-  (void)hipEventRecord(c->prof_ev[c->prof_used + 1], st);
+inline void prof_end(specdec_ctx* c, hipStream_t st, const sd::KernelTimer& t) {
+  sd::set_kernel_timer(nullptr);
+  if (!t.used) (void)hipEventRecord(c->prof_ev[c->prof_used + 1], st);
   c->prof_used += 2;
 }
 // launch `expr` (a kernels.h launcher on stream st) as kernel kind `kind`
 #define LAUNCH(c, kind, st, expr)            \
   do {                                       \
-    bool p_ = prof_begin(c, kind, st);       \
-    HIPCHK(c, expr);                         \
-    if (p_) prof_end(c, st);                 \
+    sd::KernelTimer kt_;                     \
+    bool p_ = prof_begin(c, kind, st, kt_);  \
+    hipError_t le_ = (expr);                 \
+    if (p_) prof_end(c, st, kt_);            \
+    if (le_ != hipSuccess)                   \
+      return fail(c, SPECDEC_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(le_)); \
   } while (0)
 
 bool desc_ok(const specdec_model_desc* d) {

@@ -105,9 +105,9 @@ static hipError_t attention_launch(hipStream_t st, const AttnArgs& a) {
   const int qgroups = (a.T + nqt * 16 - 1) / (nqt * 16);
   const long units = (long)a.B * a.H * qgroups;
   const unsigned blocks = (unsigned)(a.key_split ? units : (units + 3) / 4);
-  if (nqt == 1) hipLaunchKernelGGL((attn_kernel<1, VBLK, KV8>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
-  else if (nqt == 2) hipLaunchKernelGGL((attn_kernel<2, VBLK, KV8>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
-  else hipLaunchKernelGGL((attn_kernel<4, VBLK, KV8>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
+  if (nqt == 1) SD_LAUNCH_TIMED((attn_kernel<1, VBLK, KV8>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
+  else if (nqt == 2) SD_LAUNCH_TIMED((attn_kernel<2, VBLK, KV8>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
+  else SD_LAUNCH_TIMED((attn_kernel<4, VBLK, KV8>), dim3(blocks), dim3(kAttnThreads), 0, st, a);
   return hipGetLastError();
 }
 

@@ -5,6 +5,10 @@
 
 namespace sd {
 
+static thread_local KernelTimer* g_kernel_timer = nullptr;
+void set_kernel_timer(KernelTimer* t) { g_kernel_timer = t; }
+KernelTimer* kernel_timer() { return g_kernel_timer; }
+
 // Workgroup ids are dealt round-robin to the 8 XCDs (id % 8), each with its own L2.  Tiles are
 // numbered n-major (m fastest) and XCD x takes the contiguous run [x*per, (x+1)*per): the
 // tiles that run together on one XCD then share a few weight column-panels and the
@@ -244,7 +248,7 @@ static hipError_t launch_cfg(hipStream_t st, const bf16* A, int lda, const bf16*
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, Cfg::kSmemBytes);
   if (attr != hipSuccess) return attr;
   const int MT = (M + Cfg::kBM - 1) / Cfg::kBM, NT = (N + Cfg::kBN - 1) / Cfg::kBN;
-  hipLaunchKernelGGL((gemm_kernel<Cfg, Epi>), dim3(xcd_grid(MT, NT)), dim3(Cfg::kThreads), Cfg::kSmemBytes, st,
+  SD_LAUNCH_TIMED((gemm_kernel<Cfg, Epi>), dim3(xcd_grid(MT, NT)), dim3(Cfg::kThreads), Cfg::kSmemBytes, st,
                      A, lda, W, K, M, N, K, MT, NT, epi, m_real);
   return hipGetLastError();
 }
@@ -541,7 +545,7 @@ static hipError_t launch_ln_cfg(hipStream_t st, const bf16* A, int lda, const bf
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, kBytes);
   if (attr != hipSuccess) return attr;
   const int MT = (M + Cfg::kBM - 1) / Cfg::kBM, NT = (N + Cfg::kBN - 1) / Cfg::kBN;
-  hipLaunchKernelGGL((gemm_ln_kernel<Cfg, Epi>), dim3(xcd_grid(MT, NT)), dim3(Cfg::kThreads), kBytes, st,
+  SD_LAUNCH_TIMED((gemm_ln_kernel<Cfg, Epi>), dim3(xcd_grid(MT, NT)), dim3(Cfg::kThreads), kBytes, st,
                      A, lda, W, K, M, N, K, MT, NT, epi, m_real);
   return hipGetLastError();
 }
@@ -910,16 +914,16 @@ hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int 
     }();
     if (attr256 != hipSuccess) return attr256;
     if (stats)
-      hipLaunchKernelGGL(vocab256_kernel<false>, dim3(xcd_grid(MT256, NT256)), dim3(CfgVocab256::kThreads), kSmem256, st, A, E, M, V, K, MT256, NT256, NT, row_draft ? zd_row : nullptr, part, logits);
+      SD_LAUNCH_TIMED(vocab256_kernel<false>, dim3(xcd_grid(MT256, NT256)), dim3(CfgVocab256::kThreads), kSmem256, st, A, E, M, V, K, MT256, NT256, NT, row_draft ? zd_row : nullptr, part, logits);
     else
-      hipLaunchKernelGGL(vocab256_kernel<true>, dim3(xcd_grid(MT256, NT256)), dim3(CfgVocab256::kThreads), kSmem256, st, A, E, M, V, K, MT256, NT256, NT, nullptr, part, logits);
+      SD_LAUNCH_TIMED(vocab256_kernel<true>, dim3(xcd_grid(MT256, NT256)), dim3(CfgVocab256::kThreads), kSmem256, st, A, E, M, V, K, MT256, NT256, NT, nullptr, part, logits);
     return hipGetLastError();
   }
   if (stats)
-    hipLaunchKernelGGL(vocab_kernel<false>, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
+    SD_LAUNCH_TIMED(vocab_kernel<false>, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
                        A, E, M, V, K, MT, NT, row_draft ? zd_row : nullptr, part, logits);
   else
-    hipLaunchKernelGGL(vocab_kernel<true>, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
+    SD_LAUNCH_TIMED(vocab_kernel<true>, dim3(xcd_grid(MT, NT)), dim3(CfgVocab::kThreads), CfgVocab::kSmemBytes, st,
                        A, E, M, V, K, MT, NT, nullptr, part, logits);
   return hipGetLastError();
 }

@@ -3,6 +3,7 @@
 // api.hip before anything is launched.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace sd {
@@ -100,6 +101,28 @@ constexpr int kRowStats = 8;   // floats per row of merged statistics
 int vocab_tile_cols(int M);
 hipError_t vocab_stats(hipStream_t st, const bf16* A, const bf16* E, int M, int V, int K,
                        const int* row_draft, float* zd_row, float* part, float* logits, bool force_wide = false);
+
+// ---- per-kernel timing ----------------------------------------------------------------
+// While a KernelTimer is set for the calling thread, the next launch of a pass's main kernel (the GEMM,
+// attention and vocabulary kernels: SD_LAUNCH_TIMED) records the kernel's own begin and end in its two
+// events (the extended launch call), not the moments the stream reaches markers before and after it, and
+// says so in `used`.  Launch sites without it leave the timer alone; the caller then brackets the call.
+struct KernelTimer {
+  hipEvent_t start = nullptr, stop = nullptr;
+  bool used = false;
+};
+void set_kernel_timer(KernelTimer* t);   // nullptr: none
+KernelTimer* kernel_timer();
+#define SD_LAUNCH_TIMED(kernel, grid, block, smem, st, ...)                                               \
+  do {                                                                                                    \
+    sd::KernelTimer* kt_ = sd::kernel_timer();                                                            \
+    if (kt_ && !kt_->used) {                                                                              \
+      kt_->used = true;                                                                                   \
+      hipExtLaunchKernelGGL(kernel, grid, block, smem, st, kt_->start, kt_->stop, 0, __VA_ARGS__);        \
+    } else {                                                                                              \
+      hipLaunchKernelGGL(kernel, grid, block, smem, st, __VA_ARGS__);                                     \
+    }                                                                                                     \
+  } while (0)
 
 // ---- attn.hip ------------------------------------------------------------------------
 struct AttnArgs {

@@ -481,3 +481,30 @@ def test_random_medium_shapes_general_kernels():
         assert err <= tol, (case_no, B, k, hi, S, opt, err)
         assert not cases.compare_decisions(case, out["accept"], out["next"])[2], (case_no, B, k, opt)
     print(f"[random medium shapes] 8 cases, worst max-abs logit err {worst:.3e}")
+
+
+def test_kernel_kind_timing_counts_and_leaves_results_alone():
+    """specdec_profile_select / specdec_profile_read: the number of timed launches per kind is the number the
+    pass makes (3 residual-sum projections, 2 attentions, 1 QKV projection per layer, one vocabulary kernel),
+    every duration is positive and small, for the kernels timed by their own begin / end (general kernels) and
+    for those bracketed on the stream (small-batch kernels), and timing changes no result."""
+    for B, k in ((40, 4), (5, 4)):                      # general kernels / fused small-batch kernels
+        case = small_case(seed=61, B=B, k=k)
+        ses = gh.open_verifier(case)
+        ref = gh.gpu_verify(ses, case)
+        Ld = case.desc.dec_layers
+        for kind, per_pass in ((0, 3 * Ld), (3, 2 * Ld), (2, Ld), (4, 1)):
+            sd.specdec_profile_select(ses.ctx, kind)
+            sd.specdec_rewind(ses.ctx, ses.i32(case.lens))
+            out = gh.gpu_verify(ses, case)
+            ms, n = sd.specdec_profile_read(ses.ctx)
+            if B * (k + 1) > 32:
+                assert n == per_pass, (B, kind, n, per_pass)
+            elif kind in (0, 4):                         # the fused kernels: attention runs inside kind 0
+                assert n >= 1, (B, kind, n)
+            assert n == 0 or 0.0 < ms < 5.0 * n, (B, kind, ms, n)
+            assert np.array_equal(out["logits"], ref["logits"]) and np.array_equal(out["accept"], ref["accept"])
+        sd.specdec_profile_select(ses.ctx, -1)
+        ms, n = sd.specdec_profile_read(ses.ctx)
+        assert n == 0
+        ses.close()
