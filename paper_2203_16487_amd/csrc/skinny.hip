@@ -270,9 +270,10 @@ __global__ __launch_bounds__(kSkThreads) void sk_vocab_kernel(SkSrc src, int R, 
   const int n0 = blockIdx.x * 64 + wave * 16;
   constexpr int steps = d / 32, S1 = steps < kSkW ? steps : kSkW;
   typename SkFrag<WT>::type wf[S1];
+  const int dtok = sk_draft_tok(R, row_draft);   // first: the draft's embedding row then travels with the tile
   sk_wload<S1>(E, d, n0, V, 0, wf);
   SkDraft<PER, WT> dr;
-  sk_draft_fetch<PER, WT>(dr, R, E, V, row_draft, wscale);
+  sk_draft_fetch<PER, WT>(dr, R, E, V, dtok, wscale);
   float ws[4];   // this lane's columns n0 + 4 (lane / 16) + r
 #pragma unroll
   for (int r = 0; r < 4; ++r) ws[r] = sk_wscale<WT>(wscale, min(n0 + 4 * (lane >> 4) + r, V - 1));

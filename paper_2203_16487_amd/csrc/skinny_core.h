@@ -440,21 +440,33 @@ struct SkDraft {
   float scale;                             // row scale of the draft's embedding row (1 for bf16 weights)
   bool has;
 };
+// The draft of this lane's row (waves 0 and 1: row wave*16 + lane%16; others: -1).  Requested on its own,
+// before the block's weight tile, so that waiting for it does not wait for the tile and the draft's
+// embedding row is fetched while the tile streams in.
+__device__ __forceinline__ int sk_draft_tok(int R, const int* __restrict__ row_draft) {
+  const int wave = threadIdx.x >> 6;
+  if (wave >= 2) return -1;
+  return row_draft[min(wave * 16 + (int)(threadIdx.x & 15), R - 1)];
+}
 template <int PER, class WT>
-__device__ __forceinline__ void sk_draft_fetch(SkDraft<PER, WT>& dr, int R, const WT* __restrict__ E, int V,
-                                               const int* __restrict__ row_draft, const float* __restrict__ wscale) {
+__device__ __forceinline__ void sk_draft_fetch(SkDraft<PER, WT>& dr, int R, const WT* __restrict__ E, int V, int tok,
+                                               const float* __restrict__ wscale) {
   constexpr int d = 64 * PER;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, lq = lane & 15, g = lane >> 4;
   dr.has = false;
   if (wave >= 2) return;
   const int row = wave * 16 + lq;
-  const int tok = row_draft[min(row, R - 1)];
   dr.has = row < R && tok >= 0 && tok < V;
   dr.scale = wscale ? wscale[dr.has ? tok : 0] : 1.f;
   const WT* wp = E + (size_t)(dr.has ? tok : 0) * d + 8 * g;
 #pragma unroll
   for (int s = 0; s < SkDraft<PER, WT>::kSteps; ++s)
     dr.wf[s] = *reinterpret_cast<const typename SkFrag<WT>::type*>(wp + s * 32);
+}
+template <int PER, class WT>
+__device__ __forceinline__ void sk_draft_fetch(SkDraft<PER, WT>& dr, int R, const WT* __restrict__ E, int V,
+                                               const int* __restrict__ row_draft, const float* __restrict__ wscale) {
+  sk_draft_fetch<PER, WT>(dr, R, E, V, sk_draft_tok(R, row_draft), wscale);
 }
 template <int PER, class WT, class Out>
 __device__ __forceinline__ void sk_draft_logit(const SkDraft<PER, WT>& dr, const bf16* hb, int R, Out&& out) {
