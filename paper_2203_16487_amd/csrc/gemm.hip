@@ -259,7 +259,8 @@ static hipError_t launch(hipStream_t st, const bf16* A, int lda, const bf16* W, 
   if (M <= 0 || N <= 0) return hipSuccess;
   // enough 128x128 tiles to give every CU one?  else take 64x64 tiles
   const long wide_tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
-  if (wide_tiles >= 200) return launch_cfg<CfgWide>(st, A, lda, W, M, N, K, epi, m_real);
+  // (a K of 512 is eight stages: a launch is then mostly its tiles' fixed costs, and the small tiles' are smaller)
+  if (wide_tiles >= 200 && K > 512) return launch_cfg<CfgWide>(st, A, lda, W, M, N, K, epi, m_real);
   return launch_cfg<CfgSmall>(st, A, lda, W, M, N, K, epi, m_real);
 }
 
@@ -559,7 +560,7 @@ static hipError_t launch_ln(hipStream_t st, const bf16* A, int lda, const bf16* 
   if constexpr (Epi::kVec == 2) {
     if (N >= 3072 && M >= 1024) return launch_ln_cfg<CfgTall>(st, A, lda, W, M, N, K, epi, m_real);
   }
-  if (wide_tiles >= 200) return launch_ln_cfg<CfgWide>(st, A, lda, W, M, N, K, epi, m_real);
+  if (wide_tiles >= 200 && K > 512) return launch_ln_cfg<CfgWide>(st, A, lda, W, M, N, K, epi, m_real);
   return launch_ln_cfg<CfgSmall>(st, A, lda, W, M, N, K, epi, m_real);
 }
 
