@@ -49,6 +49,15 @@ MEASURED_TRAFFIC_BYTES = {
 }
 
 
+def kind_roofline(work_item, avg_s):
+    """(bound, algorithmic amount per launch) and the mean launch duration -> achieved rate and fraction of peak."""
+    bound, amount = work_item
+    peak, unit, scale = (PEAK_BF16_TFLOPS, "TFLOP/s", 1e12) if bound == "mfma" else (PEAK_HBM_GBS, "GB/s", 1e9)
+    rate = amount / max(avg_s, 1e-12) / scale
+    return {"bound": bound, "achieved": round(rate, 1), "unit": unit, "frac": round(rate / peak, 4),
+            "avg_launch_us": round(avg_s * 1e6, 2)}
+
+
 def _force_prefix(sd, ses, desc, B, k, L, prefix):
     """Decode state with a given stream, built by the library itself: the tokens are forced
     through verify+commit (accept_len / next_token given by the caller), so the KV cache holds
@@ -589,7 +598,10 @@ def main():
                    "tokens_per_step": tokens_per_step, "seed": SEED, "encode_ms_once": encode_ms},
         "batch128": {"iteration_us": sec * 1e6, "step_tflops": step_flops / sec / 1e12,
                      "mfma_frac": step_flops / sec / 1e12 / PEAK_BF16_TFLOPS,
-                     "kernel_ms_per_step": {kname: round(v[0], 4) for kname, v in per_kind.items()}},
+                     "kernel_ms_per_step": {kname: round(v[0], 4) for kname, v in per_kind.items()},
+                     # every kind against its own bound, from the three-step ranking passes (the dominant one is
+                     # timed over many more launches in "roofline")
+                     "kernel_roofline": {kname: kind_roofline(work[kname], v[1] * 1e-3) for kname, v in per_kind.items()}},
         "roofline": roof,
     }
     # verify-only latency at batch 128 (same state)
